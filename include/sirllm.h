@@ -1,0 +1,187 @@
+/*
+ * sirllm.h -- C ABI of the SirLLM memory-retention hot path for AMD MI355X (gfx950).
+ *
+ * One dialogue turn of the method (paper: Section 3.2 "Token Entropy", Section 3.3
+ * "Streaming Infinite Retentive LLM", Algorithm 1) adds four data-parallel operations
+ * around the language model's forward pass:
+ *
+ *   score    e_i = -log P(x_i | x_<i)            token entropy of every new token   (Sec. 3.2)
+ *   decay    E <- E * eta_decay                  once per dialogue round            (Sec. 3.3, Alg. 1 last line)
+ *   select   Id_sink, Id_entropy = Top_k(E), Id_recent                              (Sec. 3.1, Sec. 3.3)
+ *   compact  KV <- KV[Id], E <- E[Id]            for every layer and KV head        (Sec. 3.3, Alg. 1 eviction branch)
+ *
+ * The language model itself is not part of this library: logits, token ids and the K/V
+ * tensors are inputs.
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller, valid on the device that
+ *     is current when the call is made.  Policy and layout structs are HOST pointers and are
+ *     read before the call returns.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue work on it and return without synchronising.  The library allocates nothing,
+ *     creates no streams and keeps no state between calls.
+ *   - All shapes are host integers and are uniform over the `n_streams` independent dialogue
+ *     streams of a call.
+ *   - Return value: SIRLLM_OK (0) or a negative sirllm_status.  Arguments are validated on
+ *     the host before anything is enqueued; on a validation error nothing has been launched.
+ *   - Alignment: no alignment beyond the natural alignment of the element type is required.
+ *     The kernels take the widest access (16, 8, 4, 2 or 1 bytes) that all of a call's
+ *     pointers and strides allow; 16-byte aligned pointers, strides and rows run fastest.
+ *
+ * Notation (used throughout):
+ *   n_held   slots already in the cache, each with a score          n_new   tokens this turn
+ *   n_cand   = n_held + n_new                                        budget  = n_sink + n_topk + n_recent
+ *   n_keep   = min(n_cand, budget)
+ */
+#ifndef SIRLLM_H
+#define SIRLLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SIRLLM_OK              =  0,
+    SIRLLM_ERR_INVALID_ARG = -1,  /* null pointer, negative size, inconsistent shapes, overlapping src/dst */
+    SIRLLM_ERR_UNSUPPORTED = -2,  /* a size above a documented limit, unknown dtype */
+    SIRLLM_ERR_WORKSPACE   = -3,  /* workspace smaller than sirllm_workspace_bytes() or misaligned */
+    SIRLLM_ERR_HIP         = -4   /* the HIP runtime refused a launch; hipGetLastError() has the detail */
+} sirllm_status;
+
+typedef enum {
+    SIRLLM_F32  = 0,              /* IEEE binary32 */
+    SIRLLM_BF16 = 1               /* bfloat16: the upper 16 bits of a binary32 */
+} sirllm_dtype;
+
+/* Retention policy (Sec. 3.1: n_sink, n_recent; Sec. 3.3: k of Top_k and eta_decay).
+ * Any of the three sizes may be 0.  decay must be finite and >= 0. */
+typedef struct {
+    int32_t n_sink;     /* first n_sink cache slots are always kept */
+    int32_t n_topk;     /* k: how many of the remaining slots are kept by decayed score */
+    int32_t n_recent;   /* last n_recent candidate slots are always kept */
+    float   decay;      /* eta_decay, multiplied once into every held score per call */
+} sirllm_policy;
+
+/* Addressing of a K or V cache.  Element (stream s, layer l, kv head h, slot p, channel d)
+ * lives at  base + elem_bytes * (s*stride_stream + l*stride_layer + h*stride_head
+ *                                + p*stride_pos + d),   0 <= d < head_dim  (channels contiguous).
+ * Strides are in elements and must be >= 0; stride_pos >= head_dim.  The K/V payload is
+ * treated as opaque bytes. */
+typedef struct {
+    int32_t n_layers;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t elem_bytes;   /* 1, 2, 4 or 8 */
+    int64_t stride_stream;
+    int64_t stride_layer;
+    int64_t stride_head;
+    int64_t stride_pos;
+} sirllm_kv_layout;
+
+/* Largest n_cand = n_held + n_new per stream that decay_select / step accept. */
+#define SIRLLM_MAX_CAND 32768
+
+/*
+ * Token entropy (Sec. 3.2, the displayed definition of e_i):
+ *     scores_out[r] = logsumexp_v(logits[r][0:vocab]) - logits[r][token_ids[r]],   0 <= r < n_rows
+ * with the natural logarithm, i.e. minus the log-softmax probability of the token that
+ * actually occurred.  Row r of `logits` starts at element r*ld (ld >= vocab) and is the
+ * next-token distribution from which token_ids[r] was drawn; the library does no shifting.
+ * Inputs are widened exactly to binary32; max, sum and log are accumulated in binary32.
+ *   logits      device, n_rows x ld elements of `dt`, read once
+ *   token_ids   device, n_rows int32; an id outside [0, vocab) yields a quiet NaN score
+ *   scores_out  device, n_rows float
+ * -inf logits are allowed and contribute 0.  A row with no finite maximum (all -inf, any
+ * +inf, any NaN) yields NaN.  n_rows == 0 is a no-op.
+ * workspace: sirllm_workspace_bytes(0, 0, n_rows, vocab) bytes, 256-byte aligned (may be
+ * NULL when that is 0).
+ */
+int sirllm_score(const void* logits, sirllm_dtype dt, int64_t n_rows, int32_t vocab, int64_t ld,
+                 const int32_t* token_ids, float* scores_out,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Decay, select and index build (Sec. 3.3: E <- E*eta, Id_entropy = Top_k(E), E <- E[Id];
+ * Sec. 3.1: Id_sink, Id_recent; Alg. 1 eviction branch and its trigger "cache size > L").
+ * For every stream s, with E = scores + s*scores_stride:
+ *   1. E[i] <- fl32(E[i] * decay) for i < n_held (one rounded binary32 multiply, denormals
+ *      kept); the n_new entries E[n_held : n_cand) are this turn's scores and enter undecayed.
+ *      The input array is not modified; the decayed values appear in scores_out.
+ *   2. If n_cand <= budget nothing is evicted: kept_idx = 0..n_cand-1.
+ *      Otherwise kept = [0, n_sink)  U  Top_k of the middle region [n_sink, n_cand-n_recent)
+ *      U  [n_cand-n_recent, n_cand).  Top_k takes the n_topk largest decayed scores; equal
+ *      scores (IEEE ==, so +0 == -0) go to the lower slot.  NaNs are ordered by bit pattern:
+ *      a NaN with the sign bit clear ranks above +inf, one with it set below -inf.
+ *   3. kept_idx[s*idx_stride + j], j < n_keep, lists the kept slots in ascending order (the
+ *      in-cache position j of Sec. 3.3's worked example), and
+ *      scores_out[s*out_stride + j] = E[kept_idx[j]].
+ * Limits: n_cand <= SIRLLM_MAX_CAND (else SIRLLM_ERR_UNSUPPORTED).  n_streams == 0 or
+ * n_cand == 0 is a no-op.  scores_out must not overlap scores.
+ */
+int sirllm_decay_select(const float* scores, int64_t scores_stride,
+                        int32_t n_streams, int32_t n_held, int32_t n_new,
+                        const sirllm_policy* policy,
+                        int32_t* kept_idx, int64_t idx_stride,
+                        float* scores_out, int64_t out_stride,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * KV compaction (Sec. 3.3: KV_cache <- KV_cache[Id], for the keys and the values of every
+ * layer and head).  Out of place:
+ *     dst(s, l, h, j, :) = src(s, l, h, kept_idx[s*idx_stride + j], :),   0 <= j < n_keep
+ * for K (k_src -> k_dst) and V (v_src -> v_dst).  src and dst layouts must agree in
+ * n_layers, n_kv_heads, head_dim and elem_bytes; strides may differ.  v_src/v_dst may both be
+ * NULL to move one tensor only.  Source and destination must not overlap.
+ *   n_src   number of valid slots per (stream, layer, head) in the source; an index outside
+ *           [0, n_src) cannot be reported without a device read-back, so the destination row
+ *           is zero-filled instead of reading out of bounds.
+ * n_keep == 0 or n_streams == 0 is a no-op.
+ */
+int sirllm_compact_kv(const void* k_src, const void* v_src, const sirllm_kv_layout* src, int32_t n_src,
+                      void* k_dst, void* v_dst, const sirllm_kv_layout* dst,
+                      const int32_t* kept_idx, int64_t idx_stride,
+                      int32_t n_streams, int32_t n_keep, void* hip_stream);
+
+/*
+ * One whole retention step (Alg. 1 with the loop rotated so that a call is
+ * score -> decay held -> select -> compact; multiplying every candidate by the same
+ * eta > 0 cannot change a comparison, so the kept sets equal those of the printed order).
+ *   logits, token_ids   n_streams*n_new rows, row s*n_new + r belongs to stream s, token r
+ *   scores              per stream: [0, n_held) held scores (input, unchanged),
+ *                       [n_held, n_cand) receives this turn's scores (output)
+ *   k_src, v_src        caches holding n_cand slots per stream (the new tokens' K/V already
+ *                       appended at slots [n_held, n_cand))
+ *   kept_idx, scores_out, k_dst, v_dst   as in sirllm_decay_select / sirllm_compact_kv
+ * When n_cand <= budget nothing is evicted: kept_idx = 0..n_cand-1, scores_out holds the
+ * decayed and new scores, k_dst/v_dst are NOT written (they may be NULL) and the cache
+ * stays in k_src/v_src.
+ * workspace: sirllm_workspace_bytes(n_streams, n_cand, n_streams*n_new, vocab) bytes.
+ */
+int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld,
+                const int32_t* token_ids,
+                float* scores, int64_t scores_stride,
+                int32_t n_streams, int32_t n_held, int32_t n_new,
+                const sirllm_policy* policy,
+                const void* k_src, const void* v_src, const sirllm_kv_layout* src,
+                void* k_dst, void* v_dst, const sirllm_kv_layout* dst,
+                int32_t* kept_idx, int64_t idx_stride,
+                float* scores_out, int64_t out_stride,
+                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of device workspace the calls above need for these sizes (pass 0 for the sizes a
+ * call does not have).  Never fails; the result is a multiple of 256. */
+size_t sirllm_workspace_bytes(int32_t n_streams, int32_t n_cand, int64_t n_rows, int32_t vocab);
+
+/* Static, NUL-terminated description of a status code. */
+const char* sirllm_status_string(int status);
+
+/* Library version, "major.minor.patch". */
+const char* sirllm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SIRLLM_H */

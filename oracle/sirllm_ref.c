@@ -1,0 +1,302 @@
+/*
+ * sirllm_ref.c -- CPU oracle of the SirLLM retention step.  TEST INFRASTRUCTURE ONLY:
+ * called by the tests, the smoke check and the benchmark's CPU-baseline leg, never by the
+ * product path.  Plain C, host memory, double-precision accumulation, no blocking, no
+ * fusion: each function is the definition in the paper written out.
+ *
+ * Readings taken where the paper leaves a choice (each is checked by a test):
+ *   - "token entropy" is the printed formula, the surprisal of the token that occurred
+ *     (Sec. 3.2), not the Shannon entropy of the row; natural logarithm.
+ *   - index sets are 0-based and half open: sinks [0, n_sink), recent [n_cand-n_recent, n_cand)
+ *     (Sec. 3.1 prints n_sink+1 indices, but Sec. 4.1 fixes the sink size at 4 and the worked
+ *     example of Sec. 3.3 has sinks 0,1,2,3).
+ *   - Top_k runs over the slots that are neither sink nor recent, so the three sets are
+ *     disjoint and the cache holds exactly the budget after an eviction.
+ *   - kept slots are listed in ascending slot order (Sec. 3.3's example is ascending).
+ *   - "E <- E + E_t" in Algorithm 1 appends; the decay multiplies only the scores that were
+ *     already held when the turn began (new scores enter the selection undecayed).
+ *   - the eviction trigger is "n_cand > budget" (Algorithm 1: cache size > L).
+ *   - equal scores: the lower slot wins.
+ *
+ * Parity status: every function below is pinned by tests/test_oracle_*.py against closed
+ * forms, library routines, brute force and the paper's worked example.  What is NOT pinned:
+ * the paper prints no numeric score, kept set or cache content from its experiments, so
+ * agreement with the authors' own runs is "parity unpinned".
+ */
+#include "sirllm_ref.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static int g_threads = 1;
+
+int sirllm_ref_set_threads(int n)
+{
+    if (n < 1) n = 1;
+#ifdef _OPENMP
+    g_threads = n;
+#else
+    g_threads = 1;
+#endif
+    return g_threads;
+}
+
+int sirllm_ref_get_threads(void) { return g_threads; }
+
+/* ------------------------------------------------------------------------------------ */
+/* Sec. 3.2:  e = -log P(x) = logsumexp(z) - z[x]                                        */
+/* ------------------------------------------------------------------------------------ */
+
+static double logit_at(const void* logits, int dtype, int64_t index)
+{
+    if (dtype == SIRLLM_REF_F32)
+        return (double)((const float*)logits)[index];
+    /* bfloat16 is the top half of a binary32 */
+    uint32_t bits = (uint32_t)((const uint16_t*)logits)[index] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+int sirllm_ref_score(const void* logits, int dtype, int64_t n_rows, int32_t vocab, int64_t ld,
+                     const int32_t* token_ids, float* scores_out)
+{
+    if (n_rows < 0 || vocab < 1 || ld < vocab) return -1;
+    if (dtype != SIRLLM_REF_F32 && dtype != SIRLLM_REF_BF16) return -1;
+    if (n_rows == 0) return 0;
+    if (!logits || !token_ids || !scores_out) return -1;
+
+    int64_t r;
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+#endif
+    for (r = 0; r < n_rows; ++r) {
+        const int64_t base = r * ld;
+        const int32_t tok = token_ids[r];
+        if (tok < 0 || tok >= vocab) {          /* no such token: no probability to take the log of */
+            scores_out[r] = (float)NAN;
+            continue;
+        }
+        double m = -INFINITY;
+        for (int32_t v = 0; v < vocab; ++v) {
+            double z = logit_at(logits, dtype, base + v);
+            if (z > m) m = z;
+        }
+        double s = 0.0;
+        for (int32_t v = 0; v < vocab; ++v)
+            s += exp(logit_at(logits, dtype, base + v) - m);
+        double e = (m - logit_at(logits, dtype, base + tok)) + log(s);
+        scores_out[r] = (float)e;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* Sec. 3.3 / 3.1: decay, Top_k, sink and recent sets                                     */
+/* ------------------------------------------------------------------------------------ */
+
+typedef struct { float score; int32_t slot; } scored_slot;
+
+/* -1: x is a NaN with the sign bit set, +1: a NaN with it clear, 0: a number */
+static int nan_class(float x)
+{
+    if (x == x) return 0;
+    return signbit(x) ? -1 : 1;
+}
+
+/* >0 when a ranks above b, <0 when below, 0 when they tie.  Numbers by IEEE comparison
+ * (+0 ties with -0).  NaNs have no IEEE order, so they are placed by bit pattern: sign-clear
+ * NaNs above everything, sign-set NaNs below everything, and within a class in the order
+ * their magnitude bits would have if they were numbers of that sign. */
+static int rank_cmp(float a, float b)
+{
+    int ca = nan_class(a), cb = nan_class(b);
+    if (ca == 0 && cb == 0) return (a > b) - (a < b);
+    if (ca != cb) return (ca > cb) - (ca < cb);
+    uint32_t ua, ub;
+    memcpy(&ua, &a, 4);
+    memcpy(&ub, &b, 4);
+    ua &= 0x7fffffffu;
+    ub &= 0x7fffffffu;
+    int mag = (ua > ub) - (ua < ub);
+    return ca > 0 ? mag : -mag;
+}
+
+/* qsort order: higher score first; among equals the lower slot first */
+static int by_score_then_slot(const void* pa, const void* pb)
+{
+    const scored_slot* a = (const scored_slot*)pa;
+    const scored_slot* b = (const scored_slot*)pb;
+    int c = rank_cmp(a->score, b->score);
+    if (c != 0) return -c;
+    return (a->slot > b->slot) - (a->slot < b->slot);
+}
+
+static int policy_ok(const sirllm_ref_policy* p)
+{
+    return p && p->n_sink >= 0 && p->n_topk >= 0 && p->n_recent >= 0;
+}
+
+int sirllm_ref_decay_select(const float* scores, int64_t scores_stride,
+                            int32_t n_streams, int32_t n_held, int32_t n_new,
+                            const sirllm_ref_policy* policy,
+                            int32_t* kept_idx, int64_t idx_stride,
+                            float* scores_out, int64_t out_stride)
+{
+    if (n_streams < 0 || n_held < 0 || n_new < 0 || !policy_ok(policy)) return -1;
+    const int64_t n_cand = (int64_t)n_held + n_new;
+    const int64_t budget = (int64_t)policy->n_sink + policy->n_topk + policy->n_recent;
+    if (n_streams == 0 || n_cand == 0) return 0;
+    if (!scores || !kept_idx || !scores_out) return -1;
+    const float eta = policy->decay;
+
+    for (int32_t s = 0; s < n_streams; ++s) {
+        const float* E_in = scores + (int64_t)s * scores_stride;
+        int32_t* idx = kept_idx + (int64_t)s * idx_stride;
+        float* E_out = scores_out + (int64_t)s * out_stride;
+
+        /* E: the entropy cache after "append" and "decay" */
+        float* E = (float*)malloc((size_t)n_cand * sizeof(float));
+        char* keep = (char*)calloc((size_t)n_cand, 1);
+        if (!E || !keep) { free(E); free(keep); return -1; }
+        for (int64_t i = 0; i < n_cand; ++i) {
+            if (i < n_held) {
+                volatile float prod = E_in[i] * eta;   /* one binary32 multiply, rounded to nearest even */
+                E[i] = prod;
+            } else {
+                E[i] = E_in[i];
+            }
+        }
+
+        if (n_cand <= budget) {
+            for (int64_t i = 0; i < n_cand; ++i) keep[i] = 1;       /* trigger not reached */
+        } else {
+            const int64_t mid_lo = policy->n_sink;
+            const int64_t mid_hi = n_cand - policy->n_recent;
+            for (int64_t i = 0; i < mid_lo; ++i) keep[i] = 1;        /* Id_sink   */
+            for (int64_t i = mid_hi; i < n_cand; ++i) keep[i] = 1;   /* Id_recent */
+            const int64_t n_mid = mid_hi - mid_lo;
+            scored_slot* mid = (scored_slot*)malloc((size_t)(n_mid > 0 ? n_mid : 1) * sizeof(scored_slot));
+            if (!mid) { free(E); free(keep); return -1; }
+            for (int64_t i = 0; i < n_mid; ++i) {
+                mid[i].score = E[mid_lo + i];
+                mid[i].slot = (int32_t)(mid_lo + i);
+            }
+            qsort(mid, (size_t)n_mid, sizeof(scored_slot), by_score_then_slot);
+            for (int64_t i = 0; i < policy->n_topk; ++i) keep[mid[i].slot] = 1;   /* Id_entropy */
+            free(mid);
+        }
+
+        int64_t j = 0;
+        for (int64_t i = 0; i < n_cand; ++i) {
+            if (keep[i]) {
+                idx[j] = (int32_t)i;
+                E_out[j] = E[i];
+                ++j;
+            }
+        }
+        free(E);
+        free(keep);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* Sec. 3.3: KV_cache <- KV_cache[Id]                                                    */
+/* ------------------------------------------------------------------------------------ */
+
+static int layout_ok(const sirllm_ref_kv_layout* L)
+{
+    return L && L->n_layers >= 0 && L->n_kv_heads >= 0 && L->head_dim >= 0 && L->elem_bytes > 0 &&
+           L->stride_stream >= 0 && L->stride_layer >= 0 && L->stride_head >= 0 && L->stride_pos >= 0;
+}
+
+static void gather_one(const char* src, const sirllm_ref_kv_layout* S, int32_t n_src,
+                       char* dst, const sirllm_ref_kv_layout* D,
+                       const int32_t* kept_idx, int64_t idx_stride, int32_t n_streams, int32_t n_keep)
+{
+    const size_t row_bytes = (size_t)S->head_dim * (size_t)S->elem_bytes;
+    const int64_t planes = (int64_t)n_streams * S->n_layers * S->n_kv_heads;
+    int64_t p;
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+#endif
+    for (p = 0; p < planes; ++p) {
+        const int64_t h = p % S->n_kv_heads;
+        const int64_t l = (p / S->n_kv_heads) % S->n_layers;
+        const int64_t s = p / ((int64_t)S->n_kv_heads * S->n_layers);
+        const char* sp = src + (size_t)S->elem_bytes * (size_t)(s * S->stride_stream + l * S->stride_layer + h * S->stride_head);
+        char* dp = dst + (size_t)D->elem_bytes * (size_t)(s * D->stride_stream + l * D->stride_layer + h * D->stride_head);
+        const int32_t* idx = kept_idx + s * idx_stride;
+        for (int32_t j = 0; j < n_keep; ++j) {
+            char* drow = dp + (size_t)D->elem_bytes * (size_t)((int64_t)j * D->stride_pos);
+            const int32_t i = idx[j];
+            if (i < 0 || i >= n_src)
+                memset(drow, 0, row_bytes);      /* no such slot: defined as an all-zero row */
+            else
+                memcpy(drow, sp + (size_t)S->elem_bytes * (size_t)((int64_t)i * S->stride_pos), row_bytes);
+        }
+    }
+}
+
+int sirllm_ref_compact_kv(const void* k_src, const void* v_src, const sirllm_ref_kv_layout* src, int32_t n_src,
+                          void* k_dst, void* v_dst, const sirllm_ref_kv_layout* dst,
+                          const int32_t* kept_idx, int64_t idx_stride,
+                          int32_t n_streams, int32_t n_keep)
+{
+    if (!layout_ok(src) || !layout_ok(dst) || n_streams < 0 || n_keep < 0 || n_src < 0) return -1;
+    if (src->n_layers != dst->n_layers || src->n_kv_heads != dst->n_kv_heads ||
+        src->head_dim != dst->head_dim || src->elem_bytes != dst->elem_bytes) return -1;
+    if (n_streams == 0 || n_keep == 0) return 0;
+    if (!k_src || !k_dst || !kept_idx) return -1;
+    if ((v_src == NULL) != (v_dst == NULL)) return -1;
+    gather_one((const char*)k_src, src, n_src, (char*)k_dst, dst, kept_idx, idx_stride, n_streams, n_keep);
+    if (v_src)
+        gather_one((const char*)v_src, src, n_src, (char*)v_dst, dst, kept_idx, idx_stride, n_streams, n_keep);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* Algorithm 1, one turn                                                                 */
+/* ------------------------------------------------------------------------------------ */
+
+int sirllm_ref_step(const void* logits, int dtype, int32_t vocab, int64_t ld, const int32_t* token_ids,
+                    float* scores, int64_t scores_stride,
+                    int32_t n_streams, int32_t n_held, int32_t n_new,
+                    const sirllm_ref_policy* policy,
+                    const void* k_src, const void* v_src, const sirllm_ref_kv_layout* src,
+                    void* k_dst, void* v_dst, const sirllm_ref_kv_layout* dst,
+                    int32_t* kept_idx, int64_t idx_stride,
+                    float* scores_out, int64_t out_stride)
+{
+    if (n_streams < 0 || n_held < 0 || n_new < 0 || !policy_ok(policy)) return -1;
+    const int64_t n_cand = (int64_t)n_held + n_new;
+    const int64_t budget = (int64_t)policy->n_sink + policy->n_topk + policy->n_recent;
+    if (n_streams == 0 || n_cand == 0) return 0;
+    if (!scores) return -1;
+
+    /* E_t = Entropy([I_t, R_t]);  E <- E ++ E_t */
+    for (int32_t s = 0; s < n_streams && n_new > 0; ++s) {
+        const size_t esz = dtype == SIRLLM_REF_F32 ? 4 : 2;
+        const char* rows = (const char*)logits + esz * (size_t)((int64_t)s * n_new * ld);
+        int rc = sirllm_ref_score(rows, dtype, n_new, vocab, ld, token_ids + (int64_t)s * n_new,
+                                  scores + (int64_t)s * scores_stride + n_held);
+        if (rc) return rc;
+    }
+    /* E <- E * eta (held part), Top_k, index list, E <- E[Id] */
+    int rc = sirllm_ref_decay_select(scores, scores_stride, n_streams, n_held, n_new, policy,
+                                     kept_idx, idx_stride, scores_out, out_stride);
+    if (rc) return rc;
+    /* KV <- KV[Id], only when the cache is over budget */
+    if (n_cand > budget) {
+        rc = sirllm_ref_compact_kv(k_src, v_src, src, (int32_t)n_cand, k_dst, v_dst, dst,
+                                   kept_idx, idx_stride, n_streams, (int32_t)budget);
+        if (rc) return rc;
+    }
+    return 0;
+}

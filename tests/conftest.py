@@ -1,0 +1,21 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run under gpurun); everything else runs on CPU")
+
+
+@pytest.fixture(scope="session")
+def ref():
+    """The CPU oracle's numpy front end, compiled on demand."""
+    from oracle import build as obuild
+    obuild.build(force=False)
+    from oracle import ref as r
+    return r
