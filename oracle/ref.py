@@ -31,26 +31,31 @@ class _CLayout(C.Structure):
 _lib = None
 
 
+def load(path):
+    """Open a build of the oracle and declare its signatures."""
+    L = C.CDLL(path)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    L.sirllm_ref_score.argtypes = [vp, C.c_int, i64, i32, i64, vp, vp]
+    L.sirllm_ref_decay_select.argtypes = [vp, i64, i32, i32, i32, C.POINTER(_CPolicy), vp, i64, vp, i64]
+    L.sirllm_ref_compact_kv.argtypes = [vp, vp, C.POINTER(_CLayout), i32, vp, vp, C.POINTER(_CLayout),
+                                        vp, i64, i32, i32]
+    L.sirllm_ref_step.argtypes = [vp, C.c_int, i32, i64, vp, vp, i64, i32, i32, i32, C.POINTER(_CPolicy),
+                                  vp, vp, C.POINTER(_CLayout), vp, vp, C.POINTER(_CLayout),
+                                  vp, i64, vp, i64]
+    for f in (L.sirllm_ref_score, L.sirllm_ref_decay_select, L.sirllm_ref_compact_kv, L.sirllm_ref_step,
+              L.sirllm_ref_set_threads, L.sirllm_ref_get_threads):
+        f.restype = C.c_int
+    L.sirllm_ref_set_threads.argtypes = [C.c_int]
+    return L
+
+
 def lib():
     global _lib
     if _lib is None:
         path = _build.LIB
         if not os.path.exists(path):
             path = _build.build()
-        L = C.CDLL(path)
-        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
-        L.sirllm_ref_score.argtypes = [vp, C.c_int, i64, i32, i64, vp, vp]
-        L.sirllm_ref_decay_select.argtypes = [vp, i64, i32, i32, i32, C.POINTER(_CPolicy), vp, i64, vp, i64]
-        L.sirllm_ref_compact_kv.argtypes = [vp, vp, C.POINTER(_CLayout), i32, vp, vp, C.POINTER(_CLayout),
-                                            vp, i64, i32, i32]
-        L.sirllm_ref_step.argtypes = [vp, C.c_int, i32, i64, vp, vp, i64, i32, i32, i32, C.POINTER(_CPolicy),
-                                      vp, vp, C.POINTER(_CLayout), vp, vp, C.POINTER(_CLayout),
-                                      vp, i64, vp, i64]
-        for f in (L.sirllm_ref_score, L.sirllm_ref_decay_select, L.sirllm_ref_compact_kv, L.sirllm_ref_step,
-                  L.sirllm_ref_set_threads, L.sirllm_ref_get_threads):
-            f.restype = C.c_int
-        L.sirllm_ref_set_threads.argtypes = [C.c_int]
-        _lib = L
+        _lib = load(path)
     return _lib
 
 
