@@ -1,0 +1,244 @@
+"""Thin ctypes binding of libsirllm.so: the entry points of include/sirllm.h under the same names.
+
+Argument marshalling only -- device tensors come in as ``torch.Tensor`` (PyTorch supplies device
+memory and the stream), go out as raw pointers, sizes and strides; every step of the path runs in
+the library's HIP kernels.  There is no fallback: importing this module without a built library
+raises, and a non-zero status from the library raises ``SirllmError``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from collections import namedtuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsirllm.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first (python -m paper_2405_12528_amd.build, or "
+        "__graft_entry__.build()).  There is no CPU or PyTorch fallback for the retention step.")
+
+_lib = C.CDLL(LIB_PATH)
+
+SIRLLM_OK, SIRLLM_ERR_INVALID_ARG, SIRLLM_ERR_UNSUPPORTED, SIRLLM_ERR_WORKSPACE, SIRLLM_ERR_HIP = 0, -1, -2, -3, -4
+SIRLLM_F32, SIRLLM_BF16 = 0, 1
+SIRLLM_MAX_CAND = 32768
+
+Policy = namedtuple("Policy", "n_sink n_topk n_recent decay")
+
+
+class sirllm_policy(C.Structure):
+    _fields_ = [("n_sink", C.c_int32), ("n_topk", C.c_int32), ("n_recent", C.c_int32), ("decay", C.c_float)]
+
+
+class sirllm_kv_layout(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("elem_bytes", C.c_int32), ("stride_stream", C.c_int64), ("stride_layer", C.c_int64),
+                ("stride_head", C.c_int64), ("stride_pos", C.c_int64)]
+
+
+EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step",
+           "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
+
+_vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+_PP, _LP = C.POINTER(sirllm_policy), C.POINTER(sirllm_kv_layout)
+_lib.sirllm_score.argtypes = [_vp, C.c_int, _i64, _i32, _i64, _vp, _vp, _vp, _sz, _vp]
+_lib.sirllm_decay_select.argtypes = [_vp, _i64, _i32, _i32, _i32, _PP, _vp, _i64, _vp, _i64, _vp, _sz, _vp]
+_lib.sirllm_compact_kv.argtypes = [_vp, _vp, _LP, _i32, _vp, _vp, _LP, _vp, _i64, _i32, _i32, _vp]
+_lib.sirllm_step.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _i32, _i32, _PP,
+                             _vp, _vp, _LP, _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _sz, _vp]
+for _n in ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step"):
+    getattr(_lib, _n).restype = C.c_int
+_lib.sirllm_workspace_bytes.argtypes = [_i32, _i32, _i64, _i32]
+_lib.sirllm_workspace_bytes.restype = _sz
+_lib.sirllm_status_string.argtypes = [C.c_int]
+_lib.sirllm_status_string.restype = C.c_char_p
+_lib.sirllm_version.restype = C.c_char_p
+
+
+class SirllmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status}: {sirllm_status_string(status)}")
+
+
+def raw():
+    """The ctypes library handle, for callers that pass raw pointers themselves."""
+    return _lib
+
+
+def sirllm_status_string(status: int) -> str:
+    return _lib.sirllm_status_string(int(status)).decode()
+
+
+def sirllm_version() -> str:
+    return _lib.sirllm_version().decode()
+
+
+def sirllm_workspace_bytes(n_streams: int, n_cand: int, n_rows: int, vocab: int) -> int:
+    return int(_lib.sirllm_workspace_bytes(n_streams, n_cand, n_rows, vocab))
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SIRLLM_F32
+    if t.dtype == torch.bfloat16:
+        return SIRLLM_BF16
+    raise TypeError(f"logits dtype {t.dtype} not supported (float32 or bfloat16)")
+
+
+def _on_device(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise ValueError("libsirllm takes device tensors only")
+
+
+def _policy(p) -> sirllm_policy:
+    return sirllm_policy(int(p.n_sink), int(p.n_topk), int(p.n_recent), float(p.decay))
+
+
+def kv_layout(t: torch.Tensor) -> sirllm_kv_layout:
+    """Layout struct of a [streams, layers, kv_heads, slots, head_dim] tensor (any strides, last axis contiguous)."""
+    if t.dim() != 5:
+        raise ValueError("K/V tensors are [streams, layers, kv_heads, slots, head_dim]")
+    if t.shape[4] > 1 and t.stride(4) != 1:
+        raise ValueError("head_dim must be contiguous")
+    return sirllm_kv_layout(t.shape[1], t.shape[2], t.shape[4], t.element_size(),
+                            t.stride(0), t.stride(1), t.stride(2), t.stride(3))
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def _check(rc, where):
+    if rc != SIRLLM_OK:
+        raise SirllmError(rc, where)
+
+
+def sirllm_score(logits: torch.Tensor, token_ids: torch.Tensor, scores_out: torch.Tensor, vocab: int | None = None,
+                 workspace: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """scores_out[r] = logsumexp(logits[r, :vocab]) - logits[r, token_ids[r]];  logits is [n_rows, ld]."""
+    _on_device(logits, token_ids, scores_out, workspace)
+    if logits.dim() != 2 or (logits.shape[1] > 1 and logits.stride(1) != 1):
+        raise ValueError("logits must be [n_rows, ld] with contiguous rows")
+    n_rows = logits.shape[0]
+    ld = logits.stride(0) if n_rows > 1 else logits.shape[1]
+    vocab = logits.shape[1] if vocab is None else int(vocab)
+    if token_ids.dtype != torch.int32 or scores_out.dtype != torch.float32:
+        raise TypeError("token_ids must be int32 and scores_out float32")
+    if token_ids.numel() < n_rows or scores_out.numel() < n_rows or not token_ids.is_contiguous() \
+            or not scores_out.is_contiguous():
+        raise ValueError("token_ids / scores_out must be contiguous with n_rows entries")
+    wp, wb = _ws(workspace)
+    _check(_lib.sirllm_score(_ptr(logits), _dtype_code(logits), n_rows, vocab, ld, _ptr(token_ids),
+                             _ptr(scores_out), wp, wb, _stream(stream)), "sirllm_score")
+    return scores_out
+
+
+def sirllm_decay_select(scores: torch.Tensor, n_held: int, n_new: int, policy, kept_idx: torch.Tensor,
+                        scores_out: torch.Tensor, workspace: torch.Tensor | None = None, stream=None):
+    """scores [n_streams, >= n_held+n_new] f32; kept_idx [n_streams, >= n_keep] i32; scores_out likewise f32."""
+    _on_device(scores, kept_idx, scores_out, workspace)
+    for t, dt in ((scores, torch.float32), (kept_idx, torch.int32), (scores_out, torch.float32)):
+        if t.dim() != 2 or t.dtype != dt or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise ValueError("scores / kept_idx / scores_out must be 2-D with contiguous rows (f32 / i32 / f32)")
+    n_streams = scores.shape[0]
+    if kept_idx.shape[0] != n_streams or scores_out.shape[0] != n_streams:
+        raise ValueError("one row per stream in every array")
+    p = _policy(policy)
+    wp, wb = _ws(workspace)
+    _check(_lib.sirllm_decay_select(_ptr(scores), _row_stride(scores), n_streams, n_held, n_new, C.byref(p),
+                                    _ptr(kept_idx), _row_stride(kept_idx), _ptr(scores_out), _row_stride(scores_out),
+                                    wp, wb, _stream(stream)), "sirllm_decay_select")
+    return kept_idx, scores_out
+
+
+def _row_stride(t: torch.Tensor) -> int:
+    return t.stride(0) if t.shape[0] > 1 else max(t.shape[1], 1)
+
+
+def sirllm_compact_kv(k_src: torch.Tensor, v_src, k_dst: torch.Tensor, v_dst, kept_idx: torch.Tensor,
+                      n_keep: int, n_src: int | None = None, stream=None):
+    """dst[s, l, h, j, :] = src[s, l, h, kept_idx[s, j], :] for j < n_keep, for K and (if given) V."""
+    _on_device(k_src, v_src, k_dst, v_dst, kept_idx)
+    if kept_idx.dim() != 2 or kept_idx.dtype != torch.int32 or (kept_idx.shape[1] > 1 and kept_idx.stride(1) != 1):
+        raise ValueError("kept_idx must be [n_streams, >= n_keep] int32 with contiguous rows")
+    ls, ld = kv_layout(k_src), kv_layout(k_dst)
+    if v_src is not None:
+        if kv_layout_tuple(v_src) != kv_layout_tuple(k_src) or kv_layout_tuple(v_dst) != kv_layout_tuple(k_dst):
+            raise ValueError("K and V must share one layout")
+    n_streams = k_src.shape[0]
+    n_src = k_src.shape[3] if n_src is None else int(n_src)
+    if k_dst.shape[3] < n_keep or k_src.shape[3] < n_src or kept_idx.shape[0] != n_streams \
+            or k_dst.shape[0] != n_streams:
+        raise ValueError("destination has fewer than n_keep slots, or stream counts differ")
+    _check(_lib.sirllm_compact_kv(_ptr(k_src), _ptr(v_src), C.byref(ls), n_src, _ptr(k_dst), _ptr(v_dst),
+                                  C.byref(ld), _ptr(kept_idx), _row_stride(kept_idx), n_streams, int(n_keep),
+                                  _stream(stream)), "sirllm_compact_kv")
+    return k_dst, v_dst
+
+
+def kv_layout_tuple(t):
+    L = kv_layout(t)
+    return tuple(getattr(L, f) for f, _ in sirllm_kv_layout._fields_)
+
+
+def sirllm_step(logits: torch.Tensor, token_ids: torch.Tensor, vocab: int, scores: torch.Tensor, n_held: int,
+                n_new: int, policy, k_src: torch.Tensor, v_src: torch.Tensor, k_dst, v_dst,
+                kept_idx: torch.Tensor, scores_out: torch.Tensor, workspace: torch.Tensor | None = None,
+                stream=None) -> int:
+    """One retention step for n_streams = scores.shape[0] streams; returns n_keep.
+
+    logits [n_streams*n_new, ld]; scores [n_streams, >= n_cand] (held scores in, new scores written
+    behind them); k_src/v_src [streams, layers, kv_heads, >= n_cand, head_dim]; k_dst/v_dst the same
+    with >= n_keep slots (may be None when n_cand <= budget: nothing is evicted then)."""
+    _on_device(logits, token_ids, scores, k_src, v_src, k_dst, v_dst, kept_idx, scores_out, workspace)
+    n_streams = scores.shape[0]
+    if logits.dim() != 2 or (logits.shape[1] > 1 and logits.stride(1) != 1):
+        raise ValueError("logits must be [n_streams*n_new, ld] with contiguous rows")
+    if logits.shape[0] != n_streams * n_new or token_ids.numel() != n_streams * n_new:
+        raise ValueError("one logits row and one token id per new token")
+    if token_ids.dtype != torch.int32 or not token_ids.is_contiguous():
+        raise TypeError("token_ids must be contiguous int32")
+    for t, dt in ((scores, torch.float32), (kept_idx, torch.int32), (scores_out, torch.float32)):
+        if t.dim() != 2 or t.dtype != dt or (t.shape[1] > 1 and t.stride(1) != 1) or t.shape[0] != n_streams:
+            raise ValueError("scores / kept_idx / scores_out must be [n_streams, n] with contiguous rows")
+    ld = logits.stride(0) if logits.shape[0] > 1 else logits.shape[1]
+    p = _policy(policy)
+    n_cand = n_held + n_new
+    budget = p.n_sink + p.n_topk + p.n_recent
+    n_keep = min(n_cand, budget)
+    ls = kv_layout(k_src)
+    if kv_layout_tuple(v_src) != kv_layout_tuple(k_src):
+        raise ValueError("K and V must share one layout")
+    if k_src.shape[0] != n_streams or k_src.shape[3] < n_cand:
+        raise ValueError("source cache must hold n_cand slots for every stream")
+    if k_dst is not None:
+        ldst = kv_layout(k_dst)
+        if kv_layout_tuple(v_dst) != kv_layout_tuple(k_dst) or k_dst.shape[3] < n_keep or k_dst.shape[0] != n_streams:
+            raise ValueError("destination cache must hold n_keep slots for every stream, K and V alike")
+    else:
+        ldst = ls
+    wp, wb = _ws(workspace)
+    _check(_lib.sirllm_step(_ptr(logits), _dtype_code(logits), int(vocab), ld, _ptr(token_ids),
+                            _ptr(scores), _row_stride(scores), n_streams, n_held, n_new, C.byref(p),
+                            _ptr(k_src), _ptr(v_src), C.byref(ls), _ptr(k_dst), _ptr(v_dst), C.byref(ldst),
+                            _ptr(kept_idx), _row_stride(kept_idx), _ptr(scores_out), _row_stride(scores_out),
+                            wp, wb, _stream(stream)), "sirllm_step")
+    return n_keep

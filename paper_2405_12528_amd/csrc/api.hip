@@ -1,0 +1,284 @@
+// The exported C ABI of libsirllm (declared in sirllm.h): host-side argument validation and
+// the order in which the kernels of one retention step are enqueued.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+
+#include "common.h"
+#include "tuning.h"
+
+namespace sirllm {
+namespace tuning {
+int get(const char* name, int dflt)
+{
+    static const bool active = [] {
+        const char* t = std::getenv("SIRLLM_TUNE");
+        return t && *t;
+    }();
+    if (!active) return dflt;
+    const char* v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : dflt;
+}
+}  // namespace tuning
+
+namespace {
+
+constexpr size_t kWorkspaceAlign = 256;
+
+bool policy_ok(const sirllm_policy* p)
+{
+    if (!p) return false;
+    if (p->n_sink < 0 || p->n_topk < 0 || p->n_recent < 0) return false;
+    if (!(p->decay >= 0.0f) || std::isinf(p->decay)) return false;       // rejects NaN too
+    return true;
+}
+
+int64_t budget_of(const sirllm_policy* p) { return (int64_t)p->n_sink + p->n_topk + p->n_recent; }
+
+bool layout_ok(const sirllm_kv_layout* L)
+{
+    if (!L) return false;
+    if (L->n_layers < 0 || L->n_kv_heads < 0 || L->head_dim < 0) return false;
+    if (L->elem_bytes != 1 && L->elem_bytes != 2 && L->elem_bytes != 4 && L->elem_bytes != 8) return false;
+    if (L->stride_stream < 0 || L->stride_layer < 0 || L->stride_head < 0 || L->stride_pos < 0) return false;
+    if (L->stride_pos < L->head_dim) return false;
+    return true;
+}
+
+// Bytes from the base pointer to one past the last byte a layout with n_pos slots can touch.
+int64_t extent_bytes(const sirllm_kv_layout* L, int32_t n_streams, int32_t n_pos)
+{
+    if (n_streams <= 0 || n_pos <= 0 || L->n_layers <= 0 || L->n_kv_heads <= 0 || L->head_dim <= 0) return 0;
+    const int64_t last = (int64_t)(n_streams - 1) * L->stride_stream + (int64_t)(L->n_layers - 1) * L->stride_layer +
+                         (int64_t)(L->n_kv_heads - 1) * L->stride_head + (int64_t)(n_pos - 1) * L->stride_pos +
+                         L->head_dim;
+    return last * L->elem_bytes;
+}
+
+bool ranges_overlap(const void* a, int64_t a_bytes, const void* b, int64_t b_bytes)
+{
+    if (!a || !b || a_bytes <= 0 || b_bytes <= 0) return false;
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + (uint64_t)b_bytes && b0 < a0 + (uint64_t)a_bytes;
+}
+
+int workspace_check(void* workspace, size_t workspace_bytes, size_t need)
+{
+    if (need == 0) return SIRLLM_OK;
+    if (!workspace || workspace_bytes < need) return SIRLLM_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & (kWorkspaceAlign - 1)) != 0) return SIRLLM_ERR_WORKSPACE;
+    return SIRLLM_OK;
+}
+
+int validate_score(const void* logits, sirllm_dtype dt, int64_t n_rows, int32_t vocab, int64_t ld,
+                   const int32_t* token_ids)
+{
+    if (dt != SIRLLM_F32 && dt != SIRLLM_BF16) return SIRLLM_ERR_UNSUPPORTED;
+    if (n_rows < 0 || vocab < 1 || ld < vocab) return SIRLLM_ERR_INVALID_ARG;
+    if (n_rows > 0x7fffffffLL) return SIRLLM_ERR_UNSUPPORTED;
+    if (n_rows > 0 && (!logits || !token_ids)) return SIRLLM_ERR_INVALID_ARG;
+    const uintptr_t esize = dt == SIRLLM_F32 ? 4 : 2;
+    if (((uintptr_t)logits & (esize - 1)) != 0) return SIRLLM_ERR_INVALID_ARG;
+    return SIRLLM_OK;
+}
+
+int validate_select(const float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held, int32_t n_new,
+                    const sirllm_policy* policy, const int32_t* kept_idx, int64_t idx_stride,
+                    const float* scores_out, int64_t out_stride)
+{
+    if (!policy_ok(policy)) return SIRLLM_ERR_INVALID_ARG;
+    if (n_streams < 0 || n_held < 0 || n_new < 0) return SIRLLM_ERR_INVALID_ARG;
+    const int64_t n_cand = (int64_t)n_held + n_new;
+    if (n_cand > SIRLLM_MAX_CAND) return SIRLLM_ERR_UNSUPPORTED;
+    if (n_streams == 0 || n_cand == 0) return SIRLLM_OK;
+    if (!scores || !kept_idx || !scores_out) return SIRLLM_ERR_INVALID_ARG;
+    const int64_t n_keep = n_cand < budget_of(policy) ? n_cand : budget_of(policy);
+    if (scores_stride < n_cand || idx_stride < n_keep || out_stride < n_keep) return SIRLLM_ERR_INVALID_ARG;
+    if (ranges_overlap(scores, ((int64_t)(n_streams - 1) * scores_stride + n_cand) * 4,
+                       scores_out, ((int64_t)(n_streams - 1) * out_stride + n_keep) * 4))
+        return SIRLLM_ERR_INVALID_ARG;
+    return SIRLLM_OK;
+}
+
+int validate_compact(const void* k_src, const void* v_src, const sirllm_kv_layout* src, int32_t n_src,
+                     void* k_dst, void* v_dst, const sirllm_kv_layout* dst, const int32_t* kept_idx,
+                     int64_t idx_stride, int32_t n_streams, int32_t n_keep)
+{
+    if (!layout_ok(src) || !layout_ok(dst)) return SIRLLM_ERR_INVALID_ARG;
+    if (src->n_layers != dst->n_layers || src->n_kv_heads != dst->n_kv_heads || src->head_dim != dst->head_dim ||
+        src->elem_bytes != dst->elem_bytes)
+        return SIRLLM_ERR_INVALID_ARG;
+    if (n_streams < 0 || n_keep < 0 || n_src < 0) return SIRLLM_ERR_INVALID_ARG;
+    if (n_streams == 0 || n_keep == 0) return SIRLLM_OK;
+    if (!k_src || !k_dst || !kept_idx) return SIRLLM_ERR_INVALID_ARG;
+    if ((v_src == nullptr) != (v_dst == nullptr)) return SIRLLM_ERR_INVALID_ARG;
+    if (idx_stride < n_keep) return SIRLLM_ERR_INVALID_ARG;
+    if ((int64_t)src->head_dim * src->elem_bytes > 0x7fffffffLL) return SIRLLM_ERR_UNSUPPORTED;
+    const uintptr_t em = (uintptr_t)src->elem_bytes - 1;
+    if (((uintptr_t)k_src & em) || ((uintptr_t)k_dst & em) || ((uintptr_t)v_src & em) || ((uintptr_t)v_dst & em))
+        return SIRLLM_ERR_INVALID_ARG;
+    const int64_t sb = extent_bytes(src, n_streams, n_src), db = extent_bytes(dst, n_streams, n_keep);
+    const void* srcs[2] = {k_src, v_src};
+    const void* dsts[2] = {k_dst, v_dst};
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j)
+            if (ranges_overlap(srcs[i], sb, dsts[j], db)) return SIRLLM_ERR_INVALID_ARG;
+    if (ranges_overlap(k_dst, db, v_dst, db)) return SIRLLM_ERR_INVALID_ARG;
+    return SIRLLM_OK;
+}
+
+SelectArgs make_select_args(const float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held,
+                            int32_t n_new, const sirllm_policy* p, int32_t* kept_idx, int64_t idx_stride,
+                            float* scores_out, int64_t out_stride)
+{
+    SelectArgs a;
+    a.scores = scores; a.scores_stride = scores_stride;
+    a.n_streams = n_streams; a.n_held = n_held; a.n_cand = n_held + n_new;
+    a.n_sink = p->n_sink; a.n_topk = p->n_topk; a.n_recent = p->n_recent; a.decay = p->decay;
+    a.kept_idx = kept_idx; a.idx_stride = idx_stride;
+    a.scores_out = scores_out; a.out_stride = out_stride;
+    return a;
+}
+
+GatherArgs make_gather_args(const void* k_src, const void* v_src, const sirllm_kv_layout* src, int32_t n_src,
+                            void* k_dst, void* v_dst, const sirllm_kv_layout* dst, const int32_t* kept_idx,
+                            int64_t idx_stride, int32_t n_streams, int32_t n_keep)
+{
+    GatherArgs g;
+    const int64_t eb = src->elem_bytes;
+    g.src[0] = (const char*)k_src; g.src[1] = (const char*)v_src;
+    g.dst[0] = (char*)k_dst; g.dst[1] = (char*)v_dst;
+    g.s_stream = src->stride_stream * eb; g.s_layer = src->stride_layer * eb;
+    g.s_head = src->stride_head * eb; g.s_pos = src->stride_pos * eb;
+    g.d_stream = dst->stride_stream * eb; g.d_layer = dst->stride_layer * eb;
+    g.d_head = dst->stride_head * eb; g.d_pos = dst->stride_pos * eb;
+    g.n_layers = src->n_layers; g.n_heads = src->n_kv_heads; g.n_tensors = v_src ? 2 : 1;
+    g.n_streams = n_streams; g.n_keep = n_keep; g.n_src = n_src;
+    g.row_bytes = (int32_t)((int64_t)src->head_dim * eb);
+    g.kept_idx = kept_idx; g.idx_stride = idx_stride;
+    return g;
+}
+
+int hip_status(hipError_t e) { return e == hipSuccess ? SIRLLM_OK : SIRLLM_ERR_HIP; }
+
+}  // namespace
+}  // namespace sirllm
+
+using namespace sirllm;
+
+extern "C" {
+
+size_t sirllm_workspace_bytes(int32_t n_streams, int32_t n_cand, int64_t n_rows, int32_t vocab)
+{
+    (void)n_streams; (void)n_cand; (void)n_rows; (void)vocab;
+    return 0;   // every kernel keeps its partial results in registers and LDS
+}
+
+const char* sirllm_status_string(int status)
+{
+    switch (status) {
+    case SIRLLM_OK:              return "ok";
+    case SIRLLM_ERR_INVALID_ARG: return "invalid argument (null pointer, negative size, inconsistent shapes or overlapping buffers)";
+    case SIRLLM_ERR_UNSUPPORTED: return "unsupported (size above a documented limit or unknown dtype)";
+    case SIRLLM_ERR_WORKSPACE:   return "workspace too small or not 256-byte aligned";
+    case SIRLLM_ERR_HIP:         return "HIP runtime error at kernel launch";
+    default:                     return "unknown status";
+    }
+}
+
+const char* sirllm_version(void) { return "0.1.0"; }
+
+int sirllm_score(const void* logits, sirllm_dtype dt, int64_t n_rows, int32_t vocab, int64_t ld,
+                 const int32_t* token_ids, float* scores_out, void* workspace, size_t workspace_bytes,
+                 void* hip_stream)
+{
+    int rc = validate_score(logits, dt, n_rows, vocab, ld, token_ids);
+    if (rc) return rc;
+    if (n_rows == 0) return SIRLLM_OK;
+    if (!scores_out) return SIRLLM_ERR_INVALID_ARG;
+    rc = workspace_check(workspace, workspace_bytes, sirllm_workspace_bytes(0, 0, n_rows, vocab));
+    if (rc) return rc;
+    ScoreArgs a;
+    a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
+    a.n_rows = n_rows; a.rows_per_stream = n_rows;
+    a.out_a = scores_out; a.stride_a = 0; a.out_b = nullptr; a.stride_b = 0;
+    return hip_status(launch_score(a, dt, (hipStream_t)hip_stream));
+}
+
+int sirllm_decay_select(const float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held,
+                        int32_t n_new, const sirllm_policy* policy, int32_t* kept_idx, int64_t idx_stride,
+                        float* scores_out, int64_t out_stride, void* workspace, size_t workspace_bytes,
+                        void* hip_stream)
+{
+    int rc = validate_select(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx, idx_stride,
+                             scores_out, out_stride);
+    if (rc) return rc;
+    const int32_t n_cand = n_held + n_new;
+    if (n_streams == 0 || n_cand == 0) return SIRLLM_OK;
+    rc = workspace_check(workspace, workspace_bytes, sirllm_workspace_bytes(n_streams, n_cand, 0, 0));
+    if (rc) return rc;
+    const SelectArgs a = make_select_args(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx,
+                                          idx_stride, scores_out, out_stride);
+    if ((int64_t)n_cand <= budget_of(policy)) return hip_status(launch_keep_all(a, (hipStream_t)hip_stream));
+    return hip_status(launch_select(a, (hipStream_t)hip_stream));
+}
+
+int sirllm_compact_kv(const void* k_src, const void* v_src, const sirllm_kv_layout* src, int32_t n_src,
+                      void* k_dst, void* v_dst, const sirllm_kv_layout* dst, const int32_t* kept_idx,
+                      int64_t idx_stride, int32_t n_streams, int32_t n_keep, void* hip_stream)
+{
+    int rc = validate_compact(k_src, v_src, src, n_src, k_dst, v_dst, dst, kept_idx, idx_stride, n_streams, n_keep);
+    if (rc) return rc;
+    if (n_streams == 0 || n_keep == 0) return SIRLLM_OK;
+    const GatherArgs g = make_gather_args(k_src, v_src, src, n_src, k_dst, v_dst, dst, kept_idx, idx_stride,
+                                          n_streams, n_keep);
+    return hip_status(launch_gather(g, (hipStream_t)hip_stream));
+}
+
+int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
+                float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held, int32_t n_new,
+                const sirllm_policy* policy, const void* k_src, const void* v_src, const sirllm_kv_layout* src,
+                void* k_dst, void* v_dst, const sirllm_kv_layout* dst, int32_t* kept_idx, int64_t idx_stride,
+                float* scores_out, int64_t out_stride, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (n_streams < 0 || n_held < 0 || n_new < 0) return SIRLLM_ERR_INVALID_ARG;
+    const int64_t n_rows = (int64_t)n_streams * n_new;
+    int rc = validate_score(logits, dt, n_rows, vocab, ld, token_ids);
+    if (rc) return rc;
+    rc = validate_select(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx, idx_stride,
+                         scores_out, out_stride);
+    if (rc) return rc;
+    const int32_t n_cand = n_held + n_new;
+    if (n_streams == 0 || n_cand == 0) return SIRLLM_OK;
+    const bool evict = (int64_t)n_cand > budget_of(policy);
+    const int32_t n_keep = evict ? (int32_t)budget_of(policy) : n_cand;
+    if (evict) {
+        rc = validate_compact(k_src, v_src, src, n_cand, k_dst, v_dst, dst, kept_idx, idx_stride, n_streams, n_keep);
+        if (rc) return rc;
+    }
+    rc = workspace_check(workspace, workspace_bytes, sirllm_workspace_bytes(n_streams, n_cand, n_rows, vocab));
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    // E_t = Entropy(new tokens), appended behind the held scores
+    if (n_rows > 0) {
+        ScoreArgs a;
+        a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
+        a.n_rows = n_rows; a.rows_per_stream = n_new;
+        a.out_a = scores + n_held; a.stride_a = scores_stride; a.out_b = nullptr; a.stride_b = 0;
+        rc = hip_status(launch_score(a, dt, stream));
+        if (rc) return rc;
+    }
+    // E <- E * eta on the held part; Id = sink + Top_k + recent; E <- E[Id]
+    const SelectArgs s = make_select_args(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx,
+                                          idx_stride, scores_out, out_stride);
+    if (!evict) return hip_status(launch_keep_all(s, stream));
+    rc = hip_status(launch_select(s, stream));
+    if (rc) return rc;
+    // KV <- KV[Id]
+    const GatherArgs g = make_gather_args(k_src, v_src, src, n_cand, k_dst, v_dst, dst, kept_idx, idx_stride,
+                                          n_streams, n_keep);
+    return hip_status(launch_gather(g, stream));
+}
+
+}  // extern "C"

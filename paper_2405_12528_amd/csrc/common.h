@@ -1,0 +1,65 @@
+// Internal declarations shared by the HIP translation units of libsirllm (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sirllm.h"
+
+namespace sirllm {
+
+constexpr int kWave = 64;                    // CDNA wavefront width
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// ---- score.hip --------------------------------------------------------------------------
+// Token entropy of n_rows rows.  Row `row` belongs to stream row / rows_per_stream, token
+// t = row % rows_per_stream; its score goes to out_a[stream*stride_a + t] and, when out_b is
+// not null, also to out_b[stream*stride_b + t].
+struct ScoreArgs {
+    const void* logits;
+    int64_t ld;               // elements between rows
+    int32_t vocab;
+    const int32_t* token_ids;
+    int64_t n_rows;
+    int64_t rows_per_stream;  // >= 1
+    float* out_a;
+    int64_t stride_a;
+    float* out_b;
+    int64_t stride_b;
+};
+hipError_t launch_score(const ScoreArgs& a, sirllm_dtype dt, hipStream_t stream);
+
+// ---- select.hip -------------------------------------------------------------------------
+struct SelectArgs {
+    const float* scores;      // [n_streams][scores_stride]
+    int64_t scores_stride;
+    int32_t n_streams, n_held, n_cand;
+    int32_t n_sink, n_topk, n_recent;
+    float decay;
+    int32_t* kept_idx;
+    int64_t idx_stride;
+    float* scores_out;
+    int64_t out_stride;
+};
+// n_cand > budget: decay + radix select + index build, one workgroup per stream.
+hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
+// n_cand <= budget: identity index list, decayed scores.
+hipError_t launch_keep_all(const SelectArgs& a, hipStream_t stream);
+
+// ---- gather.hip -------------------------------------------------------------------------
+struct GatherArgs {
+    const char* src[2];       // K, V (V may be null: then only tensor 0 is moved)
+    char* dst[2];
+    int64_t s_stream, s_layer, s_head, s_pos;   // source strides in bytes
+    int64_t d_stream, d_layer, d_head, d_pos;   // destination strides in bytes
+    int32_t n_layers, n_heads, n_tensors;
+    int32_t n_streams, n_keep, n_src;
+    int32_t row_bytes;
+    const int32_t* kept_idx;
+    int64_t idx_stride;
+};
+hipError_t launch_gather(const GatherArgs& a, hipStream_t stream);
+
+}  // namespace sirllm

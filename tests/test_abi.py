@@ -1,0 +1,156 @@
+"""The C-ABI library loads without a GPU, exports every symbol include/sirllm.h declares, and
+rejects bad arguments on the host before anything is launched.  CPU only: no compute calls."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_2405_12528_amd import build
+    if not os.path.exists(build.LIB):
+        build.build()
+    from paper_2405_12528_amd import binding
+    return binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sirllm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sirllm_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(b):
+    names = declared_functions()
+    assert set(names) >= {"sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step"}
+    for n in names:
+        assert hasattr(b.raw(), n), f"{n} is declared in sirllm.h but not exported by libsirllm.so"
+    assert set(b.EXPORTS) == set(names)
+
+
+def test_status_strings_and_version(b):
+    assert b.sirllm_status_string(0) == "ok"
+    for code in (-1, -2, -3, -4):
+        assert len(b.sirllm_status_string(code)) > 5
+    assert re.fullmatch(r"\d+\.\d+\.\d+", b.sirllm_version())
+    assert b.sirllm_workspace_bytes(32, 2304, 8192, 32000) % 256 == 0
+
+
+def test_struct_sizes_match_the_header(b):
+    # int32 x3 + float; int32 x4 + int64 x4
+    assert C.sizeof(b.sirllm_policy) == 16
+    assert C.sizeof(b.sirllm_kv_layout) == 48
+
+
+FAKE = 0x1000  # a non-null, 16-byte aligned "pointer"; validation never dereferences it
+
+
+def test_score_argument_errors(b):
+    L = b.raw()
+    assert L.sirllm_score(FAKE, 7, 4, 10, 10, FAKE, FAKE, None, 0, None) == b.SIRLLM_ERR_UNSUPPORTED   # dtype
+    assert L.sirllm_score(FAKE, 0, -1, 10, 10, FAKE, FAKE, None, 0, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert L.sirllm_score(FAKE, 0, 4, 0, 10, FAKE, FAKE, None, 0, None) == b.SIRLLM_ERR_INVALID_ARG    # vocab < 1
+    assert L.sirllm_score(FAKE, 0, 4, 10, 9, FAKE, FAKE, None, 0, None) == b.SIRLLM_ERR_INVALID_ARG    # ld < vocab
+    assert L.sirllm_score(None, 0, 4, 10, 10, FAKE, FAKE, None, 0, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert L.sirllm_score(FAKE, 0, 4, 10, 10, None, FAKE, None, 0, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert L.sirllm_score(FAKE, 0, 4, 10, 10, FAKE, None, None, 0, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert L.sirllm_score(FAKE + 2, 0, 4, 10, 10, FAKE, FAKE, None, 0, None) == b.SIRLLM_ERR_INVALID_ARG  # f32 at +2
+    assert L.sirllm_score(FAKE, 0, 2**31, 10, 10, FAKE, FAKE, None, 0, None) == b.SIRLLM_ERR_UNSUPPORTED
+    assert L.sirllm_score(None, 0, 0, 10, 10, None, None, None, 0, None) == b.SIRLLM_OK                 # empty
+
+
+def test_decay_select_argument_errors(b):
+    L = b.raw()
+    p = b.sirllm_policy(4, 20, 8, 0.9)
+    def call(scores=FAKE, stride=100, n_streams=1, n_held=60, n_new=40, pol=p, idx=FAKE + 0x10000, istr=32,
+             out=FAKE + 0x20000, ostr=32):
+        return L.sirllm_decay_select(scores, stride, n_streams, n_held, n_new, C.byref(pol) if pol else None,
+                                     idx, istr, out, ostr, None, 0, None)
+    assert call(n_held=-1) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(n_streams=-1) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(pol=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(pol=b.sirllm_policy(-1, 20, 8, 0.9)) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(pol=b.sirllm_policy(4, 20, 8, float("nan"))) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(pol=b.sirllm_policy(4, 20, 8, -0.5)) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(pol=b.sirllm_policy(4, 20, 8, float("inf"))) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(scores=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(idx=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(out=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(stride=99) == b.SIRLLM_ERR_INVALID_ARG          # stride < n_cand
+    assert call(istr=31) == b.SIRLLM_ERR_INVALID_ARG            # idx_stride < n_keep
+    assert call(ostr=31) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(out=FAKE + 16) == b.SIRLLM_ERR_INVALID_ARG      # scores_out overlaps scores
+    assert call(n_held=b.SIRLLM_MAX_CAND, n_new=1, stride=40000) == b.SIRLLM_ERR_UNSUPPORTED
+    assert call(n_streams=0) == b.SIRLLM_OK
+    assert call(n_held=0, n_new=0) == b.SIRLLM_OK
+    # budget sums that overflow int32 are fine: the sum is taken in 64 bits and n_cand <= budget keeps all
+    assert call(pol=b.sirllm_policy(2**31 - 1, 2**31 - 1, 2**31 - 1, 1.0), n_streams=0) == b.SIRLLM_OK
+
+
+def test_compact_kv_argument_errors(b):
+    L = b.raw()
+    lay = lambda **kw: b.sirllm_kv_layout(**{**dict(n_layers=2, n_kv_heads=2, head_dim=16, elem_bytes=4,
+                                                    stride_stream=2 * 2 * 64 * 16, stride_layer=2 * 64 * 16,
+                                                    stride_head=64 * 16, stride_pos=16), **kw})
+    S, D = lay(), lay()
+    src, dst, idx = 0x100000, 0x900000, 0x50000
+    def call(ks=src, vs=None, s=S, n_src=64, kd=dst, vd=None, d=D, ix=idx, istr=32, n_streams=1, n_keep=32):
+        return L.sirllm_compact_kv(ks, vs, C.byref(s) if s else None, n_src, kd, vd, C.byref(d) if d else None,
+                                   ix, istr, n_streams, n_keep, None)
+    assert call(s=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(d=lay(head_dim=8)) == b.SIRLLM_ERR_INVALID_ARG           # layouts disagree
+    assert call(d=lay(elem_bytes=2)) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(s=lay(elem_bytes=3), d=lay(elem_bytes=3)) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(s=lay(stride_pos=8)) == b.SIRLLM_ERR_INVALID_ARG         # rows would overlap
+    assert call(s=lay(stride_head=-1)) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(ks=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(kd=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(ix=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(vs=src + 0x400000) == b.SIRLLM_ERR_INVALID_ARG           # V source without V destination
+    assert call(n_keep=-1) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(istr=31) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(kd=src + 64) == b.SIRLLM_ERR_INVALID_ARG                 # destination overlaps source
+    assert call(ks=src + 2) == b.SIRLLM_ERR_INVALID_ARG                  # 4-byte elements at an odd address
+    assert call(n_keep=0) == b.SIRLLM_OK
+    assert call(n_streams=0) == b.SIRLLM_OK
+
+
+def test_step_argument_errors(b):
+    L = b.raw()
+    p = b.sirllm_policy(4, 20, 8, 0.9)
+    lay = b.sirllm_kv_layout(2, 2, 16, 4, 2 * 2 * 128 * 16, 2 * 128 * 16, 128 * 16, 16)
+    def call(logits=0x1000, dt=0, vocab=1000, ld=1000, tok=0x2000000, scores=0x3000000, sstr=128, n_streams=1,
+             n_held=32, n_new=64, ksrc=0x10000000, vsrc=0x20000000, kdst=0x30000000, vdst=0x40000000,
+             idx=0x5000000, istr=32, out=0x6000000, ostr=32):
+        return L.sirllm_step(logits, dt, vocab, ld, tok, scores, sstr, n_streams, n_held, n_new, C.byref(p),
+                             ksrc, vsrc, C.byref(lay), kdst, vdst, C.byref(lay), idx, istr, out, ostr, None, 0, None)
+    assert call(dt=5) == b.SIRLLM_ERR_UNSUPPORTED
+    assert call(logits=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(ld=999) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(scores=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(n_new=-1) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(kdst=None) == b.SIRLLM_ERR_INVALID_ARG              # eviction needs a destination
+    assert call(kdst=0x10000000 + 4096) == b.SIRLLM_ERR_INVALID_ARG  # ... that does not overlap the source
+    assert call(n_held=40000) == b.SIRLLM_ERR_UNSUPPORTED
+    assert call(n_streams=0, logits=None, tok=None) == b.SIRLLM_OK
+
+
+def test_binding_refuses_host_tensors(b):
+    import torch
+    z = torch.zeros(2, 8)
+    with pytest.raises(ValueError):
+        b.sirllm_score(z, torch.zeros(2, dtype=torch.int32), torch.zeros(2))
+
+
+def test_product_path_never_touches_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2405_12528_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), f"{f} imports the oracle"
+                assert "sirllm_ref" not in text, f"{f} names the oracle's library"

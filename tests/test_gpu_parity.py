@@ -1,0 +1,358 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI, on one MI355X.
+
+Scores: |gpu - ref| <= 1e-6 + 1e-5*|ref| (binary32 accumulation against the oracle's double).
+Kept indices, compacted scores and compacted K/V: bit exact, with the oracle fed the GPU's own
+scores where a selection depends on them (both sides then decide on identical binary32 values).
+"""
+import numpy as np
+import pytest
+import torch
+
+from helpers import to_np
+from paper_2405_12528_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def b():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2405_12528_amd import binding
+    return binding
+
+
+def assert_scores_close(gpu: np.ndarray, want: np.ndarray):
+    nan_w, nan_g = np.isnan(want), np.isnan(gpu)
+    np.testing.assert_array_equal(nan_g, nan_w)
+    inf_w = np.isinf(want)
+    np.testing.assert_array_equal(gpu[inf_w], want[inf_w])
+    ok = ~(nan_w | inf_w)
+    err = np.abs(gpu[ok].astype(np.float64) - want[ok].astype(np.float64))
+    tol = 1e-6 + 1e-5 * np.abs(want[ok].astype(np.float64))
+    bad = err > tol
+    assert not bad.any(), f"{bad.sum()} scores off; worst {err.max():.3e} (tolerance {tol[err.argmax()]:.3e})"
+
+
+def gpu_score(b, z: torch.Tensor, tok: torch.Tensor, vocab=None):
+    out = torch.full((z.shape[0],), -12345.0, dtype=torch.float32, device=DEV)
+    b.sirllm_score(z, tok, out, vocab=vocab)
+    torch.cuda.synchronize()
+    return to_np(out)
+
+
+# ------------------------------------------------------------------------------------- score
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n_rows,V,ld", [
+    (64, 1000, 1000),        # the tiny workload's shape
+    (37, 2311, 2311),        # odd length: rows start at every alignment, scalar head and tail
+    (9, 4099, 4200),         # padded rows
+    (3, 1, 1), (4, 3, 3), (5, 7, 9), (6, 17, 17), (2, 255, 255), (2, 4096, 4096), (2, 4097, 4097),
+    (5, 32000, 32000),       # several sweeps of a 1024-thread workgroup and a ragged last sweep
+    (3, 128256, 128256),
+    (1100, 515, 520),        # 512-thread workgroups
+    (2100, 300, 300),        # 256-thread workgroups
+])
+def test_score_matches_oracle(b, ref, dtype, n_rows, V, ld):
+    g = torch.Generator(device=DEV).manual_seed(n_rows * 7919 + V)
+    z = torch.randn((n_rows, ld), generator=g, device=DEV) * 3.0
+    z[::3, V // 2] += 8.0
+    if ld > V:
+        z[:, V:] = 1.0e4
+    z = z.to(dtype)
+    tok = torch.randint(0, V, (n_rows,), generator=g, device=DEV, dtype=torch.int32)
+    got = gpu_score(b, z, tok, vocab=V)
+    want = ref.score(to_np(z), to_np(tok), vocab=V)
+    assert_scores_close(got, want)
+
+
+def test_score_workload_generators(b, ref):
+    for name, rows in (("tiny", 64), ("llama2_7b", 48), ("llama3_8b", 24)):
+        w = synth.WORKLOADS[name]
+        z = synth.make_logits(w, turn=1, device=DEV, n_rows=rows)
+        tok = synth.make_token_ids(w, turn=1, device=DEV, n_rows=rows)
+        assert_scores_close(gpu_score(b, z, tok), ref.score(to_np(z), to_np(tok)))
+
+
+def test_score_closed_forms(b):
+    for V in (1000, 32000, 128256):
+        z = torch.full((2, V), -3.25, device=DEV)
+        tok = torch.tensor([0, V - 1], dtype=torch.int32, device=DEV)
+        np.testing.assert_allclose(gpu_score(b, z, tok), np.log(V), rtol=1e-6)
+        np.testing.assert_allclose(gpu_score(b, z.to(torch.bfloat16), tok), np.log(V), rtol=1e-6)
+    z = torch.zeros((1, 1000), device=DEV)
+    z[0, 123] = 60.0
+    assert gpu_score(b, z, torch.tensor([123], dtype=torch.int32, device=DEV))[0] == 0.0
+
+
+def test_score_non_finite_and_bad_tokens(b, ref):
+    V = 600
+    z = torch.zeros((8, V), device=DEV)
+    z[0, 3] = -np.inf
+    z[1, 3] = -np.inf
+    z[2, :] = -np.inf
+    z[3, 5] = np.inf
+    z[4, 7] = np.nan
+    z[5, :300] = -np.inf          # whole lanes see nothing finite, others do
+    z[6, 300:] = -np.inf
+    tok = torch.tensor([0, 3, 0, 0, 0, 400, 10, V], dtype=torch.int32, device=DEV)
+    got = gpu_score(b, z, tok)
+    want = ref.score(to_np(z), to_np(tok))
+    assert_scores_close(got, want)
+    assert got[1] == np.inf and np.isnan(got[[2, 3, 4, 7]]).all()
+    zb = z.to(torch.bfloat16)
+    assert_scores_close(gpu_score(b, zb, tok), ref.score(to_np(zb), to_np(tok)))
+
+
+def test_score_empty(b):
+    z = torch.zeros((0, 16), device=DEV)
+    b.sirllm_score(z, torch.zeros(0, dtype=torch.int32, device=DEV), torch.zeros(0, device=DEV))
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------ decay + select
+def gpu_select(b, E: np.ndarray, n_held, n_new, pol, pad=3):
+    n_streams, n_cand = E.shape
+    n_keep = min(n_cand, pol.n_sink + pol.n_topk + pol.n_recent)
+    Ed = torch.full((n_streams, n_cand + pad), 777.0, device=DEV)
+    Ed[:, :n_cand] = torch.from_numpy(E).to(DEV)
+    idx = torch.full((n_streams, n_keep + pad), -7, dtype=torch.int32, device=DEV)
+    out = torch.full((n_streams, n_keep + pad), -7.0, device=DEV)
+    b.sirllm_decay_select(Ed, n_held, n_new, pol, idx, out)
+    torch.cuda.synchronize()
+    idx, out = to_np(idx), to_np(out)
+    assert (idx[:, n_keep:] == -7).all() and (out[:, n_keep:] == -7.0).all()      # nothing written past n_keep
+    return idx[:, :n_keep], out[:, :n_keep]
+
+
+def check_select(b, ref, E, n_held, n_new, pol):
+    gi, go = gpu_select(b, E, n_held, n_new, pol)
+    ri, ro = ref.decay_select(E, n_held, n_new, ref.Policy(*pol))
+    np.testing.assert_array_equal(gi, ri)
+    np.testing.assert_array_equal(go.view(np.uint32), ro.view(np.uint32))
+
+
+SELECT_CASES = [
+    # n_streams, n_held, n_new, n_sink, k, n_recent, decay, levels (0 = continuous)
+    (1, 32, 64, 4, 20, 8, 0.9, 0),            # tiny workload, steady state
+    (1, 0, 64, 4, 20, 8, 0.9, 0),             # tiny workload, first turn
+    (3, 100, 50, 4, 30, 10, 0.9, 5),          # heavy ties
+    (2, 3584, 512, 4, 1532, 512, 0.9, 0),     # llama-2 shape
+    (2, 7168, 1024, 4, 3068, 1024, 0.85, 40), # mistral shape, ties
+    (1, 6144, 2048, 4, 2044, 2048, 0.9, 0),   # llama-3 shape
+    (4, 2048, 256, 4, 1788, 256, 0.9, 0),     # batched dialogue shape
+    (2, 1000, 24, 4, 1020, 0, 1.0, 0),        # the paper's own setting: 1024 = 4 + 1020 + 0, eta = 1
+    (2, 500, 54, 4, 508, 0, 0.7, 0),          # 512 = 4 + 508 + 0
+    (1, 40, 10, 0, 7, 0, 0.5, 3),             # no sink, no recent
+    (1, 40, 10, 4, 0, 6, 0.5, 0),             # k = 0: StreamLLM
+    (1, 40, 10, 0, 0, 6, 0.5, 0),             # sliding window
+    (1, 40, 10, 4, 1, 0, 0.5, 2),
+    (1, 30, 10, 4, 35, 1, 0.9, 0),            # k = all but one middle slot
+    (2, 20, 12, 4, 20, 8, 0.9, 0),            # n_cand == budget
+    (2, 10, 5, 4, 20, 8, 0.9, 0),             # n_cand < budget
+    (1, 1, 0, 1, 0, 0, 0.9, 0),
+    (1, 1020, 5, 4, 100, 8, 0.9, 0),          # crosses the 1024-slot boundary (two slots per thread)
+    (1, 32700, 68, 4, 16000, 68, 0.9, 1000),  # the largest size, ragged
+    (2, 20000, 0, 4, 9000, 100, 0.99, 0),     # no new tokens at all
+]
+
+
+@pytest.mark.parametrize("case", SELECT_CASES, ids=[str(c[:6]) for c in SELECT_CASES])
+def test_decay_select_matches_oracle(b, ref, case):
+    n_streams, n_held, n_new, n_sink, k, n_recent, decay, levels = case
+    rng = np.random.default_rng(n_held * 31 + n_new)
+    n_cand = n_held + n_new
+    if levels:
+        E = (rng.integers(0, levels, (n_streams, n_cand)) / 8.0).astype(np.float32)
+    else:
+        E = rng.gamma(2.0, 2.0, (n_streams, n_cand)).astype(np.float32)
+    check_select(b, ref, E, n_held, n_new, b.Policy(n_sink, k, n_recent, decay))
+
+
+def test_decay_select_adversarial_values(b, ref):
+    pol = b.Policy(2, 5, 2, 0.5)
+    n = 64
+    # all equal: pure tie-break
+    check_select(b, ref, np.full((1, n), 2.5, np.float32), 40, 24, pol)
+    # signed zeros, negatives, infinities, NaNs of both signs, denormals
+    special = np.array([0.0, -0.0, 1e-41, -1e-41, np.inf, -np.inf, 3.0, -3.0], dtype=np.float32)
+    E = np.tile(special, n // len(special))[None, :].copy()
+    E.view(np.uint32)[0, 9] = 0x7FC00000
+    E.view(np.uint32)[0, 17] = 0xFFC00000
+    for k in (1, 3, 9, 20, 40, 59):
+        check_select(b, ref, E, 0, n, b.Policy(2, k, 2, 0.5))       # undecayed: every bit pattern survives
+    check_select(b, ref, E, n, 0, b.Policy(2, 9, 2, 0.5))            # decayed: denormals halve, never flush
+    # scores that differ only in the last bit
+    base = np.float32(5.0)
+    E = np.nextafter(np.full(n, base, np.float32), np.float32(9), dtype=np.float32)
+    E[::2] = base
+    check_select(b, ref, E[None, :].copy(), 0, n, b.Policy(1, 20, 1, 1.0))
+
+
+def test_decay_keeps_denormals(b):
+    E = np.array([[1e-41, 2e-45, 1.0, 1.0]], dtype=np.float32)
+    _, out = gpu_select(b, E, 4, 0, b.Policy(1, 1, 1, 0.5))             # budget 3 < 4: selection path
+    want = E * np.float32(0.5)
+    assert out[0, 0] == want[0, 0] and out[0, 0] != 0
+    _, out = gpu_select(b, E, 4, 0, b.Policy(2, 2, 2, 0.5))             # keep-all path
+    np.testing.assert_array_equal(out.view(np.uint32), want.view(np.uint32))
+
+
+def test_decay_select_is_deterministic(b):
+    rng = np.random.default_rng(9)
+    E = (rng.integers(0, 9, (2, 5000)) / 4.0).astype(np.float32)
+    pol = b.Policy(4, 2000, 300, 0.9)
+    first = gpu_select(b, E, 4500, 500, pol)
+    for _ in range(20):
+        again = gpu_select(b, E, 4500, 500, pol)
+        np.testing.assert_array_equal(first[0], again[0])
+        np.testing.assert_array_equal(first[1].view(np.uint32), again[1].view(np.uint32))
+
+
+# ----------------------------------------------------------------------------------- compact
+def run_compact(b, ref, k_src, v_src, kept, n_src=None):
+    n_streams, n_keep = kept.shape
+    shape = k_src.shape[:3] + (n_keep + 2,) + k_src.shape[4:]
+    k_dst = torch.full(shape, 77, dtype=k_src.dtype, device=DEV)
+    v_dst = None if v_src is None else torch.full(shape, 77, dtype=v_src.dtype, device=DEV)
+    kd = torch.from_numpy(kept).to(DEV)
+    b.sirllm_compact_kv(k_src, v_src, k_dst, v_dst, kd, n_keep, n_src=n_src)
+    torch.cuda.synchronize()
+    rk, rv = ref.compact_kv(to_np_strided(k_src), None if v_src is None else to_np_strided(v_src), kept, n_src=n_src)
+    gk = to_np(k_dst)
+    np.testing.assert_array_equal(gk[:, :, :, :n_keep], rk)
+    assert (gk[:, :, :, n_keep:] == 77).all()                            # slots past n_keep untouched
+    if v_src is not None:
+        gv = to_np(v_dst)
+        np.testing.assert_array_equal(gv[:, :, :, :n_keep], rv)
+        assert (gv[:, :, :, n_keep:] == 77).all()
+
+
+def to_np_strided(t):
+    """Host copy of a possibly strided device view, as a contiguous array (the oracle takes any strides itself)."""
+    return to_np(t)
+
+
+@pytest.mark.parametrize("S,L,H,P,D,dtype", [
+    (1, 2, 2, 96, 16, torch.float32),       # tiny workload: 64-byte rows
+    (2, 3, 2, 300, 128, torch.bfloat16),    # 256-byte rows
+    (1, 2, 3, 50, 128, torch.float16),
+    (1, 1, 2, 40, 100, torch.bfloat16),     # 200-byte rows: 8-byte vectors
+    (1, 1, 2, 40, 6, torch.int16),          # 12-byte rows: 4-byte vectors
+    (1, 2, 1, 33, 5, torch.int16),          # 10-byte rows: 2-byte vectors
+    (1, 1, 1, 33, 7, torch.uint8),          # 7-byte rows: byte copies
+    (1, 1, 2, 20, 24, torch.float64),       # 8-byte elements
+    (2, 2, 2, 1000, 64, torch.float32),     # several tiles and a ragged last tile
+])
+def test_compact_matches_oracle(b, ref, S, L, H, P, D, dtype):
+    rng = np.random.default_rng(P * 13 + D)
+    tag_k = synth.tagged_kv(S, L, H, P, D, 0)
+    tag_v = synth.tagged_kv(S, L, H, P, D, 1)
+    if dtype in (torch.uint8,):
+        tag_k, tag_v = tag_k % 251, tag_v % 241
+    elif dtype in (torch.int16, torch.float16, torch.bfloat16):
+        tag_k, tag_v = tag_k % 32749, tag_v % 32719
+    k = tag_k.to(dtype).to(DEV)
+    v = tag_v.to(dtype).to(DEV)
+    n_keep = max(1, (2 * P) // 3)
+    kept = np.stack([np.sort(rng.choice(P, n_keep, replace=False)) for _ in range(S)]).astype(np.int32)
+    run_compact(b, ref, k, v, kept)
+    run_compact(b, ref, k, None, kept[:, : max(1, n_keep // 2)])
+
+
+def test_compact_strided_views_and_bad_indices(b, ref):
+    big = synth.tagged_kv(2, 2, 3, 40, 24, 0).to(torch.float32).to(DEV)
+    k = big[:, :, :2, :30, :16]                       # padded heads, slots and channels
+    v = (big * 2)[:, :, :2, :30, :16]
+    kept = np.array([[0, 5, 29, 30, -1, 7], [1, 2, 3, 4, 100000, 28]], dtype=np.int32)   # 30, -1, 100000: no such slot
+    shape = (2, 2, 2, 9, 16)
+    k_dst = torch.full(shape, 77.0, device=DEV)
+    v_dst = torch.full(shape, 77.0, device=DEV)
+    b.sirllm_compact_kv(k, v, k_dst, v_dst, torch.from_numpy(kept).to(DEV), 6, n_src=30)
+    torch.cuda.synchronize()
+    rk, rv = ref.compact_kv(to_np(big)[:, :, :2, :30, :16], to_np(big * 2)[:, :, :2, :30, :16], kept, n_src=30)
+    np.testing.assert_array_equal(to_np(k_dst)[:, :, :, :6], rk)
+    np.testing.assert_array_equal(to_np(v_dst)[:, :, :, :6], rv)
+    assert (rk[0, :, :, 3] == 0).all() and (to_np(k_dst)[0, :, :, 4] == 0).all()
+    assert (to_np(k_dst)[:, :, :, 6:] == 77).all()
+
+
+# --------------------------------------------------------------------------------- whole step
+def gpu_step(b, w, z, tok, held, k_c, v_c, pol=None):
+    """Run sirllm_step on device tensors; returns host copies of everything it wrote."""
+    pol = pol or b.Policy(w.n_sink, w.n_topk, w.n_recent, w.decay)
+    n_streams, n_held = held.shape
+    n_new = z.shape[0] // n_streams
+    n_cand = n_held + n_new
+    n_keep = min(n_cand, pol.n_sink + pol.n_topk + pol.n_recent)
+    E = torch.full((n_streams, n_cand), -5.0, device=DEV)
+    E[:, :n_held] = held
+    idx = torch.full((n_streams, n_keep), -7, dtype=torch.int32, device=DEV)
+    out = torch.full((n_streams, n_keep), -7.0, device=DEV)
+    shape = k_c.shape[:3] + (n_keep,) + k_c.shape[4:]
+    k_dst = torch.zeros(shape, dtype=k_c.dtype, device=DEV)
+    v_dst = torch.zeros(shape, dtype=v_c.dtype, device=DEV)
+    got = b.sirllm_step(z, tok, w.vocab, E, n_held, n_new, pol, k_c, v_c, k_dst, v_dst, idx, out)
+    torch.cuda.synchronize()
+    assert got == n_keep
+    return dict(E=E, idx=idx, out=out, k=k_dst, v=v_dst, n_keep=n_keep, evicted=n_cand > n_keep)
+
+
+def check_step_against_oracle(b, ref, w, z, tok, held, k_c, v_c, g, pol=None):
+    """Scores within tolerance; then the oracle's select + gather, fed the GPU's scores, bit for bit."""
+    pol = pol or b.Policy(w.n_sink, w.n_topk, w.n_recent, w.decay)
+    n_streams, n_held = held.shape
+    n_new = z.shape[0] // n_streams
+    Eg = to_np(g["E"])
+    want = ref.score(to_np(z), to_np(tok), vocab=w.vocab).reshape(n_streams, n_new)
+    assert_scores_close(Eg[:, n_held:], want)
+    np.testing.assert_array_equal(Eg[:, :n_held].view(np.uint32), to_np(held).view(np.uint32))   # held part untouched
+    ri, ro = ref.decay_select(Eg, n_held, n_new, ref.Policy(*pol))
+    np.testing.assert_array_equal(to_np(g["idx"]), ri)
+    np.testing.assert_array_equal(to_np(g["out"]).view(np.uint32), ro.view(np.uint32))
+    if g["evicted"]:
+        rk, rv = ref.compact_kv(to_np(k_c), to_np(v_c), ri, n_src=n_held + n_new)
+        assert np.array_equal(to_np(g["k"]), rk) and np.array_equal(to_np(g["v"]), rv)
+    else:
+        assert not to_np(g["k"]).any() and not to_np(g["v"]).any()       # destination untouched
+
+
+def test_step_tiny_dialogue_four_turns(b, ref):
+    w = synth.WORKLOADS["tiny"]
+    held = torch.zeros((1, 0), device=DEV)
+    shape0 = (1, w.n_layers, w.n_kv_heads, 0, w.head_dim)
+    K = torch.zeros(shape0, device=DEV)
+    V = torch.zeros(shape0, device=DEV)
+    for turn in range(1, w.n_turns + 1):
+        z = synth.make_logits(w, turn=turn, device=DEV)
+        tok = synth.make_token_ids(w, turn=turn, device=DEV)
+        k_c = torch.cat([K, synth.make_kv(w, n_pos=w.n_new, turn=turn, device=DEV, which="k")], dim=3).contiguous()
+        v_c = torch.cat([V, synth.make_kv(w, n_pos=w.n_new, turn=turn, device=DEV, which="v")], dim=3).contiguous()
+        g = gpu_step(b, w, z, tok, held, k_c, v_c)
+        check_step_against_oracle(b, ref, w, z, tok, held, k_c, v_c, g)
+        assert g["n_keep"] == w.budget
+        held, K, V = g["out"], g["k"], g["v"]
+
+
+@pytest.mark.parametrize("n_streams,n_held,n_new,pol", [
+    (1, 100, 40, (4, 50, 40, 0.9)),     # n_new == n_recent: new tokens never compete
+    (1, 100, 40, (4, 80, 8, 0.9)),      # n_new > n_recent: selection depends on this turn's scores
+    (3, 60, 30, (4, 30, 10, 0.8)),      # several streams
+    (2, 10, 12, (4, 20, 8, 0.9)),       # under budget: nothing evicted
+    (2, 90, 0, (4, 20, 8, 0.9)),        # no new tokens: decay + select + compact only
+    (1, 0, 50, (4, 20, 8, 0.9)),        # empty cache
+])
+def test_step_small_shapes(b, ref, n_streams, n_held, n_new, pol):
+    w = synth.WORKLOADS["tiny"]
+    pol = b.Policy(*pol)
+    g0 = torch.Generator(device=DEV).manual_seed(n_held * 100 + n_new)
+    z = torch.randn((n_streams * n_new, 777), generator=g0, device=DEV) * 2
+    tok = torch.randint(0, 777, (n_streams * n_new,), generator=g0, device=DEV, dtype=torch.int32)
+    held = torch.rand((n_streams, n_held), generator=g0, device=DEV) * 6
+    k_c = torch.randn((n_streams, 2, 2, n_held + n_new, 16), generator=g0, device=DEV)
+    v_c = torch.randn((n_streams, 2, 2, n_held + n_new, 16), generator=g0, device=DEV)
+    import dataclasses
+    w2 = dataclasses.replace(w, vocab=777)
+    g = gpu_step(b, w2, z, tok, held, k_c, v_c, pol=pol)
+    check_step_against_oracle(b, ref, w2, z, tok, held, k_c, v_c, g, pol=pol)
