@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the SirLLM retention step on one MI355X.
+
+A "step" is one call of sirllm_step: score the new tokens, decay the held scores, select
+sink + top-k + recent, compact every layer's K/V.  Inputs are seeded synthetic tensors already
+resident in HBM when the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama3_8b] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama3_8b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-threads", type=int, default=0, help="0 = min(16, host cores)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (every stream, the whole step); --gpus must be 1. "
+                 "Sharding across GPUs (by stream, or by KV head with a replicated selection) is a design note "
+                 "in DESIGN.md, not code.")
+
+    import torch
+    from paper_2405_12528_amd import binding as b
+    from paper_2405_12528_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU (run it under gpurun)")
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    pol = b.Policy(w.n_sink, w.n_topk, w.n_recent, w.decay)
+    S, n_held, n_new, n_cand, n_keep = w.n_streams, w.n_held, w.n_new, w.n_cand, w.n_keep
+    log(f"[bench] {synth.describe(w)}")
+
+    # ---- inputs, resident in HBM ---------------------------------------------------------
+    logits = synth.make_logits(w, turn=1, device=dev)
+    tok = synth.make_token_ids(w, turn=1, device=dev)
+    scores = torch.zeros((S, n_cand), device=dev)
+    scores[:, :n_held] = synth.make_held_scores(w, device=dev)
+    k_src = synth.make_kv(w, device=dev, which="k")
+    v_src = synth.make_kv(w, device=dev, which="v")
+    dst_shape = (S, w.n_layers, w.n_kv_heads, n_keep, w.head_dim)
+    k_dst = torch.zeros(dst_shape, dtype=k_src.dtype, device=dev)
+    v_dst = torch.zeros(dst_shape, dtype=k_src.dtype, device=dev)
+    kept = torch.zeros((S, n_keep), dtype=torch.int32, device=dev)
+    scores_out = torch.zeros((S, n_keep), device=dev)
+    ws_bytes = b.sirllm_workspace_bytes(S, n_cand, S * n_new, w.vocab)
+    ws = torch.zeros(max(ws_bytes, 256), dtype=torch.uint8, device=dev) if ws_bytes else None
+    torch.cuda.synchronize()
+
+    def step():
+        b.sirllm_step(logits, tok, w.vocab, scores, n_held, n_new, pol, k_src, v_src, k_dst, v_dst, kept,
+                      scores_out, workspace=ws)
+
+    # ---- the timed region: exactly K steps between two synchronisations ------------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    log(f"[bench] {args.steps} steps: {ms_per_step * 1e3:.1f} us/step by events, {wall_ms / args.steps * 1e3:.1f} us/step by host clock")
+
+    bytes_ = w.algorithmic_bytes()
+    tokens_per_s = S * n_new / (ms_per_step * 1e-3)
+    step_gbps = bytes_["total"] / (ms_per_step * 1e-3) / 1e9
+
+    # ---- the dominant kernel (the K/V gather), timed launch by launch with events on the
+    #      stream it runs on, in the launch configuration the step uses ---------------------
+    def time_launches(fn, n):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        for e0, e1 in evs:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        ts = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+        return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
+
+    n_k = max(10, min(args.steps, 50))
+    gather_avg, gather_med, gather_min = time_launches(
+        lambda: b.sirllm_compact_kv(k_src, v_src, k_dst, v_dst, kept, n_keep, n_src=n_cand), n_k)
+    new_scores = torch.zeros(S * n_new, device=dev)
+    score_avg, score_med, score_min = time_launches(
+        lambda: b.sirllm_score(logits, tok, new_scores, vocab=w.vocab, workspace=ws), n_k)
+    sel_avg, sel_med, sel_min = time_launches(
+        lambda: b.sirllm_decay_select(scores, n_held, n_new, pol, kept, scores_out, workspace=ws), n_k)
+    log(f"[bench] per launch (avg/median/min us): gather {gather_avg*1e3:.1f}/{gather_med*1e3:.1f}/{gather_min*1e3:.1f}  "
+        f"score {score_avg*1e3:.1f}/{score_med*1e3:.1f}/{score_min*1e3:.1f}  "
+        f"decay_select {sel_avg*1e3:.1f}/{sel_med*1e3:.1f}/{sel_min*1e3:.1f}")
+    if bytes_["compact"] >= bytes_["score"]:
+        dom, dom_bytes, dom_ms = "gather_rows_kernel", bytes_["compact"], gather_avg
+    else:
+        dom, dom_bytes, dom_ms = "score_rows_kernel", bytes_["score"], score_avg
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_ms * 1e3, 2),
+                "step": {"algorithmic_bytes": bytes_["total"], "achieved": round(step_gbps, 1),
+                         "frac": round(step_gbps / HBM_PEAK_GBPS, 4)},
+                "kernels_us": {"gather": round(gather_avg * 1e3, 2), "score": round(score_avg * 1e3, 2),
+                               "decay_select": round(sel_avg * 1e3, 2)},
+                "score_gbps": round(bytes_["score"] / (score_avg * 1e-3) / 1e9, 1)}
+
+    # ---- the oracle on the host cores, same bytes, as a reported baseline ----------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, args, logits, tok, scores, k_src, v_src)
+
+    out = {
+        "metric": "entropy-scored tokens/sec + fused step HBM GB/s (% of MI355X peak)",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "vocab": w.vocab, "logits_dtype": w.logits_dtype, "n_streams": S,
+                   "n_new": n_new, "n_cand": n_cand, "budget": w.budget, "n_sink": w.n_sink, "n_topk": w.n_topk,
+                   "n_recent": w.n_recent, "decay": w.decay, "kv": f"{w.n_layers}x{w.n_kv_heads}x{w.head_dim} {w.kv_dtype}"},
+        "step_hbm_gbps": round(step_gbps, 1), "step_pct_of_peak": round(100 * step_gbps / HBM_PEAK_GBPS, 2),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(w, args, logits, tok, scores, k_src, v_src):
+    """The oracle's whole step on the host, on a bounded sample of the same workload: every new
+    token of stream 0 (all of the workload when it has one stream)."""
+    import numpy as np
+    from oracle import ref
+
+    def host(t):
+        t = t.detach().cpu().contiguous()
+        import torch
+        return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+
+    threads = args.cpu_threads or min(16, os.cpu_count() or 1)
+    threads = ref.set_threads(threads)
+    n_new, n_held = w.n_new, w.n_held
+    z = host(logits[:n_new])
+    t = host(tok[:n_new])
+    held = host(scores[:1, :n_held])
+    k = host(k_src[:1])
+    v = host(v_src[:1])
+    pol = ref.Policy(w.n_sink, w.n_topk, w.n_recent, w.decay)
+    ref.step(z, t, w.vocab, held, n_new, pol, k, v)                      # warm-up (page faults, thread pool)
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        ref.step(z, t, w.vocab, held, n_new, pol, k, v)
+        reps += 1
+        el = time.perf_counter() - t0
+        if reps >= 3 or el > 20.0:
+            break
+    per = el / reps
+    sample = (f"oracle sirllm_ref_step on stream 0 of {w.n_streams}: {n_new} tokens x V={w.vocab}, select over "
+              f"{w.n_cand} slots, K/V gather of {w.n_keep} slots x {w.n_layers}x2x{w.n_kv_heads} planes; "
+              f"{reps} repetitions after 1 warm-up")
+    log(f"[bench] oracle: {per:.3f} s per stream-step on {threads} threads")
+    return {"value": round(n_new / per, 1), "unit": "tokens/s", "cores": threads, "kind": "oracle", "sample": sample,
+            "seconds_per_stream_step": round(per, 4)}
+
+
+if __name__ == "__main__":
+    main()

@@ -154,7 +154,7 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, S
                 ++eq;
             }
         }
-        if (pos >= 0) { idx[pos] = i; Eo[pos] = val[q]; }
+        if (pos >= 0 && pos < n_keep) { idx[pos] = i; Eo[pos] = val[q]; }
     }
 }
 
