@@ -138,7 +138,8 @@ int sirllm_decay_select(const float* scores, int64_t scores_stride,
  *   n_src   number of valid slots per (stream, layer, head) in the source; an index outside
  *           [0, n_src) cannot be reported without a device read-back, so the destination row
  *           is zero-filled instead of reading out of bounds.
- * n_keep == 0 or n_streams == 0 is a no-op.
+ * Limit: n_keep * head_dim * elem_bytes (the bytes of one compacted plane) must stay below
+ * 2 GiB, else SIRLLM_ERR_UNSUPPORTED.  n_keep == 0 or n_streams == 0 is a no-op.
  */
 int sirllm_compact_kv(const void* k_src, const void* v_src, const sirllm_kv_layout* src, int32_t n_src,
                       void* k_dst, void* v_dst, const sirllm_kv_layout* dst,

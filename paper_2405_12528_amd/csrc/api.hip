@@ -113,7 +113,7 @@ int validate_compact(const void* k_src, const void* v_src, const sirllm_kv_layou
     if (!k_src || !k_dst || !kept_idx) return SIRLLM_ERR_INVALID_ARG;
     if ((v_src == nullptr) != (v_dst == nullptr)) return SIRLLM_ERR_INVALID_ARG;
     if (idx_stride < n_keep) return SIRLLM_ERR_INVALID_ARG;
-    if ((int64_t)src->head_dim * src->elem_bytes > 0x7fffffffLL) return SIRLLM_ERR_UNSUPPORTED;
+    if ((int64_t)src->head_dim * src->elem_bytes * n_keep > 0x7fff0000LL) return SIRLLM_ERR_UNSUPPORTED;  // per-plane bytes
     const uintptr_t em = (uintptr_t)src->elem_bytes - 1;
     if (((uintptr_t)k_src & em) || ((uintptr_t)k_dst & em) || ((uintptr_t)v_src & em) || ((uintptr_t)v_dst & em))
         return SIRLLM_ERR_INVALID_ARG;
@@ -260,21 +260,30 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, 
     if (rc) return rc;
     hipStream_t stream = (hipStream_t)hip_stream;
 
-    // E_t = Entropy(new tokens), appended behind the held scores
-    if (n_rows > 0) {
-        ScoreArgs a;
-        a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
-        a.n_rows = n_rows; a.rows_per_stream = n_new;
-        a.out_a = scores + n_held; a.stride_a = scores_stride; a.out_b = nullptr; a.stride_b = 0;
-        rc = hip_status(launch_score(a, dt, stream));
-        if (rc) return rc;
-    }
-    // E <- E * eta on the held part; Id = sink + Top_k + recent; E <- E[Id]
+    ScoreArgs a;
+    a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
+    a.n_rows = n_rows; a.rows_per_stream = n_new > 0 ? n_new : 1;
+    a.out_a = scores + n_held; a.stride_a = scores_stride; a.out_b = nullptr; a.stride_b = 0;
     const SelectArgs s = make_select_args(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx,
                                           idx_stride, scores_out, out_stride);
-    if (!evict) return hip_status(launch_keep_all(s, stream));
-    rc = hip_status(launch_select(s, stream));
-    if (rc) return rc;
+    if (evict && score_select_fusable(a, s)) {
+        // The new tokens all sit in the recent window: Top_k does not look at this turn's scores, so
+        // one launch scores the rows and selects at the same time.  New token t of a stream ends up
+        // at in-cache position n_keep - n_new + t; the scoring workgroups write it there themselves.
+        a.out_b = scores_out + (n_keep - n_new); a.stride_b = out_stride;
+        rc = hip_status(launch_score_select(a, s, dt, stream));
+        if (rc) return rc;
+    } else {
+        // E_t = Entropy(new tokens), appended behind the held scores
+        if (n_rows > 0) {
+            rc = hip_status(launch_score(a, dt, stream));
+            if (rc) return rc;
+        }
+        // E <- E * eta on the held part; Id = sink + Top_k + recent; E <- E[Id]
+        if (!evict) return hip_status(launch_keep_all(s, stream));
+        rc = hip_status(launch_select(s, stream));
+        if (rc) return rc;
+    }
     // KV <- KV[Id]
     const GatherArgs g = make_gather_args(k_src, v_src, src, n_cand, k_dst, v_dst, dst, kept_idx, idx_stride,
                                           n_streams, n_keep);

@@ -1,0 +1,66 @@
+// One launch for "score the new tokens" and "decay + select + index build" when the two do not
+// depend on each other: with n_new <= n_recent every new token lies inside the recent window,
+// so Top_k (paper Sec. 3.3) only looks at held scores and can run while the vocabulary rows are
+// still being scanned (Sec. 3.2).  The first n_streams workgroups do the selection of one
+// stream each, all others score one row each; the scorers also drop the new scores straight
+// into their known places at the tail of the compacted score cache.
+#include "common.h"
+#include "score_device.h"
+#include "select_device.h"
+#include "tuning.h"
+
+namespace sirllm {
+namespace {
+
+constexpr int kBlock = 1024;
+
+template <int ESIZE, int KPT, bool NT>
+__global__ __launch_bounds__(kBlock) void score_select_kernel(ScoreArgs sa, SelectArgs se)
+{
+    __shared__ union {
+        select_dev::SelectSmem<kBlock> sel;
+        score_dev::ScoreSmem<kBlock> sc;
+    } sm;
+    if ((int)blockIdx.x < se.n_streams) {
+        select_dev::select_stream<kBlock, KPT, true>(se, (int)blockIdx.x, sm.sel);
+    } else {
+        score_dev::score_row<ESIZE, kBlock, 4, NT>(sa, (int64_t)blockIdx.x - se.n_streams, sm.sc);
+    }
+}
+
+template <int ESIZE, int KPT>
+hipError_t launch_kpt(const ScoreArgs& sa, const SelectArgs& se, hipStream_t stream)
+{
+    const dim3 grid((unsigned)(sa.n_rows + se.n_streams)), block(kBlock);
+    if (tuning::get("SIRLLM_SCORE_NT", 1) != 0)
+        hipLaunchKernelGGL((score_select_kernel<ESIZE, KPT, true>), grid, block, 0, stream, sa, se);
+    else
+        hipLaunchKernelGGL((score_select_kernel<ESIZE, KPT, false>), grid, block, 0, stream, sa, se);
+    return hipGetLastError();
+}
+
+template <int ESIZE>
+hipError_t launch_esize(const ScoreArgs& sa, const SelectArgs& se, hipStream_t stream)
+{
+    const int need = (se.n_cand + kBlock - 1) / kBlock;
+    if (need <= 2) return launch_kpt<ESIZE, 2>(sa, se, stream);
+    return launch_kpt<ESIZE, 8>(sa, se, stream);
+}
+
+}  // namespace
+
+bool score_select_fusable(const ScoreArgs& sa, const SelectArgs& se)
+{
+    if (tuning::get("SIRLLM_FUSE_SELECT", 1) == 0) return false;
+    const int n_new = se.n_cand - se.n_held;
+    return sa.n_rows > 0 && n_new <= se.n_recent && se.n_cand <= kBlock * 8 &&   // more slots per lane would cost the scorers their occupancy
+          
+           sa.n_rows + se.n_streams <= 0x7fffffffLL;
+}
+
+hipError_t launch_score_select(const ScoreArgs& sa, const SelectArgs& se, sirllm_dtype dt, hipStream_t stream)
+{
+    return dt == SIRLLM_F32 ? launch_esize<4>(sa, se, stream) : launch_esize<2>(sa, se, stream);
+}
+
+}  // namespace sirllm

@@ -1,178 +1,17 @@
-// Token entropy e = logsumexp(z) - z[token]  (paper Sec. 3.2) as a one-pass online
-// (max, sum) reduction over each vocabulary row.  One workgroup per row; every lane streams
-// 16-byte vectors of the row, keeps a running (m, s) pair in registers, lanes are merged with
-// wavefront shuffles and waves through LDS.  HBM-read bound: each logit is read exactly once.
+// Launch of the token-entropy score kernel (paper Sec. 3.2): one workgroup per vocabulary row.
+// HBM-read bound.
 #include "common.h"
+#include "score_device.h"
 #include "tuning.h"
 
 namespace sirllm {
 namespace {
 
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr uint32_t kNegInfBits = 0xff800000u;
-
-__device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32
-
-struct MS {
-    float m;   // running maximum (-inf when nothing finite has been seen)
-    float s;   // sum of exp(z - m) over what has been seen
-};
-
-// (m, s) pairs form a monoid under this merge; a side whose m equals the merged m is not rescaled,
-// which also keeps the empty element (-inf, 0) neutral.
-__device__ __forceinline__ MS merge(MS a, MS b)
-{
-    const float m = fmaxf(a.m, b.m);
-    const float fa = (a.m == m) ? 1.0f : exp2_hw((a.m - m) * kLog2e);
-    const float fb = (b.m == m) ? 1.0f : exp2_hw((b.m - m) * kLog2e);
-    return {m, a.s * fa + b.s * fb};
-}
-
-template <int N>
-__device__ __forceinline__ void accumulate(const float (&z)[N], MS& acc)
-{
-    float cm = z[0];
-#pragma unroll
-    for (int i = 1; i < N; ++i) cm = fmaxf(cm, z[i]);
-    const float m_new = fmaxf(acc.m, cm);
-    const float f = (acc.m == m_new) ? 1.0f : exp2_hw((acc.m - m_new) * kLog2e);
-    // while no finite value has been seen the reference is 0: exp(-inf - 0) = 0, never inf - inf
-    const float ref = (m_new == -INFINITY) ? 0.0f : m_new;
-    float t[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-    for (int i = 0; i < N; ++i) t[i & 3] += exp2_hw((z[i] - ref) * kLog2e);
-    acc.s = acc.s * f + ((t[0] + t[1]) + (t[2] + t[3]));
-    acc.m = m_new;
-}
-
-template <int ESIZE> struct Elem;
-template <> struct Elem<4> {
-    static constexpr int kVec = 4;
-    static __device__ __forceinline__ float load1(const char* row, int i) { return ((const float*)row)[i]; }
-    static __device__ __forceinline__ void unpack(u32x4 v, float* z)
-    {
-        z[0] = __uint_as_float(v.x); z[1] = __uint_as_float(v.y);
-        z[2] = __uint_as_float(v.z); z[3] = __uint_as_float(v.w);
-    }
-    static __device__ __forceinline__ u32x4 neg_inf()
-    {
-        u32x4 v = {kNegInfBits, kNegInfBits, kNegInfBits, kNegInfBits};
-        return v;
-    }
-};
-template <> struct Elem<2> {   // bfloat16: the upper half of a binary32
-    static constexpr int kVec = 8;
-    static __device__ __forceinline__ float load1(const char* row, int i)
-    {
-        return __uint_as_float((uint32_t)((const uint16_t*)row)[i] << 16);
-    }
-    static __device__ __forceinline__ void unpack(u32x4 v, float* z)
-    {
-        z[0] = __uint_as_float(v.x << 16); z[1] = __uint_as_float(v.x & 0xffff0000u);
-        z[2] = __uint_as_float(v.y << 16); z[3] = __uint_as_float(v.y & 0xffff0000u);
-        z[4] = __uint_as_float(v.z << 16); z[5] = __uint_as_float(v.z & 0xffff0000u);
-        z[6] = __uint_as_float(v.w << 16); z[7] = __uint_as_float(v.w & 0xffff0000u);
-    }
-    static __device__ __forceinline__ u32x4 neg_inf()
-    {
-        u32x4 v = {0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u};
-        return v;
-    }
-};
-
-template <bool NT>
-__device__ __forceinline__ u32x4 load_vec(const u32x4* p)
-{
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
-}
-
 template <int ESIZE, int BLOCK, int UNROLL, bool NT>
 __global__ __launch_bounds__(BLOCK) void score_rows_kernel(ScoreArgs a)
 {
-    using E = Elem<ESIZE>;
-    constexpr int VEC = E::kVec;
-    const int tid = threadIdx.x;
-    const int64_t row = blockIdx.x;
-    const char* rowp = (const char*)a.logits + row * a.ld * ESIZE;
-    const int V = a.vocab;
-
-    // split the row into [0, head) scalar | nvec 16-byte aligned vectors | scalar tail
-    int head = (int)(((16u - (uint32_t)((uintptr_t)rowp & 15u)) & 15u) / ESIZE);
-    if (head > V) head = V;
-    const int nvec = (V - head) / VEC;
-    const int tail0 = head + nvec * VEC;
-
-    MS acc = {-INFINITY, 0.0f};
-    {   // at most 2*(VEC-1) scalar elements, one per thread
-        int e = -1;
-        if (tid < head) e = tid;
-        else if (tid - head < V - tail0) e = tail0 + (tid - head);
-        if (e >= 0) {
-            float z[1] = {E::load1(rowp, e)};
-            accumulate<1>(z, acc);
-        }
-    }
-
-    const u32x4* vp = (const u32x4*)(rowp + (size_t)head * ESIZE);
-    int base = 0;
-    for (; base + BLOCK * UNROLL <= nvec; base += BLOCK * UNROLL) {
-        u32x4 v[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) v[u] = load_vec<NT>(vp + base + u * BLOCK + tid);
-        float z[UNROLL * VEC];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) E::unpack(v[u], z + u * VEC);
-        accumulate<UNROLL * VEC>(z, acc);
-    }
-    if (base < nvec) {   // ragged last sweep: lanes past the end see -inf, which adds exactly 0
-        u32x4 v[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int i = base + u * BLOCK + tid;
-            v[u] = (i < nvec) ? load_vec<NT>(vp + i) : E::neg_inf();
-        }
-        float z[UNROLL * VEC];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) E::unpack(v[u], z + u * VEC);
-        accumulate<UNROLL * VEC>(z, acc);
-    }
-
-    // lanes -> wave
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        MS o = {__shfl_xor(acc.m, off, kWave), __shfl_xor(acc.s, off, kWave)};
-        acc = merge(acc, o);
-    }
-    // waves -> workgroup
-    constexpr int NW = BLOCK / kWave;
-    __shared__ float sm[NW], ss[NW];
-    if constexpr (NW > 1) {
-        if ((tid & (kWave - 1)) == 0) { sm[tid / kWave] = acc.m; ss[tid / kWave] = acc.s; }
-        __syncthreads();
-        if (tid < kWave) {
-            acc = (tid < NW) ? MS{sm[tid], ss[tid]} : MS{-INFINITY, 0.0f};
-#pragma unroll
-            for (int off = NW / 2; off > 0; off >>= 1) {
-                MS o = {__shfl_xor(acc.m, off, kWave), __shfl_xor(acc.s, off, kWave)};
-                acc = merge(acc, o);
-            }
-        }
-    }
-    if (tid == 0) {
-        const int32_t tok = a.token_ids[row];
-        float e;
-        if (tok < 0 || tok >= V) {
-            e = __uint_as_float(0x7fc00000u);
-        } else {
-            const float zt = E::load1(rowp, tok);
-            e = (acc.m - zt) + logf(acc.s);
-        }
-        const int64_t stream = row / a.rows_per_stream;
-        const int64_t t = row - stream * a.rows_per_stream;
-        a.out_a[stream * a.stride_a + t] = e;
-        if (a.out_b) a.out_b[stream * a.stride_b + t] = e;
-    }
+    __shared__ score_dev::ScoreSmem<BLOCK> sm;
+    score_dev::score_row<ESIZE, BLOCK, UNROLL, NT>(a, (int64_t)blockIdx.x, sm);
 }
 
 template <int ESIZE, int BLOCK>
@@ -187,8 +26,10 @@ hipError_t launch_one(const ScoreArgs& a, hipStream_t stream, bool nt)
 template <int ESIZE>
 hipError_t launch_esize(const ScoreArgs& a, hipStream_t stream)
 {
-    // Few rows: wider workgroups, so that the chip still holds enough waves to cover HBM latency.
-    int block = a.n_rows >= 2048 ? 256 : (a.n_rows >= 1024 ? 512 : 1024);
+    // Long rows take the widest workgroup (most waves per CU on few rows); short rows a narrower
+    // one, so that lanes are not left without a single 16-byte vector.
+    const int64_t vecs = (int64_t)a.vocab * ESIZE / 16;
+    int block = vecs >= 2048 ? 1024 : (vecs >= 1024 ? 512 : 256);
     block = tuning::get("SIRLLM_SCORE_BLOCK", block);
     const bool nt = tuning::get("SIRLLM_SCORE_NT", 1) != 0;
     switch (block) {

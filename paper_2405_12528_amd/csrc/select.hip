@@ -1,168 +1,18 @@
-// Decay, Top_k selection and index build (paper Sec. 3.3: E <- E*eta, Id_entropy = Top_k(E),
-// E <- E[Id]; Sec. 3.1: Id_sink, Id_recent).  One workgroup per dialogue stream.  Every thread
-// owns KPT consecutive candidate slots in registers.  The k-th largest key of the middle region
-// is found by an MSB-first radix select (four 8-bit digits, LDS histograms), which yields the
-// threshold key and how many slots equal to it may still be taken (lowest slots first); one
-// block-wide prefix sum over (greater, equal) counts then gives every kept slot its in-cache
-// position, so the kept list comes out in ascending slot order without sorting anything.
-// Latency bound: the data is a few tens of KB per stream.
+// Launch of decay + Top_k selection + index build (paper Sec. 3.3, Sec. 3.1): one workgroup of
+// 1024 threads per dialogue stream, and the trivial keep-everything kernel for a cache that is
+// still within its budget.
 #include "common.h"
+#include "select_device.h"
 #include "tuning.h"
 
 namespace sirllm {
 namespace {
 
-// Order-preserving map from binary32 to uint32: a > b as numbers <=> key(a) > key(b).
-// -0 is folded onto +0 so that the two tie; NaNs land above +inf (sign clear) or below -inf (sign set).
-__device__ __forceinline__ uint32_t order_key(float x)
-{
-    uint32_t b = __float_as_uint(x);
-    if (b == 0x80000000u) b = 0u;
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
-
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
-{
-    const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t o = __shfl_up(v, off, kWave);
-        if (lane >= off) v += o;
-    }
-    return v;
-}
-
-template <int BLOCK>
-struct SelectSmem {
-    uint32_t hist[256];
-    uint32_t wave_tot[BLOCK / kWave];
-    uint32_t sel_digit;
-    uint32_t sel_above;
-};
-
-template <int BLOCK, int KPT>
-__device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, SelectSmem<BLOCK>& sm)
-{
-    static_assert(BLOCK >= 256 && BLOCK % kWave == 0, "histogram scan uses the first 256 threads");
-    constexpr int NW = BLOCK / kWave;
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1);
-    const int wave = tid / kWave;
-
-    const int n_cand = a.n_cand;
-    const int mid_lo = a.n_sink;
-    const int mid_hi = n_cand - a.n_recent;
-    const int n_keep = a.n_sink + a.n_topk + a.n_recent;      // this path runs only when n_cand > budget
-    const float* E = a.scores + (int64_t)stream * a.scores_stride;
-    const int i0 = tid * KPT;
-
-    // E <- E * eta for the held slots (one rounded multiply; never fused with anything)
-    float val[KPT];
-#pragma unroll
-    for (int q = 0; q < KPT; ++q) {
-        const int i = i0 + q;
-        float e = 0.0f;
-        if (i < n_cand) {
-            e = E[i];
-            if (i < a.n_held) e = __fmul_rn(e, a.decay);
-        }
-        val[q] = e;
-    }
-
-    // ---- radix select of the n_topk-th largest key among the middle slots -------------------
-    uint32_t prefix = 0xffffffffu, mask = 0xffffffffu;   // n_topk == 0: nothing is greater, quota 0
-    uint32_t k_rem = 0;
-    if (a.n_topk > 0) {
-        prefix = 0u; mask = 0u; k_rem = (uint32_t)a.n_topk;
-        for (int shift = 24; shift >= 0; shift -= 8) {
-            if (tid < 256) sm.hist[tid] = 0u;
-            __syncthreads();
-#pragma unroll
-            for (int q = 0; q < KPT; ++q) {
-                const int i = i0 + q;
-                if (i >= mid_lo && i < mid_hi) {
-                    const uint32_t key = order_key(val[q]);
-                    if ((key & mask) == prefix) atomicAdd(&sm.hist[(key >> shift) & 255u], 1u);
-                }
-            }
-            __syncthreads();
-            // the digit d with  #(digit > d) < k_rem <= #(digit >= d)
-            const uint32_t c = (tid < 256) ? sm.hist[tid] : 0u;
-            const uint32_t inc = wave_inclusive_scan(c);
-            if (lane == kWave - 1) sm.wave_tot[wave] = inc;
-            __syncthreads();
-            if (tid < 256) {
-                uint32_t below_waves = 0u, total = 0u;
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const uint32_t t = sm.wave_tot[w];
-                    if (w < wave) below_waves += t;
-                    total += t;
-                }
-                const uint32_t above = total - (inc + below_waves);
-                if (above < k_rem && k_rem <= above + c) { sm.sel_digit = (uint32_t)tid; sm.sel_above = above; }
-            }
-            __syncthreads();
-            prefix |= sm.sel_digit << shift;
-            mask |= 255u << shift;
-            k_rem -= sm.sel_above;
-        }
-    }
-    const uint32_t tau = prefix;       // key of the n_topk-th largest middle slot
-    const uint32_t quota = k_rem;      // how many slots equal to tau are still taken, lowest first
-
-    // ---- block-wide exclusive prefix sum of (greater, equal) counts ---------------------------
-    uint32_t mine = 0u;                // greater in the low 16 bits, equal in the high 16
-#pragma unroll
-    for (int q = 0; q < KPT; ++q) {
-        const int i = i0 + q;
-        if (i >= mid_lo && i < mid_hi) {
-            const uint32_t key = order_key(val[q]);
-            mine += (key > tau) ? 1u : 0u;
-            mine += (key == tau) ? 0x10000u : 0u;
-        }
-    }
-    const uint32_t inc = wave_inclusive_scan(mine);
-    __syncthreads();                   // wave_tot is reused
-    if (lane == kWave - 1) sm.wave_tot[wave] = inc;
-    __syncthreads();
-    uint32_t before = inc - mine;
-#pragma unroll
-    for (int w = 0; w < NW; ++w)
-        if (w < wave) before += sm.wave_tot[w];
-    uint32_t g = before & 0xffffu, eq = before >> 16;
-
-    // ---- index build: kept slot i goes to in-cache position pos; E_out[pos] = E[i] ------------
-    int32_t* idx = a.kept_idx + (int64_t)stream * a.idx_stride;
-    float* Eo = a.scores_out + (int64_t)stream * a.out_stride;
-#pragma unroll
-    for (int q = 0; q < KPT; ++q) {
-        const int i = i0 + q;
-        if (i >= n_cand) break;
-        int pos = -1;
-        if (i < mid_lo) {
-            pos = i;                                            // Id_sink
-        } else if (i >= mid_hi) {
-            pos = n_keep - (n_cand - i);                        // Id_recent
-        } else {
-            const uint32_t key = order_key(val[q]);
-            if (key > tau) {
-                pos = mid_lo + (int)(g + (eq < quota ? eq : quota));
-                ++g;
-            } else if (key == tau) {
-                if (eq < quota) pos = mid_lo + (int)(g + eq);   // Id_entropy, ties to the lower slot
-                ++eq;
-            }
-        }
-        if (pos >= 0 && pos < n_keep) { idx[pos] = i; Eo[pos] = val[q]; }
-    }
-}
-
 template <int BLOCK, int KPT>
 __global__ __launch_bounds__(BLOCK) void select_kernel(SelectArgs a)
 {
-    __shared__ SelectSmem<BLOCK> sm;
-    select_stream<BLOCK, KPT>(a, (int)blockIdx.x, sm);
+    __shared__ select_dev::SelectSmem<BLOCK> sm;
+    select_dev::select_stream<BLOCK, KPT, false>(a, (int)blockIdx.x, sm);
 }
 
 __global__ __launch_bounds__(256) void keep_all_kernel(SelectArgs a)

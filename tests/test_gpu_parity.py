@@ -278,6 +278,17 @@ def test_compact_strided_views_and_bad_indices(b, ref):
     assert (to_np(k_dst)[:, :, :, 6:] == 77).all()
 
 
+def test_compact_many_planes_and_streams(b, ref):
+    # more planes than one grid dimension holds (the launch is cut into slices of 65535 planes)
+    rng = np.random.default_rng(5)
+    k = torch.from_numpy(rng.integers(0, 2**31 - 1, (1, 260, 260, 5, 4)).astype(np.int32)).to(DEV)
+    kept = np.array([[4, 0, 2]], dtype=np.int32)
+    run_compact(b, ref, k, k + 1, kept)
+    k = torch.from_numpy(rng.integers(0, 2**31 - 1, (70, 2, 1, 6, 4)).astype(np.int32)).to(DEV)
+    kept = np.stack([np.sort(rng.choice(6, 4, replace=False)) for _ in range(70)]).astype(np.int32)
+    run_compact(b, ref, k, None, kept)
+
+
 # --------------------------------------------------------------------------------- whole step
 def gpu_step(b, w, z, tok, held, k_c, v_c, pol=None):
     """Run sirllm_step on device tensors; returns host copies of everything it wrote."""
