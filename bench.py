@@ -92,20 +92,23 @@ def main():
 
     # ---- the dominant kernel (the K/V gather), timed launch by launch with events on the
     #      stream it runs on, in the launch configuration the step uses ---------------------
-    def time_launches(fn, n):
+    def time_launches(fn, n, group=8):
+        """Average, median and minimum duration of one launch: n groups of `group` back-to-back
+        launches, each group bracketed by two events on the stream the kernels run on."""
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
         for _ in range(3):
             fn()
         torch.cuda.synchronize()
         for e0, e1 in evs:
             e0.record()
-            fn()
+            for _ in range(group):
+                fn()
             e1.record()
         torch.cuda.synchronize()
-        ts = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+        ts = sorted(e0.elapsed_time(e1) / group for e0, e1 in evs)
         return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
 
-    n_k = max(10, min(args.steps, 50))
+    n_k = max(5, min(args.steps, 20))
     gather_avg, gather_med, gather_min = time_launches(
         lambda: b.sirllm_compact_kv(k_src, v_src, k_dst, v_dst, kept, n_keep, n_src=n_cand), n_k)
     new_scores = torch.zeros(S * n_new, device=dev)
@@ -116,13 +119,21 @@ def main():
     log(f"[bench] per launch (avg/median/min us): gather {gather_avg*1e3:.1f}/{gather_med*1e3:.1f}/{gather_min*1e3:.1f}  "
         f"score {score_avg*1e3:.1f}/{score_med*1e3:.1f}/{score_min*1e3:.1f}  "
         f"decay_select {sel_avg*1e3:.1f}/{sel_med*1e3:.1f}/{sel_min*1e3:.1f}")
+    # a plain copy of known size (1 GiB read + 1 GiB written) so that a counter run of this same
+    # command holds its own calibration kernel for FETCH_SIZE / WRITE_SIZE
+    calib_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    calib_dst = torch.empty_like(calib_src)
+    copy_avg, _, _ = time_launches(lambda: calib_dst.copy_(calib_src), 3, group=2)
+    log(f"[bench] plain 1 GiB device copy (torch): {copy_avg*1e3:.1f} us -> {2 * (1 << 30) / (copy_avg * 1e-3) / 1e9:.0f} GB/s")
+    del calib_src, calib_dst
     if bytes_["compact"] >= bytes_["score"]:
         dom, dom_bytes, dom_ms = "gather_rows_kernel", bytes_["compact"], gather_avg
     else:
         dom, dom_bytes, dom_ms = "score_rows_kernel", bytes_["score"], score_avg
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    traffic = committed_traffic(dom, w.name)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_ms * 1e3, 2),
                 "step": {"algorithmic_bytes": bytes_["total"], "achieved": round(step_gbps, 1),
                          "frac": round(step_gbps / HBM_PEAK_GBPS, 4)},
@@ -147,6 +158,19 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
+
+
+def committed_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` as measured by the rocprofv3 FETCH_SIZE / WRITE_SIZE counter
+    runs of this command; the figure is kept in the committed summary under profiles/ (a counter
+    run cannot be made from inside the timed process).  None when no summary covers the workload."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"{kernel}__{workload}.md")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch\s*=\s*(\d+)", open(path).read(), flags=re.M)
+    except OSError:
+        return None
+    return int(m.group(1)) if m else None
 
 
 def cpu_baseline(w, args, logits, tok, scores, k_src, v_src):
