@@ -95,6 +95,14 @@ WORKLOADS = {
                                  zipf_a=1.1, spike=0.0, spike_frac=0.0, n_sink=4, n_topk=1788, n_recent=256,
                                  decay=0.9, n_layers=32, n_kv_heads=32, head_dim=128, kv_dtype="bf16",
                                  n_cand=2304, n_streams=32, n_turns=200, checked_turns=(1, 50, 200)),
+    # The paper's own operating point (Sec. 4.2, Rock-Paper-Scissors: ~54 tokens per round, cache
+    # 1024 = 4 sink + 1020 entropy + 0 recent, decay 0.7-0.9, cache never reset), on a 7B-shaped K/V.
+    # With no recent window every new token competes in Top_k: scoring, selection and gather form a
+    # true dependency chain.
+    "rps_dialogue": Workload("rps_dialogue", vocab=32000, n_new=54, logits_dtype="bf16", sigma=3.0, zipf_a=1.1,
+                             spike=0.0, spike_frac=0.0, n_sink=4, n_topk=1020, n_recent=0, decay=0.8,
+                             n_layers=32, n_kv_heads=32, head_dim=128, kv_dtype="bf16", n_cand=1078,
+                             n_turns=2000, checked_turns=(1, 19, 20, 100, 300)),
 }
 
 _KIND = {"logits": 1, "tokens": 2, "held": 3, "kv_k": 4, "kv_v": 5, "rank": 6, "spike": 7}

@@ -121,3 +121,95 @@ def test_batched_dialogue_200_turns(b, ref):
                     assert np.array_equal(to_np(dst_t[s:s + 1, l:l + 1, h:h + 1, :n_keep]), rp), \
                         f"plane (stream {s}, layer {l}, head {h}) differs at turn {turn}"
         print(f"turn {turn}: checked", flush=True)
+
+
+@pytest.mark.timeout(600)
+def test_rps_dialogue_many_small_turns(b, ref):
+    """The paper's own operating point: ~54 tokens per round, budget 1024 = 4 + 1020 + 0, the cache never
+    reset; with no recent window the selection depends on this turn's scores (three dependent launches)."""
+    from paper_2405_12528_amd.cache import RetentiveCache
+    w = synth.WORKLOADS["rps_dialogue"]
+    ref.set_threads(16)
+    pol = (w.n_sink, w.n_topk, w.n_recent, w.decay)
+    cache = RetentiveCache(1, w.n_layers, w.n_kv_heads, w.head_dim, pol, max_new=w.n_new, device=DEV)
+    gk = torch.Generator(device=DEV).manual_seed(777)
+    last = max(w.checked_turns)
+    for turn in range(1, last + 1):
+        logits = synth.make_logits(w, turn=turn, device=DEV)
+        tok = synth.make_token_ids(w, turn=turn, device=DEV)
+        k_new, v_new = cache.new_kv_slots(w.n_new)
+        k_new.copy_(torch.randn(k_new.shape, generator=gk, device=DEV, dtype=torch.float32).to(k_new.dtype))
+        v_new.copy_(torch.randn(v_new.shape, generator=gk, device=DEV, dtype=torch.float32).to(v_new.dtype))
+        n_held = cache.n_held
+        n_cand = n_held + w.n_new
+        check = turn in w.checked_turns
+        if check:
+            held = cache.scores[:, :n_held].clone()
+            k_pre, v_pre, s_pre = cache.k, cache.v, cache.scores
+        evicted = cache.step(logits, tok, w.vocab)
+        assert evicted == (turn * w.n_new > w.budget)
+        if not check:
+            continue
+        torch.cuda.synchronize()
+        n_keep = cache.n_held
+        Eg = to_np(s_pre[:, :n_cand])
+        want = ref.score(to_np(logits), to_np(tok), vocab=w.vocab).reshape(1, w.n_new)
+        assert_scores_close(Eg[:, n_held:], want)
+        np.testing.assert_array_equal(Eg[:, :n_held].view(np.uint32), to_np(held).view(np.uint32))
+        ri, ro = ref.decay_select(Eg, n_held, w.n_new, ref.Policy(*pol))
+        np.testing.assert_array_equal(to_np(cache.kept_idx[:, :n_keep]), ri)
+        np.testing.assert_array_equal(to_np(cache.scores[:, :n_keep]).view(np.uint32), ro.view(np.uint32))
+        if evicted:
+            rk, rv = ref.compact_kv(to_np(k_pre[:, :, :, :n_cand]), to_np(v_pre[:, :, :, :n_cand]), ri)
+            assert np.array_equal(to_np(cache.k[:, :, :, :n_keep]), rk)
+            assert np.array_equal(to_np(cache.v[:, :, :, :n_keep]), rv)
+            assert n_keep == w.budget and ri[0, :4].tolist() == [0, 1, 2, 3]
+        print(f"turn {turn}: checked (evicted={evicted})", flush=True)
+
+
+def test_step_replays_from_a_captured_graph(b, ref):
+    """sirllm_step allocates nothing, synchronises nothing and clears nothing with memset nodes, so it
+    can be captured into a HIP graph; every replay must reproduce the eager result, also with eager
+    work and synchronisations between replays."""
+    w = synth.WORKLOADS["tiny"]
+    pol = b.Policy(4, 30, 0, 0.8)                       # no recent window: the three-launch path
+    S, n_held, n_new, V = 2, 60, 40, 777
+    g0 = torch.Generator(device=DEV).manual_seed(5)
+    z = torch.randn((S * n_new, V), generator=g0, device=DEV) * 2
+    tok = torch.randint(0, V, (S * n_new,), generator=g0, device=DEV, dtype=torch.int32)
+    held = torch.rand((S, n_held), generator=g0, device=DEV) * 6
+    k_c = torch.randn((S, 2, 2, n_held + n_new, 16), generator=g0, device=DEV)
+    v_c = torch.randn((S, 2, 2, n_held + n_new, 16), generator=g0, device=DEV)
+    n_keep = 34
+
+    def fresh():
+        E = torch.zeros((S, n_held + n_new), device=DEV)
+        E[:, :n_held] = held
+        return dict(E=E, idx=torch.zeros((S, n_keep), dtype=torch.int32, device=DEV),
+                    out=torch.zeros((S, n_keep), device=DEV), k=torch.zeros((S, 2, 2, n_keep, 16), device=DEV),
+                    v=torch.zeros((S, 2, 2, n_keep, 16), device=DEV))
+
+    def run(t):
+        b.sirllm_step(z, tok, V, t["E"], n_held, n_new, pol, k_c, v_c, t["k"], t["v"], t["idx"], t["out"])
+
+    eager = fresh()
+    run(eager)
+    torch.cuda.synchronize()
+    cap = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(cap)                                         # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(cap)
+    for rep in range(4):
+        for t in cap.values():                           # eager work between replays: wipe every output
+            t.zero_() if t is not cap["E"] else t[:, n_held:].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in eager:
+            assert torch.equal(cap[name], eager[name]), f"replay {rep}: {name} differs from the eager run"
