@@ -232,7 +232,7 @@ int sirllm_compact_kv(const void* k_src, const void* v_src, const sirllm_kv_layo
     if (n_streams == 0 || n_keep == 0) return SIRLLM_OK;
     const GatherArgs g = make_gather_args(k_src, v_src, src, n_src, k_dst, v_dst, dst, kept_idx, idx_stride,
                                           n_streams, n_keep);
-    return hip_status(launch_gather(g, (hipStream_t)hip_stream));
+    return hip_status(launch_gather(g, 0, n_keep, (hipStream_t)hip_stream));
 }
 
 int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
@@ -287,7 +287,7 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, 
     // KV <- KV[Id]
     const GatherArgs g = make_gather_args(k_src, v_src, src, n_cand, k_dst, v_dst, dst, kept_idx, idx_stride,
                                           n_streams, n_keep);
-    return hip_status(launch_gather(g, stream));
+    return hip_status(launch_gather(g, 0, n_keep, stream));
 }
 
 }  // extern "C"

@@ -48,13 +48,6 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
 // n_cand <= budget: identity index list, decayed scores.
 hipError_t launch_keep_all(const SelectArgs& a, hipStream_t stream);
 
-// ---- fused.hip --------------------------------------------------------------------------
-// Scoring and selection in one launch; only valid when score_select_fusable() says so (the new
-// tokens all fall inside the recent window, so the selection never reads this turn's scores).
-// The caller points sa.out_b at the tail of scores_out where the new scores belong.
-bool score_select_fusable(const ScoreArgs& sa, const SelectArgs& se);
-hipError_t launch_score_select(const ScoreArgs& sa, const SelectArgs& se, sirllm_dtype dt, hipStream_t stream);
-
 // ---- gather.hip -------------------------------------------------------------------------
 struct GatherArgs {
     const char* src[2];       // K, V (V may be null: then only tensor 0 is moved)
@@ -67,6 +60,14 @@ struct GatherArgs {
     const int32_t* kept_idx;
     int64_t idx_stride;
 };
-hipError_t launch_gather(const GatherArgs& a, hipStream_t stream);
+// Copies destination rows [row_begin, row_end) of every plane.
+hipError_t launch_gather(const GatherArgs& a, int row_begin, int row_end, hipStream_t stream);
+
+// ---- fused.hip --------------------------------------------------------------------------
+// Scoring and selection in one launch; only valid when score_select_fusable() says so (the new
+// tokens all fall inside the recent window, so the selection never reads this turn's scores).
+// The caller points sa.out_b at the tail of scores_out where the new scores belong.
+bool score_select_fusable(const ScoreArgs& sa, const SelectArgs& se);
+hipError_t launch_score_select(const ScoreArgs& sa, const SelectArgs& se, sirllm_dtype dt, hipStream_t stream);
 
 }  // namespace sirllm

@@ -3,7 +3,8 @@
 // so Top_k (paper Sec. 3.3) only looks at held scores and can run while the vocabulary rows are
 // still being scanned (Sec. 3.2).  The first n_streams workgroups do the selection of one
 // stream each, all others score one row each; the scorers also drop the new scores straight
-// into their known places at the tail of the compacted score cache.
+// into their known places at the tail of the compacted score cache.  The latency-bound
+// selection thereby hides behind the HBM-bound scan.
 #include "common.h"
 #include "score_device.h"
 #include "select_device.h"
@@ -53,8 +54,8 @@ bool score_select_fusable(const ScoreArgs& sa, const SelectArgs& se)
 {
     if (tuning::get("SIRLLM_FUSE_SELECT", 1) == 0) return false;
     const int n_new = se.n_cand - se.n_held;
-    return sa.n_rows > 0 && n_new <= se.n_recent && se.n_cand <= kBlock * 8 &&   // more slots per lane would cost the scorers their occupancy
-          
+    // more than 8 slots per lane in the selecting workgroup would cost the scorers their occupancy
+    return sa.n_rows > 0 && n_new <= se.n_recent && se.n_cand <= kBlock * 8 &&
            sa.n_rows + se.n_streams <= 0x7fffffffLL;
 }
 
