@@ -172,6 +172,37 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld,
                 float* scores_out, int64_t out_stride,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Baseline retention policies on the same compaction path (Sec. 4.1 "Baselines"): they pick the
+ * n_topk slots of the middle region [n_sink, n_cand - n_recent) without looking at any score;
+ * sinks and the recent window are kept as in sirllm_decay_select, and kept_idx comes out in the
+ * same ascending order, ready for sirllm_compact_kv.  policy->decay is ignored.
+ *   SIRLLM_BASELINE_STREAM    no middle slot at all: sinks + recent window only (StreamLLM);
+ *                             the kept count is n_sink + n_recent, whatever n_topk says.
+ *   SIRLLM_BASELINE_INTERVAL  every interval-th middle slot, interval = max(1, floor(M / n_topk)),
+ *                             M the size of the middle region (IntervalLLM).  The paper does not
+ *                             say where the comb is anchored; here it is anchored at the newest
+ *                             middle slot and runs towards older ones until n_topk slots are
+ *                             taken, so a stream keeps absorbing new tokens when interval is 1.
+ *   SIRLLM_BASELINE_RANDOM    a uniformly random n_topk-subset of the middle slots (RandomLLM):
+ *                             slot i of stream s gets the key Philox4x32-10(counter = {i, s,
+ *                             turn low word, turn high word}, key = {seed low, seed high}) word 0,
+ *                             and the n_topk largest keys are kept (equal keys: lower slot).
+ * When n_cand <= the kept count nothing is evicted: kept_idx = 0..n_cand-1.
+ * Returns, through *n_keep_out (host pointer, may be NULL), the number of kept slots per stream.
+ * Limits as for sirllm_decay_select.
+ */
+typedef enum {
+    SIRLLM_BASELINE_STREAM   = 0,
+    SIRLLM_BASELINE_INTERVAL = 1,
+    SIRLLM_BASELINE_RANDOM   = 2
+} sirllm_baseline;
+
+int sirllm_baseline_select(sirllm_baseline kind, int32_t n_streams, int32_t n_cand,
+                           const sirllm_policy* policy, uint64_t seed, uint64_t turn,
+                           int32_t* kept_idx, int64_t idx_stride, int32_t* n_keep_out,
+                           void* hip_stream);
+
 /* Bytes of device workspace the calls above need for these sizes (pass 0 for the sizes a
  * call does not have).  Never fails; the result is a multiple of 256. */
 size_t sirllm_workspace_bytes(int32_t n_streams, int32_t n_cand, int64_t n_rows, int32_t vocab);

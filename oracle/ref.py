@@ -42,6 +42,12 @@ def load(path):
     L.sirllm_ref_step.argtypes = [vp, C.c_int, i32, i64, vp, vp, i64, i32, i32, i32, C.POINTER(_CPolicy),
                                   vp, vp, C.POINTER(_CLayout), vp, vp, C.POINTER(_CLayout),
                                   vp, i64, vp, i64]
+    L.sirllm_ref_baseline_select.argtypes = [C.c_int, i32, i32, C.POINTER(_CPolicy), C.c_uint64, C.c_uint64, vp, i64,
+                                             C.POINTER(i32)]
+    L.sirllm_ref_baseline_select.restype = C.c_int
+    L.sirllm_ref_philox4x32_10.argtypes = [C.POINTER(C.c_uint32 * 4), C.POINTER(C.c_uint32 * 2),
+                                           C.POINTER(C.c_uint32 * 4)]
+    L.sirllm_ref_philox4x32_10.restype = None
     for f in (L.sirllm_ref_score, L.sirllm_ref_decay_select, L.sirllm_ref_compact_kv, L.sirllm_ref_step,
               L.sirllm_ref_set_threads, L.sirllm_ref_get_threads):
         f.restype = C.c_int
@@ -115,6 +121,28 @@ def decay_select(scores: np.ndarray, n_held: int, n_new: int, policy):
     _check(lib().sirllm_ref_decay_select(_ptr(scores), stride, n_streams, n_held, n_new, C.byref(cp),
                                          _ptr(kept), kept.shape[1], _ptr(out), out.shape[1]), "decay_select")
     return kept[:, :n_keep], out[:, :n_keep]
+
+
+STREAM, INTERVAL, RANDOM = 0, 1, 2
+
+
+def baseline_select(kind: int, n_streams: int, n_cand: int, policy, seed: int = 0, turn: int = 0) -> np.ndarray:
+    """Kept slots [n_streams, n_keep] of a baseline policy (StreamLLM / IntervalLLM / RandomLLM)."""
+    cp = _cpolicy(policy)
+    cap = max(1, min(n_cand, int(policy.n_sink) + int(policy.n_topk) + int(policy.n_recent)))
+    kept = np.full((max(n_streams, 1), cap), -1, dtype=np.int32)
+    n_keep = C.c_int32(-1)
+    _check(lib().sirllm_ref_baseline_select(int(kind), n_streams, n_cand, C.byref(cp), int(seed), int(turn),
+                                            _ptr(kept), cap, C.byref(n_keep)), "baseline_select")
+    return kept[:n_streams, :n_keep.value]
+
+
+def philox4x32_10(ctr, key):
+    c = (C.c_uint32 * 4)(*ctr)
+    k = (C.c_uint32 * 2)(*key)
+    out = (C.c_uint32 * 4)()
+    lib().sirllm_ref_philox4x32_10(C.byref(c), C.byref(k), C.byref(out))
+    return [int(x) for x in out]
 
 
 def _layout_of(a: np.ndarray) -> _CLayout:

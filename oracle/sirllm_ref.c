@@ -207,6 +207,91 @@ int sirllm_ref_decay_select(const float* scores, int64_t scores_stride,
 }
 
 /* ------------------------------------------------------------------------------------ */
+/* Sec. 4.1: the baseline policies (StreamLLM, IntervalLLM, RandomLLM)                    */
+/* ------------------------------------------------------------------------------------ */
+
+/* One round: two 32x32 -> 64 bit products, the high halves are mixed with the other counter
+ * words and the round key, the low halves pass through; the key then steps by the Weyl constants. */
+void sirllm_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+typedef struct { uint32_t key; int32_t slot; } keyed_slot;
+
+static int by_key_then_slot(const void* pa, const void* pb)
+{
+    const keyed_slot* a = (const keyed_slot*)pa;
+    const keyed_slot* b = (const keyed_slot*)pb;
+    if (a->key != b->key) return a->key > b->key ? -1 : 1;      /* larger key first */
+    return (a->slot > b->slot) - (a->slot < b->slot);
+}
+
+int sirllm_ref_baseline_select(int kind, int32_t n_streams, int32_t n_cand, const sirllm_ref_policy* policy,
+                               uint64_t seed, uint64_t turn, int32_t* kept_idx, int64_t idx_stride,
+                               int32_t* n_keep_out)
+{
+    if (kind < 0 || kind > 2 || n_streams < 0 || n_cand < 0 || !policy_ok(policy)) return -1;
+    const int64_t k = kind == 0 ? 0 : policy->n_topk;
+    const int64_t budget = (int64_t)policy->n_sink + k + policy->n_recent;
+    const int64_t n_keep = n_cand < budget ? n_cand : budget;
+    if (n_keep_out) *n_keep_out = (int32_t)n_keep;
+    if (n_streams == 0 || n_cand == 0) return 0;
+    if (!kept_idx) return -1;
+
+    for (int32_t s = 0; s < n_streams; ++s) {
+        int32_t* idx = kept_idx + (int64_t)s * idx_stride;
+        char* keep = (char*)calloc((size_t)n_cand, 1);
+        if (!keep) return -1;
+        if (n_cand <= budget) {
+            for (int64_t i = 0; i < n_cand; ++i) keep[i] = 1;
+        } else {
+            const int64_t mid_lo = policy->n_sink, mid_hi = n_cand - policy->n_recent;
+            const int64_t M = mid_hi - mid_lo;
+            for (int64_t i = 0; i < mid_lo; ++i) keep[i] = 1;
+            for (int64_t i = mid_hi; i < n_cand; ++i) keep[i] = 1;
+            if (kind == 1 && k > 0) {
+                int64_t interval = M / k;
+                if (interval < 1) interval = 1;
+                for (int64_t j = 0; j < k; ++j) keep[mid_hi - 1 - j * interval] = 1;
+            } else if (kind == 2 && k > 0) {
+                keyed_slot* mid = (keyed_slot*)malloc((size_t)M * sizeof(keyed_slot));
+                if (!mid) { free(keep); return -1; }
+                const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+                for (int64_t i = 0; i < M; ++i) {
+                    const uint32_t ctr[4] = {(uint32_t)(mid_lo + i), (uint32_t)s, (uint32_t)turn, (uint32_t)(turn >> 32)};
+                    uint32_t r[4];
+                    sirllm_ref_philox4x32_10(ctr, key, r);
+                    mid[i].key = r[0];
+                    mid[i].slot = (int32_t)(mid_lo + i);
+                }
+                qsort(mid, (size_t)M, sizeof(keyed_slot), by_key_then_slot);
+                for (int64_t j = 0; j < k; ++j) keep[mid[j].slot] = 1;
+                free(mid);
+            }
+        }
+        int64_t j = 0;
+        for (int64_t i = 0; i < n_cand; ++i)
+            if (keep[i]) idx[j++] = (int32_t)i;
+        free(keep);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------ */
 /* Sec. 3.3: KV_cache <- KV_cache[Id]                                                    */
 /* ------------------------------------------------------------------------------------ */
 

@@ -60,6 +60,18 @@ int sirllm_ref_step(const void* logits, int dtype, int32_t vocab, int64_t ld, co
                     int32_t* kept_idx, int64_t idx_stride,
                     float* scores_out, int64_t out_stride);
 
+/* Sec. 4.1 baselines: kind 0 = sink + recent only (StreamLLM), 1 = every interval-th middle slot
+ * counted back from the newest one (IntervalLLM), 2 = a uniformly random subset of the middle slots
+ * keyed by Philox4x32-10 (RandomLLM).  Writes the kept slots ascending; returns the kept count per
+ * stream through *n_keep_out. */
+int sirllm_ref_baseline_select(int kind, int32_t n_streams, int32_t n_cand, const sirllm_ref_policy* policy,
+                               uint64_t seed, uint64_t turn, int32_t* kept_idx, int64_t idx_stride,
+                               int32_t* n_keep_out);
+
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC'11):
+ * out[0..3] = ten rounds of the bijection on counter ctr[0..3] under key key[0..1]. */
+void sirllm_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
 /* Threads used by the loops over rows / planes (1 = serial).  Returns the count in effect. */
 int sirllm_ref_set_threads(int n);
 int sirllm_ref_get_threads(void);

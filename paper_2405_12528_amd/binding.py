@@ -40,7 +40,9 @@ class sirllm_kv_layout(C.Structure):
                 ("stride_head", C.c_int64), ("stride_pos", C.c_int64)]
 
 
-EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step",
+SIRLLM_BASELINE_STREAM, SIRLLM_BASELINE_INTERVAL, SIRLLM_BASELINE_RANDOM = 0, 1, 2
+
+EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step", "sirllm_baseline_select",
            "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
 
 _vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
@@ -50,6 +52,9 @@ _lib.sirllm_decay_select.argtypes = [_vp, _i64, _i32, _i32, _i32, _PP, _vp, _i64
 _lib.sirllm_compact_kv.argtypes = [_vp, _vp, _LP, _i32, _vp, _vp, _LP, _vp, _i64, _i32, _i32, _vp]
 _lib.sirllm_step.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _i32, _i32, _PP,
                              _vp, _vp, _LP, _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _sz, _vp]
+_lib.sirllm_baseline_select.argtypes = [C.c_int, _i32, _i32, _PP, C.c_uint64, C.c_uint64, _vp, _i64,
+                                        C.POINTER(C.c_int32), _vp]
+_lib.sirllm_baseline_select.restype = C.c_int
 for _n in ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step"):
     getattr(_lib, _n).restype = C.c_int
 _lib.sirllm_workspace_bytes.argtypes = [_i32, _i32, _i64, _i32]
@@ -167,6 +172,20 @@ def sirllm_decay_select(scores: torch.Tensor, n_held: int, n_new: int, policy, k
                                     _ptr(kept_idx), _row_stride(kept_idx), _ptr(scores_out), _row_stride(scores_out),
                                     wp, wb, _stream(stream)), "sirllm_decay_select")
     return kept_idx, scores_out
+
+
+def sirllm_baseline_select(kind: int, n_cand: int, policy, kept_idx: torch.Tensor, seed: int = 0, turn: int = 0,
+                           stream=None) -> int:
+    """Kept slots of a score-free baseline policy for n_streams = kept_idx.shape[0] streams; returns n_keep."""
+    _on_device(kept_idx)
+    if kept_idx.dim() != 2 or kept_idx.dtype != torch.int32 or (kept_idx.shape[1] > 1 and kept_idx.stride(1) != 1):
+        raise ValueError("kept_idx must be [n_streams, >= n_keep] int32 with contiguous rows")
+    p = _policy(policy)
+    n_keep = C.c_int32(-1)
+    _check(_lib.sirllm_baseline_select(int(kind), kept_idx.shape[0], int(n_cand), C.byref(p), int(seed), int(turn),
+                                       _ptr(kept_idx), _row_stride(kept_idx), C.byref(n_keep), _stream(stream)),
+           "sirllm_baseline_select")
+    return n_keep.value
 
 
 def _row_stride(t: torch.Tensor) -> int:

@@ -137,6 +137,7 @@ SelectArgs make_select_args(const float* scores, int64_t scores_stride, int32_t 
     a.n_sink = p->n_sink; a.n_topk = p->n_topk; a.n_recent = p->n_recent; a.decay = p->decay;
     a.kept_idx = kept_idx; a.idx_stride = idx_stride;
     a.scores_out = scores_out; a.out_stride = out_stride;
+    a.seed_lo = a.seed_hi = a.turn_lo = a.turn_hi = 0;
     return a;
 }
 
@@ -221,6 +222,37 @@ int sirllm_decay_select(const float* scores, int64_t scores_stride, int32_t n_st
                                           idx_stride, scores_out, out_stride);
     if ((int64_t)n_cand <= budget_of(policy)) return hip_status(launch_keep_all(a, (hipStream_t)hip_stream));
     return hip_status(launch_select(a, (hipStream_t)hip_stream));
+}
+
+int sirllm_baseline_select(sirllm_baseline kind, int32_t n_streams, int32_t n_cand, const sirllm_policy* policy,
+                           uint64_t seed, uint64_t turn, int32_t* kept_idx, int64_t idx_stride,
+                           int32_t* n_keep_out, void* hip_stream)
+{
+    if (kind != SIRLLM_BASELINE_STREAM && kind != SIRLLM_BASELINE_INTERVAL && kind != SIRLLM_BASELINE_RANDOM)
+        return SIRLLM_ERR_UNSUPPORTED;
+    if (!policy || policy->n_sink < 0 || policy->n_topk < 0 || policy->n_recent < 0) return SIRLLM_ERR_INVALID_ARG;
+    if (n_streams < 0 || n_cand < 0) return SIRLLM_ERR_INVALID_ARG;
+    if (n_cand > SIRLLM_MAX_CAND) return SIRLLM_ERR_UNSUPPORTED;
+    sirllm_policy p = *policy;
+    p.decay = 1.0f;
+    if (kind == SIRLLM_BASELINE_STREAM) p.n_topk = 0;
+    const int64_t budget = budget_of(&p);
+    const int32_t n_keep = (int32_t)((int64_t)n_cand < budget ? n_cand : budget);
+    if (n_keep_out) *n_keep_out = n_keep;
+    if (n_streams == 0 || n_cand == 0) return SIRLLM_OK;
+    if (!kept_idx || idx_stride < n_keep) return SIRLLM_ERR_INVALID_ARG;
+    SelectArgs a = make_select_args(nullptr, 0, n_streams, n_cand, 0, &p, kept_idx, idx_stride, nullptr, 0);
+    a.seed_lo = (uint32_t)seed; a.seed_hi = (uint32_t)(seed >> 32);
+    a.turn_lo = (uint32_t)turn; a.turn_hi = (uint32_t)(turn >> 32);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if ((int64_t)n_cand <= budget) return hip_status(launch_baseline_comb(a, 0, stream));
+    if (kind == SIRLLM_BASELINE_RANDOM && p.n_topk > 0) return hip_status(launch_baseline_random(a, stream));
+    int interval = 1;
+    if (p.n_topk > 0) {
+        interval = (n_cand - p.n_sink - p.n_recent) / p.n_topk;
+        if (interval < 1) interval = 1;
+    }
+    return hip_status(launch_baseline_comb(a, interval, stream));
 }
 
 int sirllm_compact_kv(const void* k_src, const void* v_src, const sirllm_kv_layout* src, int32_t n_src,

@@ -42,6 +42,7 @@ struct SelectArgs {
     int64_t idx_stride;
     float* scores_out;
     int64_t out_stride;
+    uint32_t seed_lo, seed_hi, turn_lo, turn_hi;   // RandomLLM baseline only
 };
 // n_cand > budget: decay + radix select + index build, one workgroup per stream.
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
@@ -62,6 +63,11 @@ struct GatherArgs {
 };
 // Copies destination rows [row_begin, row_end) of every plane.
 hipError_t launch_gather(const GatherArgs& a, int row_begin, int row_end, hipStream_t stream);
+
+// ---- baseline.hip -----------------------------------------------------------------------
+// kept_idx of the score-free policies; n_topk of `a` is the number of middle slots to keep.
+hipError_t launch_baseline_comb(const SelectArgs& a, int interval, hipStream_t stream);   // stream / interval / keep-all
+hipError_t launch_baseline_random(const SelectArgs& a, hipStream_t stream);               // needs n_cand > budget
 
 // ---- fused.hip --------------------------------------------------------------------------
 // Scoring and selection in one launch; only valid when score_select_fusable() says so (the new

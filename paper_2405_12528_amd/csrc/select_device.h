@@ -41,10 +41,28 @@ struct SelectSmem {
     uint32_t sel_above;
 };
 
+// Philox4x32-10 (Salmon et al., SC'11), word 0 of the output block.
+__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                        uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return c0;
+}
+
+// RANDOM_KEYS: the keys are not scores but draws of a counter-based generator (the RandomLLM
+// baseline, paper Sec. 4.1); no score is read or written.
 // NEW_ELSEWHERE: the slots [n_held, n_cand) all lie in the recent window and their scores are
 // being written by other workgroups at the same time; this workgroup then neither reads them nor
 // writes their scores_out entries (only their kept_idx entries).
-template <int BLOCK, int KPT, bool NEW_ELSEWHERE>
+template <int BLOCK, int KPT, bool NEW_ELSEWHERE, bool RANDOM_KEYS = false>
 __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, SelectSmem<BLOCK>& sm)
 {
     static_assert(BLOCK >= 256 && BLOCK % kWave == 0, "histogram scan uses the first 256 threads");
@@ -67,12 +85,20 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, S
     for (int q = 0; q < KPT; ++q) {
         const int i = i0 + q;
         float e = 0.0f;
-        if (i < n_read) {
+        if constexpr (RANDOM_KEYS) {
+            if (i >= mid_lo && i < mid_hi)
+                e = __uint_as_float(philox4x32_10_word0((uint32_t)i, (uint32_t)stream, a.turn_lo, a.turn_hi,
+                                                        a.seed_lo, a.seed_hi));
+        } else if (i < n_read) {
             e = E[i];
             if (i < a.n_held) e = __fmul_rn(e, a.decay);
         }
         val[q] = e;
     }
+    auto key_of = [](float v) -> uint32_t {
+        if constexpr (RANDOM_KEYS) return __float_as_uint(v);
+        else return order_key(v);
+    };
 
     // ---- radix select of the n_topk-th largest key among the middle slots -------------------
     uint32_t prefix = 0xffffffffu, mask = 0xffffffffu;   // n_topk == 0: nothing is greater, quota 0
@@ -86,7 +112,7 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, S
             for (int q = 0; q < KPT; ++q) {
                 const int i = i0 + q;
                 if (i >= mid_lo && i < mid_hi) {
-                    const uint32_t key = order_key(val[q]);
+                    const uint32_t key = key_of(val[q]);
                     if ((key & mask) == prefix) atomicAdd(&sm.hist[(key >> shift) & 255u], 1u);
                 }
             }
@@ -122,7 +148,7 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, S
     for (int q = 0; q < KPT; ++q) {
         const int i = i0 + q;
         if (i >= mid_lo && i < mid_hi) {
-            const uint32_t key = order_key(val[q]);
+            const uint32_t key = key_of(val[q]);
             mine += (key > tau) ? 1u : 0u;
             mine += (key == tau) ? 0x10000u : 0u;
         }
@@ -150,7 +176,7 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, S
         } else if (i >= mid_hi) {
             pos = n_keep - (n_cand - i);                        // Id_recent
         } else {
-            const uint32_t key = order_key(val[q]);
+            const uint32_t key = key_of(val[q]);
             if (key > tau) {
                 pos = mid_lo + (int)(g + (eq < quota ? eq : quota));
                 ++g;
@@ -161,7 +187,9 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, S
         }
         if (pos >= 0 && pos < n_keep) {
             idx[pos] = i;
-            if (i < n_read) Eo[pos] = val[q];
+            if constexpr (!RANDOM_KEYS) {
+                if (i < n_read) Eo[pos] = val[q];
+            }
         }
     }
 }

@@ -139,6 +139,26 @@ def test_step_argument_errors(b):
     assert call(n_streams=0, logits=None, tok=None) == b.SIRLLM_OK
 
 
+def test_baseline_select_argument_errors(b):
+    L = b.raw()
+    p = b.sirllm_policy(4, 20, 8, 0.0)
+    n_keep = C.c_int32(-5)
+    def call(kind=1, n_streams=1, n_cand=100, pol=p, idx=FAKE, istr=32, out=n_keep):
+        return L.sirllm_baseline_select(kind, n_streams, n_cand, C.byref(pol) if pol else None, 1, 2, idx, istr,
+                                        C.byref(out) if out is not None else None, None)
+    assert call(kind=3) == b.SIRLLM_ERR_UNSUPPORTED
+    assert call(pol=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(pol=b.sirllm_policy(4, -1, 8, 0.0)) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(n_cand=-1) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(n_cand=40000) == b.SIRLLM_ERR_UNSUPPORTED
+    assert call(idx=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(istr=31) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(n_streams=0) == b.SIRLLM_OK and n_keep.value == 32       # the kept count is host arithmetic
+    assert call(kind=0, n_streams=0) == b.SIRLLM_OK and n_keep.value == 12
+    assert call(n_streams=0, n_cand=10) == b.SIRLLM_OK and n_keep.value == 10
+    assert call(n_streams=0, out=None) == b.SIRLLM_OK
+
+
 def test_binding_refuses_host_tensors(b):
     import torch
     z = torch.zeros(2, 8)

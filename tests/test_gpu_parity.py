@@ -367,3 +367,44 @@ def test_step_small_shapes(b, ref, n_streams, n_held, n_new, pol):
     w2 = dataclasses.replace(w, vocab=777)
     g = gpu_step(b, w2, z, tok, held, k_c, v_c, pol=pol)
     check_step_against_oracle(b, ref, w2, z, tok, held, k_c, v_c, g, pol=pol)
+
+
+# ------------------------------------------------------------------------- baseline policies
+BASELINE_CASES = [
+    # n_streams, n_cand, n_sink, k, n_recent
+    (2, 50, 4, 10, 6), (1, 26, 4, 5, 2), (1, 29, 4, 5, 2), (1, 20, 2, 8, 3), (3, 1078, 4, 1020, 0),
+    (2, 600, 4, 100, 16), (1, 4096, 4, 1532, 512), (2, 8192, 4, 3068, 1024), (1, 32768, 4, 16000, 68),
+    (2, 30, 4, 20, 8), (1, 40, 0, 7, 0), (1, 40, 4, 0, 6), (1, 5000, 0, 1, 0), (1, 5000, 3, 4996, 0),
+]
+
+
+@pytest.mark.parametrize("kind", [0, 1, 2])
+@pytest.mark.parametrize("case", BASELINE_CASES, ids=[str(c) for c in BASELINE_CASES])
+def test_baseline_select_matches_oracle(b, ref, kind, case):
+    n_streams, n_cand, n_sink, k, n_recent = case
+    pol = b.Policy(n_sink, k, n_recent, 0.0)
+    seed, turn = (7 << 32) | 12345, (3 << 32) | 99
+    want = ref.baseline_select(kind, n_streams, n_cand, ref.Policy(*pol), seed=seed, turn=turn)
+    n_keep = want.shape[1]
+    idx = torch.full((n_streams, n_keep + 3), -7, dtype=torch.int32, device=DEV)
+    got_keep = b.sirllm_baseline_select(kind, n_cand, pol, idx, seed=seed, turn=turn)
+    torch.cuda.synchronize()
+    assert got_keep == n_keep
+    got = to_np(idx)
+    np.testing.assert_array_equal(got[:, :n_keep], want)
+    assert (got[:, n_keep:] == -7).all()
+
+
+def test_baseline_policies_feed_the_same_compaction(b, ref):
+    # a baseline's kept list goes through sirllm_compact_kv like the entropy policy's
+    S, L, H, P, D = 2, 2, 2, 200, 32
+    k = synth.tagged_kv(S, L, H, P, D, 0).to(torch.float32).to(DEV)
+    v = synth.tagged_kv(S, L, H, P, D, 1).to(torch.float32).to(DEV)
+    pol = b.Policy(4, 60, 16, 0.0)
+    for kind in (0, 1, 2):
+        idx = torch.zeros((S, 80), dtype=torch.int32, device=DEV)
+        n_keep = b.sirllm_baseline_select(kind, P, pol, idx, seed=5, turn=kind)
+        torch.cuda.synchronize()
+        kept = to_np(idx)[:, :n_keep]
+        np.testing.assert_array_equal(kept, ref.baseline_select(kind, S, P, ref.Policy(*pol), seed=5, turn=kind))
+        run_compact(b, ref, k, v, kept)
