@@ -408,3 +408,49 @@ def test_baseline_policies_feed_the_same_compaction(b, ref):
         kept = to_np(idx)[:, :n_keep]
         np.testing.assert_array_equal(kept, ref.baseline_select(kind, S, P, ref.Policy(*pol), seed=5, turn=kind))
         run_compact(b, ref, k, v, kept)
+
+
+# --------------------------------------------------------------------- randomised whole steps
+def test_step_random_shapes(b, ref):
+    """Sixty seeded random shapes through sirllm_step: stream counts, cache fill, policy sizes, vocabulary
+    lengths, row padding, logits dtype, K/V element size and head_dim all vary together."""
+    import dataclasses
+    rng = np.random.default_rng(2024)
+    base = synth.WORKLOADS["tiny"]
+    for case in range(60):
+        S = int(rng.integers(1, 4))
+        n_held = int(rng.integers(0, 300))
+        n_new = int(rng.integers(0, 90))
+        if n_held + n_new == 0:
+            n_new = 1
+        n_sink = int(rng.integers(0, 6))
+        k = int(rng.integers(0, 200))
+        n_recent = int(rng.integers(0, 100))
+        V = int(rng.integers(1, 3000))
+        ld = V + int(rng.integers(0, 9))
+        dt = torch.bfloat16 if rng.integers(2) else torch.float32
+        kv_dt = [torch.float32, torch.bfloat16, torch.uint8][int(rng.integers(3))]
+        D = int(rng.choice([8, 16, 24, 64, 128]))
+        L, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        pol = b.Policy(n_sink, k, n_recent, float(rng.choice([1.0, 0.9, 0.5])))
+        g0 = torch.Generator(device=DEV).manual_seed(case)
+        z = (torch.randn((S * n_new, ld), generator=g0, device=DEV) * 3).to(dt)
+        if ld > V and n_new:
+            z[:, V:] = 1.0e4
+        tok = torch.randint(0, V, (S * n_new,), generator=g0, device=DEV, dtype=torch.int32)
+        levels = int(rng.choice([4, 1000000]))
+        held = (torch.randint(0, levels, (S, n_held), generator=g0, device=DEV) / 7.0).to(torch.float32)
+        n_cand = n_held + n_new
+        if kv_dt == torch.uint8:
+            k_c = torch.randint(0, 255, (S, L, H, n_cand, D), generator=g0, device=DEV, dtype=torch.uint8)
+            v_c = torch.randint(0, 255, (S, L, H, n_cand, D), generator=g0, device=DEV, dtype=torch.uint8)
+        else:
+            k_c = torch.randn((S, L, H, n_cand, D), generator=g0, device=DEV).to(kv_dt)
+            v_c = torch.randn((S, L, H, n_cand, D), generator=g0, device=DEV).to(kv_dt)
+        w2 = dataclasses.replace(base, vocab=V)
+        print(f"case {case}: S={S} held={n_held} new={n_new} pol={tuple(pol)} V={V} ld={ld} {dt} kv={kv_dt} D={D}", flush=True)
+        try:
+            g = gpu_step(b, w2, z, tok, held, k_c, v_c, pol=pol)
+            check_step_against_oracle(b, ref, w2, z, tok, held, k_c, v_c, g, pol=pol)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: {e}") from e
