@@ -147,6 +147,20 @@ int sirllm_compact_kv(const void* k_src, const void* v_src, const sirllm_kv_layo
                       int32_t n_streams, int32_t n_keep, void* hip_stream);
 
 /*
+ * The same compaction, written back into the buffer it reads (Sec. 3.3): after the call slots
+ * [0, n_keep) of every plane hold the rows kept_idx[0 : n_keep), slots >= n_keep keep whatever
+ * they held.  Needs kept_idx strictly ascending per stream with entries in [0, n_src) -- which is
+ * what sirllm_decay_select and sirllm_baseline_select produce -- because rows then only move
+ * towards the front; for any other list the result is unspecified (but nothing outside the
+ * n_src slots of a plane is touched, and entries outside [0, n_src) give zero rows).  Rows that
+ * already sit in their place are not touched at all.  Halves the K/V memory of the out-of-place
+ * call at the same traffic per moved row.  v may be NULL.  Limits as for sirllm_compact_kv.
+ */
+int sirllm_compact_kv_inplace(void* k, void* v, const sirllm_kv_layout* layout, int32_t n_src,
+                              const int32_t* kept_idx, int64_t idx_stride,
+                              int32_t n_streams, int32_t n_keep, void* hip_stream);
+
+/*
  * One whole retention step (Alg. 1 with the loop rotated so that a call is
  * score -> decay held -> select -> compact; multiplying every candidate by the same
  * eta > 0 cannot change a comparison, so the kept sets equal those of the printed order).

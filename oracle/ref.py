@@ -42,6 +42,8 @@ def load(path):
     L.sirllm_ref_step.argtypes = [vp, C.c_int, i32, i64, vp, vp, i64, i32, i32, i32, C.POINTER(_CPolicy),
                                   vp, vp, C.POINTER(_CLayout), vp, vp, C.POINTER(_CLayout),
                                   vp, i64, vp, i64]
+    L.sirllm_ref_compact_kv_inplace.argtypes = [vp, vp, C.POINTER(_CLayout), i32, vp, i64, i32, i32]
+    L.sirllm_ref_compact_kv_inplace.restype = C.c_int
     L.sirllm_ref_baseline_select.argtypes = [C.c_int, i32, i32, C.POINTER(_CPolicy), C.c_uint64, C.c_uint64, vp, i64,
                                              C.POINTER(i32)]
     L.sirllm_ref_baseline_select.restype = C.c_int
@@ -170,6 +172,19 @@ def compact_kv(k_src: np.ndarray, v_src: np.ndarray | None, kept_idx: np.ndarray
                                        C.byref(ld), _ptr(kept_idx), max(n_keep, 1) if n_keep else 1,
                                        n_streams, n_keep), "compact_kv")
     return k_dst, v_dst
+
+
+def compact_kv_inplace(k: np.ndarray, v: np.ndarray | None, kept_idx: np.ndarray, n_src: int | None = None):
+    """In-place variant: modifies k (and v); slots >= n_keep keep their content."""
+    kept_idx = np.ascontiguousarray(kept_idx, dtype=np.int32)
+    n_streams, n_keep = kept_idx.shape
+    n_src = k.shape[3] if n_src is None else int(n_src)
+    lay = _layout_of(k)
+    if v is not None:
+        assert v.shape == k.shape and v.strides == k.strides and v.dtype == k.dtype
+    _check(lib().sirllm_ref_compact_kv_inplace(_ptr(k), _ptr(v), C.byref(lay), n_src, _ptr(kept_idx),
+                                               max(n_keep, 1), n_streams, n_keep), "compact_kv_inplace")
+    return k, v
 
 
 def step(logits: np.ndarray, token_ids: np.ndarray, vocab: int, held_scores: np.ndarray, n_new: int, policy,

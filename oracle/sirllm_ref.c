@@ -346,6 +346,42 @@ int sirllm_ref_compact_kv(const void* k_src, const void* v_src, const sirllm_ref
     return 0;
 }
 
+/* In place: every plane is first set aside whole, then its kept rows are copied back to the front. */
+static int gather_one_inplace(char* buf, const sirllm_ref_kv_layout* S, int32_t n_src,
+                              const int32_t* kept_idx, int64_t idx_stride, int32_t n_streams, int32_t n_keep)
+{
+    const size_t row_bytes = (size_t)S->head_dim * (size_t)S->elem_bytes;
+    char* old = (char*)malloc(row_bytes * (size_t)(n_src > 0 ? n_src : 1));
+    if (!old) return -1;
+    for (int64_t s = 0; s < n_streams; ++s)
+        for (int64_t l = 0; l < S->n_layers; ++l)
+            for (int64_t h = 0; h < S->n_kv_heads; ++h) {
+                char* p = buf + (size_t)S->elem_bytes * (size_t)(s * S->stride_stream + l * S->stride_layer + h * S->stride_head);
+                for (int32_t i = 0; i < n_src; ++i)
+                    memcpy(old + row_bytes * (size_t)i, p + (size_t)S->elem_bytes * (size_t)((int64_t)i * S->stride_pos), row_bytes);
+                const int32_t* idx = kept_idx + s * idx_stride;
+                for (int32_t j = 0; j < n_keep; ++j) {
+                    char* drow = p + (size_t)S->elem_bytes * (size_t)((int64_t)j * S->stride_pos);
+                    if (idx[j] < 0 || idx[j] >= n_src) memset(drow, 0, row_bytes);
+                    else memcpy(drow, old + row_bytes * (size_t)idx[j], row_bytes);
+                }
+            }
+    free(old);
+    return 0;
+}
+
+int sirllm_ref_compact_kv_inplace(void* k, void* v, const sirllm_ref_kv_layout* layout, int32_t n_src,
+                                  const int32_t* kept_idx, int64_t idx_stride,
+                                  int32_t n_streams, int32_t n_keep)
+{
+    if (!layout_ok(layout) || n_streams < 0 || n_keep < 0 || n_src < 0 || n_keep > n_src) return -1;
+    if (n_streams == 0 || n_keep == 0) return 0;
+    if (!k || !kept_idx) return -1;
+    int rc = gather_one_inplace((char*)k, layout, n_src, kept_idx, idx_stride, n_streams, n_keep);
+    if (rc == 0 && v) rc = gather_one_inplace((char*)v, layout, n_src, kept_idx, idx_stride, n_streams, n_keep);
+    return rc;
+}
+
 /* ------------------------------------------------------------------------------------ */
 /* Algorithm 1, one turn                                                                 */
 /* ------------------------------------------------------------------------------------ */

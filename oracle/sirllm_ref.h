@@ -50,6 +50,12 @@ int sirllm_ref_compact_kv(const void* k_src, const void* v_src, const sirllm_ref
                           const int32_t* kept_idx, int64_t idx_stride,
                           int32_t n_streams, int32_t n_keep);
 
+/* The same, written back into the buffer it reads: slots [0, n_keep) become the kept rows, slots
+ * >= n_keep keep their content. */
+int sirllm_ref_compact_kv_inplace(void* k, void* v, const sirllm_ref_kv_layout* layout, int32_t n_src,
+                                  const int32_t* kept_idx, int64_t idx_stride,
+                                  int32_t n_streams, int32_t n_keep);
+
 /* Algorithm 1, one turn, in the order score -> append -> decay held -> select -> compact. */
 int sirllm_ref_step(const void* logits, int dtype, int32_t vocab, int64_t ld, const int32_t* token_ids,
                     float* scores, int64_t scores_stride,

@@ -43,7 +43,7 @@ class sirllm_kv_layout(C.Structure):
 SIRLLM_BASELINE_STREAM, SIRLLM_BASELINE_INTERVAL, SIRLLM_BASELINE_RANDOM = 0, 1, 2
 
 EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step", "sirllm_baseline_select",
-           "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
+           "sirllm_compact_kv_inplace", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
 
 _vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
 _PP, _LP = C.POINTER(sirllm_policy), C.POINTER(sirllm_kv_layout)
@@ -55,6 +55,8 @@ _lib.sirllm_step.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _i3
 _lib.sirllm_baseline_select.argtypes = [C.c_int, _i32, _i32, _PP, C.c_uint64, C.c_uint64, _vp, _i64,
                                         C.POINTER(C.c_int32), _vp]
 _lib.sirllm_baseline_select.restype = C.c_int
+_lib.sirllm_compact_kv_inplace.argtypes = [_vp, _vp, _LP, _i32, _vp, _i64, _i32, _i32, _vp]
+_lib.sirllm_compact_kv_inplace.restype = C.c_int
 for _n in ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step"):
     getattr(_lib, _n).restype = C.c_int
 _lib.sirllm_workspace_bytes.argtypes = [_i32, _i32, _i64, _i32]
@@ -211,6 +213,24 @@ def sirllm_compact_kv(k_src: torch.Tensor, v_src, k_dst: torch.Tensor, v_dst, ke
                                   C.byref(ld), _ptr(kept_idx), _row_stride(kept_idx), n_streams, int(n_keep),
                                   _stream(stream)), "sirllm_compact_kv")
     return k_dst, v_dst
+
+
+def sirllm_compact_kv_inplace(k: torch.Tensor, v, kept_idx: torch.Tensor, n_keep: int, n_src: int | None = None,
+                              stream=None):
+    """k[s, l, h, j, :] = k[s, l, h, kept_idx[s, j], :] for j < n_keep, in place (kept_idx strictly ascending)."""
+    _on_device(k, v, kept_idx)
+    if kept_idx.dim() != 2 or kept_idx.dtype != torch.int32 or (kept_idx.shape[1] > 1 and kept_idx.stride(1) != 1):
+        raise ValueError("kept_idx must be [n_streams, >= n_keep] int32 with contiguous rows")
+    lay = kv_layout(k)
+    if v is not None and kv_layout_tuple(v) != kv_layout_tuple(k):
+        raise ValueError("K and V must share one layout")
+    n_src = k.shape[3] if n_src is None else int(n_src)
+    if k.shape[3] < n_src or kept_idx.shape[0] != k.shape[0]:
+        raise ValueError("cache has fewer than n_src slots, or stream counts differ")
+    _check(_lib.sirllm_compact_kv_inplace(_ptr(k), _ptr(v), C.byref(lay), n_src, _ptr(kept_idx),
+                                          _row_stride(kept_idx), k.shape[0], int(n_keep), _stream(stream)),
+           "sirllm_compact_kv_inplace")
+    return k, v
 
 
 def kv_layout_tuple(t):

@@ -267,6 +267,23 @@ int sirllm_compact_kv(const void* k_src, const void* v_src, const sirllm_kv_layo
     return hip_status(launch_gather(g, 0, n_keep, (hipStream_t)hip_stream));
 }
 
+int sirllm_compact_kv_inplace(void* k, void* v, const sirllm_kv_layout* layout, int32_t n_src,
+                              const int32_t* kept_idx, int64_t idx_stride, int32_t n_streams, int32_t n_keep,
+                              void* hip_stream)
+{
+    if (!layout_ok(layout)) return SIRLLM_ERR_INVALID_ARG;
+    if (n_streams < 0 || n_keep < 0 || n_src < 0 || n_keep > n_src) return SIRLLM_ERR_INVALID_ARG;
+    if (n_streams == 0 || n_keep == 0) return SIRLLM_OK;
+    if (!k || !kept_idx || idx_stride < n_keep) return SIRLLM_ERR_INVALID_ARG;
+    if ((int64_t)layout->head_dim * layout->elem_bytes * n_keep > 0x7fff0000LL) return SIRLLM_ERR_UNSUPPORTED;
+    const uintptr_t em = (uintptr_t)layout->elem_bytes - 1;
+    if (((uintptr_t)k & em) || ((uintptr_t)v & em)) return SIRLLM_ERR_INVALID_ARG;
+    if (ranges_overlap(k, extent_bytes(layout, n_streams, n_src), v, extent_bytes(layout, n_streams, n_src)))
+        return SIRLLM_ERR_INVALID_ARG;
+    const GatherArgs g = make_gather_args(k, v, layout, n_src, k, v, layout, kept_idx, idx_stride, n_streams, n_keep);
+    return hip_status(launch_gather_inplace(g, (hipStream_t)hip_stream));
+}
+
 int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
                 float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held, int32_t n_new,
                 const sirllm_policy* policy, const void* k_src, const void* v_src, const sirllm_kv_layout* src,

@@ -64,6 +64,10 @@ struct GatherArgs {
 // Copies destination rows [row_begin, row_end) of every plane.
 hipError_t launch_gather(const GatherArgs& a, int row_begin, int row_end, hipStream_t stream);
 
+// ---- gather_inplace.hip -----------------------------------------------------------------
+// src and dst of `a` are the same buffers and layouts; kept_idx must be strictly ascending.
+hipError_t launch_gather_inplace(const GatherArgs& a, hipStream_t stream);
+
 // ---- baseline.hip -----------------------------------------------------------------------
 // kept_idx of the score-free policies; n_topk of `a` is the number of middle slots to keep.
 hipError_t launch_baseline_comb(const SelectArgs& a, int interval, hipStream_t stream);   // stream / interval / keep-all

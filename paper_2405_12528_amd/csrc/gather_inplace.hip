@@ -1,0 +1,132 @@
+// In-place KV compaction (paper Sec. 3.3: KV_cache <- KV_cache[Id], written back into the same
+// buffer).  The kept list is strictly ascending, so row j always comes from a slot kept_idx[j] >= j:
+// rows only move towards the front.  One workgroup owns one plane (stream, layer, K|V, head) and
+// walks it front to back in chunks: every lane loads its vectors of the chunk, the workgroup waits
+// until all of those loads have landed, then stores.  A chunk writes rows [c0, c1) and reads rows
+// >= c0; the next chunk reads rows >= c1 only, so nothing a chunk writes is ever read again and
+// no ordering between workgroups is needed.  Rows that stay where they are (the sinks, any
+// leading run of kept slots) are neither read nor written.  Same HBM traffic per moved row as the
+// out-of-place gather, half the K/V memory.
+#include "common.h"
+#include "gather_device.h"
+#include "tuning.h"
+
+namespace sirllm {
+namespace {
+
+using gather_dev::GatherLaunch;
+
+template <typename VecT, int BLOCK, int UNROLL, bool NT, bool POW2, bool OFF64>
+__global__ __launch_bounds__(BLOCK) void gather_inplace_kernel(GatherLaunch g)
+{
+    const GatherArgs& a = g.a;
+    using off_t = typename std::conditional<OFF64, int64_t, uint32_t>::type;
+    const int plane = g.plane0 + (int)blockIdx.x;
+    const int stream = g.stream0 + (int)blockIdx.y;
+    const int tensor = plane >= g.lh ? 1 : 0;
+    const int ph = plane - tensor * g.lh;
+    int64_t so;
+    if (g.uniform) {
+        so = ph * a.s_head;
+    } else {
+        const int l = ph / a.n_heads, h = ph - l * a.n_heads;
+        so = l * a.s_layer + h * a.s_head;
+    }
+    char* base = a.dst[tensor] + stream * a.s_stream + so;
+    const int32_t* idx = a.kept_idx + stream * a.idx_stride;
+
+    const int n_items = (g.row_end - g.row_begin) * g.vpr;
+    for (int c0 = 0; c0 < n_items; c0 += BLOCK * UNROLL) {
+        VecT v[UNROLL];
+        off_t doff[UNROLL];
+        bool moved[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int w = c0 + u * BLOCK + (int)threadIdx.x;
+            moved[u] = false;
+            v[u] = VecT{};
+            doff[u] = 0;
+            if (w < n_items) {
+                int j, c;
+                if constexpr (POW2) { j = w >> g.shift; c = w & (g.vpr - 1); }
+                else                { j = w / g.vpr;    c = w - j * g.vpr; }
+                j += g.row_begin;
+                const uint32_t i = (uint32_t)idx[j];
+                moved[u] = i != (uint32_t)j;
+                doff[u] = (off_t)j * (off_t)a.s_pos + (off_t)(c * (int)sizeof(VecT));
+                if (moved[u] && i < (uint32_t)a.n_src)       // an index with no source slot leaves a zero row
+                    v[u] = gather_dev::ld<VecT, NT>(base + ((off_t)i * (off_t)a.s_pos + (off_t)(c * (int)sizeof(VecT))));
+            }
+        }
+        // every load of this chunk must have returned before any lane overwrites a row of it
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            if (moved[u]) gather_dev::st<VecT, NT>(base + doff[u], v[u]);
+    }
+}
+
+template <typename VecT, int BLOCK, int UNROLL>
+void launch_shape(const GatherLaunch& g, dim3 grid, bool pow2, bool off64, hipStream_t stream)
+{
+    const dim3 block(BLOCK);
+    if (pow2) {
+        if (off64) hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, true, true>), grid, block, 0, stream, g);
+        else       hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, true, false>), grid, block, 0, stream, g);
+    } else {
+        if (off64) hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, false, true>), grid, block, 0, stream, g);
+        else       hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, false, false>), grid, block, 0, stream, g);
+    }
+}
+
+template <typename VecT>
+hipError_t launch_vec(const GatherArgs& a, hipStream_t stream)
+{
+    GatherLaunch g;
+    bool pow2, off64;
+    if (!gather_dev::fill_launch<VecT>(g, a, 0, a.n_keep, &pow2, &off64)) return hipErrorInvalidValue;
+    const int block = tuning::get("SIRLLM_INPLACE_BLOCK", 512);
+    const int unroll = tuning::get("SIRLLM_INPLACE_UNROLL", 4);
+    const int planes = a.n_tensors * g.lh;
+    constexpr int kMaxDim = 65535;
+    for (int s0 = 0; s0 < a.n_streams; s0 += kMaxDim) {
+        g.stream0 = s0;
+        g.plane0 = 0;
+        const dim3 grid((unsigned)planes, (unsigned)min(kMaxDim, a.n_streams - s0));
+        if (block == 1024) {
+            if (unroll == 2)      launch_shape<VecT, 1024, 2>(g, grid, pow2, off64, stream);
+            else if (unroll == 8) launch_shape<VecT, 1024, 8>(g, grid, pow2, off64, stream);
+            else                  launch_shape<VecT, 1024, 4>(g, grid, pow2, off64, stream);
+        } else if (block == 256) {
+            if (unroll == 2)      launch_shape<VecT, 256, 2>(g, grid, pow2, off64, stream);
+            else if (unroll == 8) launch_shape<VecT, 256, 8>(g, grid, pow2, off64, stream);
+            else                  launch_shape<VecT, 256, 4>(g, grid, pow2, off64, stream);
+        } else {
+            if (unroll == 2)      launch_shape<VecT, 512, 2>(g, grid, pow2, off64, stream);
+            else if (unroll == 8) launch_shape<VecT, 512, 8>(g, grid, pow2, off64, stream);
+            else                  launch_shape<VecT, 512, 4>(g, grid, pow2, off64, stream);
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace
+
+// a.src and a.dst name the same buffers; the s_* strides are used for both sides.
+hipError_t launch_gather_inplace(const GatherArgs& a, hipStream_t stream)
+{
+    if (a.n_keep <= 0 || a.n_streams <= 0 || a.row_bytes <= 0 || a.n_layers <= 0 || a.n_heads <= 0)
+        return hipSuccess;
+    switch (gather_dev::vector_bytes(a)) {
+    case 16: return launch_vec<u32x4>(a, stream);
+    case 8:  return launch_vec<u32x2>(a, stream);
+    case 4:  return launch_vec<uint32_t>(a, stream);
+    case 2:  return launch_vec<uint16_t>(a, stream);
+    default: return launch_vec<uint8_t>(a, stream);
+    }
+}
+
+}  // namespace sirllm

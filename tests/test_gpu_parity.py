@@ -454,3 +454,52 @@ def test_step_random_shapes(b, ref):
             check_step_against_oracle(b, ref, w2, z, tok, held, k_c, v_c, g, pol=pol)
         except AssertionError as e:
             raise AssertionError(f"case {case}: {e}") from e
+
+
+# ------------------------------------------------------------------------ in-place compaction
+@pytest.mark.parametrize("S,L,H,P,D,dtype,frac", [
+    (1, 2, 2, 96, 16, torch.float32, 0.33),
+    (2, 3, 2, 300, 128, torch.bfloat16, 0.6),
+    (1, 1, 2, 40, 100, torch.bfloat16, 0.5),      # 8-byte vectors
+    (1, 2, 1, 33, 5, torch.int16, 0.7),           # 2-byte vectors
+    (1, 1, 1, 33, 7, torch.uint8, 0.5),
+    (2, 2, 2, 5000, 64, torch.float32, 0.5),      # many chunks per plane
+    (1, 2, 2, 4096, 128, torch.bfloat16, 0.97),   # almost everything kept: short moves
+    (1, 2, 2, 1078, 128, torch.bfloat16, 0.95),
+])
+def test_compact_inplace_matches_oracle(b, ref, S, L, H, P, D, dtype, frac):
+    rng = np.random.default_rng(P * 7 + D)
+    mod = 251 if dtype == torch.uint8 else (32749 if dtype in (torch.int16, torch.bfloat16) else 1 << 31)
+    k = (synth.tagged_kv(S, L, H, P, D, 0) % mod).to(dtype).to(DEV)
+    v = (synth.tagged_kv(S, L, H, P, D, 1) % mod).to(dtype).to(DEV)
+    n_keep = max(1, int(P * frac))
+    kept = np.stack([np.sort(rng.choice(P, n_keep, replace=False)) for _ in range(S)]).astype(np.int32)
+    kept[0, :min(4, n_keep)] = np.arange(min(4, n_keep))       # sinks stay put
+    kept = np.sort(kept, axis=1)
+    if len(np.unique(kept[0])) != n_keep:
+        kept[0] = np.sort(rng.choice(P, n_keep, replace=False))
+    hk, hv = to_np(k).copy(), to_np(v).copy()
+    ref.compact_kv_inplace(hk, hv, kept)
+    b.sirllm_compact_kv_inplace(k, v, torch.from_numpy(kept).to(DEV), n_keep)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(k), hk), "K differs (kept rows or the untouched tail)"
+    assert np.array_equal(to_np(v), hv), "V differs"
+    # shifts by one: every row is the source of its left neighbour
+    k2 = (synth.tagged_kv(S, L, H, P, D, 0) % mod).to(dtype).to(DEV)
+    chain = np.arange(1, P, dtype=np.int32)[None, :].repeat(S, 0)
+    h2 = to_np(k2).copy()
+    ref.compact_kv_inplace(h2, None, chain)
+    b.sirllm_compact_kv_inplace(k2, None, torch.from_numpy(chain).to(DEV), P - 1)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(k2), h2)
+
+
+def test_compact_inplace_strided_view_and_bad_indices(b, ref):
+    big = synth.tagged_kv(2, 2, 3, 40, 24, 0).to(torch.float32).to(DEV)
+    host = to_np(big).copy()
+    view = big[:, :, :2, :30, :16]
+    kept = np.array([[0, 5, 29, 30, 31, 35], [1, 2, 3, 4, 100000, 100001]], dtype=np.int32)   # last ones: no such slot
+    ref.compact_kv_inplace(host[:, :, :2, :30, :16], None, kept, n_src=30)
+    b.sirllm_compact_kv_inplace(view, None, torch.from_numpy(kept).to(DEV), 6, n_src=30)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(big), host)                    # padding heads / slots / channels untouched too

@@ -120,3 +120,26 @@ def test_tiny_dialogue_four_turns(ref):
             src = to_np(synth.make_kv(w, n_pos=w.n_new, turn=int(t0), which="k"))
             np.testing.assert_array_equal(K[0, :, :, j, :], src[0, :, :, i0, :])
     assert E.shape == (1, w.budget)
+
+
+def test_inplace_gather_equals_out_of_place_and_leaves_the_tail(ref):
+    rng = np.random.default_rng(8)
+    S, L, H, Pn, D = 2, 2, 3, 40, 8
+    k = to_np(synth.tagged_kv(S, L, H, Pn, D, which=0))
+    v = to_np(synth.tagged_kv(S, L, H, Pn, D, which=1))
+    kept = np.stack([np.sort(rng.choice(Pn, 17, replace=False)) for _ in range(S)]).astype(np.int32)
+    kept[0, :5] = [0, 1, 2, 3, 4]                              # a leading run that does not move
+    want_k = np.stack([k[s][:, :, kept[s], :] for s in range(S)])     # numpy fancy indexing on the old content
+    want_v = np.stack([v[s][:, :, kept[s], :] for s in range(S)])
+    k2, v2 = k.copy(), v.copy()
+    ref.compact_kv_inplace(k2, v2, kept)
+    np.testing.assert_array_equal(k2[:, :, :, :17], want_k)
+    np.testing.assert_array_equal(v2[:, :, :, :17], want_v)
+    np.testing.assert_array_equal(k2[:, :, :, 17:], k[:, :, :, 17:])  # slots past n_keep untouched
+    kd, vd = ref.compact_kv(k, v, kept)
+    np.testing.assert_array_equal(k2[:, :, :, :17], kd)
+    # a chain where every row is the source of its left neighbour: needs the old content throughout
+    chain = np.arange(1, 31, dtype=np.int32)[None, :].repeat(S, 0)
+    k3 = k.copy()
+    ref.compact_kv_inplace(k3, None, chain)
+    np.testing.assert_array_equal(k3[:, :, :, :30], k[:, :, :, 1:31])
