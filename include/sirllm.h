@@ -187,6 +187,38 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * One retention step for a RAGGED batch, compacting in place: every stream has its own cache fill
+ * and its own number of new tokens, as in a serving batch whose dialogues are at different turns.
+ * Per stream s (Alg. 1, same order and readings as sirllm_step):
+ *     n_new[s]  = cu_new[s+1] - cu_new[s]        its rows of `logits` / `token_ids` are [cu_new[s], cu_new[s+1])
+ *     n_cand[s] = n_held[s] + n_new[s]
+ *   - the new scores are written to scores[s*scores_stride + n_held[s] + t];
+ *   - held scores are decayed; if n_cand[s] > budget the stream is selected and its K/V compacted in
+ *     place to `budget` slots, else everything is kept and its K/V is not touched;
+ *   - kept_idx / scores_out rows as in sirllm_decay_select; n_keep_out[s] = min(n_cand[s], budget)
+ *     is written to DEVICE memory (it is the stream's n_held for the next turn).
+ *   n_held, cu_new, n_keep_out   device arrays of n_streams, n_streams+1, n_streams int32
+ *   total_new                    host copy of cu_new[n_streams]
+ *   max_cand                     host upper bound of n_cand[s]; sizes the launch.  A stream whose
+ *                                n_cand[s] exceeds it (or whose sizes are negative) is left alone and
+ *                                gets n_keep_out[s] = -1.
+ *   k, v, layout                 caches holding n_cand[s] slots of stream s (new tokens already appended);
+ *                                rewritten in place as by sirllm_compact_kv_inplace.  v may be NULL.
+ * scores_stride >= max_cand; idx_stride, out_stride >= min(max_cand, budget).  Three launches
+ * (score, select, gather), or two when max_cand <= budget.
+ */
+int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld,
+                       const int32_t* token_ids,
+                       float* scores, int64_t scores_stride,
+                       int32_t n_streams, const int32_t* n_held, const int32_t* cu_new,
+                       int64_t total_new, int32_t max_cand,
+                       const sirllm_policy* policy,
+                       void* k, void* v, const sirllm_kv_layout* layout,
+                       int32_t* kept_idx, int64_t idx_stride,
+                       float* scores_out, int64_t out_stride, int32_t* n_keep_out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Baseline retention policies on the same compaction path (Sec. 4.1 "Baselines"): they pick the
  * n_topk slots of the middle region [n_sink, n_cand - n_recent) without looking at any score;
  * sinks and the recent window are kept as in sirllm_decay_select, and kept_idx comes out in the

@@ -220,3 +220,29 @@ def step(logits: np.ndarray, token_ids: np.ndarray, vocab: int, held_scores: np.
         v_dst = v_src[:, :, :, :n_cand].copy()
     return dict(new_scores=E[:, n_held:n_cand].copy(), kept_idx=kept[:, :n_keep], scores_out=out[:, :n_keep],
                 k=k_dst, v=v_dst, evicted=evicted)
+
+
+def step_ragged(logits: np.ndarray, token_ids: np.ndarray, vocab: int, scores: np.ndarray, n_held, n_new, policy,
+                k: np.ndarray, v: np.ndarray | None):
+    """Ragged batch, in place: stream s has n_held[s] cached slots and n_new[s] new tokens (its logits rows
+    follow those of stream s-1).  Each stream goes through the same pinned pieces as a uniform step:
+    score -> append -> decay held -> select -> compact in place.  Modifies scores (new scores appended) and
+    k / v; returns (kept_idx list, scores_out list, n_keep list)."""
+    n_streams = scores.shape[0]
+    tok = np.ascontiguousarray(token_ids, dtype=np.int32)
+    budget = int(policy.n_sink) + int(policy.n_topk) + int(policy.n_recent)
+    kept_all, out_all, keep_n = [], [], []
+    r0 = 0
+    for s in range(n_streams):
+        h, n = int(n_held[s]), int(n_new[s])
+        if n:
+            scores[s, h:h + n] = score(np.ascontiguousarray(logits[r0:r0 + n]), tok[r0:r0 + n], vocab=vocab)
+        r0 += n
+        if h + n == 0:
+            kept_all.append(np.zeros(0, np.int32)); out_all.append(np.zeros(0, np.float32)); keep_n.append(0)
+            continue
+        ki, so = decay_select(scores[s:s + 1, :h + n], h, n, policy)
+        if h + n > budget:
+            compact_kv_inplace(k[s:s + 1], None if v is None else v[s:s + 1], ki, n_src=h + n)
+        kept_all.append(ki[0]); out_all.append(so[0]); keep_n.append(ki.shape[1])
+    return kept_all, out_all, keep_n

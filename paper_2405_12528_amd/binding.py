@@ -43,7 +43,7 @@ class sirllm_kv_layout(C.Structure):
 SIRLLM_BASELINE_STREAM, SIRLLM_BASELINE_INTERVAL, SIRLLM_BASELINE_RANDOM = 0, 1, 2
 
 EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step", "sirllm_baseline_select",
-           "sirllm_compact_kv_inplace", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
+           "sirllm_compact_kv_inplace", "sirllm_step_ragged", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
 
 _vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
 _PP, _LP = C.POINTER(sirllm_policy), C.POINTER(sirllm_kv_layout)
@@ -57,6 +57,9 @@ _lib.sirllm_baseline_select.argtypes = [C.c_int, _i32, _i32, _PP, C.c_uint64, C.
 _lib.sirllm_baseline_select.restype = C.c_int
 _lib.sirllm_compact_kv_inplace.argtypes = [_vp, _vp, _LP, _i32, _vp, _i64, _i32, _i32, _vp]
 _lib.sirllm_compact_kv_inplace.restype = C.c_int
+_lib.sirllm_step_ragged.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _vp, _vp, _i64, _i32, _PP,
+                                    _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _vp]
+_lib.sirllm_step_ragged.restype = C.c_int
 for _n in ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step"):
     getattr(_lib, _n).restype = C.c_int
 _lib.sirllm_workspace_bytes.argtypes = [_i32, _i32, _i64, _i32]
@@ -281,3 +284,37 @@ def sirllm_step(logits: torch.Tensor, token_ids: torch.Tensor, vocab: int, score
                             _ptr(kept_idx), _row_stride(kept_idx), _ptr(scores_out), _row_stride(scores_out),
                             wp, wb, _stream(stream)), "sirllm_step")
     return n_keep
+
+
+def sirllm_step_ragged(logits: torch.Tensor, token_ids: torch.Tensor, vocab: int, scores: torch.Tensor,
+                       n_held: torch.Tensor, cu_new: torch.Tensor, total_new: int, max_cand: int, policy,
+                       k: torch.Tensor, v, kept_idx: torch.Tensor, scores_out: torch.Tensor,
+                       n_keep_out: torch.Tensor, workspace: torch.Tensor | None = None, stream=None) -> None:
+    """Ragged in-place step: per-stream sizes in the device int32 arrays n_held [S] and cu_new [S+1]."""
+    _on_device(logits, token_ids, scores, n_held, cu_new, k, v, kept_idx, scores_out, n_keep_out, workspace)
+    n_streams = scores.shape[0]
+    for t, n in ((n_held, n_streams), (cu_new, n_streams + 1), (n_keep_out, n_streams)):
+        if t.dtype != torch.int32 or t.dim() != 1 or t.numel() != n or not t.is_contiguous():
+            raise ValueError("n_held [S], cu_new [S+1], n_keep_out [S] must be contiguous int32 device vectors")
+    if logits.dim() != 2 or (logits.shape[1] > 1 and logits.stride(1) != 1) or logits.shape[0] != total_new:
+        raise ValueError("logits must be [total_new, ld] with contiguous rows")
+    if token_ids.dtype != torch.int32 or not token_ids.is_contiguous() or token_ids.numel() != total_new:
+        raise TypeError("token_ids must be contiguous int32 with total_new entries")
+    for t, dt in ((scores, torch.float32), (kept_idx, torch.int32), (scores_out, torch.float32)):
+        if t.dim() != 2 or t.dtype != dt or (t.shape[1] > 1 and t.stride(1) != 1) or t.shape[0] != n_streams:
+            raise ValueError("scores / kept_idx / scores_out must be [n_streams, n] with contiguous rows")
+    ld = logits.stride(0) if logits.shape[0] > 1 else logits.shape[1]
+    lay = kv_layout(k)
+    if v is not None and kv_layout_tuple(v) != kv_layout_tuple(k):
+        raise ValueError("K and V must share one layout")
+    if k.shape[0] != n_streams or k.shape[3] < max_cand:
+        raise ValueError("the cache must hold max_cand slots for every stream")
+    p = _policy(policy)
+    wp, wb = _ws(workspace)
+    dtc = _dtype_code(logits) if total_new > 0 else SIRLLM_F32
+    _check(_lib.sirllm_step_ragged(_ptr(logits) if total_new else None, dtc, int(vocab), ld,
+                                   _ptr(token_ids) if total_new else None, _ptr(scores), _row_stride(scores),
+                                   n_streams, _ptr(n_held), _ptr(cu_new), int(total_new), int(max_cand), C.byref(p),
+                                   _ptr(k), _ptr(v), C.byref(lay), _ptr(kept_idx), _row_stride(kept_idx),
+                                   _ptr(scores_out), _row_stride(scores_out), _ptr(n_keep_out), wp, wb,
+                                   _stream(stream)), "sirllm_step_ragged")

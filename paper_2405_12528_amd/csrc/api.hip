@@ -138,6 +138,7 @@ SelectArgs make_select_args(const float* scores, int64_t scores_stride, int32_t 
     a.kept_idx = kept_idx; a.idx_stride = idx_stride;
     a.scores_out = scores_out; a.out_stride = out_stride;
     a.seed_lo = a.seed_hi = a.turn_lo = a.turn_hi = 0;
+    a.held_dev = nullptr; a.cu_new_dev = nullptr; a.n_keep_dev = nullptr;
     return a;
 }
 
@@ -203,6 +204,7 @@ int sirllm_score(const void* logits, sirllm_dtype dt, int64_t n_rows, int32_t vo
     a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
     a.n_rows = n_rows; a.rows_per_stream = n_rows;
     a.out_a = scores_out; a.stride_a = 0; a.out_b = nullptr; a.stride_b = 0;
+    a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0;
     return hip_status(launch_score(a, dt, (hipStream_t)hip_stream));
 }
 
@@ -313,6 +315,7 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, 
     a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
     a.n_rows = n_rows; a.rows_per_stream = n_new > 0 ? n_new : 1;
     a.out_a = scores + n_held; a.stride_a = scores_stride; a.out_b = nullptr; a.stride_b = 0;
+    a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0;
     const SelectArgs s = make_select_args(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx,
                                           idx_stride, scores_out, out_stride);
     if (evict && score_select_fusable(a, s)) {
@@ -337,6 +340,58 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, 
     const GatherArgs g = make_gather_args(k_src, v_src, src, n_cand, k_dst, v_dst, dst, kept_idx, idx_stride,
                                           n_streams, n_keep);
     return hip_status(launch_gather(g, 0, n_keep, stream));
+}
+
+int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
+                       float* scores, int64_t scores_stride, int32_t n_streams, const int32_t* n_held,
+                       const int32_t* cu_new, int64_t total_new, int32_t max_cand, const sirllm_policy* policy,
+                       void* k, void* v, const sirllm_kv_layout* layout, int32_t* kept_idx, int64_t idx_stride,
+                       float* scores_out, int64_t out_stride, int32_t* n_keep_out, void* workspace,
+                       size_t workspace_bytes, void* hip_stream)
+{
+    if (n_streams < 0 || total_new < 0 || max_cand < 0) return SIRLLM_ERR_INVALID_ARG;
+    int rc = validate_score(logits, dt, total_new, vocab, ld, token_ids);
+    if (rc) return rc;
+    if (!policy_ok(policy)) return SIRLLM_ERR_INVALID_ARG;
+    if (max_cand > SIRLLM_MAX_CAND) return SIRLLM_ERR_UNSUPPORTED;
+    if (n_streams == 0) return SIRLLM_OK;
+    if (!n_held || !cu_new || !n_keep_out || !scores || !kept_idx || !scores_out) return SIRLLM_ERR_INVALID_ARG;
+    const int64_t budget = budget_of(policy);
+    const int64_t keep_bound = max_cand < budget ? max_cand : budget;
+    if (scores_stride < max_cand || idx_stride < keep_bound || out_stride < keep_bound) return SIRLLM_ERR_INVALID_ARG;
+    if (ranges_overlap(scores, ((int64_t)(n_streams - 1) * scores_stride + max_cand) * 4,
+                       scores_out, ((int64_t)(n_streams - 1) * out_stride + keep_bound) * 4))
+        return SIRLLM_ERR_INVALID_ARG;
+    const bool may_evict = max_cand > budget;
+    if (may_evict) {
+        if (!layout_ok(layout) || !k) return SIRLLM_ERR_INVALID_ARG;
+        if ((int64_t)layout->head_dim * layout->elem_bytes * budget > 0x7fff0000LL) return SIRLLM_ERR_UNSUPPORTED;
+        const uintptr_t em = (uintptr_t)layout->elem_bytes - 1;
+        if (((uintptr_t)k & em) || ((uintptr_t)v & em)) return SIRLLM_ERR_INVALID_ARG;
+        if (ranges_overlap(k, extent_bytes(layout, n_streams, max_cand), v, extent_bytes(layout, n_streams, max_cand)))
+            return SIRLLM_ERR_INVALID_ARG;
+    }
+    rc = workspace_check(workspace, workspace_bytes, sirllm_workspace_bytes(n_streams, max_cand, total_new, vocab));
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    if (total_new > 0) {
+        ScoreArgs a;
+        a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
+        a.n_rows = total_new; a.rows_per_stream = 1;
+        a.out_a = scores; a.stride_a = scores_stride; a.out_b = nullptr; a.stride_b = 0;
+        a.cu_rows = cu_new; a.held_dev = n_held; a.n_streams_r = n_streams;
+        rc = hip_status(launch_score(a, dt, stream));
+        if (rc) return rc;
+    }
+    SelectArgs s = make_select_args(scores, scores_stride, n_streams, 0, max_cand, policy, kept_idx, idx_stride,
+                                    scores_out, out_stride);
+    s.held_dev = n_held; s.cu_new_dev = cu_new; s.n_keep_dev = n_keep_out;
+    rc = hip_status(launch_select_ragged(s, stream));
+    if (rc || !may_evict) return rc;
+    const GatherArgs g = make_gather_args(k, v, layout, max_cand, k, v, layout, kept_idx, idx_stride, n_streams,
+                                          (int32_t)budget);
+    return hip_status(launch_gather_inplace_ragged(g, n_held, cu_new, (int32_t)budget, stream));
 }
 
 }  // extern "C"

@@ -17,6 +17,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // Token entropy of n_rows rows.  Row `row` belongs to stream row / rows_per_stream, token
 // t = row % rows_per_stream; its score goes to out_a[stream*stride_a + t] and, when out_b is
 // not null, also to out_b[stream*stride_b + t].
+// Ragged batches (cu_rows != null): stream s owns rows [cu_rows[s], cu_rows[s+1]) and its token t
+// goes to out_a[s*stride_a + held_dev[s] + t].
 struct ScoreArgs {
     const void* logits;
     int64_t ld;               // elements between rows
@@ -28,6 +30,9 @@ struct ScoreArgs {
     int64_t stride_a;
     float* out_b;
     int64_t stride_b;
+    const int32_t* cu_rows;   // device [n_streams_r + 1], or null for uniform batches
+    const int32_t* held_dev;  // device [n_streams_r]
+    int32_t n_streams_r;
 };
 hipError_t launch_score(const ScoreArgs& a, sirllm_dtype dt, hipStream_t stream);
 
@@ -43,11 +48,17 @@ struct SelectArgs {
     float* scores_out;
     int64_t out_stride;
     uint32_t seed_lo, seed_hi, turn_lo, turn_hi;   // RandomLLM baseline only
+    // Ragged batches: per-stream sizes in device memory (n_held / n_cand above are then upper bounds).
+    const int32_t* held_dev;  // [n_streams]
+    const int32_t* cu_new_dev;// [n_streams + 1]
+    int32_t* n_keep_dev;      // [n_streams], written: min(n_cand[s], budget), or -1 when n_cand[s] exceeds the bound
 };
 // n_cand > budget: decay + radix select + index build, one workgroup per stream.
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
 // n_cand <= budget: identity index list, decayed scores.
 hipError_t launch_keep_all(const SelectArgs& a, hipStream_t stream);
+// Ragged batches: every stream takes its own branch (keep all, or select) on its own sizes.
+hipError_t launch_select_ragged(const SelectArgs& a, hipStream_t stream);
 
 // ---- gather.hip -------------------------------------------------------------------------
 struct GatherArgs {
@@ -67,6 +78,10 @@ hipError_t launch_gather(const GatherArgs& a, int row_begin, int row_end, hipStr
 // ---- gather_inplace.hip -----------------------------------------------------------------
 // src and dst of `a` are the same buffers and layouts; kept_idx must be strictly ascending.
 hipError_t launch_gather_inplace(const GatherArgs& a, hipStream_t stream);
+// Ragged batches: stream s holds held_dev[s] + (cu_new_dev[s+1] - cu_new_dev[s]) slots and is compacted
+// to `budget` slots only when it holds more; a.n_keep and a.n_src are upper bounds.
+hipError_t launch_gather_inplace_ragged(const GatherArgs& a, const int32_t* held_dev, const int32_t* cu_new_dev,
+                                        int32_t budget, hipStream_t stream);
 
 // ---- baseline.hip -----------------------------------------------------------------------
 // kept_idx of the score-free policies; n_topk of `a` is the number of middle slots to keep.

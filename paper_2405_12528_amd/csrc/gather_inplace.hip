@@ -16,9 +16,22 @@ namespace {
 
 using gather_dev::GatherLaunch;
 
+struct Ragged {
+    const int32_t* held_dev;    // null: uniform batch
+    const int32_t* cu_new_dev;
+    int32_t budget;
+};
+
 template <typename VecT, int BLOCK, int UNROLL, bool NT, bool POW2, bool OFF64>
-__global__ __launch_bounds__(BLOCK) void gather_inplace_kernel(GatherLaunch g)
+__global__ __launch_bounds__(BLOCK) void gather_inplace_kernel(GatherLaunch g, Ragged rg)
 {
+    if (rg.held_dev) {
+        // ragged batch: this stream's own slot count decides whether anything moves at all
+        const int s = g.stream0 + (int)blockIdx.y;
+        const int n_cand = rg.held_dev[s] + (rg.cu_new_dev[s + 1] - rg.cu_new_dev[s]);
+        if (n_cand <= rg.budget || n_cand > g.a.n_src) return;      // uniform over the workgroup
+        g.a.n_src = n_cand;
+    }
     const GatherArgs& a = g.a;
     using off_t = typename std::conditional<OFF64, int64_t, uint32_t>::type;
     const int plane = g.plane0 + (int)blockIdx.x;
@@ -68,26 +81,26 @@ __global__ __launch_bounds__(BLOCK) void gather_inplace_kernel(GatherLaunch g)
 }
 
 template <typename VecT, int BLOCK, int UNROLL>
-void launch_shape(const GatherLaunch& g, dim3 grid, bool pow2, bool off64, hipStream_t stream)
+void launch_shape(const GatherLaunch& g, const Ragged& rg, dim3 grid, bool pow2, bool off64, hipStream_t stream)
 {
     const dim3 block(BLOCK);
     if (pow2) {
-        if (off64) hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, true, true>), grid, block, 0, stream, g);
-        else       hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, true, false>), grid, block, 0, stream, g);
+        if (off64) hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, true, true>), grid, block, 0, stream, g, rg);
+        else       hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, true, false>), grid, block, 0, stream, g, rg);
     } else {
-        if (off64) hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, false, true>), grid, block, 0, stream, g);
-        else       hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, false, false>), grid, block, 0, stream, g);
+        if (off64) hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, false, true>), grid, block, 0, stream, g, rg);
+        else       hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, false, false>), grid, block, 0, stream, g, rg);
     }
 }
 
 template <typename VecT>
-hipError_t launch_vec(const GatherArgs& a, hipStream_t stream)
+hipError_t launch_vec(const GatherArgs& a, const Ragged& rg, hipStream_t stream)
 {
     GatherLaunch g;
     bool pow2, off64;
     if (!gather_dev::fill_launch<VecT>(g, a, 0, a.n_keep, &pow2, &off64)) return hipErrorInvalidValue;
-    const int block = tuning::get("SIRLLM_INPLACE_BLOCK", 512);
-    const int unroll = tuning::get("SIRLLM_INPLACE_UNROLL", 4);
+    const int block = tuning::get("SIRLLM_INPLACE_BLOCK", 1024);
+    const int unroll = tuning::get("SIRLLM_INPLACE_UNROLL", 2);
     const int planes = a.n_tensors * g.lh;
     constexpr int kMaxDim = 65535;
     for (int s0 = 0; s0 < a.n_streams; s0 += kMaxDim) {
@@ -95,17 +108,17 @@ hipError_t launch_vec(const GatherArgs& a, hipStream_t stream)
         g.plane0 = 0;
         const dim3 grid((unsigned)planes, (unsigned)min(kMaxDim, a.n_streams - s0));
         if (block == 1024) {
-            if (unroll == 2)      launch_shape<VecT, 1024, 2>(g, grid, pow2, off64, stream);
-            else if (unroll == 8) launch_shape<VecT, 1024, 8>(g, grid, pow2, off64, stream);
-            else                  launch_shape<VecT, 1024, 4>(g, grid, pow2, off64, stream);
+            if (unroll == 2)      launch_shape<VecT, 1024, 2>(g, rg, grid, pow2, off64, stream);
+            else if (unroll == 8) launch_shape<VecT, 1024, 8>(g, rg, grid, pow2, off64, stream);
+            else                  launch_shape<VecT, 1024, 4>(g, rg, grid, pow2, off64, stream);
         } else if (block == 256) {
-            if (unroll == 2)      launch_shape<VecT, 256, 2>(g, grid, pow2, off64, stream);
-            else if (unroll == 8) launch_shape<VecT, 256, 8>(g, grid, pow2, off64, stream);
-            else                  launch_shape<VecT, 256, 4>(g, grid, pow2, off64, stream);
+            if (unroll == 2)      launch_shape<VecT, 256, 2>(g, rg, grid, pow2, off64, stream);
+            else if (unroll == 8) launch_shape<VecT, 256, 8>(g, rg, grid, pow2, off64, stream);
+            else                  launch_shape<VecT, 256, 4>(g, rg, grid, pow2, off64, stream);
         } else {
-            if (unroll == 2)      launch_shape<VecT, 512, 2>(g, grid, pow2, off64, stream);
-            else if (unroll == 8) launch_shape<VecT, 512, 8>(g, grid, pow2, off64, stream);
-            else                  launch_shape<VecT, 512, 4>(g, grid, pow2, off64, stream);
+            if (unroll == 2)      launch_shape<VecT, 512, 2>(g, rg, grid, pow2, off64, stream);
+            else if (unroll == 8) launch_shape<VecT, 512, 8>(g, rg, grid, pow2, off64, stream);
+            else                  launch_shape<VecT, 512, 4>(g, rg, grid, pow2, off64, stream);
         }
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -115,18 +128,31 @@ hipError_t launch_vec(const GatherArgs& a, hipStream_t stream)
 
 }  // namespace
 
-// a.src and a.dst name the same buffers; the s_* strides are used for both sides.
-hipError_t launch_gather_inplace(const GatherArgs& a, hipStream_t stream)
+namespace {
+hipError_t launch_any(const GatherArgs& a, const Ragged& rg, hipStream_t stream)
 {
     if (a.n_keep <= 0 || a.n_streams <= 0 || a.row_bytes <= 0 || a.n_layers <= 0 || a.n_heads <= 0)
         return hipSuccess;
     switch (gather_dev::vector_bytes(a)) {
-    case 16: return launch_vec<u32x4>(a, stream);
-    case 8:  return launch_vec<u32x2>(a, stream);
-    case 4:  return launch_vec<uint32_t>(a, stream);
-    case 2:  return launch_vec<uint16_t>(a, stream);
-    default: return launch_vec<uint8_t>(a, stream);
+    case 16: return launch_vec<u32x4>(a, rg, stream);
+    case 8:  return launch_vec<u32x2>(a, rg, stream);
+    case 4:  return launch_vec<uint32_t>(a, rg, stream);
+    case 2:  return launch_vec<uint16_t>(a, rg, stream);
+    default: return launch_vec<uint8_t>(a, rg, stream);
     }
+}
+}  // namespace
+
+// a.src and a.dst name the same buffers; the s_* strides are used for both sides.
+hipError_t launch_gather_inplace(const GatherArgs& a, hipStream_t stream)
+{
+    return launch_any(a, Ragged{nullptr, nullptr, 0}, stream);
+}
+
+hipError_t launch_gather_inplace_ragged(const GatherArgs& a, const int32_t* held_dev, const int32_t* cu_new_dev,
+                                        int32_t budget, hipStream_t stream)
+{
+    return launch_any(a, Ragged{held_dev, cu_new_dev, budget}, stream);
 }
 
 }  // namespace sirllm

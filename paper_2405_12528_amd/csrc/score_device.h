@@ -174,10 +174,22 @@ __device__ __forceinline__ void score_row(const ScoreArgs& a, int64_t row, Score
             const float zt = E::load1(rowp, tok);
             e = (acc.m - zt) + logf(acc.s);
         }
-        const int64_t stream = row / a.rows_per_stream;
-        const int64_t t = row - stream * a.rows_per_stream;
-        a.out_a[stream * a.stride_a + t] = e;
-        if (a.out_b) a.out_b[stream * a.stride_b + t] = e;
+        if (a.cu_rows) {
+            // ragged batch: the stream whose row range holds `row` (largest s with cu_rows[s] <= row)
+            int lo = 0, hi = a.n_streams_r;
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if ((int64_t)a.cu_rows[mid] <= row) lo = mid; else hi = mid;
+            }
+            const int64_t pos = (int64_t)a.held_dev[lo] + (row - a.cu_rows[lo]);
+            if (pos >= 0 && pos < a.stride_a)            // sizes the caller did not promise are dropped, not written
+                a.out_a[lo * a.stride_a + pos] = e;
+        } else {
+            const int64_t stream = row / a.rows_per_stream;
+            const int64_t t = row - stream * a.rows_per_stream;
+            a.out_a[stream * a.stride_a + t] = e;
+            if (a.out_b) a.out_b[stream * a.stride_b + t] = e;
+        }
     }
 }
 

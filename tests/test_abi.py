@@ -159,6 +159,41 @@ def test_baseline_select_argument_errors(b):
     assert call(n_streams=0, out=None) == b.SIRLLM_OK
 
 
+def test_inplace_and_ragged_argument_errors(b):
+    L = b.raw()
+    lay = b.sirllm_kv_layout(2, 2, 16, 4, 2 * 2 * 128 * 16, 2 * 128 * 16, 128 * 16, 16)
+    def inplace(k=0x10000000, v=None, l=lay, n_src=100, idx=0x5000000, istr=32, n_streams=1, n_keep=32):
+        return L.sirllm_compact_kv_inplace(k, v, C.byref(l) if l else None, n_src, idx, istr, n_streams, n_keep, None)
+    assert inplace(l=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert inplace(k=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert inplace(idx=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert inplace(n_keep=101) == b.SIRLLM_ERR_INVALID_ARG            # cannot keep more than there is
+    assert inplace(istr=31) == b.SIRLLM_ERR_INVALID_ARG
+    assert inplace(v=0x10000000 + 64) == b.SIRLLM_ERR_INVALID_ARG     # K and V overlap
+    assert inplace(k=0x10000002) == b.SIRLLM_ERR_INVALID_ARG
+    assert inplace(n_keep=0) == b.SIRLLM_OK and inplace(n_streams=0) == b.SIRLLM_OK
+    p = b.sirllm_policy(4, 20, 8, 0.9)
+    def ragged(logits=0x1000, dt=0, vocab=1000, ld=1000, tok=0x2000000, scores=0x3000000, sstr=128, n_streams=2,
+               held=0x7000000, cu=0x7100000, total=64, max_cand=100, pol=p, k=0x10000000, v=0x20000000, l=lay,
+               idx=0x5000000, istr=32, out=0x6000000, ostr=32, keep=0x7200000):
+        return L.sirllm_step_ragged(logits, dt, vocab, ld, tok, scores, sstr, n_streams, held, cu, total, max_cand,
+                                    C.byref(pol) if pol else None, k, v, C.byref(l) if l else None, idx, istr, out,
+                                    ostr, keep, None, 0, None)
+    assert ragged(dt=9) == b.SIRLLM_ERR_UNSUPPORTED
+    assert ragged(total=-1) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged(logits=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged(pol=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged(max_cand=40000) == b.SIRLLM_ERR_UNSUPPORTED
+    assert ragged(held=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged(cu=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged(keep=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged(sstr=99) == b.SIRLLM_ERR_INVALID_ARG                 # scores_stride < max_cand
+    assert ragged(istr=31) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged(k=None) == b.SIRLLM_ERR_INVALID_ARG                  # max_cand > budget: a cache is needed
+    assert ragged(l=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged(n_streams=0) == b.SIRLLM_OK
+
+
 def test_binding_refuses_host_tensors(b):
     import torch
     z = torch.zeros(2, 8)

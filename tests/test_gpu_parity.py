@@ -503,3 +503,87 @@ def test_compact_inplace_strided_view_and_bad_indices(b, ref):
     b.sirllm_compact_kv_inplace(view, None, torch.from_numpy(kept).to(DEV), 6, n_src=30)
     torch.cuda.synchronize()
     assert np.array_equal(to_np(big), host)                    # padding heads / slots / channels untouched too
+
+
+# ------------------------------------------------------------------------------ ragged batches
+def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=torch.float32, cap=None):
+    """One ragged step on the GPU and in the oracle; compares everything the step writes."""
+    n_held, n_new = np.asarray(n_held), np.asarray(n_new)
+    n_cand = n_held + n_new
+    max_cand = int(n_cand.max()) if cap is None else cap
+    budget = pol.n_sink + pol.n_topk + pol.n_recent
+    total = int(n_new.sum())
+    g0 = torch.Generator(device=DEV).manual_seed(int(rng.integers(1 << 30)))
+    z = (torch.randn((total, V + 3), generator=g0, device=DEV) * 3).to(dt)
+    if total:
+        z[:, V:] = 1.0e4
+    tok = torch.randint(0, V, (total,), generator=g0, device=DEV, dtype=torch.int32)
+    scores = torch.full((S, max_cand + 2), -3.0, device=DEV)
+    for s in range(S):
+        fill = min(int(n_held[s]), max_cand + 2)          # a stream beyond the promised bound only fills what exists
+        scores[s, :fill] = torch.randint(0, 50, (fill,), generator=g0, device=DEV) / 7.0
+    k = torch.randn((S, L, H, max_cand + 1, D), generator=g0, device=DEV).to(kv_dt)
+    v = torch.randn((S, L, H, max_cand + 1, D), generator=g0, device=DEV).to(kv_dt)
+    keep_cap = min(max_cand, budget)
+    kept = torch.full((S, keep_cap + 1), -7, dtype=torch.int32, device=DEV)
+    out = torch.full((S, keep_cap + 1), -7.0, device=DEV)
+    n_keep_dev = torch.full((S,), -9, dtype=torch.int32, device=DEV)
+    held_dev = torch.from_numpy(n_held.astype(np.int32)).to(DEV)
+    cu = torch.from_numpy(np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)).to(DEV)
+    hs, hk, hv = to_np(scores).copy(), to_np(k).copy(), to_np(v).copy()
+    b.sirllm_step_ragged(z, tok, V, scores, held_dev, cu, total, max_cand, pol, k, v, kept, out, n_keep_dev)
+    torch.cuda.synchronize()
+    gs, gkeep = to_np(scores), to_np(n_keep_dev)
+    # scores: tolerance; then teacher-force the oracle with the GPU's scores for everything exact
+    want_scores = hs.copy()
+    if total:
+        e = ref.score(to_np(z), to_np(tok), vocab=V)
+        r0 = 0
+        for s in range(S):
+            if n_cand[s] <= max_cand:
+                want_scores[s, n_held[s]:n_cand[s]] = e[r0:r0 + n_new[s]]
+            r0 += n_new[s]
+    for s in range(S):
+        fits = n_cand[s] <= max_cand
+        if not fits:
+            assert gkeep[s] == -1
+            np.testing.assert_array_equal(gs[s], hs[s])       # flagged and left alone
+            continue
+        assert_scores_close(gs[s, n_held[s]:n_cand[s]], want_scores[s, n_held[s]:n_cand[s]])
+        np.testing.assert_array_equal(gs[s, :n_held[s]], hs[s, :n_held[s]])
+        np.testing.assert_array_equal(gs[s, n_cand[s]:], hs[s, n_cand[s]:])
+    ok = [s for s in range(S) if n_cand[s] <= max_cand]
+    forced = gs.copy()
+    # the oracle recomputes the new scores itself; overwrite them with the GPU's afterwards by calling the pieces
+    for s in ok:
+        h, n = int(n_held[s]), int(n_new[s])
+        if h + n == 0:
+            assert gkeep[s] == 0
+            continue
+        ki, so = ref.decay_select(forced[s:s + 1, :h + n], h, n, ref.Policy(*pol))
+        assert gkeep[s] == ki.shape[1]
+        np.testing.assert_array_equal(to_np(kept)[s, :ki.shape[1]], ki[0])
+        np.testing.assert_array_equal(to_np(out)[s, :ki.shape[1]].view(np.uint32), so[0].view(np.uint32))
+        assert (to_np(kept)[s, ki.shape[1]:] == -7).all()
+        if h + n > budget:
+            ref.compact_kv_inplace(hk[s:s + 1], hv[s:s + 1], ki, n_src=h + n)
+    assert np.array_equal(to_np(k), hk), "K differs (compacted streams, untouched streams or tails)"
+    assert np.array_equal(to_np(v), hv), "V differs"
+
+
+def test_step_ragged_matches_oracle(b, ref):
+    rng = np.random.default_rng(77)
+    pol = b.Policy(4, 20, 8, 0.9)                       # budget 32
+    # streams under, at and over the budget; empty streams; streams without new tokens
+    run_ragged(b, ref, rng, 6, pol, 500, torch.float32, [0, 10, 24, 40, 90, 0], [5, 22, 8, 0, 17, 0])
+    run_ragged(b, ref, rng, 3, pol, 777, torch.bfloat16, [100, 31, 0], [1, 1, 64], kv_dt=torch.bfloat16, D=128)
+    run_ragged(b, ref, rng, 1, pol, 64, torch.float32, [200], [0])
+    run_ragged(b, ref, rng, 4, b.Policy(4, 1020, 0, 0.8), 300, torch.bfloat16, [1024, 1000, 500, 1024], [54, 54, 54, 1],
+               L=1, H=2, D=64, kv_dt=torch.bfloat16)
+    # a stream larger than the promised bound is flagged and left alone
+    run_ragged(b, ref, rng, 3, pol, 100, torch.float32, [10, 60, 20], [5, 30, 5], cap=40)
+    for _ in range(10):
+        S = int(rng.integers(1, 9))
+        run_ragged(b, ref, rng, S, b.Policy(int(rng.integers(0, 5)), int(rng.integers(0, 60)), int(rng.integers(0, 20)), 0.7),
+                   int(rng.integers(2, 900)), torch.float32 if rng.integers(2) else torch.bfloat16,
+                   rng.integers(0, 150, S), rng.integers(0, 40, S))

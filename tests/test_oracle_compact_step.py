@@ -143,3 +143,35 @@ def test_inplace_gather_equals_out_of_place_and_leaves_the_tail(ref):
     k3 = k.copy()
     ref.compact_kv_inplace(k3, None, chain)
     np.testing.assert_array_equal(k3[:, :, :, :30], k[:, :, :, 1:31])
+
+
+def test_ragged_step_is_the_uniform_step_stream_by_stream(ref):
+    # every stream of a ragged batch must come out exactly as if it had been stepped alone
+    rng = np.random.default_rng(3)
+    pol = ref.Policy(4, 20, 8, 0.9)
+    V, S, L, H, D = 300, 4, 2, 2, 8
+    n_held, n_new = [0, 40, 10, 90], [12, 30, 0, 7]
+    cap = max(h + n for h, n in zip(n_held, n_new))
+    z = (rng.standard_normal((sum(n_new), V)) * 2).astype(np.float32)
+    tok = rng.integers(0, V, sum(n_new)).astype(np.int32)
+    scores = np.full((S, cap), np.nan, dtype=np.float32)
+    for s in range(S):
+        scores[s, :n_held[s]] = rng.gamma(2.0, 2.0, n_held[s])
+    k = rng.standard_normal((S, L, H, cap, D)).astype(np.float32)
+    v = rng.standard_normal((S, L, H, cap, D)).astype(np.float32)
+    k0, v0, s0 = k.copy(), v.copy(), scores.copy()
+    kept, out, keep_n = ref.step_ragged(z, tok, V, scores, n_held, n_new, pol, k, v)
+    r0 = 0
+    for s in range(S):
+        h, n = n_held[s], n_new[s]
+        alone = ref.step(np.ascontiguousarray(z[r0:r0 + n]).reshape(n, V), tok[r0:r0 + n], V, s0[s:s + 1, :h], n, pol,
+                         np.ascontiguousarray(k0[s:s + 1, :, :, :h + n]), np.ascontiguousarray(v0[s:s + 1, :, :, :h + n]))
+        r0 += n
+        np.testing.assert_array_equal(kept[s], alone["kept_idx"][0])
+        np.testing.assert_array_equal(out[s], alone["scores_out"][0])
+        np.testing.assert_array_equal(scores[s, h:h + n], alone["new_scores"][0])
+        assert keep_n[s] == min(h + n, 32)
+        np.testing.assert_array_equal(k[s, :, :, :keep_n[s]], alone["k"][0])
+        np.testing.assert_array_equal(v[s, :, :, :keep_n[s]], alone["v"][0])
+        if h + n <= 32:
+            np.testing.assert_array_equal(k[s], k0[s])          # nothing evicted: cache untouched
