@@ -213,3 +213,62 @@ def test_step_replays_from_a_captured_graph(b, ref):
         torch.cuda.synchronize()
         for name in eager:
             assert torch.equal(cap[name], eager[name]), f"replay {rep}: {name} differs from the eager run"
+
+
+def test_ragged_dialogues_of_unequal_length(b, ref):
+    """Six dialogues in one serving batch, each with its own arrival turn and its own number of tokens per
+    turn (some turns idle), stepped together by sirllm_step_ragged with in-place compaction; the oracle
+    replays every stream on its own and every turn is compared in full."""
+    from paper_2405_12528_amd.cache import RaggedRetentiveCache
+    S, L, H, D, V = 6, 2, 2, 16, 400
+    pol = (4, 20, 8, 0.9)
+    rng = np.random.default_rng(11)
+    cache = RaggedRetentiveCache(S, L, H, D, pol, max_new=40, kv_dtype=torch.float32, device=DEV)
+    g0 = torch.Generator(device=DEV).manual_seed(3)
+    # oracle state per stream
+    oE = [np.zeros((1, 0), np.float32) for _ in range(S)]
+    oK = [np.zeros((1, L, H, 0, D), np.float32) for _ in range(S)]
+    oV = [np.zeros((1, L, H, 0, D), np.float32) for _ in range(S)]
+    arrival = [1, 1, 3, 5, 8, 12]
+    for turn in range(1, 31):
+        n_new = [0 if turn < arrival[s] or rng.random() < 0.2 else int(rng.integers(1, 41)) for s in range(S)]
+        if turn == 20:
+            cache.reset(2)                                        # stream 2 starts a new dialogue
+            oE[2], oK[2], oV[2] = oE[2][:, :0], oK[2][:, :, :, :0], oV[2][:, :, :, :0]
+        total = sum(n_new)
+        z = torch.randn((total, V), generator=g0, device=DEV) * 2.5
+        tok = torch.randint(0, V, (total,), generator=g0, device=DEV, dtype=torch.int32)
+        new_kv = []
+        for s in range(S):
+            ks, vs = cache.new_kv_slots(s, n_new[s])
+            ks.copy_(torch.randn(ks.shape, generator=g0, device=DEV))
+            vs.copy_(torch.randn(vs.shape, generator=g0, device=DEV))
+            new_kv.append((to_np(ks)[None], to_np(vs)[None]))
+        held_before = list(cache.n_held)
+        pre_scores = cache.scores                                   # new scores are appended to this array
+        evicted = cache.step(z, tok, V, n_new)
+        torch.cuda.synchronize()
+        zs, ts = to_np(z), to_np(tok)
+        r0 = 0
+        for s in range(S):
+            h, n = held_before[s], n_new[s]
+            assert h == oE[s].shape[1]
+            Kc = np.concatenate([oK[s], new_kv[s][0]], axis=3)
+            Vc = np.concatenate([oV[s], new_kv[s][1]], axis=3)
+            if h + n == 0:
+                continue
+            # scores within tolerance, then the oracle's selection and gather on the GPU's scores
+            g_new = to_np(pre_scores[s, h:h + n])
+            if n:
+                assert_scores_close(g_new, ref.score(np.ascontiguousarray(zs[r0:r0 + n]), ts[r0:r0 + n], vocab=V))
+            r0 += n
+            cand = np.concatenate([oE[s], g_new[None]], axis=1)
+            ki, so = ref.decay_select(cand, h, n, ref.Policy(*pol))
+            n_keep = ki.shape[1]
+            assert cache.n_held[s] == n_keep and evicted[s] == (h + n > 32)
+            np.testing.assert_array_equal(to_np(cache.kept_idx[s, :n_keep]), ki[0])
+            np.testing.assert_array_equal(to_np(cache.scores[s, :n_keep]).view(np.uint32), so[0].view(np.uint32))
+            rk, rv = ref.compact_kv(Kc, Vc, ki)
+            assert np.array_equal(to_np(cache.k[s:s + 1, :, :, :n_keep]), rk), f"turn {turn} stream {s}: K differs"
+            assert np.array_equal(to_np(cache.v[s:s + 1, :, :, :n_keep]), rv), f"turn {turn} stream {s}: V differs"
+            oE[s], oK[s], oV[s] = so, rk, rv
