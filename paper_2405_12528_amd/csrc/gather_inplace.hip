@@ -45,7 +45,8 @@ __global__ __launch_bounds__(BLOCK) void gather_inplace_kernel(GatherLaunch g, R
         const int l = ph / a.n_heads, h = ph - l * a.n_heads;
         so = l * a.s_layer + h * a.s_head;
     }
-    char* base = a.dst[tensor] + stream * a.s_stream + so;
+    // blockIdx.z picks one column part of the rows: parts never share a byte, so they need no ordering
+    char* base = a.dst[tensor] + stream * a.s_stream + so + (int64_t)blockIdx.z * (g.vpr * (int)sizeof(VecT));
     const int32_t* idx = a.kept_idx + stream * a.idx_stride;
 
     const int n_items = (g.row_end - g.row_begin) * g.vpr;
@@ -102,11 +103,21 @@ hipError_t launch_vec(const GatherArgs& a, const Ragged& rg, hipStream_t stream)
     const int block = tuning::get("SIRLLM_INPLACE_BLOCK", 1024);
     const int unroll = tuning::get("SIRLLM_INPLACE_UNROLL", 2);
     const int planes = a.n_tensors * g.lh;
+    // Few planes cannot fill the chip with one workgroup each: cut every row into column parts that are
+    // compacted by workgroups of their own (only when vectors per row is a power of two).
+    int parts = 1;
+    while (pow2 && parts < g.vpr && (int64_t)planes * a.n_streams * parts < 512) parts <<= 1;
+    parts = tuning::get("SIRLLM_INPLACE_PARTS", parts);
+    while (parts > 1 && (!pow2 || g.vpr % parts != 0)) parts >>= 1;
+    if (parts < 1) parts = 1;
+    g.vpr /= parts;
+    g.shift = 0;
+    while (pow2 && (1 << g.shift) < g.vpr) ++g.shift;
     constexpr int kMaxDim = 65535;
     for (int s0 = 0; s0 < a.n_streams; s0 += kMaxDim) {
         g.stream0 = s0;
         g.plane0 = 0;
-        const dim3 grid((unsigned)planes, (unsigned)min(kMaxDim, a.n_streams - s0));
+        const dim3 grid((unsigned)planes, (unsigned)min(kMaxDim, a.n_streams - s0), (unsigned)parts);
         if (block == 1024) {
             if (unroll == 2)      launch_shape<VecT, 1024, 2>(g, rg, grid, pow2, off64, stream);
             else if (unroll == 8) launch_shape<VecT, 1024, 8>(g, rg, grid, pow2, off64, stream);
