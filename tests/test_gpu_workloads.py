@@ -272,3 +272,38 @@ def test_ragged_dialogues_of_unequal_length(b, ref):
             assert np.array_equal(to_np(cache.k[s:s + 1, :, :, :n_keep]), rk), f"turn {turn} stream {s}: K differs"
             assert np.array_equal(to_np(cache.v[s:s + 1, :, :, :n_keep]), rv), f"turn {turn} stream {s}: V differs"
             oE[s], oK[s], oV[s] = so, rk, rv
+
+
+def test_c_example_runs_without_torch():
+    """examples/step_example.c: the C ABI driven from plain C with the HIP runtime only."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = os.path.join(root, "examples", "step_example")
+    if not os.path.exists(exe):                     # built by build(); compile it here only if nothing is there
+        from paper_2405_12528_amd import build
+        build.build_example()
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
+    assert r.stdout.startswith("ok: libsirllm")
+
+
+@pytest.mark.timeout(300)
+def test_score_rows_beyond_4_gib(b, ref):
+    """Row offsets need 64 bits: 9000 rows x 128256 fp32 logits are 4.6 GB; the oracle checks the first
+    rows, rows on either side of the 2 GiB and 4 GiB marks, and the last rows."""
+    V, n_rows = 128256, 9000
+    g0 = torch.Generator(device=DEV).manual_seed(1)
+    z = torch.empty((n_rows, V), device=DEV)
+    for r0 in range(0, n_rows, 1000):
+        z[r0:r0 + 1000] = torch.randn((min(1000, n_rows - r0), V), generator=g0, device=DEV) * 3
+    tok = torch.randint(0, V, (n_rows,), generator=g0, device=DEV, dtype=torch.int32)
+    out = torch.zeros(n_rows, device=DEV)
+    b.sirllm_score(z, tok, out)
+    torch.cuda.synchronize()
+    per_row = V * 4
+    marks = sorted({0, 1, (2 << 30) // per_row, (2 << 30) // per_row + 1, (4 << 30) // per_row, (4 << 30) // per_row + 1,
+                    n_rows - 2, n_rows - 1})
+    rows = torch.tensor(marks, device=DEV)
+    want = ref.score(to_np(z[rows]), to_np(tok[rows]))
+    assert_scores_close(to_np(out[rows]), want)
