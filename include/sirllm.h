@@ -104,6 +104,26 @@ int sirllm_score(const void* logits, sirllm_dtype dt, int64_t n_rows, int32_t vo
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Token entropy of rows that arrive in CHUNKS OF COLUMNS -- the shards of a vocabulary-parallel
+ * LM head, or the tiles of an LM head that never materialises a whole row.  Softmax statistics
+ * form a monoid: a chunk is summarised by (m, s) = (max, sum of exp(z - m)), two summaries merge as
+ * m = max(m1, m2), s = s1*exp(m1 - m) + s2*exp(m2 - m), and the chunk that holds the token's column
+ * also reports z_tok.  Merging all chunks gives exactly the quantity of Sec. 3.2,
+ * e = (m - z_tok) + log s; across GPUs the merge is one all-reduce of 3 floats per row.
+ *   sirllm_score_partial   columns [v_begin, v_begin + n_cols) of every row: logits_chunk is
+ *                          n_rows x ld elements whose column c is vocabulary entry v_begin + c;
+ *                          token_ids are GLOBAL ids; writes partial[3*r + {0,1,2}] = m, s, z_tok
+ *                          (z_tok = NaN when the token is not in this chunk).
+ *   sirllm_score_merge     n_parts partial arrays, part p at partials + p*part_stride floats
+ *                          (part_stride >= 3*n_rows) -> scores_out[n_rows].  A token that no chunk
+ *                          holds scores NaN.
+ */
+int sirllm_score_partial(const void* logits_chunk, sirllm_dtype dt, int64_t n_rows, int32_t n_cols, int64_t ld,
+                         int32_t v_begin, const int32_t* token_ids, float* partial, void* hip_stream);
+int sirllm_score_merge(const float* partials, int32_t n_parts, int64_t part_stride, int64_t n_rows,
+                       float* scores_out, void* hip_stream);
+
+/*
  * Decay, select and index build (Sec. 3.3: E <- E*eta, Id_entropy = Top_k(E), E <- E[Id];
  * Sec. 3.1: Id_sink, Id_recent; Alg. 1 eviction branch and its trigger "cache size > L").
  * For every stream s, with E = scores + s*scores_stride:

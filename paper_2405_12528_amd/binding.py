@@ -43,7 +43,8 @@ class sirllm_kv_layout(C.Structure):
 SIRLLM_BASELINE_STREAM, SIRLLM_BASELINE_INTERVAL, SIRLLM_BASELINE_RANDOM = 0, 1, 2
 
 EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step", "sirllm_baseline_select",
-           "sirllm_compact_kv_inplace", "sirllm_step_ragged", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
+           "sirllm_compact_kv_inplace", "sirllm_step_ragged", "sirllm_score_partial",
+           "sirllm_score_merge", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
 
 _vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
 _PP, _LP = C.POINTER(sirllm_policy), C.POINTER(sirllm_kv_layout)
@@ -60,6 +61,10 @@ _lib.sirllm_compact_kv_inplace.restype = C.c_int
 _lib.sirllm_step_ragged.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _vp, _vp, _i64, _i32, _PP,
                                     _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _vp]
 _lib.sirllm_step_ragged.restype = C.c_int
+_lib.sirllm_score_partial.argtypes = [_vp, C.c_int, _i64, _i32, _i64, _i32, _vp, _vp, _vp]
+_lib.sirllm_score_partial.restype = C.c_int
+_lib.sirllm_score_merge.argtypes = [_vp, _i32, _i64, _i64, _vp, _vp]
+_lib.sirllm_score_merge.restype = C.c_int
 for _n in ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step"):
     getattr(_lib, _n).restype = C.c_int
 _lib.sirllm_workspace_bytes.argtypes = [_i32, _i32, _i64, _i32]
@@ -318,3 +323,32 @@ def sirllm_step_ragged(logits: torch.Tensor, token_ids: torch.Tensor, vocab: int
                                    _ptr(k), _ptr(v), C.byref(lay), _ptr(kept_idx), _row_stride(kept_idx),
                                    _ptr(scores_out), _row_stride(scores_out), _ptr(n_keep_out), wp, wb,
                                    _stream(stream)), "sirllm_step_ragged")
+
+
+def sirllm_score_partial(logits_chunk: torch.Tensor, v_begin: int, token_ids: torch.Tensor, partial: torch.Tensor,
+                         stream=None) -> torch.Tensor:
+    """(m, s, z_tok) per row for the vocabulary columns [v_begin, v_begin + logits_chunk.shape[1])."""
+    _on_device(logits_chunk, token_ids, partial)
+    if logits_chunk.dim() != 2 or (logits_chunk.shape[1] > 1 and logits_chunk.stride(1) != 1):
+        raise ValueError("logits_chunk must be [n_rows, n_cols] with contiguous rows (a column slice is fine)")
+    n_rows, n_cols = logits_chunk.shape
+    ld = logits_chunk.stride(0) if n_rows > 1 else n_cols
+    if partial.dtype != torch.float32 or not partial.is_contiguous() or partial.numel() < 3 * n_rows:
+        raise ValueError("partial must be contiguous float32 with 3*n_rows entries")
+    if token_ids.dtype != torch.int32 or not token_ids.is_contiguous() or token_ids.numel() < n_rows:
+        raise TypeError("token_ids must be contiguous int32 with n_rows entries")
+    _check(_lib.sirllm_score_partial(_ptr(logits_chunk), _dtype_code(logits_chunk), n_rows, n_cols, ld, int(v_begin),
+                                     _ptr(token_ids), _ptr(partial), _stream(stream)), "sirllm_score_partial")
+    return partial
+
+
+def sirllm_score_merge(partials: torch.Tensor, n_rows: int, scores_out: torch.Tensor, stream=None) -> torch.Tensor:
+    """partials is [n_parts, >= 3*n_rows] float32 (one row per chunk); writes scores_out[n_rows]."""
+    _on_device(partials, scores_out)
+    if partials.dim() != 2 or partials.dtype != torch.float32 or (partials.shape[1] > 1 and partials.stride(1) != 1):
+        raise ValueError("partials must be [n_parts, >= 3*n_rows] float32 with contiguous rows")
+    if scores_out.dtype != torch.float32 or not scores_out.is_contiguous() or scores_out.numel() < n_rows:
+        raise ValueError("scores_out must be contiguous float32 with n_rows entries")
+    _check(_lib.sirllm_score_merge(_ptr(partials), partials.shape[0], _row_stride(partials), int(n_rows),
+                                   _ptr(scores_out), _stream(stream)), "sirllm_score_merge")
+    return scores_out

@@ -204,8 +204,34 @@ int sirllm_score(const void* logits, sirllm_dtype dt, int64_t n_rows, int32_t vo
     a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
     a.n_rows = n_rows; a.rows_per_stream = n_rows;
     a.out_a = scores_out; a.stride_a = 0; a.out_b = nullptr; a.stride_b = 0;
-    a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0;
+    a.partial = nullptr; a.v_begin = 0; a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0;
     return hip_status(launch_score(a, dt, (hipStream_t)hip_stream));
+}
+
+int sirllm_score_partial(const void* logits_chunk, sirllm_dtype dt, int64_t n_rows, int32_t n_cols, int64_t ld,
+                         int32_t v_begin, const int32_t* token_ids, float* partial, void* hip_stream)
+{
+    int rc = validate_score(logits_chunk, dt, n_rows, n_cols, ld, token_ids);
+    if (rc) return rc;
+    if (v_begin < 0) return SIRLLM_ERR_INVALID_ARG;
+    if (n_rows == 0) return SIRLLM_OK;
+    if (!partial) return SIRLLM_ERR_INVALID_ARG;
+    ScoreArgs a;
+    a.logits = logits_chunk; a.ld = ld; a.vocab = n_cols; a.token_ids = token_ids;
+    a.n_rows = n_rows; a.rows_per_stream = n_rows;
+    a.out_a = nullptr; a.stride_a = 0; a.out_b = nullptr; a.stride_b = 0;
+    a.partial = partial; a.v_begin = v_begin; a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0;
+    return hip_status(launch_score(a, dt, (hipStream_t)hip_stream));
+}
+
+int sirllm_score_merge(const float* partials, int32_t n_parts, int64_t part_stride, int64_t n_rows,
+                       float* scores_out, void* hip_stream)
+{
+    if (n_parts < 1 || n_rows < 0 || n_rows > 0x7fffffffLL) return SIRLLM_ERR_INVALID_ARG;
+    if (n_rows == 0) return SIRLLM_OK;
+    if (!partials || !scores_out) return SIRLLM_ERR_INVALID_ARG;
+    if (n_parts > 1 && part_stride < 3 * n_rows) return SIRLLM_ERR_INVALID_ARG;
+    return hip_status(launch_score_merge(partials, n_parts, part_stride, n_rows, scores_out, (hipStream_t)hip_stream));
 }
 
 int sirllm_decay_select(const float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held,
@@ -315,7 +341,7 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, 
     a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
     a.n_rows = n_rows; a.rows_per_stream = n_new > 0 ? n_new : 1;
     a.out_a = scores + n_held; a.stride_a = scores_stride; a.out_b = nullptr; a.stride_b = 0;
-    a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0;
+    a.partial = nullptr; a.v_begin = 0; a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0;
     const SelectArgs s = make_select_args(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx,
                                           idx_stride, scores_out, out_stride);
     if (evict && score_select_fusable(a, s)) {
@@ -380,7 +406,7 @@ int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64
         a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
         a.n_rows = total_new; a.rows_per_stream = 1;
         a.out_a = scores; a.stride_a = scores_stride; a.out_b = nullptr; a.stride_b = 0;
-        a.cu_rows = cu_new; a.held_dev = n_held; a.n_streams_r = n_streams;
+        a.partial = nullptr; a.v_begin = 0; a.cu_rows = cu_new; a.held_dev = n_held; a.n_streams_r = n_streams;
         rc = hip_status(launch_score(a, dt, stream));
         if (rc) return rc;
     }

@@ -30,11 +30,16 @@ struct ScoreArgs {
     int64_t stride_a;
     float* out_b;
     int64_t stride_b;
+    float* partial;           // not null: the row is a chunk of columns starting at v_begin; write (m, s, z_tok)
+    int32_t v_begin;          //           triples to partial[3*row ..] instead of a finished score
     const int32_t* cu_rows;   // device [n_streams_r + 1], or null for uniform batches
     const int32_t* held_dev;  // device [n_streams_r]
     int32_t n_streams_r;
 };
 hipError_t launch_score(const ScoreArgs& a, sirllm_dtype dt, hipStream_t stream);
+// Merges n_parts sets of (m, s, z_tok) triples (set p starts at partials + p*part_stride) into scores.
+hipError_t launch_score_merge(const float* partials, int32_t n_parts, int64_t part_stride, int64_t n_rows,
+                              float* scores_out, hipStream_t stream);
 
 // ---- select.hip -------------------------------------------------------------------------
 struct SelectArgs {

@@ -14,6 +14,24 @@ __global__ __launch_bounds__(BLOCK) void score_rows_kernel(ScoreArgs a)
     score_dev::score_row<ESIZE, BLOCK, UNROLL, NT>(a, (int64_t)blockIdx.x, sm);
 }
 
+// One thread per row: fold the chunks' (m, s) with the same merge the lanes use, pick the chunk that
+// saw the token's logit, finish e = (m - z_tok) + log s.
+__global__ __launch_bounds__(256) void score_merge_kernel(const float* partials, int n_parts, int64_t part_stride,
+                                                          int64_t n_rows, float* out)
+{
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= n_rows) return;
+    score_dev::MS acc = {-INFINITY, 0.0f};
+    float zt = __uint_as_float(0x7fc00000u);
+    for (int p = 0; p < n_parts; ++p) {
+        const float* t = partials + p * part_stride + 3 * row;
+        acc = score_dev::merge(acc, score_dev::MS{t[0], t[1]});
+        const float z = t[2];
+        if (zt != zt && z == z) zt = z;
+    }
+    out[row] = (acc.m - zt) + logf(acc.s);
+}
+
 template <int ESIZE, int BLOCK>
 hipError_t launch_one(const ScoreArgs& a, hipStream_t stream, bool nt)
 {
@@ -45,6 +63,16 @@ hipError_t launch_score(const ScoreArgs& a, sirllm_dtype dt, hipStream_t stream)
 {
     if (a.n_rows <= 0) return hipSuccess;
     return dt == SIRLLM_F32 ? launch_esize<4>(a, stream) : launch_esize<2>(a, stream);
+}
+
+hipError_t launch_score_merge(const float* partials, int32_t n_parts, int64_t part_stride, int64_t n_rows,
+                              float* scores_out, hipStream_t stream)
+{
+    if (n_rows <= 0) return hipSuccess;
+    const int64_t blocks = (n_rows + 255) / 256;
+    hipLaunchKernelGGL(score_merge_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, partials, n_parts,
+                       part_stride, n_rows, scores_out);
+    return hipGetLastError();
 }
 
 }  // namespace sirllm

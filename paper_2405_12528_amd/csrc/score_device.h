@@ -165,6 +165,15 @@ __device__ __forceinline__ void score_row(const ScoreArgs& a, int64_t row, Score
             }
         }
     }
+    if (tid == 0 && a.partial) {
+        // a chunk of columns [v_begin, v_begin + V) of a longer row: leave the monoid element and, if the
+        // token's column is in this chunk, its logit (NaN says "not in this chunk")
+        const int64_t local = (int64_t)a.token_ids[row] - a.v_begin;
+        a.partial[3 * row + 0] = acc.m;
+        a.partial[3 * row + 1] = acc.s;
+        a.partial[3 * row + 2] = (local >= 0 && local < V) ? E::load1(rowp, (int)local) : __uint_as_float(0x7fc00000u);
+        return;
+    }
     if (tid == 0) {
         const int32_t tok = a.token_ids[row];
         float e;

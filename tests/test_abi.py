@@ -194,6 +194,20 @@ def test_inplace_and_ragged_argument_errors(b):
     assert ragged(n_streams=0) == b.SIRLLM_OK
 
 
+def test_score_chunk_argument_errors(b):
+    L = b.raw()
+    assert L.sirllm_score_partial(FAKE, 0, 4, 10, 10, -1, FAKE, FAKE, None) == b.SIRLLM_ERR_INVALID_ARG   # v_begin < 0
+    assert L.sirllm_score_partial(FAKE, 0, 4, 10, 9, 0, FAKE, FAKE, None) == b.SIRLLM_ERR_INVALID_ARG    # ld < n_cols
+    assert L.sirllm_score_partial(FAKE, 3, 4, 10, 10, 0, FAKE, FAKE, None) == b.SIRLLM_ERR_UNSUPPORTED
+    assert L.sirllm_score_partial(FAKE, 0, 4, 10, 10, 0, FAKE, None, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert L.sirllm_score_partial(None, 0, 0, 10, 10, 0, None, None, None) == b.SIRLLM_OK
+    assert L.sirllm_score_merge(FAKE, 0, 100, 4, FAKE, None) == b.SIRLLM_ERR_INVALID_ARG                 # no parts
+    assert L.sirllm_score_merge(FAKE, 2, 11, 4, FAKE, None) == b.SIRLLM_ERR_INVALID_ARG                  # parts overlap
+    assert L.sirllm_score_merge(None, 2, 12, 4, FAKE, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert L.sirllm_score_merge(FAKE, 2, 12, 4, None, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert L.sirllm_score_merge(None, 2, 12, 0, None, None) == b.SIRLLM_OK
+
+
 def test_binding_refuses_host_tensors(b):
     import torch
     z = torch.zeros(2, 8)

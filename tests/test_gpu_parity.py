@@ -587,3 +587,54 @@ def test_step_ragged_matches_oracle(b, ref):
         run_ragged(b, ref, rng, S, b.Policy(int(rng.integers(0, 5)), int(rng.integers(0, 60)), int(rng.integers(0, 20)), 0.7),
                    int(rng.integers(2, 900)), torch.float32 if rng.integers(2) else torch.bfloat16,
                    rng.integers(0, 150, S), rng.integers(0, 40, S))
+
+
+# ------------------------------------------------------------- scoring from chunks of columns
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n_rows,V,cuts", [
+    (33, 1000, [0, 1000]),                       # a single chunk is the whole row
+    (33, 1000, [0, 1, 500, 999, 1000]),          # one-column chunks at both ends
+    (7, 32000, [0, 4000, 8000, 12000, 16000, 20000, 24000, 28000, 32000]),   # eight vocabulary shards
+    (5, 128256, [0, 16032, 50001, 128256]),      # unequal shards, odd boundaries
+    (64, 777, [0, 100, 101, 102, 640, 777]),
+])
+def test_score_from_column_chunks_matches_oracle(b, ref, dtype, n_rows, V, cuts):
+    g = torch.Generator(device=DEV).manual_seed(V + n_rows)
+    z = (torch.randn((n_rows, V), generator=g, device=DEV) * 3.0)
+    z[::2, V // 3] += 9.0
+    z = z.to(dtype)
+    tok = torch.randint(0, V, (n_rows,), generator=g, device=DEV, dtype=torch.int32)
+    tok[0], tok[-1] = 0, V - 1
+    n_parts = len(cuts) - 1
+    parts = torch.full((n_parts, 3 * n_rows + 5), 7.0, device=DEV)
+    for p in range(n_parts):                      # column slices of the full tensor: ld stays V
+        b.sirllm_score_partial(z[:, cuts[p]:cuts[p + 1]], cuts[p], tok, parts[p])
+    out = torch.zeros(n_rows, device=DEV)
+    b.sirllm_score_merge(parts, n_rows, out)
+    torch.cuda.synchronize()
+    want = ref.score(to_np(z), to_np(tok))
+    assert_scores_close(to_np(out), want)
+    # the whole-row kernel and the chunked path agree with each other to rounding as well
+    whole = gpu_score(b, z, tok)
+    np.testing.assert_allclose(to_np(out), whole, rtol=3e-6, atol=1e-6)
+    assert (to_np(parts)[:, 3 * n_rows:] == 7.0).all()
+
+
+def test_score_chunks_special_cases(b, ref):
+    V = 600
+    z = torch.zeros((5, V), device=DEV)
+    z[0, :300] = -np.inf                         # a whole chunk of -inf merges as the neutral element
+    z[1, :] = -np.inf                            # every chunk empty: NaN
+    z[2, 450] = np.inf                           # +inf in one chunk: NaN
+    z[3, 10] = np.nan
+    tok = torch.tensor([400, 5, 0, 0, V + 3], dtype=torch.int32, device=DEV)   # last: no chunk holds the token
+    parts = torch.zeros((2, 15), device=DEV)
+    b.sirllm_score_partial(z[:, :300], 0, tok, parts[0])
+    b.sirllm_score_partial(z[:, 300:], 300, tok, parts[1])
+    out = torch.zeros(5, device=DEV)
+    b.sirllm_score_merge(parts, 5, out)
+    torch.cuda.synchronize()
+    got = to_np(out)
+    want = ref.score(to_np(z), to_np(tok))
+    assert_scores_close(got, want)
+    assert abs(got[0] - np.log(300)) < 1e-5 and np.isnan(got[1:]).all()
