@@ -53,7 +53,8 @@ typedef enum {
 
 typedef enum {
     SIRLLM_F32  = 0,              /* IEEE binary32 */
-    SIRLLM_BF16 = 1               /* bfloat16: the upper 16 bits of a binary32 */
+    SIRLLM_BF16 = 1,              /* bfloat16: the upper 16 bits of a binary32 */
+    SIRLLM_F16  = 2               /* IEEE binary16 */
 } sirllm_dtype;
 
 /* Retention policy (Sec. 3.1: n_sink, n_recent; Sec. 3.3: k of Top_k and eta_decay).
@@ -90,7 +91,8 @@ typedef struct {
  * with the natural logarithm, i.e. minus the log-softmax probability of the token that
  * actually occurred.  Row r of `logits` starts at element r*ld (ld >= vocab) and is the
  * next-token distribution from which token_ids[r] was drawn; the library does no shifting.
- * Inputs are widened exactly to binary32; max, sum and log are accumulated in binary32.
+ * Inputs (binary32, bfloat16 or binary16) are widened exactly to binary32; max, sum and log are
+ * accumulated in binary32.
  *   logits      device, n_rows x ld elements of `dt`, read once
  *   token_ids   device, n_rows int32; an id outside [0, vocab) yields a quiet NaN score
  *   scores_out  device, n_rows float

@@ -15,7 +15,7 @@ from . import build as _build
 
 Policy = namedtuple("Policy", "n_sink n_topk n_recent decay")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 
 
 class _CPolicy(C.Structure):
@@ -85,7 +85,9 @@ def _logits_dtype(logits):
         return F32
     if logits.dtype == np.uint16:
         return BF16
-    raise TypeError("logits must be float32 or uint16 (bfloat16 bit patterns)")
+    if logits.dtype == np.float16:
+        return F16
+    raise TypeError("logits must be float32, float16 or uint16 (bfloat16 bit patterns)")
 
 
 def _cpolicy(p):

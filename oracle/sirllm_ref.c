@@ -56,18 +56,28 @@ static double logit_at(const void* logits, int dtype, int64_t index)
 {
     if (dtype == SIRLLM_REF_F32)
         return (double)((const float*)logits)[index];
-    /* bfloat16 is the top half of a binary32 */
-    uint32_t bits = (uint32_t)((const uint16_t*)logits)[index] << 16;
-    float f;
-    memcpy(&f, &bits, sizeof f);
-    return (double)f;
+    if (dtype == SIRLLM_REF_BF16) {
+        /* bfloat16 is the top half of a binary32 */
+        uint32_t bits = (uint32_t)((const uint16_t*)logits)[index] << 16;
+        float f;
+        memcpy(&f, &bits, sizeof f);
+        return (double)f;
+    }
+    /* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits */
+    const uint16_t h = ((const uint16_t*)logits)[index];
+    const int sign = h >> 15, expo = (h >> 10) & 31, frac = h & 1023;
+    double mag;
+    if (expo == 31) mag = frac ? (double)NAN : (double)INFINITY;
+    else if (expo == 0) mag = ldexp((double)frac, -24);              /* subnormal: frac * 2^-10 * 2^-14 */
+    else mag = ldexp(1.0 + frac / 1024.0, expo - 15);
+    return sign ? -mag : mag;
 }
 
 int sirllm_ref_score(const void* logits, int dtype, int64_t n_rows, int32_t vocab, int64_t ld,
                      const int32_t* token_ids, float* scores_out)
 {
     if (n_rows < 0 || vocab < 1 || ld < vocab) return -1;
-    if (dtype != SIRLLM_REF_F32 && dtype != SIRLLM_REF_BF16) return -1;
+    if (dtype != SIRLLM_REF_F32 && dtype != SIRLLM_REF_BF16 && dtype != SIRLLM_REF_F16) return -1;
     if (n_rows == 0) return 0;
     if (!logits || !token_ids || !scores_out) return -1;
 
@@ -403,7 +413,7 @@ int sirllm_ref_step(const void* logits, int dtype, int32_t vocab, int64_t ld, co
 
     /* E_t = Entropy([I_t, R_t]);  E <- E ++ E_t */
     for (int32_t s = 0; s < n_streams && n_new > 0; ++s) {
-        const size_t esz = dtype == SIRLLM_REF_F32 ? 4 : 2;
+        const size_t esz = dtype == SIRLLM_REF_F32 ? 4 : 2;   /* bfloat16 and binary16 are two bytes */
         const char* rows = (const char*)logits + esz * (size_t)((int64_t)s * n_new * ld);
         int rc = sirllm_ref_score(rows, dtype, n_new, vocab, ld, token_ids + (int64_t)s * n_new,
                                   scores + (int64_t)s * scores_stride + n_held);

@@ -20,7 +20,7 @@
 extern "C" {
 #endif
 
-enum { SIRLLM_REF_F32 = 0, SIRLLM_REF_BF16 = 1 };
+enum { SIRLLM_REF_F32 = 0, SIRLLM_REF_BF16 = 1, SIRLLM_REF_F16 = 2 };
 
 typedef struct {
     int32_t n_sink, n_topk, n_recent;

@@ -24,7 +24,7 @@ if not os.path.exists(LIB_PATH):
 _lib = C.CDLL(LIB_PATH)
 
 SIRLLM_OK, SIRLLM_ERR_INVALID_ARG, SIRLLM_ERR_UNSUPPORTED, SIRLLM_ERR_WORKSPACE, SIRLLM_ERR_HIP = 0, -1, -2, -3, -4
-SIRLLM_F32, SIRLLM_BF16 = 0, 1
+SIRLLM_F32, SIRLLM_BF16, SIRLLM_F16 = 0, 1, 2
 SIRLLM_MAX_CAND = 32768
 
 Policy = namedtuple("Policy", "n_sink n_topk n_recent decay")
@@ -112,7 +112,9 @@ def _dtype_code(t: torch.Tensor) -> int:
         return SIRLLM_F32
     if t.dtype == torch.bfloat16:
         return SIRLLM_BF16
-    raise TypeError(f"logits dtype {t.dtype} not supported (float32 or bfloat16)")
+    if t.dtype == torch.float16:
+        return SIRLLM_F16
+    raise TypeError(f"logits dtype {t.dtype} not supported (float32, bfloat16 or float16)")
 
 
 def _on_device(*ts):

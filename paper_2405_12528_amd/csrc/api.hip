@@ -73,7 +73,7 @@ int workspace_check(void* workspace, size_t workspace_bytes, size_t need)
 int validate_score(const void* logits, sirllm_dtype dt, int64_t n_rows, int32_t vocab, int64_t ld,
                    const int32_t* token_ids)
 {
-    if (dt != SIRLLM_F32 && dt != SIRLLM_BF16) return SIRLLM_ERR_UNSUPPORTED;
+    if (dt != SIRLLM_F32 && dt != SIRLLM_BF16 && dt != SIRLLM_F16) return SIRLLM_ERR_UNSUPPORTED;
     if (n_rows < 0 || vocab < 1 || ld < vocab) return SIRLLM_ERR_INVALID_ARG;
     if (n_rows > 0x7fffffffLL) return SIRLLM_ERR_UNSUPPORTED;
     if (n_rows > 0 && (!logits || !token_ids)) return SIRLLM_ERR_INVALID_ARG;

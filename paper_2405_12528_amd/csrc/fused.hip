@@ -15,7 +15,7 @@ namespace {
 
 constexpr int kBlock = 1024;
 
-template <int ESIZE, int KPT, bool NT>
+template <int DT, int KPT, bool NT>
 __global__ __launch_bounds__(kBlock) void score_select_kernel(ScoreArgs sa, SelectArgs se)
 {
     __shared__ union {
@@ -25,27 +25,27 @@ __global__ __launch_bounds__(kBlock) void score_select_kernel(ScoreArgs sa, Sele
     if ((int)blockIdx.x < se.n_streams) {
         select_dev::select_stream<kBlock, KPT, true>(se, (int)blockIdx.x, sm.sel);
     } else {
-        score_dev::score_row<ESIZE, kBlock, 4, NT>(sa, (int64_t)blockIdx.x - se.n_streams, sm.sc);
+        score_dev::score_row<DT, kBlock, 4, NT>(sa, (int64_t)blockIdx.x - se.n_streams, sm.sc);
     }
 }
 
-template <int ESIZE, int KPT>
+template <int DT, int KPT>
 hipError_t launch_kpt(const ScoreArgs& sa, const SelectArgs& se, hipStream_t stream)
 {
     const dim3 grid((unsigned)(sa.n_rows + se.n_streams)), block(kBlock);
     if (tuning::get("SIRLLM_SCORE_NT", 1) != 0)
-        hipLaunchKernelGGL((score_select_kernel<ESIZE, KPT, true>), grid, block, 0, stream, sa, se);
+        hipLaunchKernelGGL((score_select_kernel<DT, KPT, true>), grid, block, 0, stream, sa, se);
     else
-        hipLaunchKernelGGL((score_select_kernel<ESIZE, KPT, false>), grid, block, 0, stream, sa, se);
+        hipLaunchKernelGGL((score_select_kernel<DT, KPT, false>), grid, block, 0, stream, sa, se);
     return hipGetLastError();
 }
 
-template <int ESIZE>
+template <int DT>
 hipError_t launch_esize(const ScoreArgs& sa, const SelectArgs& se, hipStream_t stream)
 {
     const int need = (se.n_cand + kBlock - 1) / kBlock;
-    if (need <= 2) return launch_kpt<ESIZE, 2>(sa, se, stream);
-    return launch_kpt<ESIZE, 8>(sa, se, stream);
+    if (need <= 2) return launch_kpt<DT, 2>(sa, se, stream);
+    return launch_kpt<DT, 8>(sa, se, stream);
 }
 
 }  // namespace
@@ -61,7 +61,11 @@ bool score_select_fusable(const ScoreArgs& sa, const SelectArgs& se)
 
 hipError_t launch_score_select(const ScoreArgs& sa, const SelectArgs& se, sirllm_dtype dt, hipStream_t stream)
 {
-    return dt == SIRLLM_F32 ? launch_esize<4>(sa, se, stream) : launch_esize<2>(sa, se, stream);
+    switch (dt) {
+    case SIRLLM_F32:  return launch_esize<SIRLLM_F32>(sa, se, stream);
+    case SIRLLM_BF16: return launch_esize<SIRLLM_BF16>(sa, se, stream);
+    default:          return launch_esize<SIRLLM_F16>(sa, se, stream);
+    }
 }
 
 }  // namespace sirllm

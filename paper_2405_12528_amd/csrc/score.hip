@@ -7,11 +7,11 @@
 namespace sirllm {
 namespace {
 
-template <int ESIZE, int BLOCK, int UNROLL, bool NT>
+template <int DT, int BLOCK, int UNROLL, bool NT>
 __global__ __launch_bounds__(BLOCK) void score_rows_kernel(ScoreArgs a)
 {
     __shared__ score_dev::ScoreSmem<BLOCK> sm;
-    score_dev::score_row<ESIZE, BLOCK, UNROLL, NT>(a, (int64_t)blockIdx.x, sm);
+    score_dev::score_row<DT, BLOCK, UNROLL, NT>(a, (int64_t)blockIdx.x, sm);
 }
 
 // One thread per row: fold the chunks' (m, s) with the same merge the lanes use, pick the chunk that
@@ -32,28 +32,28 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const float* partials,
     out[row] = (acc.m - zt) + logf(acc.s);
 }
 
-template <int ESIZE, int BLOCK>
+template <int DT, int BLOCK>
 hipError_t launch_one(const ScoreArgs& a, hipStream_t stream, bool nt)
 {
     const dim3 grid((unsigned)a.n_rows), block(BLOCK);
-    if (nt) hipLaunchKernelGGL((score_rows_kernel<ESIZE, BLOCK, 4, true>), grid, block, 0, stream, a);
-    else    hipLaunchKernelGGL((score_rows_kernel<ESIZE, BLOCK, 4, false>), grid, block, 0, stream, a);
+    if (nt) hipLaunchKernelGGL((score_rows_kernel<DT, BLOCK, 4, true>), grid, block, 0, stream, a);
+    else    hipLaunchKernelGGL((score_rows_kernel<DT, BLOCK, 4, false>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 
-template <int ESIZE>
+template <int DT>
 hipError_t launch_esize(const ScoreArgs& a, hipStream_t stream)
 {
     // Long rows take the widest workgroup (most waves per CU on few rows); short rows a narrower
     // one, so that lanes are not left without a single 16-byte vector.
-    const int64_t vecs = (int64_t)a.vocab * ESIZE / 16;
+    const int64_t vecs = (int64_t)a.vocab * score_dev::Elem<DT>::kSize / 16;
     int block = vecs >= 2048 ? 1024 : (vecs >= 1024 ? 512 : 256);
     block = tuning::get("SIRLLM_SCORE_BLOCK", block);
     const bool nt = tuning::get("SIRLLM_SCORE_NT", 1) != 0;
     switch (block) {
-    case 256:  return launch_one<ESIZE, 256>(a, stream, nt);
-    case 512:  return launch_one<ESIZE, 512>(a, stream, nt);
-    default:   return launch_one<ESIZE, 1024>(a, stream, nt);
+    case 256:  return launch_one<DT, 256>(a, stream, nt);
+    case 512:  return launch_one<DT, 512>(a, stream, nt);
+    default:   return launch_one<DT, 1024>(a, stream, nt);
     }
 }
 
@@ -62,7 +62,11 @@ hipError_t launch_esize(const ScoreArgs& a, hipStream_t stream)
 hipError_t launch_score(const ScoreArgs& a, sirllm_dtype dt, hipStream_t stream)
 {
     if (a.n_rows <= 0) return hipSuccess;
-    return dt == SIRLLM_F32 ? launch_esize<4>(a, stream) : launch_esize<2>(a, stream);
+    switch (dt) {
+    case SIRLLM_F32:  return launch_esize<SIRLLM_F32>(a, stream);
+    case SIRLLM_BF16: return launch_esize<SIRLLM_BF16>(a, stream);
+    default:          return launch_esize<SIRLLM_F16>(a, stream);
+    }
 }
 
 hipError_t launch_score_merge(const float* partials, int32_t n_parts, int64_t part_stride, int64_t n_rows,

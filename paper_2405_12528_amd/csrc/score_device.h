@@ -46,8 +46,10 @@ __device__ __forceinline__ void accumulate(const float (&z)[N], MS& acc)
     acc.m = m_new;
 }
 
-template <int ESIZE> struct Elem;
-template <> struct Elem<4> {
+// Element traits by sirllm_dtype code.
+template <int DT> struct Elem;
+template <> struct Elem<SIRLLM_F32> {
+    static constexpr int kSize = 4;
     static constexpr int kVec = 4;
     static __device__ __forceinline__ float load1(const char* row, int i) { return ((const float*)row)[i]; }
     static __device__ __forceinline__ void unpack(u32x4 v, float* z)
@@ -61,7 +63,8 @@ template <> struct Elem<4> {
         return v;
     }
 };
-template <> struct Elem<2> {   // bfloat16: the upper half of a binary32
+template <> struct Elem<SIRLLM_BF16> {   // bfloat16: the upper half of a binary32
+    static constexpr int kSize = 2;
     static constexpr int kVec = 8;
     static __device__ __forceinline__ float load1(const char* row, int i)
     {
@@ -81,6 +84,31 @@ template <> struct Elem<2> {   // bfloat16: the upper half of a binary32
     }
 };
 
+template <> struct Elem<SIRLLM_F16> {    // IEEE binary16, widened exactly by v_cvt_f32_f16
+    static constexpr int kSize = 2;
+    static constexpr int kVec = 8;
+    typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ float load1(const char* row, int i)
+    {
+        return (float)__builtin_bit_cast(_Float16, ((const uint16_t*)row)[i]);
+    }
+    static __device__ __forceinline__ void unpack(u32x4 v, float* z)
+    {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const half2_t h = __builtin_bit_cast(half2_t, w[i]);
+            z[2 * i] = (float)h.x;
+            z[2 * i + 1] = (float)h.y;
+        }
+    }
+    static __device__ __forceinline__ u32x4 neg_inf()
+    {
+        u32x4 v = {0xfc00fc00u, 0xfc00fc00u, 0xfc00fc00u, 0xfc00fc00u};
+        return v;
+    }
+};
+
 template <bool NT>
 __device__ __forceinline__ u32x4 load_vec(const u32x4* p)
 {
@@ -95,11 +123,12 @@ struct ScoreSmem {
 };
 
 // Scores row `row` with the whole workgroup (BLOCK threads); thread 0 writes the result.
-template <int ESIZE, int BLOCK, int UNROLL, bool NT>
+template <int DT, int BLOCK, int UNROLL, bool NT>
 __device__ __forceinline__ void score_row(const ScoreArgs& a, int64_t row, ScoreSmem<BLOCK>& sm)
 {
-    using E = Elem<ESIZE>;
+    using E = Elem<DT>;
     constexpr int VEC = E::kVec;
+    constexpr int ESIZE = E::kSize;
     const int tid = threadIdx.x;
     const char* rowp = (const char*)a.logits + row * a.ld * ESIZE;
     const int V = a.vocab;

@@ -16,6 +16,7 @@ def bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
 
 
 def logits_f64(a: np.ndarray) -> np.ndarray:
+    """Exact widening to float64: uint16 = bfloat16 bit patterns, float16 / float32 by numpy's own conversion."""
     return bf16_bits_to_f64(a) if a.dtype == np.uint16 else a.astype(np.float64)
 
 

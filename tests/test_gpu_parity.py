@@ -43,7 +43,7 @@ def gpu_score(b, z: torch.Tensor, tok: torch.Tensor, vocab=None):
 
 
 # ------------------------------------------------------------------------------------- score
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 @pytest.mark.parametrize("n_rows,V,ld", [
     (64, 1000, 1000),        # the tiny workload's shape
     (37, 2311, 2311),        # odd length: rows start at every alignment, scalar head and tail
@@ -60,6 +60,8 @@ def test_score_matches_oracle(b, ref, dtype, n_rows, V, ld):
     z[::3, V // 2] += 8.0
     if ld > V:
         z[:, V:] = 1.0e4
+    if ld > V and dtype == torch.float16:
+        z[:, V:] = 6.0e4                                   # the padding sentinel must fit binary16
     z = z.to(dtype)
     tok = torch.randint(0, V, (n_rows,), generator=g, device=DEV, dtype=torch.int32)
     got = gpu_score(b, z, tok, vocab=V)
@@ -101,8 +103,21 @@ def test_score_non_finite_and_bad_tokens(b, ref):
     want = ref.score(to_np(z), to_np(tok))
     assert_scores_close(got, want)
     assert got[1] == np.inf and np.isnan(got[[2, 3, 4, 7]]).all()
-    zb = z.to(torch.bfloat16)
-    assert_scores_close(gpu_score(b, zb, tok), ref.score(to_np(zb), to_np(tok)))
+    for dt in (torch.bfloat16, torch.float16):
+        zb = z.to(dt)
+        assert_scores_close(gpu_score(b, zb, tok), ref.score(to_np(zb), to_np(tok)))
+
+
+def test_score_binary16_subnormals_and_extremes(b, ref):
+    # all finite binary16 values in one row, including subnormals and +-65504
+    bits = torch.arange(0, 1 << 16, dtype=torch.int32)
+    h = bits.to(torch.int16).view(torch.float16)
+    h = h[torch.isfinite(h)]
+    z = h[None, :].repeat(3, 1).contiguous().to(DEV)
+    z[1] = z[1] / 8                                        # a row whose maximum is not the format's maximum
+    z[2, : z.shape[1] // 2] = 0
+    tok = torch.tensor([5, 40000, 1], dtype=torch.int32, device=DEV)
+    assert_scores_close(gpu_score(b, z, tok), ref.score(to_np(z), to_np(tok)))
 
 
 def test_score_empty(b):
@@ -590,7 +605,7 @@ def test_step_ragged_matches_oracle(b, ref):
 
 
 # ------------------------------------------------------------- scoring from chunks of columns
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 @pytest.mark.parametrize("n_rows,V,cuts", [
     (33, 1000, [0, 1000]),                       # a single chunk is the whole row
     (33, 1000, [0, 1, 500, 999, 1000]),          # one-column chunks at both ends

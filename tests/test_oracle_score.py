@@ -53,13 +53,13 @@ def test_two_valued_row_closed_form(ref, V, a):
     assert abs(e[0] - shannon) > 1e-3
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_matches_float64_library_log_softmax(ref, dtype):
     rng = np.random.default_rng(1)
     n, V = 37, 2311
     z = (rng.standard_normal((n, V)) * 3.0).astype(np.float32)
     z[::3, rng.integers(0, V)] += 8.0
-    zin = z if dtype == "f32" else f32_to_bf16_bits(z)
+    zin = z if dtype == "f32" else (f32_to_bf16_bits(z) if dtype == "bf16" else z.astype(np.float16))
     tok = rng.integers(0, V, n).astype(np.int32)
     e = ref.score(zin, tok)
     z64 = logits_f64(zin)
@@ -67,6 +67,21 @@ def test_matches_float64_library_log_softmax(ref, dtype):
     np.testing.assert_allclose(e, want.astype(np.float32), rtol=2e-7, atol=0)
     ce = torch.nn.functional.cross_entropy(torch.from_numpy(z64), torch.from_numpy(tok).long(), reduction="none")
     np.testing.assert_allclose(e, ce.numpy().astype(np.float32), rtol=2e-7, atol=0)
+
+
+def test_binary16_decoding_against_numpy(ref):
+    # every binary16 bit pattern that is a number, as a one-column row: e = 0, and as the odd one out in a
+    # two-column row against numpy's own float16 -> float64 conversion (subnormals, both zeros, extremes)
+    bits = np.arange(0, 1 << 16, dtype=np.uint16)
+    h = bits.view(np.float16)
+    ok = np.isfinite(h)
+    z = np.zeros((int(ok.sum()), 2), dtype=np.float16)
+    z[:, 1] = h[ok]
+    v = h[ok].astype(np.float64)
+    e0 = ref.score(z, np.zeros(len(z), dtype=np.int32))
+    np.testing.assert_allclose(e0, np.logaddexp(0.0, v).astype(np.float32), rtol=2e-7, atol=1e-12)      # log(1 + e^v)
+    e1 = ref.score(z, np.ones(len(z), dtype=np.int32))
+    np.testing.assert_allclose(e1, (np.logaddexp(0.0, v) - v).astype(np.float32), rtol=2e-7, atol=1e-12)
 
 
 def test_token_id_selects_the_column_not_the_row(ref):
