@@ -108,32 +108,26 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, S
         for (int shift = 24; shift >= 0; shift -= 8) {
             if (tid < 256) sm.hist[tid] = 0u;
             __syncthreads();
+            // A lane first folds its own slots: those whose digit equals the digit of its first live slot
+            // go into the histogram with one add.  In the first pass (sign and high exponent bits, nearly
+            // the same for every score) that is all of them, which takes the pile-up on one or two bins
+            // down by a factor KPT; in later passes digits differ and most slots add on their own.
+            {
+                uint32_t d0 = 0xffffffffu, n0 = 0u;
 #pragma unroll
-            for (int q = 0; q < KPT; ++q) {
-                const int i = i0 + q;
-                bool live = false;
-                uint32_t digit = 0u;
-                if (i >= mid_lo && i < mid_hi) {
-                    const uint32_t key = key_of(val[q]);
-                    live = (key & mask) == prefix;
-                    digit = (key >> shift) & 255u;
-                }
-                if (shift == 24 && !RANDOM_KEYS) {
-                    // The top byte of a score key (sign and high exponent bits) takes only a handful of
-                    // values, so plain atomics would pile the whole wave onto one or two bins.  Up to four
-                    // rounds of "all lanes that share the first live lane's digit add their count with one
-                    // atomic"; whatever is left after that goes the plain way.
-                    for (int round = 0; round < 4; ++round) {
-                        const uint64_t pending = __ballot(live);
-                        if (pending == 0) break;
-                        const int leader = __ffsll((long long)pending) - 1;
-                        const uint32_t d0 = __shfl(digit, leader, kWave);
-                        const uint64_t same = __ballot(live && digit == d0);
-                        if (lane == leader) atomicAdd(&sm.hist[d0], (uint32_t)__popcll(same));
-                        if (digit == d0) live = false;
+                for (int q = 0; q < KPT; ++q) {
+                    const int i = i0 + q;
+                    if (i >= mid_lo && i < mid_hi) {
+                        const uint32_t key = key_of(val[q]);
+                        if ((key & mask) == prefix) {
+                            const uint32_t digit = (key >> shift) & 255u;
+                            if (d0 == 0xffffffffu) d0 = digit;
+                            if (digit == d0) ++n0;
+                            else atomicAdd(&sm.hist[digit], 1u);
+                        }
                     }
                 }
-                if (live) atomicAdd(&sm.hist[digit], 1u);
+                if (n0) atomicAdd(&sm.hist[d0], n0);
             }
             __syncthreads();
             // the digit d with  #(digit > d) < k_rem <= #(digit >= d)
