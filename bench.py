@@ -52,8 +52,15 @@ def main():
     log(f"[bench] {synth.describe(w)}")
 
     # ---- inputs, resident in HBM ---------------------------------------------------------
-    logits = synth.make_logits(w, turn=1, device=dev)
-    tok = synth.make_token_ids(w, turn=1, device=dev)
+    # Logits smaller than the 256 MB Infinity Cache would be served from it if one buffer were reused step
+    # after step: rotate among enough distinct sets that at least 600 MB of logits pass between two uses of
+    # the same set.  (The K/V sets are above 1.5 GB in every large workload and need no rotation.)
+    logit_bytes = S * n_new * w.vocab * w.logit_bytes
+    n_sets = 1 if logit_bytes >= 600e6 or w.name == "tiny" else min(32, -(-int(600e6) // logit_bytes))
+    logit_sets = [synth.make_logits(w, turn=1 + i, device=dev) for i in range(n_sets)]
+    tok_sets = [synth.make_token_ids(w, turn=1 + i, device=dev) for i in range(n_sets)]
+    logits, tok = logit_sets[0], tok_sets[0]
+    log(f"[bench] rotating among {n_sets} logits set(s) of {logit_bytes / 1e6:.1f} MB")
     scores = torch.zeros((S, n_cand), device=dev)
     scores[:, :n_held] = synth.make_held_scores(w, device=dev)
     k_src = synth.make_kv(w, device=dev, which="k")
@@ -67,9 +74,13 @@ def main():
     ws = torch.zeros(max(ws_bytes, 256), dtype=torch.uint8, device=dev) if ws_bytes else None
     torch.cuda.synchronize()
 
+    turn = [0]
+
     def step():
-        b.sirllm_step(logits, tok, w.vocab, scores, n_held, n_new, pol, k_src, v_src, k_dst, v_dst, kept,
-                      scores_out, workspace=ws)
+        i = turn[0] % n_sets
+        turn[0] += 1
+        b.sirllm_step(logit_sets[i], tok_sets[i], w.vocab, scores, n_held, n_new, pol, k_src, v_src, k_dst, v_dst,
+                      kept, scores_out, workspace=ws)
 
     # ---- the timed region: exactly K steps between two synchronisations ------------------
     for _ in range(args.warmup):
@@ -112,8 +123,12 @@ def main():
     gather_avg, gather_med, gather_min = time_launches(
         lambda: b.sirllm_compact_kv(k_src, v_src, k_dst, v_dst, kept, n_keep, n_src=n_cand), n_k)
     new_scores = torch.zeros(S * n_new, device=dev)
-    score_avg, score_med, score_min = time_launches(
-        lambda: b.sirllm_score(logits, tok, new_scores, vocab=w.vocab, workspace=ws), n_k)
+    def score_only():
+        i = turn[0] % n_sets
+        turn[0] += 1
+        b.sirllm_score(logit_sets[i], tok_sets[i], new_scores, vocab=w.vocab, workspace=ws)
+
+    score_avg, score_med, score_min = time_launches(score_only, n_k)
     sel_avg, sel_med, sel_min = time_launches(
         lambda: b.sirllm_decay_select(scores, n_held, n_new, pol, kept, scores_out, workspace=ws), n_k)
     log(f"[bench] per launch (avg/median/min us): gather {gather_avg*1e3:.1f}/{gather_med*1e3:.1f}/{gather_min*1e3:.1f}  "
