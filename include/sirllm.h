@@ -82,8 +82,10 @@ typedef struct {
     int64_t stride_pos;
 } sirllm_kv_layout;
 
-/* Largest n_cand = n_held + n_new per stream that decay_select / step accept. */
-#define SIRLLM_MAX_CAND 32768
+/* Largest n_cand = n_held + n_new per stream that decay_select / step accept.  Up to 32768 slots a
+ * stream is selected by one workgroup without any scratch; above that the selection runs as a
+ * multi-workgroup radix select and needs the workspace (see sirllm_workspace_bytes). */
+#define SIRLLM_MAX_CAND 16777216
 
 /*
  * Token entropy (Sec. 3.2, the displayed definition of e_i):
@@ -142,6 +144,10 @@ int sirllm_score_merge(const float* partials, int32_t n_parts, int64_t part_stri
  *      scores_out[s*out_stride + j] = E[kept_idx[j]].
  * Limits: n_cand <= SIRLLM_MAX_CAND (else SIRLLM_ERR_UNSUPPORTED).  n_streams == 0 or
  * n_cand == 0 is a no-op.  scores_out must not overlap scores.
+ * workspace: sirllm_workspace_bytes(n_streams, n_cand, 0, 0) bytes of device scratch, 256-byte aligned;
+ * that is 0 (NULL accepted) up to 32768 slots per stream.  Above, the scratch is required
+ * (SIRLLM_ERR_WORKSPACE without it); it is cleared by the call itself and carries nothing over, but
+ * calls that share it must be ordered on one stream.
  */
 int sirllm_decay_select(const float* scores, int64_t scores_stride,
                         int32_t n_streams, int32_t n_held, int32_t n_new,
@@ -227,7 +233,8 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld,
  *   k, v, layout                 caches holding n_cand[s] slots of stream s (new tokens already appended);
  *                                rewritten in place as by sirllm_compact_kv_inplace.  v may be NULL.
  * scores_stride >= max_cand; idx_stride, out_stride >= min(max_cand, budget).  Three launches
- * (score, select, gather), or two when max_cand <= budget.
+ * (score, select, gather), or two when max_cand <= budget.  max_cand <= 32768 (every stream is
+ * selected by one workgroup), else SIRLLM_ERR_UNSUPPORTED.
  */
 int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld,
                        const int32_t* token_ids,
@@ -258,7 +265,7 @@ int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64
  *                             and the n_topk largest keys are kept (equal keys: lower slot).
  * When n_cand <= the kept count nothing is evicted: kept_idx = 0..n_cand-1.
  * Returns, through *n_keep_out (host pointer, may be NULL), the number of kept slots per stream.
- * Limits as for sirllm_decay_select.
+ * Limits as for sirllm_decay_select; SIRLLM_BASELINE_RANDOM takes at most 32768 slots per stream.
  */
 typedef enum {
     SIRLLM_BASELINE_STREAM   = 0,
@@ -272,7 +279,8 @@ int sirllm_baseline_select(sirllm_baseline kind, int32_t n_streams, int32_t n_ca
                            void* hip_stream);
 
 /* Bytes of device workspace the calls above need for these sizes (pass 0 for the sizes a
- * call does not have).  Never fails; the result is a multiple of 256. */
+ * call does not have): 0 unless n_cand exceeds 32768, then about 4 KB + n_cand/1024 bytes per stream.
+ * Never fails; the result is a multiple of 256. */
 size_t sirllm_workspace_bytes(int32_t n_streams, int32_t n_cand, int64_t n_rows, int32_t vocab);
 
 /* Static, NUL-terminated description of a status code. */

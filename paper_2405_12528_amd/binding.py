@@ -25,7 +25,8 @@ _lib = C.CDLL(LIB_PATH)
 
 SIRLLM_OK, SIRLLM_ERR_INVALID_ARG, SIRLLM_ERR_UNSUPPORTED, SIRLLM_ERR_WORKSPACE, SIRLLM_ERR_HIP = 0, -1, -2, -3, -4
 SIRLLM_F32, SIRLLM_BF16, SIRLLM_F16 = 0, 1, 2
-SIRLLM_MAX_CAND = 32768
+SIRLLM_MAX_CAND = 16777216
+SIRLLM_SINGLE_WG_CAND = 32768
 
 Policy = namedtuple("Policy", "n_sink n_topk n_recent decay")
 

@@ -92,8 +92,9 @@ class RaggedRetentiveCache:
         self.policy = b.Policy(*policy)
         self.budget = self.policy.n_sink + self.policy.n_topk + self.policy.n_recent
         self.capacity = self.budget + max_new
-        if self.capacity > b.SIRLLM_MAX_CAND:
-            raise ValueError(f"budget + max_new = {self.capacity} exceeds SIRLLM_MAX_CAND = {b.SIRLLM_MAX_CAND}")
+        if self.capacity > b.SIRLLM_SINGLE_WG_CAND:
+            raise ValueError(f"budget + max_new = {self.capacity} exceeds the ragged path's limit of "
+                             f"{b.SIRLLM_SINGLE_WG_CAND} slots per stream")
         self.n_streams, self.max_new, self.device = n_streams, max_new, device
         shape = (n_streams, n_layers, n_kv_heads, self.capacity, head_dim)
         self.k = torch.zeros(shape, dtype=kv_dtype, device=device)

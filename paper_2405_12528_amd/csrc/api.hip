@@ -172,8 +172,12 @@ extern "C" {
 
 size_t sirllm_workspace_bytes(int32_t n_streams, int32_t n_cand, int64_t n_rows, int32_t vocab)
 {
-    (void)n_streams; (void)n_cand; (void)n_rows; (void)vocab;
-    return 0;   // every kernel keeps its partial results in registers and LDS
+    (void)n_rows; (void)vocab;
+    // Only the selection over more than 32768 slots per stream needs scratch (global histograms and per-tile
+    // counts of its multi-workgroup radix select); every other kernel keeps its partial results in
+    // registers and LDS.
+    if (n_streams < 0 || n_cand < 0) return 0;
+    return (select_large_scratch_bytes(n_streams, n_cand) + 255) / 256 * 256;
 }
 
 const char* sirllm_status_string(int status)
@@ -249,6 +253,7 @@ int sirllm_decay_select(const float* scores, int64_t scores_stride, int32_t n_st
     const SelectArgs a = make_select_args(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx,
                                           idx_stride, scores_out, out_stride);
     if ((int64_t)n_cand <= budget_of(policy)) return hip_status(launch_keep_all(a, (hipStream_t)hip_stream));
+    if (n_cand > SIRLLM_SINGLE_WG_CAND) return hip_status(launch_select_large(a, workspace, (hipStream_t)hip_stream));
     return hip_status(launch_select(a, (hipStream_t)hip_stream));
 }
 
@@ -274,7 +279,10 @@ int sirllm_baseline_select(sirllm_baseline kind, int32_t n_streams, int32_t n_ca
     a.turn_lo = (uint32_t)turn; a.turn_hi = (uint32_t)(turn >> 32);
     hipStream_t stream = (hipStream_t)hip_stream;
     if ((int64_t)n_cand <= budget) return hip_status(launch_baseline_comb(a, 0, stream));
-    if (kind == SIRLLM_BASELINE_RANDOM && p.n_topk > 0) return hip_status(launch_baseline_random(a, stream));
+    if (kind == SIRLLM_BASELINE_RANDOM && p.n_topk > 0) {
+        if (n_cand > SIRLLM_SINGLE_WG_CAND) return SIRLLM_ERR_UNSUPPORTED;   // the random subset is drawn by one workgroup
+        return hip_status(launch_baseline_random(a, stream));
+    }
     int interval = 1;
     if (p.n_topk > 0) {
         interval = (n_cand - p.n_sink - p.n_recent) / p.n_topk;
@@ -359,7 +367,8 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, 
         }
         // E <- E * eta on the held part; Id = sink + Top_k + recent; E <- E[Id]
         if (!evict) return hip_status(launch_keep_all(s, stream));
-        rc = hip_status(launch_select(s, stream));
+        rc = hip_status(n_cand > SIRLLM_SINGLE_WG_CAND ? launch_select_large(s, workspace, stream)
+                                                         : launch_select(s, stream));
         if (rc) return rc;
     }
     // KV <- KV[Id]
@@ -379,7 +388,7 @@ int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64
     int rc = validate_score(logits, dt, total_new, vocab, ld, token_ids);
     if (rc) return rc;
     if (!policy_ok(policy)) return SIRLLM_ERR_INVALID_ARG;
-    if (max_cand > SIRLLM_MAX_CAND) return SIRLLM_ERR_UNSUPPORTED;
+    if (max_cand > SIRLLM_SINGLE_WG_CAND) return SIRLLM_ERR_UNSUPPORTED;   // ragged streams are selected by one workgroup each
     if (n_streams == 0) return SIRLLM_OK;
     if (!n_held || !cu_new || !n_keep_out || !scores || !kept_idx || !scores_out) return SIRLLM_ERR_INVALID_ARG;
     const int64_t budget = budget_of(policy);

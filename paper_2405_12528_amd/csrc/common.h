@@ -65,6 +65,13 @@ hipError_t launch_keep_all(const SelectArgs& a, hipStream_t stream);
 // Ragged batches: every stream takes its own branch (keep all, or select) on its own sizes.
 hipError_t launch_select_ragged(const SelectArgs& a, hipStream_t stream);
 
+// ---- select_large.hip -------------------------------------------------------------------
+// One workgroup holds at most this many candidate slots of a stream in registers; larger caches go
+// through the multi-workgroup path, which needs scratch.
+#define SIRLLM_SINGLE_WG_CAND 32768
+size_t select_large_scratch_bytes(int32_t n_streams, int32_t n_cand);
+hipError_t launch_select_large(const SelectArgs& a, void* scratch, hipStream_t stream);
+
 // ---- gather.hip -------------------------------------------------------------------------
 struct GatherArgs {
     const char* src[2];       // K, V (V may be null: then only tensor 0 is moved)

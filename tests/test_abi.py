@@ -135,7 +135,7 @@ def test_step_argument_errors(b):
     assert call(n_new=-1) == b.SIRLLM_ERR_INVALID_ARG
     assert call(kdst=None) == b.SIRLLM_ERR_INVALID_ARG              # eviction needs a destination
     assert call(kdst=0x10000000 + 4096) == b.SIRLLM_ERR_INVALID_ARG  # ... that does not overlap the source
-    assert call(n_held=40000) == b.SIRLLM_ERR_UNSUPPORTED
+    assert call(n_held=b.SIRLLM_MAX_CAND) == b.SIRLLM_ERR_UNSUPPORTED
     assert call(n_streams=0, logits=None, tok=None) == b.SIRLLM_OK
 
 
@@ -150,7 +150,8 @@ def test_baseline_select_argument_errors(b):
     assert call(pol=None) == b.SIRLLM_ERR_INVALID_ARG
     assert call(pol=b.sirllm_policy(4, -1, 8, 0.0)) == b.SIRLLM_ERR_INVALID_ARG
     assert call(n_cand=-1) == b.SIRLLM_ERR_INVALID_ARG
-    assert call(n_cand=40000) == b.SIRLLM_ERR_UNSUPPORTED
+    assert call(n_cand=b.SIRLLM_MAX_CAND + 1) == b.SIRLLM_ERR_UNSUPPORTED
+    assert call(kind=2, n_cand=40000, istr=40000) == b.SIRLLM_ERR_UNSUPPORTED      # random subsets: one workgroup only
     assert call(idx=None) == b.SIRLLM_ERR_INVALID_ARG
     assert call(istr=31) == b.SIRLLM_ERR_INVALID_ARG
     assert call(n_streams=0) == b.SIRLLM_OK and n_keep.value == 32       # the kept count is host arithmetic
@@ -206,6 +207,20 @@ def test_score_chunk_argument_errors(b):
     assert L.sirllm_score_merge(None, 2, 12, 4, FAKE, None) == b.SIRLLM_ERR_INVALID_ARG
     assert L.sirllm_score_merge(FAKE, 2, 12, 4, None, None) == b.SIRLLM_ERR_INVALID_ARG
     assert L.sirllm_score_merge(None, 2, 12, 0, None, None) == b.SIRLLM_OK
+
+
+def test_large_caches_need_the_workspace(b):
+    L = b.raw()
+    p = b.sirllm_policy(4, 20000, 512, 0.9)
+    need = b.sirllm_workspace_bytes(2, 40000, 0, 0)
+    assert need > 0 and need % 256 == 0
+    assert b.sirllm_workspace_bytes(2, 32768, 0, 0) == 0
+    def call(ws, ws_bytes):
+        return L.sirllm_decay_select(FAKE, 40000, 2, 39000, 1000, C.byref(p), FAKE + 0x100000, 20516,
+                                     FAKE + 0x200000, 20516, ws, ws_bytes, None)
+    assert call(None, 0) == b.SIRLLM_ERR_WORKSPACE
+    assert call(0x40000, need - 1) == b.SIRLLM_ERR_WORKSPACE
+    assert call(0x40010, need) == b.SIRLLM_ERR_WORKSPACE                  # not 256-byte aligned
 
 
 def test_binding_refuses_host_tensors(b):

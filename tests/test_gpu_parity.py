@@ -653,3 +653,90 @@ def test_score_chunks_special_cases(b, ref):
     want = ref.score(to_np(z), to_np(tok))
     assert_scores_close(got, want)
     assert abs(got[0] - np.log(300)) < 1e-5 and np.isnan(got[1:]).all()
+
+
+# ------------------------------------------------- caches beyond one workgroup (> 32768 slots)
+LARGE_CASES = [
+    # n_streams, n_held, n_new, n_sink, k, n_recent, decay, levels
+    (1, 32000, 769, 4, 16000, 512, 0.9, 0),          # just over the one-workgroup limit
+    (2, 39000, 1000, 4, 20000, 512, 0.9, 50),        # heavy ties across tiles
+    (1, 131072, 2048, 4, 100000, 2048, 0.85, 0),     # a 128K-context cache
+    (3, 50000, 0, 4, 1, 0, 0.5, 3),                  # k = 1 among three score levels
+    (1, 60000, 5000, 0, 0, 1000, 0.9, 0),            # k = 0: sliding window
+    (1, 60000, 5000, 4, 60995, 0, 1.0, 7),           # all but one middle slot kept
+    (2, 500000, 24000, 4, 262144, 2048, 0.9, 1000),  # half a million slots
+    (1, 40000, 100, 4, 50000, 512, 0.9, 0),          # under budget: keep-all path
+]
+
+
+@pytest.mark.parametrize("case", LARGE_CASES, ids=[str(c[:6]) for c in LARGE_CASES])
+def test_large_decay_select_matches_oracle(b, ref, case):
+    n_streams, n_held, n_new, n_sink, k, n_recent, decay, levels = case
+    rng = np.random.default_rng(n_held + 3 * n_new)
+    n_cand = n_held + n_new
+    if levels:
+        E = (rng.integers(0, levels, (n_streams, n_cand)) / 8.0).astype(np.float32)
+    else:
+        E = rng.gamma(2.0, 2.0, (n_streams, n_cand)).astype(np.float32)
+    pol = b.Policy(n_sink, k, n_recent, decay)
+    n_keep = min(n_cand, n_sink + k + n_recent)
+    Ed = torch.from_numpy(E).to(DEV)
+    idx = torch.full((n_streams, n_keep + 3), -7, dtype=torch.int32, device=DEV)
+    out = torch.full((n_streams, n_keep + 3), -7.0, device=DEV)
+    nbytes = b.sirllm_workspace_bytes(n_streams, n_cand, 0, 0)
+    ws = torch.full((nbytes + 256,), 0x5A, dtype=torch.uint8, device=DEV)     # dirty on purpose: the call clears what it needs
+    for rep in range(2):                                                       # a second call on the used scratch
+        b.sirllm_decay_select(Ed, n_held, n_new, pol, idx, out, workspace=ws[:nbytes] if nbytes else None)
+        torch.cuda.synchronize()
+        ri, ro = ref.decay_select(E, n_held, n_new, ref.Policy(*pol))
+        np.testing.assert_array_equal(to_np(idx)[:, :n_keep], ri)
+        np.testing.assert_array_equal(to_np(out)[:, :n_keep].view(np.uint32), ro.view(np.uint32))
+        assert (to_np(idx)[:, n_keep:] == -7).all()
+    assert bool((ws[nbytes:] == 0x5A).all())
+
+
+def test_large_select_special_values(b, ref):
+    n = 70000
+    special = np.array([0.0, -0.0, 1e-41, -1e-41, np.inf, -np.inf, 3.0, -3.0, 2.5, 2.5], dtype=np.float32)
+    E = np.tile(special, n // len(special))[None, :].copy()
+    E.view(np.uint32)[0, 9] = 0x7FC00000
+    E.view(np.uint32)[0, 50017] = 0xFFC00000
+    ws = torch.zeros(b.sirllm_workspace_bytes(1, n, 0, 0), dtype=torch.uint8, device=DEV)
+    for k in (1, 6999, 7000, 7001, 35000, 69000):
+        pol = b.Policy(2, k, 2, 0.5)
+        n_keep = 4 + k
+        idx = torch.zeros((1, n_keep), dtype=torch.int32, device=DEV)
+        out = torch.zeros((1, n_keep), device=DEV)
+        b.sirllm_decay_select(torch.from_numpy(E).to(DEV), 35000, 35000, pol, idx, out, workspace=ws)
+        torch.cuda.synchronize()
+        ri, ro = ref.decay_select(E, 35000, 35000, ref.Policy(*pol))
+        np.testing.assert_array_equal(to_np(idx), ri)
+        np.testing.assert_array_equal(to_np(out).view(np.uint32), ro.view(np.uint32))
+
+
+def test_step_with_a_large_cache(b, ref):
+    # the whole step over 40000 candidate slots (selection through the multi-workgroup path), small planes
+    import dataclasses
+    w2 = dataclasses.replace(synth.WORKLOADS["tiny"], vocab=500)
+    pol = b.Policy(4, 30000, 512, 0.9)
+    S, n_held, n_new = 1, 39000, 1000
+    g0 = torch.Generator(device=DEV).manual_seed(21)
+    z = torch.randn((S * n_new, 500), generator=g0, device=DEV) * 2
+    tok = torch.randint(0, 500, (S * n_new,), generator=g0, device=DEV, dtype=torch.int32)
+    held = torch.rand((S, n_held), generator=g0, device=DEV) * 6
+    k_c = torch.randn((S, 1, 2, n_held + n_new, 8), generator=g0, device=DEV)
+    v_c = torch.randn((S, 1, 2, n_held + n_new, 8), generator=g0, device=DEV)
+    n_cand, n_keep = n_held + n_new, 30516
+    E = torch.full((S, n_cand), -5.0, device=DEV)
+    E[:, :n_held] = held
+    idx = torch.full((S, n_keep), -7, dtype=torch.int32, device=DEV)
+    out = torch.full((S, n_keep), -7.0, device=DEV)
+    k_d = torch.zeros((S, 1, 2, n_keep, 8), device=DEV)
+    v_d = torch.zeros((S, 1, 2, n_keep, 8), device=DEV)
+    ws = torch.zeros(b.sirllm_workspace_bytes(S, n_cand, S * n_new, 500), dtype=torch.uint8, device=DEV)
+    with pytest.raises(b.SirllmError):                       # the scratch is not optional here
+        b.sirllm_step(z, tok, 500, E, n_held, n_new, pol, k_c, v_c, k_d, v_d, idx, out)
+    b.sirllm_step(z, tok, 500, E, n_held, n_new, pol, k_c, v_c, k_d, v_d, idx, out, workspace=ws)
+    torch.cuda.synchronize()
+    g = dict(E=E, idx=idx, out=out, k=k_d, v=v_d, n_keep=n_keep, evicted=True)
+    check_step_against_oracle(b, ref, w2, z, tok, held, k_c, v_c, g, pol=pol)
