@@ -31,6 +31,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama3_8b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ragged-inplace", action="store_true",
+                    help="also time sirllm_step_ragged (per-stream sizes in device memory, in-place compaction) on "
+                         "the same shapes; reported under 'ragged_inplace' in the JSON line")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = min(16, host cores)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -156,6 +159,24 @@ def main():
                                "decay_select": round(sel_avg * 1e3, 2)},
                 "score_gbps": round(bytes_["score"] / (score_avg * 1e-3) / 1e9, 1)}
 
+    # ---- optional: the ragged in-place step on the same shapes --------------------------------
+    ragged = None
+    if args.ragged_inplace and n_cand <= b.SIRLLM_SINGLE_WG_CAND:
+        held_dev = torch.full((S,), n_held, dtype=torch.int32, device=dev)
+        cu_dev = torch.arange(0, (S + 1) * n_new, n_new, dtype=torch.int32, device=dev)
+        keep_dev = torch.zeros(S, dtype=torch.int32, device=dev)
+
+        def ragged_step():      # repeated in place on the same buffers: the data changes, the traffic does not
+            i = turn[0] % n_sets
+            turn[0] += 1
+            b.sirllm_step_ragged(logit_sets[i], tok_sets[i], w.vocab, scores, held_dev, cu_dev, S * n_new, n_cand, pol,
+                                 k_src, v_src, kept, scores_out, keep_dev, workspace=ws)
+
+        r_avg, r_med, r_min = time_launches(ragged_step, n_k, group=4)
+        ragged = {"ms_per_step": round(r_avg, 5), "hbm_gbps": round(bytes_["total"] / (r_avg * 1e-3) / 1e9, 1),
+                  "frac": round(bytes_["total"] / (r_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        log(f"[bench] ragged in-place step: {r_avg*1e3:.1f} us -> {ragged['hbm_gbps']:.0f} GB/s")
+
     # ---- the oracle on the host cores, same bytes, as a reported baseline ----------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -172,6 +193,8 @@ def main():
         "step_hbm_gbps": round(step_gbps, 1), "step_pct_of_peak": round(100 * step_gbps / HBM_PEAK_GBPS, 2),
         "roofline": roofline, "cpu_baseline": cpu,
     }
+    if ragged:
+        out["ragged_inplace"] = ragged
     print(json.dumps(out), flush=True)
 
 

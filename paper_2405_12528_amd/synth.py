@@ -103,6 +103,12 @@ WORKLOADS = {
                              spike=0.0, spike_frac=0.0, n_sink=4, n_topk=1020, n_recent=0, decay=0.8,
                              n_layers=32, n_kv_heads=32, head_dim=128, kv_dtype="bf16", n_cand=1078,
                              n_turns=2000, checked_turns=(1, 19, 20, 100, 300)),
+    # A long-context cache: the Llama-3-8B shape with a 128K-slot budget (the pre-training length of its
+    # long-context variants), 2048 new tokens per turn.  35 GB of K/V in flight per step; the selection runs
+    # over 133120 candidate slots, beyond what one workgroup holds.
+    "llama3_128k": Workload("llama3_128k", vocab=128256, n_new=2048, logits_dtype="f32", sigma=4.0, zipf_a=1.05,
+                            spike=0.0, spike_frac=0.0, n_sink=4, n_topk=129020, n_recent=2048, decay=0.9,
+                            n_layers=32, n_kv_heads=8, head_dim=128, kv_dtype="bf16", n_cand=133120),
 }
 
 _KIND = {"logits": 1, "tokens": 2, "held": 3, "kv_k": 4, "kv_v": 5, "rank": 6, "spike": 7}

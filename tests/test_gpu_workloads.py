@@ -62,6 +62,45 @@ def test_full_size_step(b, ref, name):
     assert np.array_equal(to_np(v_dst), rv), "compacted V differs from the oracle"
 
 
+@pytest.mark.timeout(600)
+def test_long_context_step(b, ref):
+    """A 128K-slot budget at the Llama-3-8B shape: 133120 candidates (selection by the multi-workgroup path),
+    35 GB of K/V read and written.  Scores and the kept set are checked in full, K/V on sampled planes."""
+    w = synth.WORKLOADS["llama3_128k"]
+    ref.set_threads(16)
+    pol = b.Policy(w.n_sink, w.n_topk, w.n_recent, w.decay)
+    S, n_held, n_new, n_cand, n_keep = w.n_streams, w.n_held, w.n_new, w.n_cand, w.n_keep
+    logits = synth.make_logits(w, turn=1, device=DEV)
+    tok = synth.make_token_ids(w, turn=1, device=DEV)
+    scores = torch.full((S, n_cand), -3.0, device=DEV)
+    held = synth.make_held_scores(w, device=DEV)
+    scores[:, :n_held] = held
+    k_src = synth.make_kv(w, device=DEV, which="k")
+    v_src = synth.make_kv(w, device=DEV, which="v")
+    dst_shape = (S, w.n_layers, w.n_kv_heads, n_keep, w.head_dim)
+    k_dst = torch.zeros(dst_shape, dtype=k_src.dtype, device=DEV)
+    v_dst = torch.zeros(dst_shape, dtype=k_src.dtype, device=DEV)
+    kept = torch.full((S, n_keep), -1, dtype=torch.int32, device=DEV)
+    out = torch.full((S, n_keep), -1.0, device=DEV)
+    ws = torch.zeros(b.sirllm_workspace_bytes(S, n_cand, S * n_new, w.vocab), dtype=torch.uint8, device=DEV)
+    assert ws.numel() > 0
+    b.sirllm_step(logits, tok, w.vocab, scores, n_held, n_new, pol, k_src, v_src, k_dst, v_dst, kept, out, workspace=ws)
+    torch.cuda.synchronize()
+    Eg = to_np(scores)
+    want = ref.score(to_np(logits), to_np(tok), vocab=w.vocab).reshape(S, n_new)
+    assert_scores_close(Eg[:, n_held:], want)
+    ri, ro = ref.decay_select(Eg, n_held, n_new, ref.Policy(*pol))
+    np.testing.assert_array_equal(to_np(kept), ri)
+    np.testing.assert_array_equal(to_np(out).view(np.uint32), ro.view(np.uint32))
+    assert ri.shape[1] == w.budget == 131072
+    rng = np.random.default_rng(1)
+    for _ in range(10):
+        l, h = int(rng.integers(w.n_layers)), int(rng.integers(w.n_kv_heads))
+        src_t, dst_t = (k_src, k_dst) if rng.integers(2) else (v_src, v_dst)
+        rp, _ = ref.compact_kv(to_np(src_t[:, l:l + 1, h:h + 1]), None, ri)
+        assert np.array_equal(to_np(dst_t[:, l:l + 1, h:h + 1]), rp), f"plane (layer {l}, head {h}) differs"
+
+
 @pytest.mark.timeout(900)
 def test_batched_dialogue_200_turns(b, ref):
     """32 streams x 200 turns x 256 tokens; scores persist across turns; checked at turns 1, 50, 200."""
