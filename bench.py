@@ -170,7 +170,7 @@ def main():
             i = turn[0] % n_sets
             turn[0] += 1
             b.sirllm_step_ragged(logit_sets[i], tok_sets[i], w.vocab, scores, held_dev, cu_dev, S * n_new, n_cand, pol,
-                                 k_src, v_src, kept, scores_out, keep_dev, workspace=ws)
+                                 k_src, v_src, kept, scores_out, keep_dev, max_new=n_new, workspace=ws)
 
         r_avg, r_med, r_min = time_launches(ragged_step, n_k, group=4)
         ragged = {"ms_per_step": round(r_avg, 5), "hbm_gbps": round(bytes_["total"] / (r_avg * 1e-3) / 1e9, 1),

@@ -227,20 +227,22 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld,
  *     is written to DEVICE memory (it is the stream's n_held for the next turn).
  *   n_held, cu_new, n_keep_out   device arrays of n_streams, n_streams+1, n_streams int32
  *   total_new                    host copy of cu_new[n_streams]
- *   max_cand                     host upper bound of n_cand[s]; sizes the launch.  A stream whose
- *                                n_cand[s] exceeds it (or whose sizes are negative) is left alone and
- *                                gets n_keep_out[s] = -1.
+ *   max_cand, max_new            host upper bounds of n_cand[s] and n_new[s]; they size the launches.  A
+ *                                stream whose sizes exceed them (or are negative) gets n_keep_out[s] = -1:
+ *                                its kept_idx row and its K/V are left alone, its score rows are
+ *                                unspecified.  When max_new <= n_recent no new token can compete in
+ *                                Top_k, and scoring and selection share one launch.
  *   k, v, layout                 caches holding n_cand[s] slots of stream s (new tokens already appended);
  *                                rewritten in place as by sirllm_compact_kv_inplace.  v may be NULL.
- * scores_stride >= max_cand; idx_stride, out_stride >= min(max_cand, budget).  Three launches
- * (score, select, gather), or two when max_cand <= budget.  max_cand <= 32768 (every stream is
+ * scores_stride >= max_cand; idx_stride, out_stride >= min(max_cand, budget).  At most three launches
+ * (score, select, gather).  max_cand <= 32768 (every stream is
  * selected by one workgroup), else SIRLLM_ERR_UNSUPPORTED.
  */
 int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld,
                        const int32_t* token_ids,
                        float* scores, int64_t scores_stride,
                        int32_t n_streams, const int32_t* n_held, const int32_t* cu_new,
-                       int64_t total_new, int32_t max_cand,
+                       int64_t total_new, int32_t max_cand, int32_t max_new,
                        const sirllm_policy* policy,
                        void* k, void* v, const sirllm_kv_layout* layout,
                        int32_t* kept_idx, int64_t idx_stride,

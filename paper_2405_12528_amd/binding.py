@@ -59,7 +59,7 @@ _lib.sirllm_baseline_select.argtypes = [C.c_int, _i32, _i32, _PP, C.c_uint64, C.
 _lib.sirllm_baseline_select.restype = C.c_int
 _lib.sirllm_compact_kv_inplace.argtypes = [_vp, _vp, _LP, _i32, _vp, _i64, _i32, _i32, _vp]
 _lib.sirllm_compact_kv_inplace.restype = C.c_int
-_lib.sirllm_step_ragged.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _vp, _vp, _i64, _i32, _PP,
+_lib.sirllm_step_ragged.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _vp, _vp, _i64, _i32, _i32, _PP,
                                     _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _vp]
 _lib.sirllm_step_ragged.restype = C.c_int
 _lib.sirllm_score_partial.argtypes = [_vp, C.c_int, _i64, _i32, _i64, _i32, _vp, _vp, _vp]
@@ -297,8 +297,11 @@ def sirllm_step(logits: torch.Tensor, token_ids: torch.Tensor, vocab: int, score
 def sirllm_step_ragged(logits: torch.Tensor, token_ids: torch.Tensor, vocab: int, scores: torch.Tensor,
                        n_held: torch.Tensor, cu_new: torch.Tensor, total_new: int, max_cand: int, policy,
                        k: torch.Tensor, v, kept_idx: torch.Tensor, scores_out: torch.Tensor,
-                       n_keep_out: torch.Tensor, workspace: torch.Tensor | None = None, stream=None) -> None:
-    """Ragged in-place step: per-stream sizes in the device int32 arrays n_held [S] and cu_new [S+1]."""
+                       n_keep_out: torch.Tensor, max_new: int | None = None, workspace: torch.Tensor | None = None,
+                       stream=None) -> None:
+    """Ragged in-place step: per-stream sizes in the device int32 arrays n_held [S] and cu_new [S+1];
+    max_cand / max_new are host upper bounds of n_held[s] + n_new[s] and n_new[s] (max_new defaults to
+    min(total_new, max_cand), which is always a valid bound)."""
     _on_device(logits, token_ids, scores, n_held, cu_new, k, v, kept_idx, scores_out, n_keep_out, workspace)
     n_streams = scores.shape[0]
     for t, n in ((n_held, n_streams), (cu_new, n_streams + 1), (n_keep_out, n_streams)):
@@ -322,7 +325,8 @@ def sirllm_step_ragged(logits: torch.Tensor, token_ids: torch.Tensor, vocab: int
     dtc = _dtype_code(logits) if total_new > 0 else SIRLLM_F32
     _check(_lib.sirllm_step_ragged(_ptr(logits) if total_new else None, dtc, int(vocab), ld,
                                    _ptr(token_ids) if total_new else None, _ptr(scores), _row_stride(scores),
-                                   n_streams, _ptr(n_held), _ptr(cu_new), int(total_new), int(max_cand), C.byref(p),
+                                   n_streams, _ptr(n_held), _ptr(cu_new), int(total_new), int(max_cand),
+                                   int(min(total_new, max_cand) if max_new is None else max_new), C.byref(p),
                                    _ptr(k), _ptr(v), C.byref(lay), _ptr(kept_idx), _row_stride(kept_idx),
                                    _ptr(scores_out), _row_stride(scores_out), _ptr(n_keep_out), wp, wb,
                                    _stream(stream)), "sirllm_step_ragged")

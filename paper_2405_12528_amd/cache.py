@@ -131,7 +131,8 @@ class RaggedRetentiveCache:
         cur, oth = self._cur, 1 - self._cur
         b.sirllm_step_ragged(logits, token_ids, vocab, self._scores[cur], self._held_dev[cur], cu_dev, cu[-1],
                              max_cand, self.policy, self.k, self.v, self.kept_idx, self._scores[oth],
-                             self._held_dev[oth], workspace=self._ws, stream=stream)
+                             self._held_dev[oth], max_new=max(int(n) for n in n_new), workspace=self._ws,
+                             stream=stream)
         self._cur = oth
         evicted = [h + int(n) > self.budget for h, n in zip(self.n_held, n_new)]
         self.n_held = [min(h + int(n), self.budget) for h, n in zip(self.n_held, n_new)]

@@ -138,7 +138,7 @@ SelectArgs make_select_args(const float* scores, int64_t scores_stride, int32_t 
     a.kept_idx = kept_idx; a.idx_stride = idx_stride;
     a.scores_out = scores_out; a.out_stride = out_stride;
     a.seed_lo = a.seed_hi = a.turn_lo = a.turn_hi = 0;
-    a.held_dev = nullptr; a.cu_new_dev = nullptr; a.n_keep_dev = nullptr;
+    a.held_dev = nullptr; a.cu_new_dev = nullptr; a.n_keep_dev = nullptr; a.max_new = 0x7fffffff;
     return a;
 }
 
@@ -208,7 +208,7 @@ int sirllm_score(const void* logits, sirllm_dtype dt, int64_t n_rows, int32_t vo
     a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
     a.n_rows = n_rows; a.rows_per_stream = n_rows;
     a.out_a = scores_out; a.stride_a = 0; a.out_b = nullptr; a.stride_b = 0;
-    a.partial = nullptr; a.v_begin = 0; a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0;
+    a.partial = nullptr; a.v_begin = 0; a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0; a.budget_r = 0;
     return hip_status(launch_score(a, dt, (hipStream_t)hip_stream));
 }
 
@@ -224,7 +224,7 @@ int sirllm_score_partial(const void* logits_chunk, sirllm_dtype dt, int64_t n_ro
     a.logits = logits_chunk; a.ld = ld; a.vocab = n_cols; a.token_ids = token_ids;
     a.n_rows = n_rows; a.rows_per_stream = n_rows;
     a.out_a = nullptr; a.stride_a = 0; a.out_b = nullptr; a.stride_b = 0;
-    a.partial = partial; a.v_begin = v_begin; a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0;
+    a.partial = partial; a.v_begin = v_begin; a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0; a.budget_r = 0;
     return hip_status(launch_score(a, dt, (hipStream_t)hip_stream));
 }
 
@@ -349,7 +349,7 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, 
     a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
     a.n_rows = n_rows; a.rows_per_stream = n_new > 0 ? n_new : 1;
     a.out_a = scores + n_held; a.stride_a = scores_stride; a.out_b = nullptr; a.stride_b = 0;
-    a.partial = nullptr; a.v_begin = 0; a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0;
+    a.partial = nullptr; a.v_begin = 0; a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0; a.budget_r = 0;
     const SelectArgs s = make_select_args(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx,
                                           idx_stride, scores_out, out_stride);
     if (evict && score_select_fusable(a, s)) {
@@ -379,12 +379,13 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, 
 
 int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
                        float* scores, int64_t scores_stride, int32_t n_streams, const int32_t* n_held,
-                       const int32_t* cu_new, int64_t total_new, int32_t max_cand, const sirllm_policy* policy,
+                       const int32_t* cu_new, int64_t total_new, int32_t max_cand, int32_t max_new,
+                       const sirllm_policy* policy,
                        void* k, void* v, const sirllm_kv_layout* layout, int32_t* kept_idx, int64_t idx_stride,
                        float* scores_out, int64_t out_stride, int32_t* n_keep_out, void* workspace,
                        size_t workspace_bytes, void* hip_stream)
 {
-    if (n_streams < 0 || total_new < 0 || max_cand < 0) return SIRLLM_ERR_INVALID_ARG;
+    if (n_streams < 0 || total_new < 0 || max_cand < 0 || max_new < 0 || max_new > max_cand) return SIRLLM_ERR_INVALID_ARG;
     int rc = validate_score(logits, dt, total_new, vocab, ld, token_ids);
     if (rc) return rc;
     if (!policy_ok(policy)) return SIRLLM_ERR_INVALID_ARG;
@@ -410,19 +411,26 @@ int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64
     if (rc) return rc;
     hipStream_t stream = (hipStream_t)hip_stream;
 
-    if (total_new > 0) {
-        ScoreArgs a;
-        a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
-        a.n_rows = total_new; a.rows_per_stream = 1;
-        a.out_a = scores; a.stride_a = scores_stride; a.out_b = nullptr; a.stride_b = 0;
-        a.partial = nullptr; a.v_begin = 0; a.cu_rows = cu_new; a.held_dev = n_held; a.n_streams_r = n_streams;
-        rc = hip_status(launch_score(a, dt, stream));
-        if (rc) return rc;
-    }
+    ScoreArgs a;
+    a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
+    a.n_rows = total_new; a.rows_per_stream = 1;
+    a.out_a = scores; a.stride_a = scores_stride; a.out_b = nullptr; a.stride_b = 0;
+    a.partial = nullptr; a.v_begin = 0;
+    a.cu_rows = cu_new; a.held_dev = n_held; a.n_streams_r = n_streams; a.budget_r = (int32_t)(budget < 0x7fffffff ? budget : 0x7fffffff);
     SelectArgs s = make_select_args(scores, scores_stride, n_streams, 0, max_cand, policy, kept_idx, idx_stride,
                                     scores_out, out_stride);
-    s.held_dev = n_held; s.cu_new_dev = cu_new; s.n_keep_dev = n_keep_out;
-    rc = hip_status(launch_select_ragged(s, stream));
+    s.held_dev = n_held; s.cu_new_dev = cu_new; s.n_keep_dev = n_keep_out; s.max_new = max_new;
+    if (score_select_ragged_fusable(a, s)) {
+        // no stream brings more new tokens than the recent window holds: score and select in one launch
+        a.out_b = scores_out; a.stride_b = out_stride;
+        rc = hip_status(launch_score_select_ragged(a, s, dt, stream));
+    } else {
+        if (total_new > 0) {
+            rc = hip_status(launch_score(a, dt, stream));
+            if (rc) return rc;
+        }
+        rc = hip_status(launch_select_ragged(s, stream));
+    }
     if (rc || !may_evict) return rc;
     const GatherArgs g = make_gather_args(k, v, layout, max_cand, k, v, layout, kept_idx, idx_stride, n_streams,
                                           (int32_t)budget);

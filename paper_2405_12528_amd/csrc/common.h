@@ -35,6 +35,7 @@ struct ScoreArgs {
     const int32_t* cu_rows;   // device [n_streams_r + 1], or null for uniform batches
     const int32_t* held_dev;  // device [n_streams_r]
     int32_t n_streams_r;
+    int32_t budget_r;         // ragged + out_b: token t of stream s also goes to out_b[s*stride_b + n_keep[s] - n_new[s] + t]
 };
 hipError_t launch_score(const ScoreArgs& a, sirllm_dtype dt, hipStream_t stream);
 // Merges n_parts sets of (m, s, z_tok) triples (set p starts at partials + p*part_stride) into scores.
@@ -57,6 +58,7 @@ struct SelectArgs {
     const int32_t* held_dev;  // [n_streams]
     const int32_t* cu_new_dev;// [n_streams + 1]
     int32_t* n_keep_dev;      // [n_streams], written: min(n_cand[s], budget), or -1 when n_cand[s] exceeds the bound
+    int32_t max_new;          // ragged: the caller's bound on n_new[s] (a stream above it is flagged like one above n_cand)
 };
 // n_cand > budget: decay + radix select + index build, one workgroup per stream.
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
@@ -105,6 +107,9 @@ hipError_t launch_baseline_random(const SelectArgs& a, hipStream_t stream);     
 // tokens all fall inside the recent window, so the selection never reads this turn's scores).
 // The caller points sa.out_b at the tail of scores_out where the new scores belong.
 bool score_select_fusable(const ScoreArgs& sa, const SelectArgs& se);
+// The same for a ragged batch whose streams all bring at most n_recent new tokens (se.max_new <= se.n_recent).
+bool score_select_ragged_fusable(const ScoreArgs& sa, const SelectArgs& se);
+hipError_t launch_score_select_ragged(const ScoreArgs& sa, const SelectArgs& se, sirllm_dtype dt, hipStream_t stream);
 hipError_t launch_score_select(const ScoreArgs& sa, const SelectArgs& se, sirllm_dtype dt, hipStream_t stream);
 
 }  // namespace sirllm

@@ -29,6 +29,40 @@ __global__ __launch_bounds__(kBlock) void score_select_kernel(ScoreArgs sa, Sele
     }
 }
 
+// Ragged batch: the same split of roles, every selecting workgroup on its stream's own sizes.
+template <int DT, int KPT, bool NT>
+__global__ __launch_bounds__(kBlock) void score_select_ragged_kernel(ScoreArgs sa, SelectArgs se)
+{
+    __shared__ union {
+        select_dev::SelectSmem<kBlock> sel;
+        score_dev::ScoreSmem<kBlock> sc;
+    } sm;
+    if ((int)blockIdx.x < se.n_streams) {
+        select_dev::select_ragged_stream<kBlock, KPT, true>(se, (int)blockIdx.x, sm.sel);
+    } else {
+        score_dev::score_row<DT, kBlock, 4, NT>(sa, (int64_t)blockIdx.x - se.n_streams, sm.sc);
+    }
+}
+
+template <int DT, int KPT>
+hipError_t launch_ragged_kpt(const ScoreArgs& sa, const SelectArgs& se, hipStream_t stream)
+{
+    const dim3 grid((unsigned)(sa.n_rows + se.n_streams)), block(kBlock);
+    if (tuning::get("SIRLLM_SCORE_NT", 1) != 0)
+        hipLaunchKernelGGL((score_select_ragged_kernel<DT, KPT, true>), grid, block, 0, stream, sa, se);
+    else
+        hipLaunchKernelGGL((score_select_ragged_kernel<DT, KPT, false>), grid, block, 0, stream, sa, se);
+    return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_ragged_esize(const ScoreArgs& sa, const SelectArgs& se, hipStream_t stream)
+{
+    const int need = (se.n_cand + kBlock - 1) / kBlock;
+    if (need <= 2) return launch_ragged_kpt<DT, 2>(sa, se, stream);
+    return launch_ragged_kpt<DT, 8>(sa, se, stream);
+}
+
 template <int DT, int KPT>
 hipError_t launch_kpt(const ScoreArgs& sa, const SelectArgs& se, hipStream_t stream)
 {
@@ -57,6 +91,22 @@ bool score_select_fusable(const ScoreArgs& sa, const SelectArgs& se)
     // more than 8 slots per lane in the selecting workgroup would cost the scorers their occupancy
     return sa.n_rows > 0 && n_new <= se.n_recent && se.n_cand <= kBlock * 8 &&
            sa.n_rows + se.n_streams <= 0x7fffffffLL;
+}
+
+bool score_select_ragged_fusable(const ScoreArgs& sa, const SelectArgs& se)
+{
+    if (tuning::get("SIRLLM_FUSE_SELECT", 1) == 0) return false;
+    return sa.n_rows > 0 && se.max_new <= se.n_recent && se.n_cand <= kBlock * 8 &&
+           sa.n_rows + se.n_streams <= 0x7fffffffLL;
+}
+
+hipError_t launch_score_select_ragged(const ScoreArgs& sa, const SelectArgs& se, sirllm_dtype dt, hipStream_t stream)
+{
+    switch (dt) {
+    case SIRLLM_F32:  return launch_ragged_esize<SIRLLM_F32>(sa, se, stream);
+    case SIRLLM_BF16: return launch_ragged_esize<SIRLLM_BF16>(sa, se, stream);
+    default:          return launch_ragged_esize<SIRLLM_F16>(sa, se, stream);
+    }
 }
 
 hipError_t launch_score_select(const ScoreArgs& sa, const SelectArgs& se, sirllm_dtype dt, hipStream_t stream)

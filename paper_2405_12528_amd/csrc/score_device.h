@@ -219,9 +219,19 @@ __device__ __forceinline__ void score_row(const ScoreArgs& a, int64_t row, Score
                 const int mid = (lo + hi) >> 1;
                 if ((int64_t)a.cu_rows[mid] <= row) lo = mid; else hi = mid;
             }
-            const int64_t pos = (int64_t)a.held_dev[lo] + (row - a.cu_rows[lo]);
+            const int64_t t = row - a.cu_rows[lo];
+            const int64_t held = a.held_dev[lo];
+            const int64_t pos = held + t;
             if (pos >= 0 && pos < a.stride_a)            // sizes the caller did not promise are dropped, not written
                 a.out_a[lo * a.stride_a + pos] = e;
+            if (a.out_b) {
+                // the token's place in the compacted score cache: the new tokens are the tail of the kept list
+                const int64_t n_new = a.cu_rows[lo + 1] - a.cu_rows[lo];
+                const int64_t n_cand = held + n_new;
+                const int64_t n_keep = n_cand < a.budget_r ? n_cand : a.budget_r;
+                const int64_t posb = n_keep - n_new + t;
+                if (posb >= 0 && posb < a.stride_b) a.out_b[lo * a.stride_b + posb] = e;
+            }
         } else {
             const int64_t stream = row / a.rows_per_stream;
             const int64_t t = row - stream * a.rows_per_stream;

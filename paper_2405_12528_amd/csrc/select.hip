@@ -15,30 +15,11 @@ __global__ __launch_bounds__(BLOCK) void select_kernel(SelectArgs a)
     select_dev::select_stream<BLOCK, KPT, false>(a, (int)blockIdx.x, sm);
 }
 
-// Ragged batch: the workgroup reads its stream's own sizes, then either keeps everything (decay
-// only) or runs the selection.
 template <int BLOCK, int KPT>
 __global__ __launch_bounds__(BLOCK) void select_ragged_kernel(SelectArgs a)
 {
     __shared__ select_dev::SelectSmem<BLOCK> sm;
-    const int s = (int)blockIdx.x;
-    SelectArgs b = a;
-    b.n_held = a.held_dev[s];
-    b.n_cand = b.n_held + (a.cu_new_dev[s + 1] - a.cu_new_dev[s]);
-    const int budget = a.n_sink + a.n_topk + a.n_recent;
-    const bool fits = b.n_held >= 0 && b.n_cand >= b.n_held && b.n_cand <= a.n_cand && b.n_cand <= BLOCK * KPT;
-    if (threadIdx.x == 0) a.n_keep_dev[s] = !fits ? -1 : (b.n_cand < budget ? b.n_cand : budget);
-    if (!fits) return;                      // sizes beyond what the caller promised: flagged, nothing written
-    if (b.n_cand <= budget) {
-        for (int i = threadIdx.x; i < b.n_cand; i += BLOCK) {
-            float e = a.scores[(int64_t)s * a.scores_stride + i];
-            if (i < b.n_held) e = __fmul_rn(e, a.decay);
-            a.kept_idx[(int64_t)s * a.idx_stride + i] = i;
-            a.scores_out[(int64_t)s * a.out_stride + i] = e;
-        }
-        return;
-    }
-    select_dev::select_stream<BLOCK, KPT, false>(b, s, sm);
+    select_dev::select_ragged_stream<BLOCK, KPT, false>(a, (int)blockIdx.x, sm);
 }
 
 __global__ __launch_bounds__(256) void keep_all_kernel(SelectArgs a)

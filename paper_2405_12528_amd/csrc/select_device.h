@@ -207,5 +207,34 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, S
     }
 }
 
+// One stream of a ragged batch: the workgroup reads the stream's own sizes, flags sizes beyond what the
+// caller promised, then either keeps everything (decay only) or runs the selection.
+template <int BLOCK, int KPT, bool NEW_ELSEWHERE>
+__device__ __forceinline__ void select_ragged_stream(const SelectArgs& a, int s, SelectSmem<BLOCK>& sm)
+{
+    SelectArgs b = a;
+    b.n_held = a.held_dev[s];
+    const int n_new = a.cu_new_dev[s + 1] - a.cu_new_dev[s];
+    b.n_cand = b.n_held + n_new;
+    const int budget = a.n_sink + a.n_topk + a.n_recent;
+    const bool fits = b.n_held >= 0 && n_new >= 0 && n_new <= a.max_new && b.n_cand <= a.n_cand &&
+                      b.n_cand <= BLOCK * KPT;
+    if (threadIdx.x == 0) a.n_keep_dev[s] = !fits ? -1 : (b.n_cand < budget ? b.n_cand : budget);
+    if (!fits) return;                      // flagged, nothing written (uniform over the workgroup)
+    if (b.n_cand <= budget) {
+        const int n_read = NEW_ELSEWHERE ? b.n_held : b.n_cand;
+        for (int i = threadIdx.x; i < b.n_cand; i += BLOCK) {
+            a.kept_idx[(int64_t)s * a.idx_stride + i] = i;
+            if (i < n_read) {
+                float e = a.scores[(int64_t)s * a.scores_stride + i];
+                if (i < b.n_held) e = __fmul_rn(e, a.decay);
+                a.scores_out[(int64_t)s * a.out_stride + i] = e;
+            }
+        }
+        return;
+    }
+    select_stream<BLOCK, KPT, NEW_ELSEWHERE>(b, s, sm);
+}
+
 }  // namespace select_dev
 }  // namespace sirllm

@@ -175,16 +175,18 @@ def test_inplace_and_ragged_argument_errors(b):
     assert inplace(n_keep=0) == b.SIRLLM_OK and inplace(n_streams=0) == b.SIRLLM_OK
     p = b.sirllm_policy(4, 20, 8, 0.9)
     def ragged(logits=0x1000, dt=0, vocab=1000, ld=1000, tok=0x2000000, scores=0x3000000, sstr=128, n_streams=2,
-               held=0x7000000, cu=0x7100000, total=64, max_cand=100, pol=p, k=0x10000000, v=0x20000000, l=lay,
-               idx=0x5000000, istr=32, out=0x6000000, ostr=32, keep=0x7200000):
+               held=0x7000000, cu=0x7100000, total=64, max_cand=100, max_new=64, pol=p, k=0x10000000, v=0x20000000,
+               l=lay, idx=0x5000000, istr=32, out=0x6000000, ostr=32, keep=0x7200000):
         return L.sirllm_step_ragged(logits, dt, vocab, ld, tok, scores, sstr, n_streams, held, cu, total, max_cand,
-                                    C.byref(pol) if pol else None, k, v, C.byref(l) if l else None, idx, istr, out,
+                                    max_new, C.byref(pol) if pol else None, k, v, C.byref(l) if l else None, idx, istr, out,
                                     ostr, keep, None, 0, None)
     assert ragged(dt=9) == b.SIRLLM_ERR_UNSUPPORTED
     assert ragged(total=-1) == b.SIRLLM_ERR_INVALID_ARG
     assert ragged(logits=None) == b.SIRLLM_ERR_INVALID_ARG
     assert ragged(pol=None) == b.SIRLLM_ERR_INVALID_ARG
     assert ragged(max_cand=40000) == b.SIRLLM_ERR_UNSUPPORTED
+    assert ragged(max_new=-1) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged(max_new=101) == b.SIRLLM_ERR_INVALID_ARG              # more new tokens than candidates
     assert ragged(held=None) == b.SIRLLM_ERR_INVALID_ARG
     assert ragged(cu=None) == b.SIRLLM_ERR_INVALID_ARG
     assert ragged(keep=None) == b.SIRLLM_ERR_INVALID_ARG

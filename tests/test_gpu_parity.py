@@ -521,7 +521,8 @@ def test_compact_inplace_strided_view_and_bad_indices(b, ref):
 
 
 # ------------------------------------------------------------------------------ ragged batches
-def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=torch.float32, cap=None):
+def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=torch.float32, cap=None,
+               tight_new=True):
     """One ragged step on the GPU and in the oracle; compares everything the step writes."""
     n_held, n_new = np.asarray(n_held), np.asarray(n_new)
     n_cand = n_held + n_new
@@ -546,7 +547,9 @@ def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=
     held_dev = torch.from_numpy(n_held.astype(np.int32)).to(DEV)
     cu = torch.from_numpy(np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)).to(DEV)
     hs, hk, hv = to_np(scores).copy(), to_np(k).copy(), to_np(v).copy()
-    b.sirllm_step_ragged(z, tok, V, scores, held_dev, cu, total, max_cand, pol, k, v, kept, out, n_keep_dev)
+    max_new = min(int(n_new.max()), max_cand) if tight_new else None
+    b.sirllm_step_ragged(z, tok, V, scores, held_dev, cu, total, max_cand, pol, k, v, kept, out, n_keep_dev,
+                         max_new=max_new)
     torch.cuda.synchronize()
     gs, gkeep = to_np(scores), to_np(n_keep_dev)
     # scores: tolerance; then teacher-force the oracle with the GPU's scores for everything exact
@@ -596,7 +599,13 @@ def test_step_ragged_matches_oracle(b, ref):
     run_ragged(b, ref, rng, 4, b.Policy(4, 1020, 0, 0.8), 300, torch.bfloat16, [1024, 1000, 500, 1024], [54, 54, 54, 1],
                L=1, H=2, D=64, kv_dt=torch.bfloat16)
     # a stream larger than the promised bound is flagged and left alone
-    run_ragged(b, ref, rng, 3, pol, 100, torch.float32, [10, 60, 20], [5, 30, 5], cap=40)
+    run_ragged(b, ref, rng, 3, pol, 100, torch.float32, [10, 60, 20], [5, 30, 5], cap=40, tight_new=False)
+    # every stream's new tokens fit the recent window: scoring and selection share a launch
+    run_ragged(b, ref, rng, 5, pol, 300, torch.float32, [0, 30, 24, 100, 3], [8, 2, 8, 7, 0])
+    run_ragged(b, ref, rng, 3, b.Policy(4, 3068, 1024, 0.85), 2000, torch.bfloat16, [7168, 100, 4000], [1024, 1000, 96],
+               L=1, H=2, D=64, kv_dt=torch.bfloat16)
+    # the same shapes with a loose bound on the new tokens: three launches
+    run_ragged(b, ref, rng, 5, pol, 300, torch.float32, [0, 30, 24, 100, 3], [8, 2, 8, 7, 0], tight_new=False)
     for _ in range(10):
         S = int(rng.integers(1, 9))
         run_ragged(b, ref, rng, S, b.Policy(int(rng.integers(0, 5)), int(rng.integers(0, 60)), int(rng.integers(0, 20)), 0.7),
