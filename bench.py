@@ -142,7 +142,8 @@ def main():
     calib_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     calib_dst = torch.empty_like(calib_src)
     copy_avg, _, _ = time_launches(lambda: calib_dst.copy_(calib_src), 3, group=2)
-    log(f"[bench] plain 1 GiB device copy (torch): {copy_avg*1e3:.1f} us -> {2 * (1 << 30) / (copy_avg * 1e-3) / 1e9:.0f} GB/s")
+    copy_gbps = 2 * (1 << 30) / (copy_avg * 1e-3) / 1e9
+    log(f"[bench] plain 1 GiB device copy (torch): {copy_avg*1e3:.1f} us -> {copy_gbps:.0f} GB/s")
     del calib_src, calib_dst
     if bytes_["compact"] >= bytes_["score"]:
         dom, dom_bytes, dom_ms = "gather_rows_kernel", bytes_["compact"], gather_avg
@@ -157,7 +158,8 @@ def main():
                          "frac": round(step_gbps / HBM_PEAK_GBPS, 4)},
                 "kernels_us": {"gather": round(gather_avg * 1e3, 2), "score": round(score_avg * 1e3, 2),
                                "decay_select": round(sel_avg * 1e3, 2)},
-                "score_gbps": round(bytes_["score"] / (score_avg * 1e-3) / 1e9, 1)}
+                "score_gbps": round(bytes_["score"] / (score_avg * 1e-3) / 1e9, 1),
+                "plain_copy_gbps": round(copy_gbps, 1)}
 
     # ---- optional: the ragged in-place step on the same shapes --------------------------------
     ragged = None
