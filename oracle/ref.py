@@ -36,6 +36,8 @@ def load(path):
     L = C.CDLL(path)
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     L.sirllm_ref_score.argtypes = [vp, C.c_int, i64, i32, i64, vp, vp]
+    L.sirllm_ref_lmhead_score.argtypes = [vp, i64, vp, i64, C.c_int, i32, i64, i32, vp, vp]
+    L.sirllm_ref_lmhead_score.restype = C.c_int
     L.sirllm_ref_decay_select.argtypes = [vp, i64, i32, i32, i32, C.POINTER(_CPolicy), vp, i64, vp, i64]
     L.sirllm_ref_compact_kv.argtypes = [vp, vp, C.POINTER(_CLayout), i32, vp, vp, C.POINTER(_CLayout),
                                         vp, i64, i32, i32]
@@ -108,6 +110,24 @@ def score(logits: np.ndarray, token_ids: np.ndarray, vocab: int | None = None) -
     out = np.empty(n_rows, dtype=np.float32)
     _check(lib().sirllm_ref_score(_ptr(logits), _logits_dtype(logits), n_rows, vocab, ld, _ptr(tok), _ptr(out)),
            "score")
+    return out
+
+
+def lmhead_score(hidden: np.ndarray, weight: np.ndarray, token_ids: np.ndarray, d_model: int | None = None,
+                 vocab: int | None = None) -> np.ndarray:
+    """Token entropy with the logits written as hidden @ weight.T: hidden is [n_rows, ld_h], weight is
+    [vocab, ld_w] (row v = output embedding of token v), same element type (bf16 as uint16 bits)."""
+    assert hidden.ndim == 2 and weight.ndim == 2 and hidden.flags.c_contiguous and weight.flags.c_contiguous
+    assert hidden.dtype == weight.dtype
+    n_rows, ld_h = hidden.shape
+    d_model = min(ld_h, weight.shape[1]) if d_model is None else int(d_model)
+    vocab = weight.shape[0] if vocab is None else int(vocab)
+    assert vocab <= weight.shape[0]
+    tok = np.ascontiguousarray(token_ids, dtype=np.int32)
+    assert tok.shape == (n_rows,)
+    out = np.empty(n_rows, dtype=np.float32)
+    _check(lib().sirllm_ref_lmhead_score(_ptr(hidden), ld_h, _ptr(weight), weight.shape[1], _logits_dtype(hidden),
+                                         d_model, n_rows, vocab, _ptr(tok), _ptr(out)), "lmhead_score")
     return out
 
 

@@ -107,6 +107,60 @@ int sirllm_ref_score(const void* logits, int dtype, int64_t n_rows, int32_t voca
 }
 
 /* ------------------------------------------------------------------------------------ */
+/* Sec. 3.2 with the logits written out as the language-model head's product:             */
+/* z[r][v] = sum_k h[r][k] * W[v][k]  (the model's last linear layer, no bias), then the   */
+/* same e = logsumexp(z[r]) - z[r][x_r].  Inputs are widened exactly, products and sums    */
+/* are taken in double in index order, nothing is rounded before the final score.          */
+/* ------------------------------------------------------------------------------------ */
+
+int sirllm_ref_lmhead_score(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, int dtype,
+                            int32_t d_model, int64_t n_rows, int32_t vocab,
+                            const int32_t* token_ids, float* scores_out)
+{
+    if (n_rows < 0 || vocab < 1 || d_model < 1 || ld_h < d_model || ld_w < d_model) return -1;
+    if (dtype != SIRLLM_REF_F32 && dtype != SIRLLM_REF_BF16 && dtype != SIRLLM_REF_F16) return -1;
+    if (n_rows == 0) return 0;
+    if (!hidden || !weight || !token_ids || !scores_out) return -1;
+
+    int failed = 0;
+    int64_t r;
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(g_threads) schedule(dynamic, 1)
+#endif
+    for (r = 0; r < n_rows; ++r) {
+        const int32_t tok = token_ids[r];
+        if (tok < 0 || tok >= vocab) {
+            scores_out[r] = (float)NAN;
+            continue;
+        }
+        double* h = (double*)malloc(sizeof(double) * (size_t)d_model);
+        double* z = (double*)malloc(sizeof(double) * (size_t)vocab);
+        if (!h || !z) {
+            free(h);
+            free(z);
+            failed = 1;
+            continue;
+        }
+        for (int32_t k = 0; k < d_model; ++k) h[k] = logit_at(hidden, dtype, r * ld_h + k);
+        for (int32_t v = 0; v < vocab; ++v) {
+            double acc = 0.0;
+            for (int32_t k = 0; k < d_model; ++k)
+                acc += h[k] * logit_at(weight, dtype, (int64_t)v * ld_w + k);
+            z[v] = acc;
+        }
+        double m = -INFINITY;
+        for (int32_t v = 0; v < vocab; ++v)
+            if (z[v] > m) m = z[v];
+        double s = 0.0;
+        for (int32_t v = 0; v < vocab; ++v) s += exp(z[v] - m);
+        scores_out[r] = (float)((m - z[tok]) + log(s));
+        free(h);
+        free(z);
+    }
+    return failed ? -1 : 0;
+}
+
+/* ------------------------------------------------------------------------------------ */
 /* Sec. 3.3 / 3.1: decay, Top_k, sink and recent sets                                     */
 /* ------------------------------------------------------------------------------------ */
 

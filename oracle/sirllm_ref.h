@@ -37,6 +37,13 @@ typedef struct {
 int sirllm_ref_score(const void* logits, int dtype, int64_t n_rows, int32_t vocab, int64_t ld,
                      const int32_t* token_ids, float* scores_out);
 
+/* Sec. 3.2 with the logits never stored: z[r][v] = sum_k hidden[r][k] * weight[v][k] (the language-model
+ * head, weight row v = the output embedding of token v), e_r = logsumexp(z[r]) - z[r][token_ids[r]].
+ * hidden is [n_rows][ld_h], weight is [vocab][ld_w], both of element type `dtype`; everything in double. */
+int sirllm_ref_lmhead_score(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, int dtype,
+                            int32_t d_model, int64_t n_rows, int32_t vocab,
+                            const int32_t* token_ids, float* scores_out);
+
 /* Sec. 3.3 + Sec. 3.1: decay the held scores, pick sink + top-k + recent, list them ascending. */
 int sirllm_ref_decay_select(const float* scores, int64_t scores_stride,
                             int32_t n_streams, int32_t n_held, int32_t n_new,

@@ -10,6 +10,7 @@ import sys
 import pytest
 
 import test_oracle_compact_step as t_cs
+import test_oracle_lmhead as t_lm
 import test_oracle_score as t_sc
 import test_oracle_select as t_se
 
@@ -53,6 +54,14 @@ MUTANTS = [
      "(size_t)((int64_t)i * D->stride_pos), row_bytes);", [t_cs.test_gather_through_strided_source]),
     ("values_gathered_from_keys", "gather_one((const char*)v_src, src,", "gather_one((const char*)k_src, src,",
      [t_cs.test_gather_equals_numpy_indexing_on_tagged_payload]),
+    ("lmhead_weight_read_transposed", "acc += h[k] * logit_at(weight, dtype, (int64_t)v * ld_w + k);",
+     "acc += h[k] * logit_at(weight, dtype, (int64_t)k * ld_w + v);", [t_lm.test_brute_force_loops_on_a_tiny_case]),
+    ("lmhead_hidden_row_stride_is_d_model", "h[k] = logit_at(hidden, dtype, r * ld_h + k);",
+     "h[k] = logit_at(hidden, dtype, r * d_model + k);", [t_lm.test_leading_dimensions_skip_the_padding]),
+    ("lmhead_dropped_token_term", "(float)((m - z[tok]) + log(s));", "(float)(log(s));",
+     [lambda r: t_lm.test_two_valued_closed_form(r, 8.0)]),
+    ("lmhead_hidden_of_row_zero", "h[k] = logit_at(hidden, dtype, r * ld_h + k);",
+     "h[k] = logit_at(hidden, dtype, 0 * ld_h + k);", [lambda r: t_lm.test_matches_float64_library_matmul_and_logsumexp(r, "bf16")]),
     ("step_compacts_even_under_budget_wrong_count", "(int32_t)budget);", "(int32_t)budget - 1);",
      [t_cs.test_step_is_score_then_decay_select_then_gather]),
 ]
