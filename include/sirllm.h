@@ -128,6 +128,31 @@ int sirllm_score_merge(const float* partials, int32_t n_parts, int64_t part_stri
                        float* scores_out, void* hip_stream);
 
 /*
+ * Token entropy straight from the language-model head.  Sec. 3.2 takes the probabilities from the
+ * model's own softmax output, i.e. from logits z = h W^T that the model computes anyway (the paper's
+ * remark that the metric needs no additional computation).  This entry point computes
+ *     scores_out[r] = logsumexp_v(z[r][0:vocab]) - z[r][token_ids[r]],   z[r][v] = sum_k hidden[r][k] * weight[v][k]
+ * on the matrix cores and reduces every tile of z to softmax statistics in registers, so the
+ * n_rows x vocab logits are never written to or read from memory.
+ *   hidden      device, n_rows x ld_h elements of `dt` (the final hidden state of each scored token's row)
+ *   weight      device, vocab x ld_w elements of `dt`; row v is the output embedding of token v (no bias)
+ *   dt          SIRLLM_BF16 or SIRLLM_F16 (products exact, accumulation in binary32); SIRLLM_F32 is
+ *               SIRLLM_ERR_UNSUPPORTED
+ *   d_model     inner dimension; d_model, ld_h and ld_w must be multiples of 8 and both base pointers
+ *               16-byte aligned (else SIRLLM_ERR_UNSUPPORTED); ld_h, ld_w < 2^21
+ *   token_ids   device, n_rows int32; an id outside [0, vocab) yields a quiet NaN score
+ *   scores_out  device, n_rows float
+ *   workspace   device scratch of sirllm_lmhead_workspace_bytes(n_rows, vocab) bytes, 256-byte aligned,
+ *               required (SIRLLM_ERR_WORKSPACE); overwritten, carries nothing between calls; calls that
+ *               share it must be ordered on one stream.
+ * n_rows == 0 is a no-op.  A non-finite product makes that row's score NaN.
+ */
+int sirllm_lmhead_score(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, sirllm_dtype dt,
+                        int32_t d_model, int64_t n_rows, int32_t vocab, const int32_t* token_ids,
+                        float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t sirllm_lmhead_workspace_bytes(int64_t n_rows, int32_t vocab);
+
+/*
  * Decay, select and index build (Sec. 3.3: E <- E*eta, Id_entropy = Top_k(E), E <- E[Id];
  * Sec. 3.1: Id_sink, Id_recent; Alg. 1 eviction branch and its trigger "cache size > L").
  * For every stream s, with E = scores + s*scores_stride:

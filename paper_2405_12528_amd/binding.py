@@ -45,7 +45,7 @@ SIRLLM_BASELINE_STREAM, SIRLLM_BASELINE_INTERVAL, SIRLLM_BASELINE_RANDOM = 0, 1,
 
 EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step", "sirllm_baseline_select",
            "sirllm_compact_kv_inplace", "sirllm_step_ragged", "sirllm_score_partial",
-           "sirllm_score_merge", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
+           "sirllm_score_merge", "sirllm_lmhead_score", "sirllm_lmhead_workspace_bytes", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
 
 _vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
 _PP, _LP = C.POINTER(sirllm_policy), C.POINTER(sirllm_kv_layout)
@@ -66,6 +66,10 @@ _lib.sirllm_score_partial.argtypes = [_vp, C.c_int, _i64, _i32, _i64, _i32, _vp,
 _lib.sirllm_score_partial.restype = C.c_int
 _lib.sirllm_score_merge.argtypes = [_vp, _i32, _i64, _i64, _vp, _vp]
 _lib.sirllm_score_merge.restype = C.c_int
+_lib.sirllm_lmhead_score.argtypes = [_vp, _i64, _vp, _i64, C.c_int, _i32, _i64, _i32, _vp, _vp, _vp, _sz, _vp]
+_lib.sirllm_lmhead_score.restype = C.c_int
+_lib.sirllm_lmhead_workspace_bytes.argtypes = [_i64, _i32]
+_lib.sirllm_lmhead_workspace_bytes.restype = _sz
 for _n in ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step"):
     getattr(_lib, _n).restype = C.c_int
 _lib.sirllm_workspace_bytes.argtypes = [_i32, _i32, _i64, _i32]
@@ -166,6 +170,38 @@ def sirllm_score(logits: torch.Tensor, token_ids: torch.Tensor, scores_out: torc
     wp, wb = _ws(workspace)
     _check(_lib.sirllm_score(_ptr(logits), _dtype_code(logits), n_rows, vocab, ld, _ptr(token_ids),
                              _ptr(scores_out), wp, wb, _stream(stream)), "sirllm_score")
+    return scores_out
+
+
+def sirllm_lmhead_workspace_bytes(n_rows: int, vocab: int) -> int:
+    return int(_lib.sirllm_lmhead_workspace_bytes(n_rows, vocab))
+
+
+def sirllm_lmhead_score(hidden: torch.Tensor, weight: torch.Tensor, token_ids: torch.Tensor, scores_out: torch.Tensor,
+                        workspace: torch.Tensor, d_model: int | None = None, vocab: int | None = None,
+                        stream=None) -> torch.Tensor:
+    """scores_out[r] = logsumexp_v(z[r, :vocab]) - z[r, token_ids[r]] with z = hidden[:, :d_model] @ weight[:, :d_model].T,
+    the logits never stored.  hidden is [n_rows, ld_h], weight [>= vocab, ld_w], bf16 or f16, rows contiguous."""
+    _on_device(hidden, weight, token_ids, scores_out, workspace)
+    for t in (hidden, weight):
+        if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise ValueError("hidden / weight must be 2-D with contiguous rows")
+    if hidden.dtype != weight.dtype:
+        raise TypeError("hidden and weight must have the same element type")
+    n_rows = hidden.shape[0]
+    d_model = min(hidden.shape[1], weight.shape[1]) if d_model is None else int(d_model)
+    vocab = weight.shape[0] if vocab is None else int(vocab)
+    if vocab > weight.shape[0] or d_model > hidden.shape[1] or d_model > weight.shape[1]:
+        raise ValueError("vocab / d_model exceed the arrays")
+    if token_ids.dtype != torch.int32 or scores_out.dtype != torch.float32:
+        raise TypeError("token_ids must be int32 and scores_out float32")
+    if token_ids.numel() < n_rows or scores_out.numel() < n_rows or not token_ids.is_contiguous() \
+            or not scores_out.is_contiguous():
+        raise ValueError("token_ids / scores_out must be contiguous with n_rows entries")
+    wp, wb = _ws(workspace)
+    _check(_lib.sirllm_lmhead_score(_ptr(hidden), _row_stride(hidden), _ptr(weight), _row_stride(weight),
+                                    _dtype_code(hidden), d_model, n_rows, vocab, _ptr(token_ids), _ptr(scores_out),
+                                    wp, wb, _stream(stream)), "sirllm_lmhead_score")
     return scores_out
 
 

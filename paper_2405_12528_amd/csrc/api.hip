@@ -238,6 +238,37 @@ int sirllm_score_merge(const float* partials, int32_t n_parts, int64_t part_stri
     return hip_status(launch_score_merge(partials, n_parts, part_stride, n_rows, scores_out, (hipStream_t)hip_stream));
 }
 
+size_t sirllm_lmhead_workspace_bytes(int64_t n_rows, int32_t vocab)
+{
+    if (n_rows <= 0 || vocab <= 0) return 0;
+    // one (m, s, z_tok) triple per row and vocabulary tile, each tile's block padded to 256 bytes
+    const size_t per_tile = ((size_t)n_rows * 3 * sizeof(float) + 255) & ~(size_t)255;
+    return per_tile * (size_t)lmhead_tiles_vocab(vocab);
+}
+
+int sirllm_lmhead_score(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, sirllm_dtype dt,
+                        int32_t d_model, int64_t n_rows, int32_t vocab, const int32_t* token_ids,
+                        float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (n_rows < 0 || n_rows > 0x7fffffffLL || vocab < 1 || d_model < 1 || ld_h < d_model || ld_w < d_model)
+        return SIRLLM_ERR_INVALID_ARG;
+    if (dt != SIRLLM_F32 && dt != SIRLLM_BF16 && dt != SIRLLM_F16) return SIRLLM_ERR_INVALID_ARG;
+    if (n_rows == 0) return SIRLLM_OK;
+    if (!hidden || !weight || !token_ids || !scores_out) return SIRLLM_ERR_INVALID_ARG;
+    if (dt == SIRLLM_F32) return SIRLLM_ERR_UNSUPPORTED;
+    if ((d_model & 7) || (ld_h & 7) || (ld_w & 7) || ld_h >= (1 << 21) || ld_w >= (1 << 21) ||
+        ((uintptr_t)hidden & 15) || ((uintptr_t)weight & 15))
+        return SIRLLM_ERR_UNSUPPORTED;
+    const int rc = workspace_check(workspace, workspace_bytes, sirllm_lmhead_workspace_bytes(n_rows, vocab));
+    if (rc) return rc;
+    LmHeadArgs a;
+    a.hidden = hidden; a.weight = weight; a.ld_h = ld_h; a.ld_w = ld_w; a.d_model = d_model; a.vocab = vocab;
+    a.n_rows = n_rows; a.token_ids = token_ids; a.partial = (float*)workspace;
+    a.part_stride = (int64_t)((((size_t)n_rows * 3 * sizeof(float) + 255) & ~(size_t)255) / sizeof(float));
+    a.n_vtiles = 0; a.n_ttiles = 0;
+    return hip_status(launch_lmhead_score(a, dt, scores_out, (hipStream_t)hip_stream));
+}
+
 int sirllm_decay_select(const float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held,
                         int32_t n_new, const sirllm_policy* policy, int32_t* kept_idx, int64_t idx_stride,
                         float* scores_out, int64_t out_stride, void* workspace, size_t workspace_bytes,

@@ -42,6 +42,23 @@ hipError_t launch_score(const ScoreArgs& a, sirllm_dtype dt, hipStream_t stream)
 hipError_t launch_score_merge(const float* partials, int32_t n_parts, int64_t part_stride, int64_t n_rows,
                               float* scores_out, hipStream_t stream);
 
+// ---- lmhead.hip -------------------------------------------------------------------------
+// Token entropy from hidden states and the output embedding matrix, logits never stored.
+struct LmHeadArgs {
+    const void* hidden;       // [n_rows][ld_h], 2-byte elements
+    const void* weight;       // [vocab][ld_w]
+    int64_t ld_h, ld_w;       // elements between rows, multiples of 8
+    int32_t d_model;          // multiple of 8
+    int32_t vocab;
+    int64_t n_rows;
+    const int32_t* token_ids;
+    float* partial;           // scratch: [n_vtiles][part_stride] floats, (m, s, z_tok) per row
+    int64_t part_stride;      // >= 3 * n_rows
+    int32_t n_vtiles, n_ttiles;   // filled in by the launcher
+};
+int lmhead_tiles_vocab(int32_t vocab);
+hipError_t launch_lmhead_score(const LmHeadArgs& a, sirllm_dtype dt, float* scores_out, hipStream_t stream);
+
 // ---- select.hip -------------------------------------------------------------------------
 struct SelectArgs {
     const float* scores;      // [n_streams][scores_stride]

@@ -41,6 +41,7 @@ class Workload:
     n_turns: int = 1
     checked_turns: tuple = field(default_factory=tuple)
     seed: int = 0
+    d_model: int = 4096        # width of the final hidden state (LM-head scoring only)
 
     @property
     def budget(self) -> int:
@@ -77,7 +78,7 @@ WORKLOADS = {
     # Tiny: 64 new tokens per turn over 4 turns, budget 32 = 4 + 20 + 8.
     "tiny": Workload("tiny", vocab=1000, n_new=64, logits_dtype="f32", sigma=2.0, zipf_a=0.0, spike=8.0,
                      spike_frac=0.3, n_sink=4, n_topk=20, n_recent=8, decay=0.9, n_layers=2, n_kv_heads=2,
-                     head_dim=16, kv_dtype="f32", n_cand=96, n_turns=4, checked_turns=(1, 2, 3, 4)),
+                     head_dim=16, kv_dtype="f32", n_cand=96, n_turns=4, checked_turns=(1, 2, 3, 4), d_model=64),
     # Llama-2-7B-shaped: 32 layers x 32 heads x 128, V = 32000.
     "llama2_7b": Workload("llama2_7b", vocab=32000, n_new=512, logits_dtype="bf16", sigma=3.0, zipf_a=1.1,
                           spike=0.0, spike_frac=0.0, n_sink=4, n_topk=1532, n_recent=512, decay=0.9,
@@ -111,7 +112,7 @@ WORKLOADS = {
                             n_layers=32, n_kv_heads=8, head_dim=128, kv_dtype="bf16", n_cand=133120),
 }
 
-_KIND = {"logits": 1, "tokens": 2, "held": 3, "kv_k": 4, "kv_v": 5, "rank": 6, "spike": 7}
+_KIND = {"logits": 1, "tokens": 2, "held": 3, "kv_k": 4, "kv_v": 5, "rank": 6, "spike": 7, "hidden": 8, "weight": 9}
 
 
 def _torch_dtype(name: str):
@@ -151,6 +152,34 @@ def make_logits(w: Workload, turn: int = 0, device="cpu", n_rows: int | None = N
             z[:, w.vocab:] = 1.0e4                    # padding: a kernel that reads it is caught at once
         out[r0:r1] = z.to(out.dtype)
     return out
+
+
+def make_lmhead(w: Workload, turn: int = 0, device="cpu", n_rows: int | None = None, dtype=torch.bfloat16,
+                d_model: int | None = None, vocab: int | None = None):
+    """Final hidden states [n_rows, d_model] and an output-embedding matrix [vocab, d_model] whose product
+    has the same shape of distribution as make_logits: hidden = N(0, 1) + 1 in every coordinate, weight row
+    v = N(0, sigma^2 / d_model) + bias_v / d_model with the workload's Zipf bias, so that
+    hidden @ weight.T ~ bias_v + N(0, ~2 sigma^2).  The weights depend on the workload only, not on the turn."""
+    n_rows = w.n_streams * w.n_new if n_rows is None else n_rows
+    d_model = w.d_model if d_model is None else d_model
+    vocab = w.vocab if vocab is None else vocab
+    gh = generator(w, "hidden", turn, device)
+    hidden = (torch.randn((n_rows, d_model), generator=gh, device=device, dtype=torch.float32) + 1.0).to(dtype)
+    gw = generator(w, "weight", 0, device)
+    weight = torch.empty((vocab, d_model), dtype=dtype, device=device)
+    bias = None
+    if w.zipf_a > 0:
+        gr = generator(w, "rank", 0, "cpu")
+        rank = torch.randperm(vocab, generator=gr).to(torch.float32) + 1.0
+        bias = (-w.zipf_a * torch.log(rank) / d_model).to(device)
+    chunk = max(1, (1 << 26) // d_model)
+    for v0 in range(0, vocab, chunk):
+        v1 = min(vocab, v0 + chunk)
+        x = torch.randn((v1 - v0, d_model), generator=gw, device=device, dtype=torch.float32) * (w.sigma / math.sqrt(d_model))
+        if bias is not None:
+            x += bias[v0:v1, None]
+        weight[v0:v1] = x.to(dtype)
+    return hidden, weight
 
 
 def make_token_ids(w: Workload, turn: int = 0, device="cpu", n_rows: int | None = None):
@@ -207,4 +236,4 @@ def describe(w: Workload) -> str:
 
 
 __all__ = ["Workload", "WORKLOADS", "generator", "make_logits", "make_token_ids", "make_held_scores",
-           "make_kv", "tagged_kv", "describe", "math"]
+           "make_kv", "make_lmhead", "tagged_kv", "describe", "math"]

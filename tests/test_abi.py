@@ -240,3 +240,30 @@ def test_product_path_never_touches_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), f"{f} imports the oracle"
                 assert "sirllm_ref" not in text, f"{f} names the oracle's library"
+
+
+def test_lmhead_argument_errors(b):
+    L = b.raw()
+    BF, F16, F32 = 1, 2, 0
+    ws = b.sirllm_lmhead_workspace_bytes(4, 1000)
+    assert ws % 256 == 0 and ws >= 4 * 3 * 4 * 4                                   # 4 vocabulary tiles of 256
+    assert b.sirllm_lmhead_workspace_bytes(0, 1000) == 0
+    ok = lambda *a: L.sirllm_lmhead_score(*a)
+    assert ok(FAKE, 64, FAKE, 64, BF, 64, 0, 1000, None, None, None, 0, None) == b.SIRLLM_OK          # no rows
+    assert ok(FAKE, 64, FAKE, 64, BF, 64, -1, 1000, FAKE, FAKE, FAKE, ws, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ok(FAKE, 64, FAKE, 64, BF, 64, 4, 0, FAKE, FAKE, FAKE, ws, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ok(FAKE, 56, FAKE, 64, BF, 64, 4, 1000, FAKE, FAKE, FAKE, ws, None) == b.SIRLLM_ERR_INVALID_ARG   # ld_h < d_model
+    assert ok(FAKE, 64, FAKE, 56, BF, 64, 4, 1000, FAKE, FAKE, FAKE, ws, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ok(None, 64, FAKE, 64, BF, 64, 4, 1000, FAKE, FAKE, FAKE, ws, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ok(FAKE, 64, None, 64, BF, 64, 4, 1000, FAKE, FAKE, FAKE, ws, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ok(FAKE, 64, FAKE, 64, BF, 64, 4, 1000, None, FAKE, FAKE, ws, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ok(FAKE, 64, FAKE, 64, BF, 64, 4, 1000, FAKE, None, FAKE, ws, None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ok(FAKE, 64, FAKE, 64, 9, 64, 4, 1000, FAKE, FAKE, FAKE, ws, None) == b.SIRLLM_ERR_INVALID_ARG    # no such dtype
+    assert ok(FAKE, 64, FAKE, 64, F32, 64, 4, 1000, FAKE, FAKE, FAKE, ws, None) == b.SIRLLM_ERR_UNSUPPORTED  # no f32 MFMA path
+    assert ok(FAKE, 64, FAKE, 64, F16, 60, 4, 1000, FAKE, FAKE, FAKE, ws, None) == b.SIRLLM_ERR_UNSUPPORTED  # d_model % 8
+    assert ok(FAKE, 68, FAKE, 64, BF, 64, 4, 1000, FAKE, FAKE, FAKE, ws, None) == b.SIRLLM_ERR_UNSUPPORTED   # ld_h % 8
+    assert ok(FAKE + 2, 64, FAKE, 64, BF, 64, 4, 1000, FAKE, FAKE, FAKE, ws, None) == b.SIRLLM_ERR_UNSUPPORTED
+    assert ok(FAKE, 64, FAKE, 1 << 21, BF, 64, 4, 1000, FAKE, FAKE, FAKE, ws, None) == b.SIRLLM_ERR_UNSUPPORTED
+    assert ok(FAKE, 64, FAKE, 64, BF, 64, 4, 1000, FAKE, FAKE, None, 0, None) == b.SIRLLM_ERR_WORKSPACE
+    assert ok(FAKE, 64, FAKE, 64, BF, 64, 4, 1000, FAKE, FAKE, FAKE, ws - 1, None) == b.SIRLLM_ERR_WORKSPACE
+    assert ok(FAKE, 64, FAKE, 64, BF, 64, 4, 1000, FAKE, FAKE, FAKE + 16, ws, None) == b.SIRLLM_ERR_WORKSPACE  # alignment

@@ -1,0 +1,150 @@
+"""Parity of sirllm_lmhead_score (token entropy straight from hidden states and the output embedding
+matrix, paper Sec. 3.2) with the CPU oracle, through the C ABI, on one MI355X.
+
+Tolerance: |gpu - ref| <= 1e-4 + 1e-5*|ref|.  The kernel's products of two bf16 / f16 numbers are exact in
+binary32; a logit is their sum over d_model terms taken 16 at a time into a binary32 accumulator, i.e.
+d_model/16 roundings of at most 2^-24 * |partial sum| each.  With errors adding like a random walk
+(sqrt(d_model/16) * 2^-24 * max |partial sum|; d_model = 4096, partial sums below ~45 on these inputs) a logit
+is within ~4e-5 of its exact value, and the score, a difference of the token's logit and a weighted mean
+of logits, within twice that; the softmax reduction itself adds the ~1e-6 of the logits path.
+"""
+import numpy as np
+import pytest
+import torch
+
+from helpers import to_np
+from paper_2405_12528_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def b():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2405_12528_amd import binding
+    return binding
+
+
+def assert_close(gpu: np.ndarray, want: np.ndarray):
+    nan_w, nan_g = np.isnan(want), np.isnan(gpu)
+    np.testing.assert_array_equal(nan_g, nan_w)
+    ok = ~nan_w
+    err = np.abs(gpu[ok].astype(np.float64) - want[ok].astype(np.float64))
+    tol = 1e-4 + 1e-5 * np.abs(want[ok].astype(np.float64))
+    bad = err > tol
+    assert not bad.any(), f"{bad.sum()} scores off; worst {err.max():.3e} (tolerance {tol[err.argmax()]:.3e})"
+    return float(err.max()) if err.size else 0.0
+
+
+def gpu_lmhead(b, h, w, tok, d_model=None, vocab=None):
+    n = h.shape[0]
+    V = w.shape[0] if vocab is None else vocab
+    out = torch.full((n,), -12345.0, dtype=torch.float32, device=DEV)
+    ws = torch.empty(max(b.sirllm_lmhead_workspace_bytes(n, V), 1), dtype=torch.uint8, device=DEV)
+    b.sirllm_lmhead_score(h, w, tok, out, ws, d_model=d_model, vocab=vocab)
+    torch.cuda.synchronize()
+    return to_np(out)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("n_rows,d,V", [
+    (64, 64, 1000),          # the tiny workload's shape: one token tile, four vocabulary tiles, ragged both ways
+    (1, 8, 1),               # the smallest legal call
+    (7, 72, 40),             # d_model not a multiple of the 64-wide pipeline stage
+    (300, 512, 1000),        # two token tiles
+    (513, 256, 777),         # three token tiles, the last one with a single row
+    (257, 128, 2049),        # nine vocabulary tiles: the tile-to-XCD deal wraps, last tile has one column
+    (5, 4096, 2500),         # the full inner dimension of the 7B / 8B shapes
+    (256, 64, 256), (255, 64, 257),
+])
+def test_lmhead_score_matches_oracle(b, ref, dtype, n_rows, d, V):
+    g = torch.Generator(device=DEV).manual_seed(n_rows * 7919 + V * 31 + d)
+    h = (torch.randn((n_rows, d), generator=g, device=DEV) + 0.5).to(dtype)
+    w = (torch.randn((V, d), generator=g, device=DEV) * (3.0 / d ** 0.5)).to(dtype)
+    w[V // 2] += (4.0 / d)                                   # one token that many rows prefer
+    tok = torch.randint(0, V, (n_rows,), generator=g, device=DEV, dtype=torch.int32)
+    tok[::3] = V // 2
+    got = gpu_lmhead(b, h, w, tok)
+    want = ref.lmhead_score(to_np(h), to_np(w), to_np(tok))
+    assert_close(got, want)
+
+
+def test_lmhead_leading_dimensions_and_subranges(b, ref):
+    # hidden and weight embedded in larger allocations whose padding would wreck the result if it were read
+    g = torch.Generator(device=DEV).manual_seed(5)
+    n, d, V = 70, 200, 900
+    hbig = torch.full((n, 256), 1.0e3, device=DEV).to(torch.bfloat16)
+    wbig = torch.full((V + 50, 320), -1.0e3, device=DEV).to(torch.bfloat16)
+    hbig[:, :d] = torch.randn((n, d), generator=g, device=DEV).to(torch.bfloat16)
+    wbig[:V, :d] = (torch.randn((V, d), generator=g, device=DEV) * 0.2).to(torch.bfloat16)
+    tok = torch.randint(0, V, (n,), generator=g, device=DEV, dtype=torch.int32)
+    got = gpu_lmhead(b, hbig, wbig, tok, d_model=d, vocab=V)
+    want = ref.lmhead_score(to_np(hbig), to_np(wbig), to_np(tok), d_model=d, vocab=V)
+    assert_close(got, want)
+    tight = ref.lmhead_score(np.ascontiguousarray(to_np(hbig)[:, :d]), np.ascontiguousarray(to_np(wbig)[:V, :d]), to_np(tok))
+    np.testing.assert_array_equal(want, tight)
+
+
+def test_lmhead_out_of_range_token_is_nan(b, ref):
+    g = torch.Generator(device=DEV).manual_seed(6)
+    n, d, V = 6, 64, 300
+    h = torch.randn((n, d), generator=g, device=DEV).to(torch.bfloat16)
+    w = torch.randn((V, d), generator=g, device=DEV).to(torch.bfloat16)
+    tok = torch.tensor([0, -1, V, V - 1, 2 ** 31 - 1, 17], dtype=torch.int32, device=DEV)
+    got = gpu_lmhead(b, h, w, tok)
+    want = ref.lmhead_score(to_np(h), to_np(w), to_np(tok))
+    assert np.isnan(want[[1, 2, 4]]).all()
+    assert_close(got, want)
+
+
+def test_lmhead_closed_forms(b):
+    # equal output embeddings -> log V for every row; a zero hidden state -> log V
+    V, d = 1000, 64
+    h = torch.randn((3, d), device=DEV).to(torch.bfloat16)
+    h[2] = 0
+    w = torch.randn((1, d), device=DEV).to(torch.bfloat16).repeat(V, 1).contiguous()
+    tok = torch.tensor([0, 500, 999], dtype=torch.int32, device=DEV)
+    got = gpu_lmhead(b, h, w, tok)
+    np.testing.assert_allclose(got, np.float32(np.log(V)), rtol=0, atol=2e-6)
+
+
+def test_lmhead_agrees_with_scoring_the_materialised_logits(b):
+    # the same quantity by the other route: logits written out in binary32, then the logits scan
+    w_ = synth.WORKLOADS["llama2_7b"]
+    n, V = 300, 32000
+    h, W = synth.make_lmhead(w_, turn=1, device=DEV, n_rows=n)
+    tok = synth.make_token_ids(w_, turn=1, device=DEV, n_rows=n)
+    got = gpu_lmhead(b, h, W, tok)
+    z = h.float() @ W.float().T
+    out = torch.empty(n, device=DEV)
+    b.sirllm_score(z, tok, out)
+    torch.cuda.synchronize()
+    assert_close(got, to_np(out))
+
+
+def test_lmhead_llama3_shape_sampled_rows_against_the_oracle(b, ref):
+    """2048 x 4096 hidden states against a 128256 x 4096 output embedding (the Llama-3-8B-shaped workload):
+    every row is checked against the logits route, 12 sampled rows against the oracle."""
+    w_ = synth.WORKLOADS["llama3_8b"]
+    h, W = synth.make_lmhead(w_, turn=1, device=DEV)
+    tok = synth.make_token_ids(w_, turn=1, device=DEV)
+    n = h.shape[0]
+    assert (n, W.shape[0], W.shape[1]) == (2048, 128256, 4096)
+    got = gpu_lmhead(b, h, W, tok)
+    assert np.isfinite(got).all() and (got > 0).all()
+    # every row, against the logits scan fed with binary32 products (256 rows at a time: 131 MB of logits)
+    other = torch.empty(n, device=DEV)
+    Wf = W.float()
+    for r0 in range(0, n, 256):
+        z = h[r0:r0 + 256].float() @ Wf.T
+        b.sirllm_score(z, tok[r0:r0 + 256], other[r0:r0 + 256])
+    torch.cuda.synchronize()
+    assert_close(got, to_np(other))
+    rows = np.random.default_rng(0).choice(n, 12, replace=False)
+    rows.sort()
+    ref.set_threads(16)
+    want = ref.lmhead_score(to_np(h[torch.from_numpy(rows).to(DEV)]), to_np(W), to_np(tok)[rows])
+    worst = assert_close(got[rows], want)
+    print(f"llama3 shape: worst |gpu - oracle| over 12 sampled rows = {worst:.2e}")
