@@ -35,6 +35,9 @@ def main():
                     help="also time sirllm_step_ragged (per-stream sizes in device memory, in-place compaction) on "
                          "the same shapes; reported under 'ragged_inplace' in the JSON line")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = min(16, host cores)")
+    ap.add_argument("--lmhead", action="store_true",
+                    help="also time sirllm_lmhead_score (scores straight from bf16 hidden states and the output "
+                         "embedding matrix, logits never stored) on the workload's rows")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (every stream, the whole step); --gpus must be 1. "
@@ -179,6 +182,23 @@ def main():
                   "frac": round(bytes_["total"] / (r_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
         log(f"[bench] ragged in-place step: {r_avg*1e3:.1f} us -> {ragged['hbm_gbps']:.0f} GB/s")
 
+    # ---- optional: scoring straight from the LM head (MFMA bound) ---------------------------------
+    lmhead = None
+    if args.lmhead:
+        hid, wmat = synth.make_lmhead(w, turn=1, device=dev)
+        lm_ws = torch.empty(b.sirllm_lmhead_workspace_bytes(hid.shape[0], w.vocab), dtype=torch.uint8, device=dev)
+        lm_avg, lm_med, lm_min = time_launches(
+            lambda: b.sirllm_lmhead_score(hid, wmat, tok, new_scores, lm_ws), n_k, group=2)
+        flops = 2.0 * hid.shape[0] * w.vocab * w.d_model
+        tfl = flops / (lm_avg * 1e-3) / 1e12
+        lmhead = {"bound": "mfma", "kernel": "lmhead_score_kernel", "dtype": "bf16", "achieved": round(tfl, 1),
+                  "peak": 2500.0, "unit": "TFLOP/s", "frac": round(tfl / 2500.0, 4), "ms": round(lm_avg, 4),
+                  "rows": hid.shape[0], "vocab": w.vocab, "d_model": w.d_model,
+                  "tokens_per_s": round(hid.shape[0] / (lm_avg * 1e-3), 1),
+                  "logits_route_ms": round(score_avg, 4)}
+        log(f"[bench] lmhead_score {hid.shape[0]} x {w.d_model} x {w.vocab}: {lm_avg*1e3:.1f}/{lm_med*1e3:.1f}/{lm_min*1e3:.1f} us "
+            f"(avg/median/min) -> {tfl:.0f} TFLOP/s = {100 * tfl / 2500:.1f} % of 2.5 PFLOP/s")
+
     # ---- the oracle on the host cores, same bytes, as a reported baseline ----------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -197,6 +217,8 @@ def main():
     }
     if ragged:
         out["ragged_inplace"] = ragged
+    if lmhead:
+        out["lmhead"] = lmhead
     print(json.dumps(out), flush=True)
 
 
