@@ -196,6 +196,14 @@ def main():
                   "rows": hid.shape[0], "vocab": w.vocab, "d_model": w.d_model,
                   "tokens_per_s": round(hid.shape[0] / (lm_avg * 1e-3), 1),
                   "logits_route_ms": round(score_avg, 4)}
+        st_ws = torch.empty(max(b.sirllm_step_lmhead_workspace_bytes(S, n_cand, hid.shape[0], w.vocab), 256),
+                            dtype=torch.uint8, device=dev)
+        st_avg, _, _ = time_launches(
+            lambda: b.sirllm_step_lmhead(hid, wmat, tok, scores, n_held, n_new, pol, k_src, v_src, k_dst, v_dst, kept,
+                                         scores_out, st_ws), n_k, group=2)
+        lmhead["step_ms"] = round(st_avg, 4)
+        lmhead["step_tokens_per_s"] = round(hid.shape[0] / (st_avg * 1e-3), 1)
+        log(f"[bench] step with the scores from the LM head: {st_avg*1e3:.1f} us")
         log(f"[bench] lmhead_score {hid.shape[0]} x {w.d_model} x {w.vocab}: {lm_avg*1e3:.1f}/{lm_med*1e3:.1f}/{lm_min*1e3:.1f} us "
             f"(avg/median/min) -> {tfl:.0f} TFLOP/s = {100 * tfl / 2500:.1f} % of 2.5 PFLOP/s")
 

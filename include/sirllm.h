@@ -240,6 +240,24 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * One dialogue turn with the scores taken straight from the language-model head: sirllm_step with its first
+ * stage replaced by sirllm_lmhead_score (Alg. 1, one loop iteration; Sec. 3.2 for the score).  hidden holds
+ * n_streams * n_new rows, stream s owning rows [s*n_new, (s+1)*n_new); every other argument, the results and the
+ * under-budget behaviour are those of sirllm_step; the restrictions on hidden / weight / dt / d_model are those
+ * of sirllm_lmhead_score.  workspace: sirllm_step_lmhead_workspace_bytes(n_streams, n_held + n_new,
+ * n_streams * n_new, vocab) bytes of device scratch, 256-byte aligned, required.
+ */
+int sirllm_step_lmhead(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, sirllm_dtype dt,
+                       int32_t d_model, int32_t vocab, const int32_t* token_ids,
+                       float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held, int32_t n_new,
+                       const sirllm_policy* policy,
+                       const void* k_src, const void* v_src, const sirllm_kv_layout* src,
+                       void* k_dst, void* v_dst, const sirllm_kv_layout* dst,
+                       int32_t* kept_idx, int64_t idx_stride, float* scores_out, int64_t out_stride,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t sirllm_step_lmhead_workspace_bytes(int32_t n_streams, int32_t n_cand, int64_t n_rows, int32_t vocab);
+
+/*
  * One retention step for a RAGGED batch, compacting in place: every stream has its own cache fill
  * and its own number of new tokens, as in a serving batch whose dialogues are at different turns.
  * Per stream s (Alg. 1, same order and readings as sirllm_step):

@@ -45,7 +45,8 @@ SIRLLM_BASELINE_STREAM, SIRLLM_BASELINE_INTERVAL, SIRLLM_BASELINE_RANDOM = 0, 1,
 
 EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step", "sirllm_baseline_select",
            "sirllm_compact_kv_inplace", "sirllm_step_ragged", "sirllm_score_partial",
-           "sirllm_score_merge", "sirllm_lmhead_score", "sirllm_lmhead_workspace_bytes", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
+           "sirllm_score_merge", "sirllm_lmhead_score", "sirllm_lmhead_workspace_bytes",
+           "sirllm_step_lmhead", "sirllm_step_lmhead_workspace_bytes", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
 
 _vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
 _PP, _LP = C.POINTER(sirllm_policy), C.POINTER(sirllm_kv_layout)
@@ -70,6 +71,11 @@ _lib.sirllm_lmhead_score.argtypes = [_vp, _i64, _vp, _i64, C.c_int, _i32, _i64, 
 _lib.sirllm_lmhead_score.restype = C.c_int
 _lib.sirllm_lmhead_workspace_bytes.argtypes = [_i64, _i32]
 _lib.sirllm_lmhead_workspace_bytes.restype = _sz
+_lib.sirllm_step_lmhead.argtypes = [_vp, _i64, _vp, _i64, C.c_int, _i32, _i32, _vp, _vp, _i64, _i32, _i32, _i32, _PP,
+                                    _vp, _vp, _LP, _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _sz, _vp]
+_lib.sirllm_step_lmhead.restype = C.c_int
+_lib.sirllm_step_lmhead_workspace_bytes.argtypes = [_i32, _i32, _i64, _i32]
+_lib.sirllm_step_lmhead_workspace_bytes.restype = _sz
 for _n in ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step"):
     getattr(_lib, _n).restype = C.c_int
 _lib.sirllm_workspace_bytes.argtypes = [_i32, _i32, _i64, _i32]
@@ -327,6 +333,58 @@ def sirllm_step(logits: torch.Tensor, token_ids: torch.Tensor, vocab: int, score
                             _ptr(k_src), _ptr(v_src), C.byref(ls), _ptr(k_dst), _ptr(v_dst), C.byref(ldst),
                             _ptr(kept_idx), _row_stride(kept_idx), _ptr(scores_out), _row_stride(scores_out),
                             wp, wb, _stream(stream)), "sirllm_step")
+    return n_keep
+
+
+def sirllm_step_lmhead_workspace_bytes(n_streams: int, n_cand: int, n_rows: int, vocab: int) -> int:
+    return int(_lib.sirllm_step_lmhead_workspace_bytes(n_streams, n_cand, n_rows, vocab))
+
+
+def sirllm_step_lmhead(hidden: torch.Tensor, weight: torch.Tensor, token_ids: torch.Tensor, scores: torch.Tensor,
+                       n_held: int, n_new: int, policy, k_src: torch.Tensor, v_src: torch.Tensor, k_dst, v_dst,
+                       kept_idx: torch.Tensor, scores_out: torch.Tensor, workspace: torch.Tensor,
+                       d_model: int | None = None, vocab: int | None = None, stream=None) -> int:
+    """sirllm_step with the scores taken from hidden [n_streams*n_new, ld_h] and weight [>= vocab, ld_w] (bf16 or
+    f16) instead of stored logits; returns n_keep."""
+    _on_device(hidden, weight, token_ids, scores, k_src, v_src, k_dst, v_dst, kept_idx, scores_out, workspace)
+    n_streams = scores.shape[0]
+    for t in (hidden, weight):
+        if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise ValueError("hidden / weight must be 2-D with contiguous rows")
+    if hidden.dtype != weight.dtype:
+        raise TypeError("hidden and weight must have the same element type")
+    if hidden.shape[0] != n_streams * n_new or token_ids.numel() != n_streams * n_new:
+        raise ValueError("one hidden-state row and one token id per new token")
+    if token_ids.dtype != torch.int32 or not token_ids.is_contiguous():
+        raise TypeError("token_ids must be contiguous int32")
+    for t, dt in ((scores, torch.float32), (kept_idx, torch.int32), (scores_out, torch.float32)):
+        if t.dim() != 2 or t.dtype != dt or (t.shape[1] > 1 and t.stride(1) != 1) or t.shape[0] != n_streams:
+            raise ValueError("scores / kept_idx / scores_out must be [n_streams, n] with contiguous rows")
+    d_model = min(hidden.shape[1], weight.shape[1]) if d_model is None else int(d_model)
+    vocab = weight.shape[0] if vocab is None else int(vocab)
+    if vocab > weight.shape[0] or d_model > hidden.shape[1] or d_model > weight.shape[1]:
+        raise ValueError("vocab / d_model exceed the arrays")
+    p = _policy(policy)
+    n_cand = n_held + n_new
+    n_keep = min(n_cand, p.n_sink + p.n_topk + p.n_recent)
+    ls = kv_layout(k_src)
+    if kv_layout_tuple(v_src) != kv_layout_tuple(k_src):
+        raise ValueError("K and V must share one layout")
+    if k_src.shape[0] != n_streams or k_src.shape[3] < n_cand:
+        raise ValueError("source cache must hold n_cand slots for every stream")
+    if k_dst is not None:
+        ldst = kv_layout(k_dst)
+        if kv_layout_tuple(v_dst) != kv_layout_tuple(k_dst) or k_dst.shape[3] < n_keep or k_dst.shape[0] != n_streams:
+            raise ValueError("destination cache must hold n_keep slots for every stream, K and V alike")
+    else:
+        ldst = ls
+    wp, wb = _ws(workspace)
+    _check(_lib.sirllm_step_lmhead(_ptr(hidden), _row_stride(hidden), _ptr(weight), _row_stride(weight),
+                                   _dtype_code(hidden), d_model, vocab, _ptr(token_ids),
+                                   _ptr(scores), _row_stride(scores), n_streams, n_held, n_new, C.byref(p),
+                                   _ptr(k_src), _ptr(v_src), C.byref(ls), _ptr(k_dst), _ptr(v_dst), C.byref(ldst),
+                                   _ptr(kept_idx), _row_stride(kept_idx), _ptr(scores_out), _row_stride(scores_out),
+                                   wp, wb, _stream(stream)), "sirllm_step_lmhead")
     return n_keep
 
 

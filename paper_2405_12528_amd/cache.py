@@ -31,6 +31,7 @@ class RetentiveCache:
         self.n_held = 0
         nbytes = b.sirllm_workspace_bytes(n_streams, self.capacity, n_streams * max_new, 1 << 20)
         self._ws = torch.zeros(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+        self._lm_ws = None                             # scratch of step_from_hidden, sized on first use
 
     # -- views of the live state ------------------------------------------------------------
     @property
@@ -69,6 +70,28 @@ class RetentiveCache:
                                self._scores[oth], workspace=self._ws, stream=stream)
         evicted = n_cand > n_keep
         # scores always move to the other array (decayed); K/V only when something was evicted
+        if evicted:
+            self._cur = oth
+        else:
+            self._scores[cur], self._scores[oth] = self._scores[oth], self._scores[cur]
+        self.n_held = n_keep
+        return evicted
+
+    def step_from_hidden(self, hidden: torch.Tensor, weight: torch.Tensor, token_ids: torch.Tensor, stream=None) -> bool:
+        """step() with the scores taken straight from the final hidden states [n_streams * n_new, d_model] and the
+        output embedding matrix [vocab, d_model] (bf16 or f16): the logits are never stored."""
+        n_new = hidden.shape[0] // self.n_streams
+        if n_new * self.n_streams != hidden.shape[0] or n_new > self.max_new:
+            raise ValueError("hidden must hold n_streams * n_new rows with n_new <= max_new")
+        cur, oth = self._cur, 1 - self._cur
+        n_cand = self.n_held + n_new
+        need = b.sirllm_step_lmhead_workspace_bytes(self.n_streams, n_cand, hidden.shape[0], weight.shape[0])
+        if self._lm_ws is None or self._lm_ws.numel() < need:
+            self._lm_ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+        n_keep = b.sirllm_step_lmhead(hidden, weight, token_ids, self._scores[cur], self.n_held, n_new, self.policy,
+                                      self._k[cur], self._v[cur], self._k[oth], self._v[oth], self.kept_idx,
+                                      self._scores[oth], self._lm_ws, stream=stream)
+        evicted = n_cand > n_keep
         if evicted:
             self._cur = oth
         else:

@@ -246,27 +246,48 @@ size_t sirllm_lmhead_workspace_bytes(int64_t n_rows, int32_t vocab)
     return per_tile * (size_t)lmhead_tiles_vocab(vocab);
 }
 
-int sirllm_lmhead_score(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, sirllm_dtype dt,
-                        int32_t d_model, int64_t n_rows, int32_t vocab, const int32_t* token_ids,
-                        float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+namespace {
+
+int validate_lmhead(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, sirllm_dtype dt,
+                    int32_t d_model, int64_t n_rows, int32_t vocab, const int32_t* token_ids)
 {
     if (n_rows < 0 || n_rows > 0x7fffffffLL || vocab < 1 || d_model < 1 || ld_h < d_model || ld_w < d_model)
         return SIRLLM_ERR_INVALID_ARG;
     if (dt != SIRLLM_F32 && dt != SIRLLM_BF16 && dt != SIRLLM_F16) return SIRLLM_ERR_INVALID_ARG;
     if (n_rows == 0) return SIRLLM_OK;
-    if (!hidden || !weight || !token_ids || !scores_out) return SIRLLM_ERR_INVALID_ARG;
+    if (!hidden || !weight || !token_ids) return SIRLLM_ERR_INVALID_ARG;
     if (dt == SIRLLM_F32) return SIRLLM_ERR_UNSUPPORTED;
     if ((d_model & 7) || (ld_h & 7) || (ld_w & 7) || ld_h >= (1 << 21) || ld_w >= (1 << 21) ||
         ((uintptr_t)hidden & 15) || ((uintptr_t)weight & 15))
         return SIRLLM_ERR_UNSUPPORTED;
-    const int rc = workspace_check(workspace, workspace_bytes, sirllm_lmhead_workspace_bytes(n_rows, vocab));
-    if (rc) return rc;
+    return SIRLLM_OK;
+}
+
+LmHeadArgs make_lmhead_args(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, int32_t d_model,
+                            int64_t n_rows, int32_t vocab, const int32_t* token_ids, void* workspace)
+{
     LmHeadArgs a;
     a.hidden = hidden; a.weight = weight; a.ld_h = ld_h; a.ld_w = ld_w; a.d_model = d_model; a.vocab = vocab;
     a.n_rows = n_rows; a.token_ids = token_ids; a.partial = (float*)workspace;
     a.part_stride = (int64_t)((((size_t)n_rows * 3 * sizeof(float) + 255) & ~(size_t)255) / sizeof(float));
     a.n_vtiles = 0; a.n_ttiles = 0;
-    return hip_status(launch_lmhead_score(a, dt, scores_out, (hipStream_t)hip_stream));
+    return a;
+}
+
+}  // namespace
+
+int sirllm_lmhead_score(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, sirllm_dtype dt,
+                        int32_t d_model, int64_t n_rows, int32_t vocab, const int32_t* token_ids,
+                        float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    int rc = validate_lmhead(hidden, ld_h, weight, ld_w, dt, d_model, n_rows, vocab, token_ids);
+    if (rc) return rc;
+    if (n_rows == 0) return SIRLLM_OK;
+    if (!scores_out) return SIRLLM_ERR_INVALID_ARG;
+    rc = workspace_check(workspace, workspace_bytes, sirllm_lmhead_workspace_bytes(n_rows, vocab));
+    if (rc) return rc;
+    const LmHeadArgs a = make_lmhead_args(hidden, ld_h, weight, ld_w, d_model, n_rows, vocab, token_ids, workspace);
+    return hip_status(launch_lmhead_score(a, dt, scores_out, n_rows, 0, (hipStream_t)hip_stream));
 }
 
 int sirllm_decay_select(const float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held,
@@ -402,6 +423,57 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, 
                                                          : launch_select(s, stream));
         if (rc) return rc;
     }
+    // KV <- KV[Id]
+    const GatherArgs g = make_gather_args(k_src, v_src, src, n_cand, k_dst, v_dst, dst, kept_idx, idx_stride,
+                                          n_streams, n_keep);
+    return hip_status(launch_gather(g, 0, n_keep, stream));
+}
+
+size_t sirllm_step_lmhead_workspace_bytes(int32_t n_streams, int32_t n_cand, int64_t n_rows, int32_t vocab)
+{
+    return sirllm_lmhead_workspace_bytes(n_rows, vocab) + sirllm_workspace_bytes(n_streams, n_cand, 0, 0);
+}
+
+int sirllm_step_lmhead(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, sirllm_dtype dt,
+                       int32_t d_model, int32_t vocab, const int32_t* token_ids,
+                       float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held, int32_t n_new,
+                       const sirllm_policy* policy, const void* k_src, const void* v_src, const sirllm_kv_layout* src,
+                       void* k_dst, void* v_dst, const sirllm_kv_layout* dst, int32_t* kept_idx, int64_t idx_stride,
+                       float* scores_out, int64_t out_stride, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (n_streams < 0 || n_held < 0 || n_new < 0) return SIRLLM_ERR_INVALID_ARG;
+    const int64_t n_rows = (int64_t)n_streams * n_new;
+    int rc = validate_lmhead(hidden, ld_h, weight, ld_w, dt, d_model, n_rows, vocab, token_ids);
+    if (rc) return rc;
+    rc = validate_select(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx, idx_stride,
+                         scores_out, out_stride);
+    if (rc) return rc;
+    const int32_t n_cand = n_held + n_new;
+    if (n_streams == 0 || n_cand == 0) return SIRLLM_OK;
+    const bool evict = (int64_t)n_cand > budget_of(policy);
+    const int32_t n_keep = evict ? (int32_t)budget_of(policy) : n_cand;
+    if (evict) {
+        rc = validate_compact(k_src, v_src, src, n_cand, k_dst, v_dst, dst, kept_idx, idx_stride, n_streams, n_keep);
+        if (rc) return rc;
+    }
+    const size_t lm_bytes = sirllm_lmhead_workspace_bytes(n_rows, vocab);
+    rc = workspace_check(workspace, workspace_bytes, sirllm_step_lmhead_workspace_bytes(n_streams, n_cand, n_rows, vocab));
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    // E_t = Entropy(new tokens) from z = h W^T, appended behind the held scores
+    if (n_rows > 0) {
+        const LmHeadArgs a = make_lmhead_args(hidden, ld_h, weight, ld_w, d_model, n_rows, vocab, token_ids, workspace);
+        rc = hip_status(launch_lmhead_score(a, dt, scores + n_held, n_new, scores_stride, stream));
+        if (rc) return rc;
+    }
+    // E <- E * eta on the held part; Id = sink + Top_k + recent; E <- E[Id]
+    const SelectArgs s = make_select_args(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx,
+                                          idx_stride, scores_out, out_stride);
+    if (!evict) return hip_status(launch_keep_all(s, stream));
+    rc = hip_status(n_cand > SIRLLM_SINGLE_WG_CAND ? launch_select_large(s, (char*)workspace + lm_bytes, stream)
+                                                     : launch_select(s, stream));
+    if (rc) return rc;
     // KV <- KV[Id]
     const GatherArgs g = make_gather_args(k_src, v_src, src, n_cand, k_dst, v_dst, dst, kept_idx, idx_stride,
                                           n_streams, n_keep);

@@ -57,7 +57,9 @@ struct LmHeadArgs {
     int32_t n_vtiles, n_ttiles;   // filled in by the launcher
 };
 int lmhead_tiles_vocab(int32_t vocab);
-hipError_t launch_lmhead_score(const LmHeadArgs& a, sirllm_dtype dt, float* scores_out, hipStream_t stream);
+// Row r is token r % rows_per_stream of stream r / rows_per_stream; its score goes to out[stream*out_stride + token].
+hipError_t launch_lmhead_score(const LmHeadArgs& a, sirllm_dtype dt, float* out, int64_t rows_per_stream,
+                               int64_t out_stride, hipStream_t stream);
 
 // ---- select.hip -------------------------------------------------------------------------
 struct SelectArgs {

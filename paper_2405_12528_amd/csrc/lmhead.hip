@@ -329,8 +329,11 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
 }
 
 // Folds the n_parts triples of every row: 16 rows per workgroup, 16 lanes per row striding over the parts.
+// Row `row` belongs to stream row / rows_per_stream and is its token t = row % rows_per_stream; the score goes
+// to out[stream * out_stride + t].
 __global__ __launch_bounds__(256) void lmhead_merge_kernel(const float* partials, int n_parts, int64_t part_stride,
-                                                           int64_t n_rows, float* out)
+                                                           int64_t n_rows, float* out, int64_t rows_per_stream,
+                                                           int64_t out_stride)
 {
     __shared__ float sm[16][16][3];
     const int r = threadIdx.x & 15, pl = threadIdx.x >> 4;
@@ -356,7 +359,8 @@ __global__ __launch_bounds__(256) void lmhead_merge_kernel(const float* partials
             const float z = sm[i][r][2];
             if (zt != zt && z == z) zt = z;
         }
-        out[row] = (acc.m - zt) + logf(acc.s);
+        const int64_t stream = row / rows_per_stream;
+        out[stream * out_stride + (row - stream * rows_per_stream)] = (acc.m - zt) + logf(acc.s);
     }
 }
 
@@ -364,7 +368,8 @@ __global__ __launch_bounds__(256) void lmhead_merge_kernel(const float* partials
 
 int lmhead_tiles_vocab(int32_t vocab) { return (vocab + BV - 1) / BV; }
 
-hipError_t launch_lmhead_score(const LmHeadArgs& args, sirllm_dtype dt, float* scores_out, hipStream_t stream)
+hipError_t launch_lmhead_score(const LmHeadArgs& args, sirllm_dtype dt, float* out, int64_t rows_per_stream,
+                               int64_t out_stride, hipStream_t stream)
 {
     if (args.n_rows <= 0) return hipSuccess;
     LmHeadArgs a = args;
@@ -384,7 +389,7 @@ hipError_t launch_lmhead_score(const LmHeadArgs& args, sirllm_dtype dt, float* s
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(lmhead_merge_kernel, dim3((unsigned)((a.n_rows + 15) / 16)), dim3(256), 0, stream,
-                       a.partial, a.n_vtiles, a.part_stride, a.n_rows, scores_out);
+                       a.partial, a.n_vtiles, a.part_stride, a.n_rows, out, rows_per_stream > 0 ? rows_per_stream : 1, out_stride);
     return hipGetLastError();
 }
 

@@ -267,3 +267,32 @@ def test_lmhead_argument_errors(b):
     assert ok(FAKE, 64, FAKE, 64, BF, 64, 4, 1000, FAKE, FAKE, None, 0, None) == b.SIRLLM_ERR_WORKSPACE
     assert ok(FAKE, 64, FAKE, 64, BF, 64, 4, 1000, FAKE, FAKE, FAKE, ws - 1, None) == b.SIRLLM_ERR_WORKSPACE
     assert ok(FAKE, 64, FAKE, 64, BF, 64, 4, 1000, FAKE, FAKE, FAKE + 16, ws, None) == b.SIRLLM_ERR_WORKSPACE  # alignment
+
+
+def test_step_lmhead_argument_errors(b):
+    L = b.raw()
+    pol = b.sirllm_policy(4, 20, 8, 0.9)
+    lay = b.sirllm_kv_layout(2, 2, 16, 4, 2 * 2 * 96 * 16, 2 * 96 * 16, 96 * 16, 16)
+    dst = b.sirllm_kv_layout(2, 2, 16, 4, 2 * 2 * 32 * 16, 2 * 32 * 16, 32 * 16, 16)
+    ws = b.sirllm_step_lmhead_workspace_bytes(1, 96, 64, 1000)
+    assert ws == b.sirllm_lmhead_workspace_bytes(64, 1000) + b.sirllm_workspace_bytes(1, 96, 0, 0)
+    K1, K2, V1, V2 = 0x100000, 0x200000, 0x300000, 0x400000
+
+    def call(hidden=FAKE, ld_h=64, weight=FAKE, ld_w=64, dt=1, d=64, vocab=1000, tok=FAKE, scores=0x10000, n_held=32,
+             n_new=64, work=0x20000, wsb=ws, out=0x40000):
+        return L.sirllm_step_lmhead(hidden, ld_h, weight, ld_w, dt, d, vocab, tok, scores, 96, 1, n_held, n_new,
+                                    C.byref(pol), K1, V1, C.byref(lay), K2, V2, C.byref(dst), 0x30000, 32, out, 32,
+                                    work, wsb, None)
+
+    assert call(n_new=-1) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(hidden=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(weight=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(tok=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(dt=0) == b.SIRLLM_ERR_UNSUPPORTED            # binary32 operands
+    assert call(d=60) == b.SIRLLM_ERR_UNSUPPORTED            # d_model % 8
+    assert call(ld_h=56) == b.SIRLLM_ERR_INVALID_ARG         # ld_h < d_model
+    assert call(scores=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(out=0x10000) == b.SIRLLM_ERR_INVALID_ARG     # scores_out overlaps scores
+    assert call(work=None, wsb=0) == b.SIRLLM_ERR_WORKSPACE
+    assert call(wsb=ws - 1) == b.SIRLLM_ERR_WORKSPACE
+    assert call(n_held=0, n_new=0) == b.SIRLLM_OK            # nothing to do

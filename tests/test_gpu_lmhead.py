@@ -148,3 +148,129 @@ def test_lmhead_llama3_shape_sampled_rows_against_the_oracle(b, ref):
     want = ref.lmhead_score(to_np(h[torch.from_numpy(rows).to(DEV)]), to_np(W), to_np(tok)[rows])
     worst = assert_close(got[rows], want)
     print(f"llama3 shape: worst |gpu - oracle| over 12 sampled rows = {worst:.2e}")
+
+
+# ------------------------------------------------------------------ the whole step, scores from the LM head
+def gpu_step_lmhead(b, pol, h, W, tok, held, k_c, v_c):
+    n_streams, n_held = held.shape
+    n_new = h.shape[0] // n_streams
+    n_cand = n_held + n_new
+    n_keep = min(n_cand, pol.n_sink + pol.n_topk + pol.n_recent)
+    E = torch.full((n_streams, n_cand), -5.0, device=DEV)
+    E[:, :n_held] = held
+    idx = torch.full((n_streams, max(n_keep, 1)), -7, dtype=torch.int32, device=DEV)
+    out = torch.full((n_streams, max(n_keep, 1)), -7.0, device=DEV)
+    shape = k_c.shape[:3] + (n_keep,) + k_c.shape[4:]
+    k_dst = torch.zeros(shape, dtype=k_c.dtype, device=DEV)
+    v_dst = torch.zeros(shape, dtype=v_c.dtype, device=DEV)
+    ws = torch.empty(max(b.sirllm_step_lmhead_workspace_bytes(n_streams, n_cand, h.shape[0], W.shape[0]), 256),
+                     dtype=torch.uint8, device=DEV)
+    got = b.sirllm_step_lmhead(h, W, tok, E, n_held, n_new, pol, k_c, v_c, k_dst, v_dst, idx, out, ws)
+    torch.cuda.synchronize()
+    assert got == n_keep
+    return dict(E=E, idx=idx[:, :n_keep], out=out[:, :n_keep], k=k_dst, v=v_dst, n_keep=n_keep, evicted=n_cand > n_keep)
+
+
+def check_step_lmhead(ref, pol, h, W, tok, held, k_c, v_c, g):
+    """New scores against the oracle's double-precision product; then the oracle's select + gather, fed the GPU's
+    scores, bit for bit."""
+    n_streams, n_held = held.shape
+    n_new = h.shape[0] // n_streams
+    Eg = to_np(g["E"])
+    if n_new:
+        want = ref.lmhead_score(to_np(h), to_np(W), to_np(tok)).reshape(n_streams, n_new)
+        assert_close(Eg[:, n_held:].reshape(-1), want.reshape(-1))
+    np.testing.assert_array_equal(Eg[:, :n_held].view(np.uint32), to_np(held).view(np.uint32))
+    ri, ro = ref.decay_select(Eg, n_held, n_new, ref.Policy(*pol))
+    np.testing.assert_array_equal(to_np(g["idx"]), ri)
+    np.testing.assert_array_equal(to_np(g["out"]).view(np.uint32), ro.view(np.uint32))
+    if g["evicted"]:
+        rk, rv = ref.compact_kv(to_np(k_c), to_np(v_c), ri, n_src=n_held + n_new)
+        assert np.array_equal(to_np(g["k"]), rk) and np.array_equal(to_np(g["v"]), rv)
+    else:
+        assert not to_np(g["k"]).any() and not to_np(g["v"]).any()
+
+
+@pytest.mark.parametrize("n_streams,n_held,n_new,pol,d,V", [
+    (1, 100, 40, (4, 50, 40, 0.9), 64, 777),     # new tokens all inside the recent window
+    (1, 100, 40, (4, 80, 8, 0.9), 64, 777),      # selection depends on this turn's scores
+    (3, 60, 30, (4, 30, 10, 0.8), 128, 1000),    # several streams: rows of one launch go to different score rows
+    (2, 10, 12, (4, 20, 8, 0.9), 72, 300),       # under budget; d_model on the general kernel
+    (2, 90, 0, (4, 20, 8, 0.9), 64, 300),        # no new tokens
+    (1, 0, 50, (4, 20, 8, 0.9), 64, 300),        # empty cache
+])
+def test_step_lmhead_small_shapes(b, ref, n_streams, n_held, n_new, pol, d, V):
+    pol = b.Policy(*pol)
+    g0 = torch.Generator(device=DEV).manual_seed(n_held * 100 + n_new + d)
+    h = torch.randn((n_streams * n_new, d), generator=g0, device=DEV).to(torch.bfloat16)
+    W = (torch.randn((V, d), generator=g0, device=DEV) * (3.0 / d ** 0.5)).to(torch.bfloat16)
+    tok = torch.randint(0, V, (n_streams * n_new,), generator=g0, device=DEV, dtype=torch.int32)
+    held = torch.rand((n_streams, n_held), generator=g0, device=DEV) * 6
+    k_c = torch.randn((n_streams, 2, 2, n_held + n_new, 16), generator=g0, device=DEV)
+    v_c = torch.randn((n_streams, 2, 2, n_held + n_new, 16), generator=g0, device=DEV)
+    g = gpu_step_lmhead(b, pol, h, W, tok, held, k_c, v_c)
+    check_step_lmhead(ref, pol, h, W, tok, held, k_c, v_c, g)
+
+
+def test_cache_step_from_hidden_four_turns(b, ref):
+    """The tiny workload through RetentiveCache.step_from_hidden: 64 tokens per turn, budget 32, the output
+    embedding fixed across turns, every turn checked against the oracle fed the GPU's scores."""
+    from paper_2405_12528_amd.cache import RetentiveCache
+    w = synth.WORKLOADS["tiny"]
+    pol = b.Policy(w.n_sink, w.n_topk, w.n_recent, w.decay)
+    cache = RetentiveCache(1, w.n_layers, w.n_kv_heads, w.head_dim, pol, max_new=w.n_new, kv_dtype=torch.float32, device=DEV)
+    for turn in range(1, w.n_turns + 1):
+        h, W = synth.make_lmhead(w, turn=turn, device=DEV)
+        tok = synth.make_token_ids(w, turn=turn, device=DEV)
+        kn, vn = cache.new_kv_slots(w.n_new)
+        kn.copy_(synth.make_kv(w, n_pos=w.n_new, turn=turn, device=DEV, which="k"))
+        vn.copy_(synth.make_kv(w, n_pos=w.n_new, turn=turn, device=DEV, which="v"))
+        n_held = cache.n_held
+        held = cache.scores[:, :n_held].clone()
+        k_c = cache.k[:, :, :, :n_held + w.n_new].clone()
+        v_c = cache.v[:, :, :, :n_held + w.n_new].clone()
+        evicted = cache.step_from_hidden(h, W, tok)
+        torch.cuda.synchronize()
+        assert evicted and cache.n_held == w.budget
+        # what the step appended behind the held scores is no longer reachable through the cache object: score again
+        new = torch.empty(w.n_new, device=DEV)
+        ws = torch.empty(b.sirllm_lmhead_workspace_bytes(w.n_new, w.vocab), dtype=torch.uint8, device=DEV)
+        b.sirllm_lmhead_score(h, W, tok, new, ws)
+        torch.cuda.synchronize()
+        want = ref.lmhead_score(to_np(h), to_np(W), to_np(tok))
+        assert_close(to_np(new), want)
+        Eg = np.concatenate([to_np(held), to_np(new)[None, :]], axis=1)
+        ri, ro = ref.decay_select(Eg, n_held, w.n_new, ref.Policy(*pol))
+        np.testing.assert_array_equal(to_np(cache.kept_idx[:, :w.budget]), ri)
+        np.testing.assert_array_equal(to_np(cache.scores[:, :w.budget]).view(np.uint32), ro.view(np.uint32))
+        rk, rv = ref.compact_kv(to_np(k_c), to_np(v_c), ri)
+        assert np.array_equal(to_np(cache.k[:, :, :, :w.budget]), rk) and np.array_equal(to_np(cache.v[:, :, :, :w.budget]), rv)
+
+
+def test_step_lmhead_mistral_shape(b, ref):
+    """Mistral-7B-shaped step (1024 new tokens, V = 32000, d_model 4096, budget 4096 of 8192 candidates, K/V 32 x 8 x
+    128 bf16) with the scores from the LM head: every score against the logits route, 8 sampled rows against the
+    oracle's product, selection and K/V against the oracle fed the GPU's scores."""
+    w = synth.WORKLOADS["mistral_7b"]
+    pol = b.Policy(w.n_sink, w.n_topk, w.n_recent, w.decay)
+    h, W = synth.make_lmhead(w, turn=1, device=DEV)
+    tok = synth.make_token_ids(w, turn=1, device=DEV)
+    held = synth.make_held_scores(w, device=DEV)
+    k_c = synth.make_kv(w, device=DEV, which="k")
+    v_c = synth.make_kv(w, device=DEV, which="v")
+    g = gpu_step_lmhead(b, pol, h, W, tok, held, k_c, v_c)
+    Eg = to_np(g["E"])
+    z = h.float() @ W.float().T
+    other = torch.empty(w.n_new, device=DEV)
+    b.sirllm_score(z, tok, other)
+    torch.cuda.synchronize()
+    assert_close(Eg[0, w.n_held:], to_np(other))
+    rows = np.sort(np.random.default_rng(1).choice(w.n_new, 8, replace=False))
+    ref.set_threads(16)
+    want = ref.lmhead_score(to_np(h[torch.from_numpy(rows).to(DEV)]), to_np(W), to_np(tok)[rows])
+    assert_close(Eg[0, w.n_held:][rows], want)
+    ri, ro = ref.decay_select(Eg, w.n_held, w.n_new, ref.Policy(*pol))
+    np.testing.assert_array_equal(to_np(g["idx"]), ri)
+    np.testing.assert_array_equal(to_np(g["out"]).view(np.uint32), ro.view(np.uint32))
+    rk, rv = ref.compact_kv(to_np(k_c), to_np(v_c), ri)
+    assert np.array_equal(to_np(g["k"]), rk) and np.array_equal(to_np(g["v"]), rv)
