@@ -243,7 +243,7 @@ size_t sirllm_lmhead_workspace_bytes(int64_t n_rows, int32_t vocab)
     if (n_rows <= 0 || vocab <= 0) return 0;
     // one (m, s, z_tok) triple per row and vocabulary tile, each tile's block padded to 256 bytes
     const size_t per_tile = ((size_t)n_rows * 3 * sizeof(float) + 255) & ~(size_t)255;
-    return per_tile * (size_t)lmhead_tiles_vocab(vocab);
+    return per_tile * (size_t)lmhead_tiles_vocab(n_rows, vocab);
 }
 
 namespace {

@@ -56,7 +56,8 @@ struct LmHeadArgs {
     int64_t part_stride;      // >= 3 * n_rows
     int32_t n_vtiles, n_ttiles;   // filled in by the launcher
 };
-int lmhead_tiles_vocab(int32_t vocab);
+// Upper bound on the number of vocabulary tiles (sets of triples in the scratch) for these sizes.
+int lmhead_tiles_vocab(int64_t n_rows, int32_t vocab);
 // Row r is token r % rows_per_stream of stream r / rows_per_stream; its score goes to out[stream*out_stride + token].
 hipError_t launch_lmhead_score(const LmHeadArgs& a, sirllm_dtype dt, float* out, int64_t rows_per_stream,
                                int64_t out_stride, hipStream_t stream);

@@ -55,38 +55,40 @@ __device__ __forceinline__ bool tile_of_block(const LmHeadArgs& a, int& vt, int&
     return vt < a.n_vtiles;
 }
 
-// Reduces the wave's 128 x 128 block of logits to per-token softmax statistics, merges the two vocabulary
-// halves through LDS and writes one (m, s, z_tok) triple per token of the tile.
-__device__ __forceinline__ void tile_epilogue(const LmHeadArgs& a, f32x16 (&acc)[4][4], float* red, int vt, int v0,
+// Reduces a wave's (32 NVB) x (32 NTB) block of logits (vocabulary x tokens) to per-token softmax statistics,
+// merges the two vocabulary halves of the tile through LDS and writes one (m, s, z_tok) triple per token of the tile.
+template <int NVB, int NTB>
+__device__ __forceinline__ void tile_epilogue(const LmHeadArgs& a, f32x16 (&acc)[NVB][NTB], float* red, int vt, int v0,
                                               int64_t t0, int wv, int wt, int lane, int tid)
 {
+    constexpr int TILE_T = 64 * NTB;
     const int frag_row = lane & 31, khalf = lane >> 5;
 #pragma unroll
-    for (int tb = 0; tb < 4; ++tb) {
-        const int T = wt * 128 + tb * 32 + frag_row;
+    for (int tb = 0; tb < NTB; ++tb) {
+        const int T = wt * (32 * NTB) + tb * 32 + frag_row;
         const int64_t row = t0 + T;
         int32_t tok = (row < a.n_rows) ? a.token_ids[row] : -1;
         if (tok >= a.vocab) tok = -1;
-        float z[64];
+        float z[16 * NVB];
         float zt = __uint_as_float(0x7fc00000u);
 #pragma unroll
-        for (int vb = 0; vb < 4; ++vb)
+        for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int v = v0 + wv * 128 + vb * 32 + 8 * (r >> 2) + 4 * khalf + (r & 3);
+                const int v = v0 + wv * (32 * NVB) + vb * 32 + 8 * (r >> 2) + 4 * khalf + (r & 3);
                 float x = acc[vb][tb][r];
                 if (v >= a.vocab) x = -INFINITY;
                 if (v == tok) zt = x;
                 z[vb * 16 + r] = x;
             }
         score_dev::MS ms = {-INFINITY, 0.0f};
-        score_dev::accumulate<64>(z, ms);
+        score_dev::accumulate<16 * NVB>(z, ms);
         const score_dev::MS o = {__shfl_xor(ms.m, 32, kWave), __shfl_xor(ms.s, 32, kWave)};
         ms = score_dev::merge(ms, o);
         const float zo = __shfl_xor(zt, 32, kWave);
         if (zt != zt) zt = zo;
         if (khalf == 0) {
-            float* p = red + (wv * BT + T) * 3;
+            float* p = red + (wv * TILE_T + T) * 3;
             p[0] = ms.m;
             p[1] = ms.s;
             p[2] = zt;
@@ -94,9 +96,9 @@ __device__ __forceinline__ void tile_epilogue(const LmHeadArgs& a, f32x16 (&acc)
     }
     __syncthreads();
     const int64_t row = t0 + tid;
-    if (row < a.n_rows) {
+    if (tid < TILE_T && row < a.n_rows) {
         const float* p0 = red + tid * 3;
-        const float* p1 = red + (BT + tid) * 3;
+        const float* p1 = red + (TILE_T + tid) * 3;
         const score_dev::MS ms = score_dev::merge(score_dev::MS{p0[0], p0[1]}, score_dev::MS{p1[0], p1[1]});
         const float zt = (p0[2] == p0[2]) ? p0[2] : p1[2];
         float* out = a.partial + (int64_t)vt * a.part_stride + 3 * row;
@@ -193,7 +195,7 @@ __global__ __launch_bounds__(256) void lmhead_score_general_kernel(LmHeadArgs a)
         __syncthreads();
     }
 
-    tile_epilogue(a, acc, (float*)(lds + 2 * kStageBytes), vt, v0, t0, wv, wt, lane, tid);
+    tile_epilogue<4, 4>(a, acc, (float*)(lds + 2 * kStageBytes), vt, v0, t0, wv, wt, lane, tid);
 }
 
 // 16 bytes per lane straight from global memory into LDS (global_load_lds_dwordx4): lane l's chunk lands at
@@ -204,128 +206,150 @@ __device__ __forceinline__ void load_to_lds(const char* g, char* lds_block)
                                      (__attribute__((address_space(3))) void*)lds_block, 16, 0, 0);
 }
 
-// Fast kernel (d_model a multiple of 32): tiles go from global memory straight into LDS, no staging
-// registers, through a ring of five 32 KB buffers (stage = 32 K elements of both tiles; buffer = stage % 5;
-// all 160 KB of the LDS).  One stage is two 16-wide slices = 32 MFMAs per wave:
-//   slice 0: MFMAs under the LDS reads of slice 1 and under 4 of this wave's 8 loads of stage ks + 4
-//   wait until this wave's loads of stage ks + 1 have landed (the 24 younger ones may stay in flight), barrier:
-//   every wave has finished reading stage ks, so its buffer is free for stage ks + 5
-//   slice 1: MFMAs under the LDS reads of slice 0 of stage ks + 1 and under the first 4 loads of stage ks + 5.
-// What bounds this kernel is the L2 -> LDS path: a CU gets bandwidth in proportion to the bytes it keeps in
-// flight (measured: ~46 GB/s per CU with 128 KB in flight), so the ring is as deep as the LDS allows (up to
-// 3.5 stages = 112 KB in flight) and loads are issued one per four MFMAs rather than in bursts.
+// Fast kernel (d_model a multiple of 32).  The workgroup is 2 x 2 waves; a wave owns NVB x NTB result blocks of
+// 32 x 32, so the tile is (64 NVB) vocabulary rows x (64 NTB) tokens:
+//   NVB = NTB = 4   256 x 256, 256 accumulator registers per lane, one workgroup per CU: MFMA bound
+//   NVB = NTB = 2   128 x 128 for up to 128 rows
+//   NVB = 2, NTB = 1   128 x 64 for up to 64 rows (a turn of a dialogue): bound by streaming W from HBM
+// Tiles go from global memory straight into LDS, no staging registers, through a ring of RING buffers (stage =
+// 32 K elements of both tiles; buffer = stage % RING).  One stage is two 16-wide slices:
+//   slice 0: MFMAs under the LDS reads of slice 1
+//   wait until this wave's loads of stage ks + 1 have landed (the younger ones stay in flight), barrier: every
+//   wave has finished reading stage ks, so its buffer is free for stage ks + RING
+//   slice 1: MFMAs under the LDS reads of slice 0 of stage ks + 1 and under this wave's loads of stage ks + RING.
 constexpr int FK = 32;
 constexpr int kFastRow = FK * 2;                       // 64 bytes per tile row
-constexpr int kFastTile = BV * kFastRow;               // 16 KB
-constexpr int kFastStage = 2 * kFastTile;              // 32 KB
-constexpr int kRing = 5;
-constexpr int kFastLds = kRing * kFastStage;      // the epilogue's scratch reuses the ring
 
 // wait for all but the n youngest vector-memory operations and for every LDS operation, then barrier
-#define SIRLLM_WAIT_BARRIER(n) asm volatile("s_waitcnt vmcnt(" #n ") lgkmcnt(0)\n\ts_barrier" ::: "memory")
+template <int N>
+__device__ __forceinline__ void wait_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
 
-template <int DT>
+template <int NVB, int NTB, int RING>
+struct FastCfg {
+    static constexpr int kBV = 64 * NVB, kBT = 64 * NTB;
+    static constexpr int kTileW = kBV * kFastRow;                  // bytes of the W tile of one stage
+    static constexpr int kStage = (kBV + kBT) * kFastRow;
+    static constexpr int kLpw = NVB + NTB;                         // 1 KB loads per wave and stage
+    static constexpr int kLds = RING * kStage;                     // the epilogue's scratch reuses the ring
+    static_assert((RING - 1) * kLpw <= 63, "vmcnt is a 6-bit counter");
+    static_assert(kLds >= 2 * kBT * 3 * 4 && kLds <= 160 * 1024, "LDS budget");
+};
+
+template <int DT, int NVB, int NTB, int RING, bool PIN>
 __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
 {
+    using Cfg = FastCfg<NVB, NTB, RING>;
     extern __shared__ __align__(16) char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wv = wave & 1, wt = wave >> 1;
     int vt, tt;
     if (!tile_of_block(a, vt, tt)) return;
-    const int v0 = vt * BV;
-    const int64_t t0 = (int64_t)tt * BT;
+    const int v0 = vt * Cfg::kBV;
+    const int64_t t0 = (int64_t)tt * Cfg::kBT;
 
-    // ---- loads: a stage is 32 blocks of 1 KB (16 rows x 64 B): blocks 0..15 the W tile, 16..31 the h tile.
-    // Wave w issues blocks 8 w + j, j = 0..7 (waves 0, 1: W; waves 2, 3: h).  Within a block lane l fills
-    // row l / 4, chunk position l % 4, which holds chunk (l % 4) ^ ((row / 4) % 4) of that row: rows are 64
-    // bytes, four to a 256-byte bank line, and the 16 rows a quarter wave reads from one chunk column land in
-    // 16 different 16-byte slots.
-    const bool is_w = wave < 2;
-    const int ld2 = (int)(is_w ? a.ld_w : a.ld_h) * 2;
-    const int rows_left = is_w ? a.vocab - v0 : (int)((a.n_rows - t0 < BT) ? a.n_rows - t0 : BT);
-    const char* gbase = is_w ? (const char*)a.weight + (int64_t)v0 * a.ld_w * 2
-                             : (const char*)a.hidden + t0 * a.ld_h * 2;
-    gbase += (((lane & 3) ^ ((lane >> 4) & 3)) << 4);
-    int goff[8];
+    // ---- loads: a stage is 4 (NVB + NTB) blocks of 1 KB (16 rows x 64 B): first the W tile, then the h tile.
+    // Wave w issues blocks kLpw w + j.  Within a block lane l fills row l / 4, chunk position l % 4, which holds
+    // chunk (l % 4) ^ ((row / 4) % 4) of that row: rows are 64 bytes, four to a 256-byte bank line, and the 16
+    // rows a quarter wave reads from one chunk column land in 16 different 16-byte slots (the LDS has 64 banks
+    // and serves a 16-byte-per-lane read 16 lanes at a time).
+    const int rows_w = a.vocab - v0;
+    const int rows_h = (int)((a.n_rows - t0 < Cfg::kBT) ? a.n_rows - t0 : Cfg::kBT);
+    const int lane_chunk = ((lane & 3) ^ ((lane >> 4) & 3)) << 4;
+    const char* gptr[Cfg::kLpw];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        int r = ((wave & 1) * 8 + j) * 16 + (lane >> 2);
+    for (int j = 0; j < Cfg::kLpw; ++j) {
+        const int blk = wave * Cfg::kLpw + j;
+        const bool is_w = blk < 4 * NVB;
+        int r = (is_w ? blk : blk - 4 * NVB) * 16 + (lane >> 2);
+        const int rows_left = is_w ? rows_w : rows_h;
         if (r >= rows_left) r = rows_left - 1;                            // rows past the end re-read the last row
-        goff[j] = r * ld2;
+        gptr[j] = (is_w ? (const char*)a.weight + ((int64_t)v0 + r) * a.ld_w * 2
+                        : (const char*)a.hidden + (t0 + r) * a.ld_h * 2) + lane_chunk;
     }
-    char* const my_blocks = lds + wave * 8 * 1024;
+    char* const my_blocks = lds + wave * Cfg::kLpw * 1024;
     const int nk = a.d_model / FK;             // >= 1
-    // ---- fragments: row = 128 * (wave half) + 32 * block + lane % 32, chunk = 2 kk + lane / 32
+    // load j of stage ks into ring buffer `buf` (a stage past the end re-reads the last one into a buffer
+    // nobody reads)
+    auto issue_load = [&](int ks, int buf, int j) {
+        load_to_lds(gptr[j] + (int64_t)(ks < nk ? ks : nk - 1) * (FK * 2), my_blocks + buf * Cfg::kStage + j * 1024);
+    };
+
+    // ---- fragments: row = 32 NVB (or NTB) * (wave half) + 32 * block + lane % 32, chunk = 2 kk + lane / 32
     const int frag_row = lane & 31, khalf = lane >> 5;
-    const int a_base = (wv * 128 + frag_row) * kFastRow;
-    const int b_base = kFastTile + (wt * 128 + frag_row) * kFastRow;
+    const int a_base = (wv * (32 * NVB) + frag_row) * kFastRow;
+    const int b_base = Cfg::kTileW + (wt * (32 * NTB) + frag_row) * kFastRow;
     int cpos[2];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) cpos[kk] = ((2 * kk + khalf) ^ ((frag_row >> 2) & 3)) << 4;
 
-    f32x16 acc[4][4];
+    f32x16 acc[NVB][NTB];
 #pragma unroll
-    for (int vb = 0; vb < 4; ++vb)
+    for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb)
+        for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[vb][tb][r] = 0.0f;
 
-    u32x4 af[2][4], bf[2][4];
-    // fragment i of slice kk: i = 0..3 the W blocks, 4..7 the h blocks
+    u32x4 af[2][NVB], bf[2][NTB];
+    // fragment i of slice kk: i < NVB the W blocks, then the h blocks
     auto read_frag = [&](const char* s, int kk, int set, int i) {
-        if (i < 4) af[set][i] = *(const u32x4*)(s + a_base + i * 32 * kFastRow + cpos[kk]);
-        else bf[set][i - 4] = *(const u32x4*)(s + b_base + (i - 4) * 32 * kFastRow + cpos[kk]);
+        if (i < NVB) af[set][i] = *(const u32x4*)(s + a_base + i * 32 * kFastRow + cpos[kk]);
+        else bf[set][i - NVB] = *(const u32x4*)(s + b_base + (i - NVB) * 32 * kFastRow + cpos[kk]);
     };
-    auto load_frags = [&](const char* s, int kk, int set) {
+    // One slice: NVB x NTB MFMAs on fragment set `use`, and in their shadow the LDS reads of the next slice
+    // (into the other set) and, in slice 1, the loads of a later stage.  With PIN the order is fixed: behind each
+    // MFMA at most one read or one load (a matrix instruction keeps its pipe busy for 32 cycles, and one read or
+    // load issues within that time); otherwise the compiler orders them (small tiles are not MFMA bound).
+    auto slice = [&](int use, const char* rs, int rkk, int ls, int lbuf, int lj0, int ln) {
+        int extra = 0;                                     // reads, then loads, handed out one per MFMA
 #pragma unroll
-        for (int i = 0; i < 8; ++i) read_frag(s, kk, set, i);
-    };
-    // load j of stage ks into ring buffer `buf` (a stage past the end re-reads the last one into a buffer
-    // nobody reads)
-    auto issue_load = [&](int ks, int buf, int j) {
-        const char* g = gbase + (int64_t)(ks < nk ? ks : nk - 1) * (FK * 2);
-        load_to_lds(g + goff[j], my_blocks + buf * kFastStage + j * 1024);
-    };
-    // One slice: 16 MFMAs on fragment set `use`, and in their shadow the 8 LDS reads of the next slice (into
-    // the other set) and 4 loads, at most one of them behind each MFMA.  The order is pinned: a matrix
-    // instruction keeps its pipe busy for 32 cycles, one LDS read or one load issues within that time, and
-    // loads that arrive at the memory pipeline one at a time do not stall the wave that issues them (a burst of
-    // four costs ~120 cycles, sixteen ~900).
-    auto slice = [&](int use, const char* rs, int rkk, int ls, int lbuf, int lj0) {
+        for (int g = 0; g < NVB; ++g)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < NTB; ++i) {
                 acc[g][i] = mfma<DT>(af[use][g], bf[use][i], acc[g][i]);
-                __builtin_amdgcn_sched_barrier(0);
-                if (i < 2) read_frag(rs, rkk, use ^ 1, 2 * g + i);
-                else if (i == 2) issue_load(ls, lbuf, lj0 + g);
-                __builtin_amdgcn_sched_barrier(0);
+                if (PIN) __builtin_amdgcn_sched_barrier(0);
+                if (extra < NVB + NTB) read_frag(rs, rkk, use ^ 1, extra);
+                else if (extra - (NVB + NTB) < ln) issue_load(ls, lbuf, lj0 + extra - (NVB + NTB));
+                ++extra;
+                if (PIN) __builtin_amdgcn_sched_barrier(0);
             }
+        // what did not fit behind an MFMA (tiles with fewer MFMAs than reads + loads)
+#pragma unroll
+        for (int e = NVB * NTB; e < NVB + NTB + Cfg::kLpw; ++e) {
+            if (e < NVB + NTB) read_frag(rs, rkk, use ^ 1, e);
+            else if (e - (NVB + NTB) < ln) issue_load(ls, lbuf, lj0 + e - (NVB + NTB));
         }
     };
 
-    for (int st = 0; st < 4; ++st)
+    // PIN tiles split a stage's loads over both slices (second half of stage ks + RING - 1 in slice 0, first half of
+    // stage ks + RING in slice 1, so that no slice issues more than one load per two MFMAs); the others issue a
+    // whole stage in slice 1.
+    constexpr int kHalf = PIN ? Cfg::kLpw / 2 : 0;
+    static_assert(!PIN || Cfg::kLpw % 2 == 0, "split loads need an even count");
+    for (int st = 0; st < RING - 1; ++st)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) issue_load(st, st, j);
+        for (int j = 0; j < Cfg::kLpw; ++j) issue_load(st, st, j);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) issue_load(4, 4, j);
-    SIRLLM_WAIT_BARRIER(28);                   // stage 0 landed (stages 1..3 and half of 4 may be in flight)
-    load_frags(lds, 0, 0);
-    int bcur = 0;                              // ks % kRing
+    for (int j = 0; j < Cfg::kLpw - kHalf; ++j) issue_load(RING - 1, RING - 1, j);
+    wait_barrier<(RING - 1) * Cfg::kLpw - kHalf>();        // stage 0 landed (the others may be in flight)
+#pragma unroll
+    for (int i = 0; i < NVB + NTB; ++i) read_frag(lds, 0, 0, i);
+    int bcur = 0;                              // ks % RING
     for (int ks = 0; ks < nk; ++ks) {
-        const int bnext = bcur == kRing - 1 ? 0 : bcur + 1;
-        const int blast = bcur == 0 ? kRing - 1 : bcur - 1;            // (ks + 4) % kRing
-        const char* cur = lds + bcur * kFastStage;
-        const char* nxt = lds + bnext * kFastStage;
-        slice(0, cur, 1, ks + 4, blast, 4);
-        SIRLLM_WAIT_BARRIER(24);               // stage ks + 1 landed; all reads of stage ks done
-        slice(1, nxt, 0, ks + 5, bcur, 0);
+        const int bnext = bcur == RING - 1 ? 0 : bcur + 1;
+        const int blast = bcur == 0 ? RING - 1 : bcur - 1;             // (ks + RING - 1) % RING
+        const char* cur = lds + bcur * Cfg::kStage;
+        const char* nxt = lds + bnext * Cfg::kStage;
+        slice(0, cur, 1, ks + RING - 1, blast, Cfg::kLpw - kHalf, kHalf);
+        wait_barrier<(RING - 2) * Cfg::kLpw>();            // stage ks + 1 landed; all reads of stage ks done
+        slice(1, nxt, 0, ks + RING, bcur, 0, Cfg::kLpw - kHalf);
         bcur = bnext;
     }
-    SIRLLM_WAIT_BARRIER(0);                    // no load may still be landing when the LDS is reused
-    tile_epilogue(a, acc, (float*)lds, vt, v0, t0, wv, wt, lane, tid);
+    wait_barrier<0>();                         // no load may still be landing when the LDS is reused
+    tile_epilogue<NVB, NTB>(a, acc, (float*)lds, vt, v0, t0, wv, wt, lane, tid);
 }
 
 // Folds the n_parts triples of every row: 16 rows per workgroup, 16 lanes per row striding over the parts.
@@ -366,27 +390,74 @@ __global__ __launch_bounds__(256) void lmhead_merge_kernel(const float* partials
 
 }  // namespace
 
-int lmhead_tiles_vocab(int32_t vocab) { return (vocab + BV - 1) / BV; }
+namespace {
+
+// Tile shape by row count: (vocabulary rows, token rows) of a workgroup tile.
+void tile_shape(int64_t n_rows, int& bv, int& bt)
+{
+    if (n_rows <= 64) { bv = 128; bt = 64; }
+    else if (n_rows <= 128) { bv = 128; bt = 128; }
+    else { bv = 256; bt = 256; }
+}
+
+template <int DT, int NVB, int NTB, int RING, bool PIN>
+hipError_t launch_fast(const LmHeadArgs& a, hipStream_t stream)
+{
+    using Cfg = FastCfg<NVB, NTB, RING>;
+    const int64_t groups = (int64_t)((a.n_vtiles + 7) / 8) * a.n_ttiles * 8;
+    if (groups > 0x7fffffff) return hipErrorInvalidValue;
+    auto fn = lmhead_score_kernel<DT, NVB, NTB, RING, PIN>;
+    hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(fn, dim3((unsigned)groups), dim3(256), Cfg::kLds, stream, a);
+    return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_general(const LmHeadArgs& a, hipStream_t stream)
+{
+    const int64_t groups = (int64_t)((a.n_vtiles + 7) / 8) * a.n_ttiles * 8;
+    if (groups > 0x7fffffff) return hipErrorInvalidValue;
+    auto fn = lmhead_score_general_kernel<DT>;
+    hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(fn, dim3((unsigned)groups), dim3(256), kLdsBytes, stream, a);
+    return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_dtype(LmHeadArgs& a, hipStream_t stream)
+{
+    if (a.d_model % FK != 0) {                 // register-staged kernel, 256 x 256 tiles
+        a.n_vtiles = (a.vocab + BV - 1) / BV;
+        a.n_ttiles = (int)((a.n_rows + BT - 1) / BT);
+        return launch_general<DT>(a, stream);
+    }
+    int bv, bt;
+    tile_shape(a.n_rows, bv, bt);
+    a.n_vtiles = (a.vocab + bv - 1) / bv;
+    a.n_ttiles = (int)((a.n_rows + bt - 1) / bt);
+    if (bt == 64) return launch_fast<DT, 2, 1, 6, false>(a, stream);
+    if (bt == 128) return launch_fast<DT, 2, 2, 5, false>(a, stream);
+    return launch_fast<DT, 4, 4, 5, true>(a, stream);
+}
+
+}  // namespace
+
+// Upper bound on the number of vocabulary tiles (= sets of triples) a call with these sizes writes.
+int lmhead_tiles_vocab(int64_t n_rows, int32_t vocab)
+{
+    int bv, bt;
+    tile_shape(n_rows, bv, bt);
+    return (vocab + bv - 1) / bv;
+}
 
 hipError_t launch_lmhead_score(const LmHeadArgs& args, sirllm_dtype dt, float* out, int64_t rows_per_stream,
                                int64_t out_stride, hipStream_t stream)
 {
     if (args.n_rows <= 0) return hipSuccess;
     LmHeadArgs a = args;
-    a.n_vtiles = lmhead_tiles_vocab(a.vocab);
-    a.n_ttiles = (int)((a.n_rows + BT - 1) / BT);
-    const int64_t groups = (int64_t)((a.n_vtiles + 7) / 8) * a.n_ttiles * 8;
-    if (groups > 0x7fffffff) return hipErrorInvalidValue;
-    const bool fast = a.d_model % FK == 0;
-    typedef void (*kernel_t)(LmHeadArgs);
-    const kernel_t fn = fast ? (dt == SIRLLM_BF16 ? lmhead_score_kernel<SIRLLM_BF16> : lmhead_score_kernel<SIRLLM_F16>)
-                             : (dt == SIRLLM_BF16 ? lmhead_score_general_kernel<SIRLLM_BF16>
-                                                  : lmhead_score_general_kernel<SIRLLM_F16>);
-    const int lds_bytes = fast ? kFastLds : kLdsBytes;
-    hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(fn, dim3((unsigned)groups), dim3(256), lds_bytes, stream, a);
-    e = hipGetLastError();
+    hipError_t e = dt == SIRLLM_BF16 ? launch_dtype<SIRLLM_BF16>(a, stream) : launch_dtype<SIRLLM_F16>(a, stream);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(lmhead_merge_kernel, dim3((unsigned)((a.n_rows + 15) / 16)), dim3(256), 0, stream,
                        a.partial, a.n_vtiles, a.part_stride, a.n_rows, out, rows_per_stream > 0 ? rows_per_stream : 1, out_stride);

@@ -71,6 +71,23 @@ def test_lmhead_score_matches_oracle(b, ref, dtype, n_rows, d, V):
     assert_close(got, want)
 
 
+@pytest.mark.parametrize("n_rows,d,V", [
+    (54, 4096, 32000),       # a turn of the Rock-Paper-Scissors-shaped dialogue: 128 x 64 tiles, W streamed once
+    (1, 4096, 32000),        # one token (decode)
+    (100, 1024, 5000),       # 65..128 rows: 128 x 128 tiles
+    (128, 512, 1000), (65, 64, 129), (64, 32, 128),
+])
+def test_lmhead_few_rows_every_row_against_the_oracle(b, ref, n_rows, d, V):
+    w_ = synth.WORKLOADS["rps_dialogue"]
+    h, W = synth.make_lmhead(w_, turn=2, device=DEV, n_rows=n_rows, d_model=d, vocab=V)
+    tok = torch.randint(0, V, (n_rows,), generator=torch.Generator(device=DEV).manual_seed(n_rows + V), device=DEV,
+                        dtype=torch.int32)
+    got = gpu_lmhead(b, h, W, tok)
+    ref.set_threads(16)
+    want = ref.lmhead_score(to_np(h), to_np(W), to_np(tok))
+    assert_close(got, want)
+
+
 def test_lmhead_leading_dimensions_and_subranges(b, ref):
     # hidden and weight embedded in larger allocations whose padding would wreck the result if it were read
     g = torch.Generator(device=DEV).manual_seed(5)
