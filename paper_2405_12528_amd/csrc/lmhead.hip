@@ -273,8 +273,16 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
     const int nk = a.d_model / FK;             // >= 1
     // load j of stage ks into ring buffer `buf` (a stage past the end re-reads the last one into a buffer
     // nobody reads)
+    // Workgroups start their walk over K at different stages (and wrap around): at any moment the chip then
+    // reads many different column stripes of W instead of one 64-byte-wide stripe with a row pitch of d_model
+    // elements, which would land on few memory channels.  A dot product does not care where its sum starts.
+    // Only with a single token tile: otherwise the workgroups that share a W tile (or an h tile) must walk in
+    // step, or they stop finding each other's lines in the L2.
+    const int kstart = a.n_ttiles == 1 ? (int)(((unsigned)vt * 37u) % (unsigned)nk) : 0;
     auto issue_load = [&](int ks, int buf, int j) {
-        load_to_lds(gptr[j] + (int64_t)(ks < nk ? ks : nk - 1) * (FK * 2), my_blocks + buf * Cfg::kStage + j * 1024);
+        int st = (ks < nk ? ks : nk - 1) + kstart;
+        if (st >= nk) st -= nk;
+        load_to_lds(gptr[j] + (int64_t)st * (FK * 2), my_blocks + buf * Cfg::kStage + j * 1024);
     };
 
     // ---- fragments: row = 32 NVB (or NTB) * (wave half) + 32 * block + lane % 32, chunk = 2 kk + lane / 32
