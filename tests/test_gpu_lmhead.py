@@ -291,3 +291,53 @@ def test_step_lmhead_mistral_shape(b, ref):
     np.testing.assert_array_equal(to_np(g["out"]).view(np.uint32), ro.view(np.uint32))
     rk, rv = ref.compact_kv(to_np(k_c), to_np(v_c), ri)
     assert np.array_equal(to_np(g["k"]), rk) and np.array_equal(to_np(g["v"]), rv)
+
+
+def test_step_lmhead_replays_from_a_captured_graph(b):
+    """sirllm_step_lmhead allocates nothing and synchronises nothing; its kernels ask for more than 64 KB of dynamic
+    LDS (a function attribute set at launch).  Captured into a HIP graph, every replay must reproduce the eager
+    result, also with eager work and synchronisations between replays."""
+    pol = b.Policy(4, 30, 0, 0.8)
+    S, n_held, n_new, V, d = 2, 60, 40, 777, 128
+    g0 = torch.Generator(device=DEV).manual_seed(5)
+    h = torch.randn((S * n_new, d), generator=g0, device=DEV).to(torch.bfloat16)
+    W = (torch.randn((V, d), generator=g0, device=DEV) * 0.3).to(torch.bfloat16)
+    tok = torch.randint(0, V, (S * n_new,), generator=g0, device=DEV, dtype=torch.int32)
+    held = torch.rand((S, n_held), generator=g0, device=DEV) * 6
+    k_c = torch.randn((S, 2, 2, n_held + n_new, 16), generator=g0, device=DEV)
+    v_c = torch.randn((S, 2, 2, n_held + n_new, 16), generator=g0, device=DEV)
+    n_keep = 34
+    ws = torch.empty(b.sirllm_step_lmhead_workspace_bytes(S, n_held + n_new, S * n_new, V), dtype=torch.uint8, device=DEV)
+
+    def fresh():
+        E = torch.zeros((S, n_held + n_new), device=DEV)
+        E[:, :n_held] = held
+        return dict(E=E, idx=torch.zeros((S, n_keep), dtype=torch.int32, device=DEV),
+                    out=torch.zeros((S, n_keep), device=DEV), k=torch.zeros((S, 2, 2, n_keep, 16), device=DEV),
+                    v=torch.zeros((S, 2, 2, n_keep, 16), device=DEV))
+
+    def run(t):
+        b.sirllm_step_lmhead(h, W, tok, t["E"], n_held, n_new, pol, k_c, v_c, t["k"], t["v"], t["idx"], t["out"], ws)
+
+    eager = fresh()
+    run(eager)
+    torch.cuda.synchronize()
+    cap = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(cap)                                         # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(cap)
+    for rep in range(4):
+        for name, t in cap.items():                      # eager work between replays: wipe every output
+            t.zero_() if name != "E" else t[:, n_held:].zero_()
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in eager:
+            assert torch.equal(cap[name], eager[name]), f"replay {rep}: {name} differs from the eager run"
