@@ -257,32 +257,35 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
     // and serves a 16-byte-per-lane read 16 lanes at a time).
     const int rows_w = a.vocab - v0;
     const int rows_h = (int)((a.n_rows - t0 < Cfg::kBT) ? a.n_rows - t0 : Cfg::kBT);
-    const int lane_chunk = ((lane & 3) ^ ((lane >> 4) & 3)) << 4;
-    const char* gptr[Cfg::kLpw];
+    // A load address is a wave-uniform base (tile origin + stage offset, scalar registers) plus a 32-bit per-lane
+    // offset (row * pitch + chunk): no vector arithmetic per load.
+    const uint32_t lane_chunk = (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+    const char* ubase[Cfg::kLpw];
+    uint32_t goff[Cfg::kLpw];
 #pragma unroll
     for (int j = 0; j < Cfg::kLpw; ++j) {
-        const int blk = wave * Cfg::kLpw + j;
+        const int blk = __builtin_amdgcn_readfirstlane(wave) * Cfg::kLpw + j;
         const bool is_w = blk < 4 * NVB;
         int r = (is_w ? blk : blk - 4 * NVB) * 16 + (lane >> 2);
         const int rows_left = is_w ? rows_w : rows_h;
         if (r >= rows_left) r = rows_left - 1;                            // rows past the end re-read the last row
-        gptr[j] = (is_w ? (const char*)a.weight + ((int64_t)v0 + r) * a.ld_w * 2
-                        : (const char*)a.hidden + (t0 + r) * a.ld_h * 2) + lane_chunk;
+        ubase[j] = is_w ? (const char*)a.weight + (int64_t)v0 * a.ld_w * 2 : (const char*)a.hidden + t0 * a.ld_h * 2;
+        goff[j] = (uint32_t)r * (uint32_t)((is_w ? a.ld_w : a.ld_h) * 2) + lane_chunk;
     }
-    char* const my_blocks = lds + wave * Cfg::kLpw * 1024;
+    char* const my_blocks = lds + __builtin_amdgcn_readfirstlane(wave) * Cfg::kLpw * 1024;
     const int nk = a.d_model / FK;             // >= 1
-    // load j of stage ks into ring buffer `buf` (a stage past the end re-reads the last one into a buffer
-    // nobody reads)
     // Workgroups start their walk over K at different stages (and wrap around): at any moment the chip then
     // reads many different column stripes of W instead of one 64-byte-wide stripe with a row pitch of d_model
     // elements, which would land on few memory channels.  A dot product does not care where its sum starts.
     // Only with a single token tile: otherwise the workgroups that share a W tile (or an h tile) must walk in
     // step, or they stop finding each other's lines in the L2.
     const int kstart = a.n_ttiles == 1 ? (int)(((unsigned)vt * 37u) % (unsigned)nk) : 0;
+    // load j of stage ks into ring buffer `buf` (a stage past the end re-reads the last one into a buffer
+    // nobody reads)
     auto issue_load = [&](int ks, int buf, int j) {
         int st = (ks < nk ? ks : nk - 1) + kstart;
         if (st >= nk) st -= nk;
-        load_to_lds(gptr[j] + (int64_t)st * (FK * 2), my_blocks + buf * Cfg::kStage + j * 1024);
+        load_to_lds(ubase[j] + (int64_t)st * (FK * 2) + goff[j], my_blocks + buf * Cfg::kStage + j * 1024);
     };
 
     // ---- fragments: row = 32 NVB (or NTB) * (wave half) + 32 * block + lane % 32, chunk = 2 kk + lane / 32
