@@ -233,12 +233,13 @@ struct FastCfg {
     static constexpr int kTileW = kBV * kFastRow;                  // bytes of the W tile of one stage
     static constexpr int kStage = (kBV + kBT) * kFastRow;
     static constexpr int kLpw = NVB + NTB;                         // 1 KB loads per wave and stage
-    static constexpr int kLds = RING * kStage;                     // the epilogue's scratch reuses the ring
+    static constexpr int kDump = 256;                              // where the L2 warm-up loads drop their bytes
+    static constexpr int kLds = RING * kStage + kDump;             // the epilogue's scratch reuses the ring
     static_assert((RING - 1) * kLpw <= 63, "vmcnt is a 6-bit counter");
-    static_assert(kLds >= 2 * kBT * 3 * 4 && kLds <= 160 * 1024, "LDS budget");
+    static_assert(RING * kStage >= 2 * kBT * 3 * 4 && kLds <= 160 * 1024, "LDS budget");
 };
 
-template <int DT, int NVB, int NTB, int RING, bool PIN>
+template <int DT, int NVB, int NTB, int RING, bool PIN, bool WARM>
 __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
 {
     using Cfg = FastCfg<NVB, NTB, RING>;
@@ -348,6 +349,36 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
     wait_barrier<(RING - 1) * Cfg::kLpw - kHalf>();        // stage 0 landed (the others may be in flight)
 #pragma unroll
     for (int i = 0; i < NVB + NTB; ++i) read_frag(lds, 0, 0, i);
+    // ---- L2 warm-up (WARM): the W tile comes from HBM, and the ring's look-ahead (RING - 1 stages, ~2 us) does
+    // not cover an HBM access under load.  Every 4 stages one wave touches, with a 4-byte-per-lane load whose data
+    // goes to a dump area in LDS (no register, same in-order completion counter as the tile loads), the W lines of
+    // stages ks + 12 .. ks + 15: one lane per 128-byte line, 32 rows x 2 lines per instruction.  The `ns`
+    // workgroups that share a W tile (same vocabulary tile, consecutive token tiles, resident together on one XCD)
+    // split its rows.  Past the end of K the lines of the tile this CU will take next are touched.
+    const int swave = __builtin_amdgcn_readfirstlane(wave);
+    const int ns = (a.n_ttiles & 7) == 0 ? 8 : (a.n_ttiles & 3) == 0 ? 4 : (a.n_ttiles & 1) == 0 ? 2 : 1;
+    auto warm = [&](int stage) {
+        int vt2 = vt, tt2 = tt;
+        if (stage >= nk) {
+            stage -= nk;
+            const int q2 = (int)(blockIdx.x >> 3) + 32;
+            vt2 = (q2 / a.n_ttiles) * 8 + (int)(blockIdx.x & 7);
+            tt2 = q2 % a.n_ttiles;
+            if (vt2 >= a.n_vtiles || stage >= nk) return;
+        }
+        const int rows_per = Cfg::kBV / ns;
+        const int rows_left = a.vocab - vt2 * Cfg::kBV;
+        int koff = stage * (FK * 2) + (lane & 1) * 128;
+        if (koff >= a.d_model * 2) koff = stage * (FK * 2);                  // a row shorter than the 256 bytes touched
+        const char* base = (const char*)a.weight + (int64_t)vt2 * Cfg::kBV * a.ld_w * 2 + koff;
+        for (int r0 = 0; r0 < rows_per; r0 += 32) {
+            int r = (tt2 % ns) * rows_per + r0 + (lane >> 1);
+            if (r >= rows_left) r = rows_left - 1;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + (int64_t)r * a.ld_w * 2),
+                                             (__attribute__((address_space(3))) void*)(lds + RING * Cfg::kStage), 4, 0, 0);
+        }
+    };
+
     int bcur = 0;                              // ks % RING
     for (int ks = 0; ks < nk; ++ks) {
         const int bnext = bcur == RING - 1 ? 0 : bcur + 1;
@@ -356,6 +387,8 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
         const char* nxt = lds + bnext * Cfg::kStage;
         slice(0, cur, 1, ks + RING - 1, blast, Cfg::kLpw - kHalf, kHalf);
         wait_barrier<(RING - 2) * Cfg::kLpw>();            // stage ks + 1 landed; all reads of stage ks done
+        // (right after a wait: the touch has three stages to come back before a younger load is waited for)
+        if (WARM && kstart == 0 && (ks & 3) == 0 && ((ks >> 2) & 3) == swave) warm(ks + 12);
         slice(1, nxt, 0, ks + RING, bcur, 0, Cfg::kLpw - kHalf);
         bcur = bnext;
     }
@@ -411,13 +444,13 @@ void tile_shape(int64_t n_rows, int& bv, int& bt)
     else { bv = 256; bt = 256; }
 }
 
-template <int DT, int NVB, int NTB, int RING, bool PIN>
+template <int DT, int NVB, int NTB, int RING, bool PIN, bool WARM>
 hipError_t launch_fast(const LmHeadArgs& a, hipStream_t stream)
 {
     using Cfg = FastCfg<NVB, NTB, RING>;
     const int64_t groups = (int64_t)((a.n_vtiles + 7) / 8) * a.n_ttiles * 8;
     if (groups > 0x7fffffff) return hipErrorInvalidValue;
-    auto fn = lmhead_score_kernel<DT, NVB, NTB, RING, PIN>;
+    auto fn = lmhead_score_kernel<DT, NVB, NTB, RING, PIN, WARM>;
     hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(fn, dim3((unsigned)groups), dim3(256), Cfg::kLds, stream, a);
@@ -448,9 +481,9 @@ hipError_t launch_dtype(LmHeadArgs& a, hipStream_t stream)
     tile_shape(a.n_rows, bv, bt);
     a.n_vtiles = (a.vocab + bv - 1) / bv;
     a.n_ttiles = (int)((a.n_rows + bt - 1) / bt);
-    if (bt == 64) return launch_fast<DT, 2, 1, 6, false>(a, stream);
-    if (bt == 128) return launch_fast<DT, 2, 2, 5, false>(a, stream);
-    return launch_fast<DT, 4, 4, 5, true>(a, stream);
+    if (bt == 64) return launch_fast<DT, 2, 1, 6, false, false>(a, stream);
+    if (bt == 128) return launch_fast<DT, 2, 2, 5, false, false>(a, stream);
+    return launch_fast<DT, 4, 4, 4, true, true>(a, stream);
 }
 
 }  // namespace
