@@ -2,9 +2,9 @@
 // buffer).  The kept list is strictly ascending, so row j always comes from a slot kept_idx[j] >= j:
 // rows only move towards the front.  One workgroup owns one plane (stream, layer, K|V, head) and
 // walks it front to back in chunks: every lane loads its vectors of the chunk, the workgroup waits
-// until all of those loads have landed, then stores.  A chunk writes rows [c0, c1) and reads rows
-// >= c0; the next chunk reads rows >= c1 only, so nothing a chunk writes is ever read again and
-// no ordering between workgroups is needed.  Rows that stay where they are (the sinks, any
+// until all of those loads have landed, then stores; the loads of the next chunk are already in flight
+// by then.  A chunk writes rows [c0, c1) and reads rows >= c0; the next chunk reads rows >= c1 only, so
+// nothing a chunk writes is ever read again and no ordering between workgroups is needed.  Rows that stay where they are (the sinks, any
 // leading run of kept slots) are neither read nor written.  Same HBM traffic per moved row as the
 // out-of-place gather, half the K/V memory.
 #include "common.h"
@@ -50,34 +50,51 @@ __global__ __launch_bounds__(BLOCK) void gather_inplace_kernel(GatherLaunch g, R
     const int32_t* idx = a.kept_idx + stream * a.idx_stride;
 
     const int n_items = (g.row_end - g.row_begin) * g.vpr;
-    for (int c0 = 0; c0 < n_items; c0 += BLOCK * UNROLL) {
-        VecT v[UNROLL];
-        off_t doff[UNROLL];
-        bool moved[UNROLL];
+    constexpr int CH = BLOCK * UNROLL;
+    VecT va[UNROLL], vb[UNROLL];
+    off_t da[UNROLL], db[UNROLL];
+    bool ma[UNROLL], mb[UNROLL];
+    // Every lane issues exactly UNROLL loads per chunk, whatever its rows need (a lane past the end, a row that
+    // stays in place or an index with no source slot re-reads a harmless address and drops the data): the wait
+    // below counts instructions.
+    auto load_chunk = [&](VecT (&v)[UNROLL], off_t (&doff)[UNROLL], bool (&moved)[UNROLL], int c0) {
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int w = c0 + u * BLOCK + (int)threadIdx.x;
-            moved[u] = false;
-            v[u] = VecT{};
-            doff[u] = 0;
-            if (w < n_items) {
-                int j, c;
-                if constexpr (POW2) { j = w >> g.shift; c = w & (g.vpr - 1); }
-                else                { j = w / g.vpr;    c = w - j * g.vpr; }
-                j += g.row_begin;
-                const uint32_t i = (uint32_t)idx[j];
-                moved[u] = i != (uint32_t)j;
-                doff[u] = (off_t)j * (off_t)a.s_pos + (off_t)(c * (int)sizeof(VecT));
-                if (moved[u] && i < (uint32_t)a.n_src)       // an index with no source slot leaves a zero row
-                    v[u] = gather_dev::ld<VecT, NT>(base + ((off_t)i * (off_t)a.s_pos + (off_t)(c * (int)sizeof(VecT))));
-            }
+            const bool in = w < n_items;
+            const int wc = in ? w : n_items - 1;
+            int j, c;
+            if constexpr (POW2) { j = wc >> g.shift; c = wc & (g.vpr - 1); }
+            else                { j = wc / g.vpr;    c = wc - j * g.vpr; }
+            j += g.row_begin;
+            const uint32_t i = (uint32_t)idx[j];
+            const bool ok = i < (uint32_t)a.n_src;                     // an index with no source slot leaves a zero row
+            moved[u] = in && i != (uint32_t)j;
+            doff[u] = (off_t)j * (off_t)a.s_pos + (off_t)(c * (int)sizeof(VecT));
+            const uint32_t isrc = (moved[u] && ok) ? i : (uint32_t)j;
+            const VecT x = gather_dev::ld<VecT, NT>(base + ((off_t)isrc * (off_t)a.s_pos + (off_t)(c * (int)sizeof(VecT))));
+            v[u] = (moved[u] && !ok) ? VecT{} : x;
         }
-        // every load of this chunk must have returned before any lane overwrites a row of it
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+    };
+    auto store_chunk = [&](const VecT (&v)[UNROLL], const off_t (&doff)[UNROLL], const bool (&moved)[UNROLL]) {
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u)
             if (moved[u]) gather_dev::st<VecT, NT>(base + doff[u], v[u]);
+    };
+    // A chunk's sources lie at or behind its own first row, i.e. behind every row an earlier chunk writes: loads may
+    // run ahead of stores, and only a chunk's own stores have to wait for its own loads (of the whole workgroup).
+    // So the loads of chunk c + 1 go out before the workgroup waits for chunk c: "all but the UNROLL youngest
+    // memory operations have completed" is exactly "chunk c has landed (and the older stores are done)".
+    load_chunk(va, da, ma, 0);
+    for (int c0 = 0; c0 < n_items; c0 += 2 * CH) {
+        load_chunk(vb, db, mb, c0 + CH);
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(UNROLL) : "memory");
+        store_chunk(va, da, ma);
+        __builtin_amdgcn_sched_barrier(0);
+        load_chunk(va, da, ma, c0 + 2 * CH);
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(UNROLL) : "memory");
+        store_chunk(vb, db, mb);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -101,7 +118,7 @@ hipError_t launch_vec(const GatherArgs& a, const Ragged& rg, hipStream_t stream)
     bool pow2, off64;
     if (!gather_dev::fill_launch<VecT>(g, a, 0, a.n_keep, &pow2, &off64)) return hipErrorInvalidValue;
     const int block = tuning::get("SIRLLM_INPLACE_BLOCK", 1024);
-    const int unroll = tuning::get("SIRLLM_INPLACE_UNROLL", 2);
+    const int unroll = tuning::get("SIRLLM_INPLACE_UNROLL", 4);
     const int planes = a.n_tensors * g.lh;
     // Few planes cannot fill the chip with one workgroup each: cut every row into column parts that are
     // compacted by workgroups of their own (only when vectors per row is a power of two).
