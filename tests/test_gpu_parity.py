@@ -675,6 +675,7 @@ LARGE_CASES = [
     (1, 60000, 5000, 4, 60995, 0, 1.0, 7),           # all but one middle slot kept
     (2, 500000, 24000, 4, 262144, 2048, 0.9, 1000),  # half a million slots
     (1, 40000, 100, 4, 50000, 512, 0.9, 0),          # under budget: keep-all path
+    (1, 16777216 - 4096, 4096, 4, 8000000, 4096, 0.9, 0),   # SIRLLM_MAX_CAND slots, the documented limit
 ]
 
 
