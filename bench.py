@@ -35,6 +35,9 @@ def main():
                     help="also time sirllm_step_ragged (per-stream sizes in device memory, in-place compaction) on "
                          "the same shapes; reported under 'ragged_inplace' in the JSON line")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = min(16, host cores)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also replay the step from a captured HIP graph (no per-launch host cost): the per-step "
+                         "latency of small turns")
     ap.add_argument("--lmhead", action="store_true",
                     help="also time sirllm_lmhead_score (scores straight from bf16 hidden states and the output "
                          "embedding matrix, logits never stored) on the workload's rows")
@@ -182,6 +185,31 @@ def main():
                   "frac": round(bytes_["total"] / (r_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
         log(f"[bench] ragged in-place step: {r_avg*1e3:.1f} us -> {ragged['hbm_gbps']:.0f} GB/s")
 
+    # ---- optional: the step replayed from a captured graph ----------------------------------------------
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()                                       # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        reps = 20
+        hgraph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(hgraph):
+            for _ in range(reps):                        # back-to-back steps in one graph, sets rotating as above
+                step()
+        hgraph.replay()
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(5):
+            hgraph.replay()
+        g1.record()
+        torch.cuda.synchronize()
+        graph_ms = g0.elapsed_time(g1) / (5 * reps)
+        log(f"[bench] step replayed from a graph of {reps} steps: {graph_ms * 1e3:.1f} us/step")
+
     # ---- optional: scoring straight from the LM head (MFMA bound) ---------------------------------
     lmhead = None
     if args.lmhead:
@@ -227,6 +255,8 @@ def main():
         out["ragged_inplace"] = ragged
     if lmhead:
         out["lmhead"] = lmhead
+    if graph_ms is not None:
+        out["graph_ms_per_step"] = round(graph_ms, 5)
     print(json.dumps(out), flush=True)
 
 
