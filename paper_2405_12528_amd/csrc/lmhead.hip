@@ -437,9 +437,11 @@ __global__ __launch_bounds__(256) void lmhead_merge_kernel(const float* partials
 namespace {
 
 // Tile shape by row count: (vocabulary rows, token rows) of a workgroup tile.
-void tile_shape(int64_t n_rows, int& bv, int& bt)
+void tile_shape(int64_t n_rows, int32_t vocab, int& bv, int& bt)
 {
-    if (n_rows <= 64) { bv = 128; bt = 64; }
+    // few rows: W is streamed once and h is re-read by every workgroup, so the tile is as tall as leaves enough
+    // workgroups to fill the chip
+    if (n_rows <= 64) { bv = vocab >= 65536 ? 256 : 128; bt = 64; }
     else if (n_rows <= 128) { bv = 128; bt = 128; }
     else { bv = 256; bt = 256; }
 }
@@ -478,9 +480,10 @@ hipError_t launch_dtype(LmHeadArgs& a, hipStream_t stream)
         return launch_general<DT>(a, stream);
     }
     int bv, bt;
-    tile_shape(a.n_rows, bv, bt);
+    tile_shape(a.n_rows, a.vocab, bv, bt);
     a.n_vtiles = (a.vocab + bv - 1) / bv;
     a.n_ttiles = (int)((a.n_rows + bt - 1) / bt);
+    if (bt == 64 && bv == 256) return launch_fast<DT, 4, 1, 4, false, false>(a, stream);
     if (bt == 64) return launch_fast<DT, 2, 1, 6, false, false>(a, stream);
     if (bt == 128) return launch_fast<DT, 2, 2, 5, false, false>(a, stream);
     return launch_fast<DT, 4, 4, 4, true, true>(a, stream);
@@ -492,7 +495,7 @@ hipError_t launch_dtype(LmHeadArgs& a, hipStream_t stream)
 int lmhead_tiles_vocab(int64_t n_rows, int32_t vocab)
 {
     int bv, bt;
-    tile_shape(n_rows, bv, bt);
+    tile_shape(n_rows, vocab, bv, bt);
     return (vocab + bv - 1) / bv;
 }
 

@@ -76,6 +76,7 @@ def test_lmhead_score_matches_oracle(b, ref, dtype, n_rows, d, V):
     (1, 4096, 32000),        # one token (decode)
     (100, 1024, 5000),       # 65..128 rows: 128 x 128 tiles
     (128, 512, 1000), (65, 64, 129), (64, 32, 128),
+    (33, 64, 70001),         # few rows, large vocabulary: 256 x 64 tiles, ragged last tile
 ])
 def test_lmhead_few_rows_every_row_against_the_oracle(b, ref, n_rows, d, V):
     w_ = synth.WORKLOADS["rps_dialogue"]
