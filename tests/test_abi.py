@@ -296,3 +296,24 @@ def test_step_lmhead_argument_errors(b):
     assert call(work=None, wsb=0) == b.SIRLLM_ERR_WORKSPACE
     assert call(wsb=ws - 1) == b.SIRLLM_ERR_WORKSPACE
     assert call(n_held=0, n_new=0) == b.SIRLLM_OK            # nothing to do
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the benchmark is a one-GPU program: asked for more it must say so and stop before touching a device
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2", "--steps", "1"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and "--gpus must be 1" in r.stderr
+    assert r.stdout.strip() == ""
+
+
+def test_product_files_name_no_working_folder():
+    # nothing that is committed may read, import or run a file under the ignored working folder
+    import subprocess
+    files = subprocess.run(["git", "ls-files"], cwd=ROOT, capture_output=True, text=True).stdout.split()
+    for f in files:
+        if f.endswith((".py", ".hip", ".h", ".c")) and not f.startswith("tests/test_abi.py"):
+            text = open(os.path.join(ROOT, f), errors="ignore").read()
+            assert "_work/" not in text and "_work\\" not in text, f
