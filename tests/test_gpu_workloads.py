@@ -5,6 +5,8 @@ Scores: every row, |gpu - ref| <= 1e-6 + 1e-5*|ref|.  Kept indices and compacted
 stream, bit exact, oracle fed the GPU's scores.  K/V: bit exact, the whole tensors for the
 single-stream workloads; for the 32-stream dialogue two whole streams plus sampled planes of
 every other stream (the oracle gathers one plane at a time there)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -346,3 +348,17 @@ def test_score_rows_beyond_4_gib(b, ref):
     rows = torch.tensor(marks, device=DEV)
     want = ref.score(to_np(z[rows]), to_np(tok[rows]))
     assert_scores_close(to_np(out[rows]), want)
+
+
+def test_python_example_runs_both_routes():
+    """examples/dialogue_loop.py: six turns through RetentiveCache from logits and from the LM head; the sinks stay
+    the first four tokens of the dialogue and the cache holds the budget."""
+    import importlib.util
+    path = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "examples", "dialogue_loop.py")
+    spec = importlib.util.spec_from_file_location("dialogue_loop", path)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    for extra in ([], ["--from-hidden"]):
+        origin = mod.main(["--turns", "6"] + extra)
+        assert origin.shape == (32, 2)
+        assert origin[-8:, 0].tolist() == [6] * 8           # the recent window is the end of the last turn
