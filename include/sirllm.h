@@ -145,7 +145,9 @@ int sirllm_score_merge(const float* partials, int32_t n_parts, int64_t part_stri
  *   workspace   device scratch of sirllm_lmhead_workspace_bytes(n_rows, vocab) bytes, 256-byte aligned,
  *               required (SIRLLM_ERR_WORKSPACE); overwritten, carries nothing between calls; calls that
  *               share it must be ordered on one stream.
- * n_rows == 0 is a no-op.  A non-finite product makes that row's score NaN.
+ * n_rows == 0 is a no-op.  A non-finite product makes that row's score NaN.  Results are deterministic for
+ * given arguments; the order of the binary32 sums depends on the tile shape chosen from n_rows and vocab, so the
+ * same row can differ in its last bits between calls with different n_rows.
  */
 int sirllm_lmhead_score(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, sirllm_dtype dt,
                         int32_t d_model, int64_t n_rows, int32_t vocab, const int32_t* token_ids,
