@@ -102,6 +102,11 @@ template <typename VecT, int BLOCK, int UNROLL>
 void launch_shape(const GatherLaunch& g, const Ragged& rg, dim3 grid, bool pow2, bool off64, hipStream_t stream)
 {
     const dim3 block(BLOCK);
+    if (tuning::get("SIRLLM_INPLACE_NT", 1) == 0) {
+        if (pow2 && !off64) hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, false, true, false>), grid, block, 0, stream, g, rg);
+        else hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, false, false, true>), grid, block, 0, stream, g, rg);
+        return;
+    }
     if (pow2) {
         if (off64) hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, true, true>), grid, block, 0, stream, g, rg);
         else       hipLaunchKernelGGL((gather_inplace_kernel<VecT, BLOCK, UNROLL, true, true, false>), grid, block, 0, stream, g, rg);
