@@ -362,3 +362,82 @@ def test_python_example_runs_both_routes():
         origin = mod.main(["--turns", "6"] + extra)
         assert origin.shape == (32, 2)
         assert origin[-8:, 0].tolist() == [6] * 8           # the recent window is the end of the last turn
+
+
+def _independent_job(seed, S, n_held, n_new, V, pol_t, D):
+    """Inputs and zeroed outputs of one step, all its own."""
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    n_cand = n_held + n_new
+    n_keep = min(n_cand, pol_t[0] + pol_t[1] + pol_t[2])
+    E = torch.zeros((S, n_cand), device=DEV)
+    E[:, :n_held] = torch.rand((S, n_held), generator=g, device=DEV) * 6
+    return dict(z=torch.randn((S * n_new, V), generator=g, device=DEV) * 2,
+                tok=torch.randint(0, V, (S * n_new,), generator=g, device=DEV, dtype=torch.int32),
+                E=E, k=torch.randn((S, 2, 3, n_cand, D), generator=g, device=DEV),
+                v=torch.randn((S, 2, 3, n_cand, D), generator=g, device=DEV),
+                kd=torch.zeros((S, 2, 3, n_keep, D), device=DEV), vd=torch.zeros((S, 2, 3, n_keep, D), device=DEV),
+                idx=torch.zeros((S, n_keep), dtype=torch.int32, device=DEV), out=torch.zeros((S, n_keep), device=DEV),
+                shape=(V, n_held, n_new), pol=pol_t)
+
+
+def _run_job(b, j, stream=None):
+    V, n_held, n_new = j["shape"]
+    b.sirllm_step(j["z"], j["tok"], V, j["E"], n_held, n_new, b.Policy(*j["pol"]), j["k"], j["v"], j["kd"], j["vd"],
+                  j["idx"], j["out"], stream=stream)
+
+
+_JOBS = [(11, 2, 3000, 500, 5003, (4, 1500, 500, 0.9), 64), (12, 1, 700, 300, 32000, (4, 400, 100, 0.8), 128),
+         (13, 3, 100, 40, 777, (4, 50, 8, 0.9), 16), (14, 1, 6000, 2000, 1000, (4, 2044, 2048, 0.9), 32)]
+
+
+def test_steps_on_two_streams_at_once_do_not_disturb_each_other(b):
+    """The library keeps no state between calls: independent steps enqueued on two streams, interleaved, give
+    the bytes the same steps give one after the other."""
+    want = [_independent_job(*a) for a in _JOBS]
+    for j in want:
+        _run_job(b, j)
+    torch.cuda.synchronize()
+    got = [_independent_job(*a) for a in _JOBS]
+    torch.cuda.synchronize()
+    s0, s1 = torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(3):
+        for i, j in enumerate(got):
+            _run_job(b, j, stream=(s0, s1)[i % 2])
+    torch.cuda.synchronize()
+    for w, g in zip(want, got):
+        for name in ("E", "kd", "vd", "idx", "out"):
+            assert torch.equal(w[name], g[name]), f"{name} differs when two streams run at once"
+
+
+def test_steps_from_two_host_threads_at_once(b):
+    """Two host threads calling into the library at the same time, each on a stream of its own."""
+    import threading
+    want = [_independent_job(*a) for a in _JOBS]
+    for j in want:
+        _run_job(b, j)
+    torch.cuda.synchronize()
+    got = [_independent_job(*a) for a in _JOBS]
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(jobs):
+        try:
+            torch.cuda.set_device(0)
+            s = torch.cuda.Stream()
+            for _ in range(20):
+                for j in jobs:
+                    _run_job(b, j, stream=s)
+            s.synchronize()
+        except Exception as e:                                   # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(got[0::2],)), threading.Thread(target=worker, args=(got[1::2],))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for w, g in zip(want, got):
+        for name in ("E", "kd", "vd", "idx", "out"):
+            assert torch.equal(w[name], g[name]), f"{name} differs when two host threads call at once"
