@@ -117,6 +117,31 @@ def test_lmhead_out_of_range_token_is_nan(b, ref):
     assert_close(got, want)
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("n,d,V", [(6, 64, 300), (70, 96, 700), (300, 72, 600)])    # fast and general kernels, all tile shapes
+def test_lmhead_non_finite_operands(b, ref, dtype, n, d, V):
+    """Non-finite logits behave as in the logits path: a -inf logit adds nothing, a token at a -inf logit scores
+    +inf, a row with a NaN or a +inf logit scores NaN."""
+    g = torch.Generator(device=DEV).manual_seed(n + d)
+    h = (torch.rand((n, d), generator=g, device=DEV) + 0.5).to(dtype)          # all positive
+    w = torch.randn((V, d), generator=g, device=DEV).to(dtype)
+    w[7, 3] = float("-inf")                                                   # logit 7 is -inf for every row ...
+    w[V - 1, d - 1] = float("-inf")                                           # ... and so is the last one
+    h[1, 5] = float("nan")                                                    # row 1: every logit NaN
+    h[3, 9] = float("inf")                                                    # row 3: +inf and -inf logits, NaN where both meet
+    tok = torch.randint(0, V, (n,), generator=g, device=DEV, dtype=torch.int32)
+    tok[2] = 7                                                                # row 2's own token sits at a -inf logit
+    tok[4] = V - 1
+    got = gpu_lmhead(b, h, w, tok)
+    want = ref.lmhead_score(to_np(h), to_np(w), to_np(tok))
+    assert np.isnan(want[1]) and np.isnan(want[3]) and np.isposinf(want[2]) and np.isposinf(want[4])
+    assert np.isfinite(want[[0, 5]]).all()
+    inf_w = np.isinf(want)
+    np.testing.assert_array_equal(np.isinf(got), inf_w)
+    np.testing.assert_array_equal(got[inf_w], want[inf_w])
+    assert_close(np.where(inf_w, 0, got), np.where(inf_w, 0, want))
+
+
 def test_lmhead_closed_forms(b):
     # equal output embeddings -> log V for every row; a zero hidden state -> log V
     V, d = 1000, 64
