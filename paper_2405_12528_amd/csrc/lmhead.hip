@@ -396,33 +396,53 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
     tile_epilogue<NVB, NTB>(a, acc, (float*)lds, vt, v0, t0, wv, wt, lane, tid);
 }
 
-// Folds the n_parts triples of every row: 16 rows per workgroup, 16 lanes per row striding over the parts.
+// Folds the n_parts triples of every row: 4 rows per workgroup, 64 lanes per row striding over the parts (the
+// chain of dependent merges is n_parts / 64 long, then a shuffle tree inside each wave and one exchange through LDS).
 // Row `row` belongs to stream row / rows_per_stream and is its token t = row % rows_per_stream; the score goes
 // to out[stream * out_stride + t].
 __global__ __launch_bounds__(256) void lmhead_merge_kernel(const float* partials, int n_parts, int64_t part_stride,
                                                            int64_t n_rows, float* out, int64_t rows_per_stream,
                                                            int64_t out_stride)
 {
-    __shared__ float sm[16][16][3];
-    const int r = threadIdx.x & 15, pl = threadIdx.x >> 4;
-    const int64_t row = (int64_t)blockIdx.x * 16 + r;
+    constexpr int R = 4, PL = 256 / R;           // rows per workgroup, part lanes per row
+    __shared__ float sm[4][R][3];
+    const int r = threadIdx.x & (R - 1), pl = threadIdx.x >> 2;
+    const int64_t row = (int64_t)blockIdx.x * R + r;
     score_dev::MS acc = {-INFINITY, 0.0f};
     float zt = __uint_as_float(0x7fc00000u);
     if (row < n_rows) {
-        for (int p = pl; p < n_parts; p += 16) {
-            const float* t = partials + p * part_stride + 3 * row;
-            acc = score_dev::merge(acc, score_dev::MS{t[0], t[1]});
-            const float z = t[2];
-            if (zt != zt && z == z) zt = z;
+        const float* base = partials + 3 * row;
+        for (int p0 = pl; p0 < n_parts; p0 += 4 * PL) {
+            float t[4][3];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {         // the loads of four parts go out together
+                const int p = p0 + u * PL;
+                const float* q = base + (int64_t)min(p, n_parts - 1) * part_stride;
+                t[u][0] = q[0]; t[u][1] = q[1]; t[u][2] = q[2];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (p0 + u * PL < n_parts) {
+                    acc = score_dev::merge(acc, score_dev::MS{t[u][0], t[u][1]});
+                    if (zt != zt && t[u][2] == t[u][2]) zt = t[u][2];
+                }
+            }
         }
     }
-    sm[pl][r][0] = acc.m;
-    sm[pl][r][1] = acc.s;
-    sm[pl][r][2] = zt;
-    __syncthreads();
-    if (pl == 0 && row < n_rows) {
+    // part lanes of one row sit R lanes apart inside a wave (16 of them per wave)
 #pragma unroll
-        for (int i = 1; i < 16; ++i) {
+    for (int off = R; off < kWave; off <<= 1) {
+        const score_dev::MS o = {__shfl_xor(acc.m, off, kWave), __shfl_xor(acc.s, off, kWave)};
+        const float z = __shfl_xor(zt, off, kWave);
+        acc = score_dev::merge(acc, o);
+        if (zt != zt && z == z) zt = z;
+    }
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & (kWave - 1)) < R) { sm[wave][r][0] = acc.m; sm[wave][r][1] = acc.s; sm[wave][r][2] = zt; }
+    __syncthreads();
+    if (threadIdx.x < R && row < n_rows) {
+#pragma unroll
+        for (int i = 1; i < 4; ++i) {
             acc = score_dev::merge(acc, score_dev::MS{sm[i][r][0], sm[i][r][1]});
             const float z = sm[i][r][2];
             if (zt != zt && z == z) zt = z;
@@ -506,7 +526,7 @@ hipError_t launch_lmhead_score(const LmHeadArgs& args, sirllm_dtype dt, float* o
     LmHeadArgs a = args;
     hipError_t e = dt == SIRLLM_BF16 ? launch_dtype<SIRLLM_BF16>(a, stream) : launch_dtype<SIRLLM_F16>(a, stream);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(lmhead_merge_kernel, dim3((unsigned)((a.n_rows + 15) / 16)), dim3(256), 0, stream,
+    hipLaunchKernelGGL(lmhead_merge_kernel, dim3((unsigned)((a.n_rows + 3) / 4)), dim3(256), 0, stream,
                        a.partial, a.n_vtiles, a.part_stride, a.n_rows, out, rows_per_stream > 0 ? rows_per_stream : 1, out_stride);
     return hipGetLastError();
 }
