@@ -151,6 +151,13 @@ def main():
     copy_gbps = 2 * (1 << 30) / (copy_avg * 1e-3) / 1e9
     log(f"[bench] plain 1 GiB device copy (torch): {copy_avg*1e3:.1f} us -> {copy_gbps:.0f} GB/s")
     del calib_src, calib_dst
+    # the same gather on the identity list 0..n_keep-1: a contiguous copy of the same size through the same kernel
+    ident = torch.arange(n_keep, dtype=torch.int32, device=dev).repeat(S, 1).contiguous()
+    ident_avg, _, _ = time_launches(
+        lambda: b.sirllm_compact_kv(k_src, v_src, k_dst, v_dst, ident, n_keep, n_src=n_cand), max(3, n_k // 2))
+    ident_gbps = bytes_["compact"] / (ident_avg * 1e-3) / 1e9
+    b.sirllm_compact_kv(k_src, v_src, k_dst, v_dst, kept, n_keep, n_src=n_cand)       # leave the step's own result behind
+    log(f"[bench] the gather on the identity list (contiguous copy, same kernel): {ident_avg*1e3:.1f} us -> {ident_gbps:.0f} GB/s")
     if bytes_["compact"] >= bytes_["score"]:
         dom, dom_bytes, dom_ms = "gather_rows_kernel", bytes_["compact"], gather_avg
     else:
@@ -165,7 +172,7 @@ def main():
                 "kernels_us": {"gather": round(gather_avg * 1e3, 2), "score": round(score_avg * 1e3, 2),
                                "decay_select": round(sel_avg * 1e3, 2)},
                 "score_gbps": round(bytes_["score"] / (score_avg * 1e-3) / 1e9, 1),
-                "plain_copy_gbps": round(copy_gbps, 1)}
+                "plain_copy_gbps": round(copy_gbps, 1), "identity_gather_gbps": round(ident_gbps, 1)}
 
     # ---- optional: the ragged in-place step on the same shapes --------------------------------
     ragged = None
