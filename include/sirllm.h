@@ -70,7 +70,9 @@ typedef struct {
  * lives at  base + elem_bytes * (s*stride_stream + l*stride_layer + h*stride_head
  *                                + p*stride_pos + d),   0 <= d < head_dim  (channels contiguous).
  * Strides are in elements and must be >= 0; stride_pos >= head_dim.  The K/V payload is
- * treated as opaque bytes. */
+ * treated as opaque bytes.  Any order of the four outer dimensions can be described; when the heads of a slot
+ * lie back to back (stride_head == head_dim: [slot][head][dim] caches), and likewise the layers, in both the
+ * source and the destination, the compaction copies them as one longer row. */
 typedef struct {
     int32_t n_layers;
     int32_t n_kv_heads;

@@ -158,6 +158,25 @@ GatherArgs make_gather_args(const void* k_src, const void* v_src, const sirllm_k
     g.n_streams = n_streams; g.n_keep = n_keep; g.n_src = n_src;
     g.row_bytes = (int32_t)((int64_t)src->head_dim * eb);
     g.kept_idx = kept_idx; g.idx_stride = idx_stride;
+    // Slot-major caches ([slot][head][dim], or [slot][layer][head][dim]): the rows of consecutive heads (and then
+    // of consecutive layers) of one slot lie back to back in both layouts, so they are one longer row of one
+    // plane -- the copy then streams whole slots instead of head_dim-sized pieces a slot stride apart.
+    const int64_t kMaxRowSpan = 0x7fffffffLL - 8192;      // keeps n_keep * (vectors per row) inside 32 bits for any vector width
+    auto fits = [&](int64_t row) {
+        return row <= g.s_pos && row <= g.d_pos && row <= (1 << 24) && (int64_t)n_keep * row <= kMaxRowSpan;
+    };
+    if (g.n_heads > 1 && g.s_head == g.row_bytes && g.d_head == g.row_bytes && fits((int64_t)g.row_bytes * g.n_heads)) {
+        g.row_bytes *= g.n_heads;
+        g.n_heads = 1;
+    }
+    if (g.n_heads == 1) {
+        g.s_head = g.s_layer; g.d_head = g.d_layer;        // one head per layer: planes are a plain walk over layers
+        if (g.n_layers > 1 && g.s_layer == g.row_bytes && g.d_layer == g.row_bytes &&
+            fits((int64_t)g.row_bytes * g.n_layers)) {
+            g.row_bytes *= g.n_layers;
+            g.n_layers = 1;
+        }
+    }
     return g;
 }
 

@@ -509,6 +509,47 @@ def test_compact_inplace_matches_oracle(b, ref, S, L, H, P, D, dtype, frac):
     assert np.array_equal(to_np(k2), h2)
 
 
+@pytest.mark.parametrize("order", ["SLPHD", "SPLHD", "SLPHD_padded", "SLHPD"])
+@pytest.mark.parametrize("dtype,D", [(torch.bfloat16, 128), (torch.float32, 16), (torch.int16, 5)])
+def test_compact_slot_major_layouts(b, ref, order, dtype, D):
+    """Caches stored slot-major -- [slot][head][dim] per layer, or [slot][layer][head][dim] -- handed over as
+    strided [stream][layer][head][slot][dim] views: heads (and layers) that lie back to back are copied as one
+    longer row, and the result is the same as for any other strides.  Out of place and in place."""
+    S, L, H, P, n_keep = 2, 3, 4, 700, 333
+    rng = np.random.default_rng(P + D)
+    mod = 32749 if dtype in (torch.int16, torch.bfloat16) else 1 << 31
+
+    def store(t):            # [S, L, H, P', D] values -> the same values in the layout under test, viewed as [S, L, H, P', D]
+        t = t.to(DEV)
+        if order == "SLPHD":
+            return t.permute(0, 1, 3, 2, 4).contiguous().permute(0, 1, 3, 2, 4)
+        if order == "SPLHD":
+            return t.permute(0, 3, 1, 2, 4).contiguous().permute(0, 2, 3, 1, 4)
+        if order == "SLPHD_padded":     # heads back to back, but a gap after every slot
+            buf = torch.zeros((t.shape[0], L, t.shape[3], H + 1, D), dtype=t.dtype, device=DEV)
+            buf[:, :, :, :H] = t.permute(0, 1, 3, 2, 4)
+            return buf[:, :, :, :H].permute(0, 1, 3, 2, 4)
+        return t.contiguous()
+
+    k = store((synth.tagged_kv(S, L, H, P, D, 0) % mod).to(dtype))
+    v = store((synth.tagged_kv(S, L, H, P, D, 1) % mod).to(dtype))
+    kept = np.stack([np.sort(rng.choice(P, n_keep, replace=False)) for _ in range(S)]).astype(np.int32)
+    kept[1, 5] = P + 3                                               # no such slot: a zero row in every head and layer
+    kd = store(torch.full((S, L, H, n_keep + 2, D), 77, dtype=dtype))
+    vd = store(torch.full((S, L, H, n_keep + 2, D), 77, dtype=dtype))
+    b.sirllm_compact_kv(k, v, kd, vd, torch.from_numpy(kept).to(DEV), n_keep)
+    torch.cuda.synchronize()
+    rk, rv = ref.compact_kv(to_np(k), to_np(v), kept)
+    assert np.array_equal(to_np(kd)[:, :, :, :n_keep], rk) and np.array_equal(to_np(vd)[:, :, :, :n_keep], rv)
+    assert bool((kd[:, :, :, n_keep:] == 77).all()) and bool((vd[:, :, :, n_keep:] == 77).all())
+    kept[1] = np.sort(rng.choice(P, n_keep, replace=False))          # in place needs a strictly ascending list
+    hk, hv = to_np(k).copy(), to_np(v).copy()
+    ref.compact_kv_inplace(hk, hv, kept)
+    b.sirllm_compact_kv_inplace(k, v, torch.from_numpy(kept).to(DEV), n_keep)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(k), hk) and np.array_equal(to_np(v), hv)
+
+
 def test_compact_inplace_strided_view_and_bad_indices(b, ref):
     big = synth.tagged_kv(2, 2, 3, 40, 24, 0).to(torch.float32).to(DEV)
     host = to_np(big).copy()
