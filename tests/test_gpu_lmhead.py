@@ -89,6 +89,31 @@ def test_lmhead_few_rows_every_row_against_the_oracle(b, ref, n_rows, d, V):
     assert_close(got, want)
 
 
+def test_lmhead_random_shapes_and_paddings(b, ref):
+    """Thirty random (rows, d_model, vocabulary) triples with random row paddings on both operands: every tile shape,
+    both kernels (d_model a multiple of 32 or only of 8), ragged tiles on every side."""
+    rng = np.random.default_rng(2405)
+    ref.set_threads(16)
+    for case in range(30):
+        n = int(rng.choice([rng.integers(1, 65), rng.integers(65, 129), rng.integers(129, 700)]))
+        d = 8 * int(rng.integers(1, 66))
+        V = int(rng.integers(1, 3000))
+        ld_h, ld_w = d + 8 * int(rng.integers(0, 4)), d + 8 * int(rng.integers(0, 4))
+        dtype = (torch.bfloat16, torch.float16)[case % 2]
+        g = torch.Generator(device=DEV).manual_seed(1000 + case)
+        hbig = torch.full((n, ld_h), 300.0, device=DEV).to(dtype)                 # padding that would wreck the result
+        wbig = torch.full((V + 3, ld_w), -300.0, device=DEV).to(dtype)
+        hbig[:, :d] = (torch.randn((n, d), generator=g, device=DEV) + 0.5).to(dtype)
+        wbig[:V, :d] = (torch.randn((V, d), generator=g, device=DEV) * (3.0 / d ** 0.5)).to(dtype)
+        tok = torch.randint(0, V, (n,), generator=g, device=DEV, dtype=torch.int32)
+        got = gpu_lmhead(b, hbig, wbig, tok, d_model=d, vocab=V)
+        want = ref.lmhead_score(to_np(hbig), to_np(wbig), to_np(tok), d_model=d, vocab=V)
+        try:
+            assert_close(got, want)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: n={n} d={d} V={V} ld_h={ld_h} ld_w={ld_w} {dtype}: {e}") from None
+
+
 def test_lmhead_leading_dimensions_and_subranges(b, ref):
     # hidden and weight embedded in larger allocations whose padding would wreck the result if it were read
     g = torch.Generator(device=DEV).manual_seed(5)
