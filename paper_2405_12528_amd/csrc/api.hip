@@ -556,7 +556,7 @@ int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64
     if (rc || !may_evict) return rc;
     const GatherArgs g = make_gather_args(k, v, layout, max_cand, k, v, layout, kept_idx, idx_stride, n_streams,
                                           (int32_t)budget);
-    return hip_status(launch_gather_inplace_ragged(g, n_held, cu_new, (int32_t)budget, stream));
+    return hip_status(launch_gather_inplace_ragged(g, n_held, cu_new, n_keep_out, (int32_t)budget, stream));
 }
 
 }  // extern "C"

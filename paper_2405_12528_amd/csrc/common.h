@@ -113,9 +113,10 @@ hipError_t launch_gather(const GatherArgs& a, int row_begin, int row_end, hipStr
 // src and dst of `a` are the same buffers and layouts; kept_idx must be strictly ascending.
 hipError_t launch_gather_inplace(const GatherArgs& a, hipStream_t stream);
 // Ragged batches: stream s holds held_dev[s] + (cu_new_dev[s+1] - cu_new_dev[s]) slots and is compacted
-// to `budget` slots only when it holds more; a.n_keep and a.n_src are upper bounds.
+// to `budget` slots only when it holds more and the selection did not flag it (n_keep_dev[s] >= 0); a.n_keep and
+// a.n_src are upper bounds.
 hipError_t launch_gather_inplace_ragged(const GatherArgs& a, const int32_t* held_dev, const int32_t* cu_new_dev,
-                                        int32_t budget, hipStream_t stream);
+                                        const int32_t* n_keep_dev, int32_t budget, hipStream_t stream);
 
 // ---- baseline.hip -----------------------------------------------------------------------
 // kept_idx of the score-free policies; n_topk of `a` is the number of middle slots to keep.

@@ -19,6 +19,7 @@ using gather_dev::GatherLaunch;
 struct Ragged {
     const int32_t* held_dev;    // null: uniform batch
     const int32_t* cu_new_dev;
+    const int32_t* n_keep_dev;  // written by the selection launch that precedes this one on the stream
     int32_t budget;
 };
 
@@ -29,7 +30,9 @@ __global__ __launch_bounds__(BLOCK) void gather_inplace_kernel(GatherLaunch g, R
         // ragged batch: this stream's own slot count decides whether anything moves at all
         const int s = g.stream0 + (int)blockIdx.y;
         const int n_cand = rg.held_dev[s] + (rg.cu_new_dev[s + 1] - rg.cu_new_dev[s]);
-        if (n_cand <= rg.budget || n_cand > g.a.n_src) return;      // uniform over the workgroup
+        // A stream the selection flagged (sizes negative or beyond the caller's bounds: n_keep = -1) has no kept
+        // list of this call; its K/V stays as it is.  So does a stream that is within its budget.
+        if (rg.n_keep_dev[s] < 0 || n_cand <= rg.budget || n_cand > g.a.n_src) return;      // uniform over the workgroup
         g.a.n_src = n_cand;
     }
     const GatherArgs& a = g.a;
@@ -179,13 +182,13 @@ hipError_t launch_any(const GatherArgs& a, const Ragged& rg, hipStream_t stream)
 // a.src and a.dst name the same buffers; the s_* strides are used for both sides.
 hipError_t launch_gather_inplace(const GatherArgs& a, hipStream_t stream)
 {
-    return launch_any(a, Ragged{nullptr, nullptr, 0}, stream);
+    return launch_any(a, Ragged{nullptr, nullptr, nullptr, 0}, stream);
 }
 
 hipError_t launch_gather_inplace_ragged(const GatherArgs& a, const int32_t* held_dev, const int32_t* cu_new_dev,
-                                        int32_t budget, hipStream_t stream)
+                                        const int32_t* n_keep_dev, int32_t budget, hipStream_t stream)
 {
-    return launch_any(a, Ragged{held_dev, cu_new_dev, budget}, stream);
+    return launch_any(a, Ragged{held_dev, cu_new_dev, n_keep_dev, budget}, stream);
 }
 
 }  // namespace sirllm

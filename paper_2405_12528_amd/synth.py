@@ -103,7 +103,7 @@ WORKLOADS = {
     "rps_dialogue": Workload("rps_dialogue", vocab=32000, n_new=54, logits_dtype="bf16", sigma=3.0, zipf_a=1.1,
                              spike=0.0, spike_frac=0.0, n_sink=4, n_topk=1020, n_recent=0, decay=0.8,
                              n_layers=32, n_kv_heads=32, head_dim=128, kv_dtype="bf16", n_cand=1078,
-                             n_turns=2000, checked_turns=(1, 19, 20, 100, 300)),
+                             n_turns=2000, checked_turns=(1, 19, 20, 100, 300, 1000, 2000)),
     # A long-context cache: the Llama-3-8B shape with a 128K-slot budget (the pre-training length of its
     # long-context variants), 2048 new tokens per turn.  35 GB of K/V in flight per step; the selection runs
     # over 133120 candidate slots, beyond what one workgroup holds.

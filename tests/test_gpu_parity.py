@@ -170,11 +170,22 @@ SELECT_CASES = [
     (1, 1020, 5, 4, 100, 8, 0.9, 0),          # crosses the 1024-slot boundary (two slots per thread)
     (1, 32700, 68, 4, 16000, 68, 0.9, 1000),  # the largest size, ragged
     (2, 20000, 0, 4, 9000, 100, 0.99, 0),     # no new tokens at all
+    # 8193..16384 slots: sixteen slots per thread (select_kernel<1024, 16>)
+    (1, 8000, 193, 4, 4000, 193, 0.9, 0),     # 8193 slots, the first size of that instance
+    (2, 11000, 1000, 4, 6000, 500, 0.9, 0),   # 12000 slots, new tokens compete (n_new > n_recent)
+    (2, 11500, 800, 4, 5000, 1024, 0.85, 12), # 12300 slots, a dozen score levels: ties across the k-th boundary
+    (1, 16000, 384, 4, 16000, 0, 1.0, 3),     # 16384 slots, the last size; no recent window, eta = 1
+    (3, 12000, 0, 0, 1, 0, 0.5, 2),           # k = 1 of two levels: the lowest slot of the upper level
+    # 16385..32768 slots: thirty-two slots per thread (select_kernel<1024, 32>)
+    (1, 16001, 384, 4, 8000, 384, 0.9, 0),    # 16385 slots, the first size of that instance
+    (2, 24000, 2000, 4, 13000, 1000, 0.9, 25),
 ]
 
 
 @pytest.mark.parametrize("case", SELECT_CASES, ids=[str(c[:6]) for c in SELECT_CASES])
 def test_decay_select_matches_oracle(b, ref, case):
+    """One workgroup per stream keeps ceil(n_cand / 1024) slots per thread, rounded up to 1, 2, 4, 8, 16 or 32: the
+    cases cover every one of those instances of the kernel, each at a first / last size and with ties."""
     n_streams, n_held, n_new, n_sink, k, n_recent, decay, levels = case
     rng = np.random.default_rng(n_held * 31 + n_new)
     n_cand = n_held + n_new
@@ -390,6 +401,10 @@ BASELINE_CASES = [
     (2, 50, 4, 10, 6), (1, 26, 4, 5, 2), (1, 29, 4, 5, 2), (1, 20, 2, 8, 3), (3, 1078, 4, 1020, 0),
     (2, 600, 4, 100, 16), (1, 4096, 4, 1532, 512), (2, 8192, 4, 3068, 1024), (1, 32768, 4, 16000, 68),
     (2, 30, 4, 20, 8), (1, 40, 0, 7, 0), (1, 40, 4, 0, 6), (1, 5000, 0, 1, 0), (1, 5000, 3, 4996, 0),
+    # the random policy's workgroup keeps 1, 4, 8, 16 or 32 slots per thread: 8193..16384 slots reach the 16-slot
+    # instance, 16385..32768 the 32-slot one
+    (1, 8193, 4, 4000, 193), (2, 12000, 4, 6000, 500), (1, 16384, 4, 1, 0), (2, 12345, 0, 12000, 45),
+    (1, 16385, 4, 8000, 384), (2, 26000, 4, 13000, 1000),
 ]
 
 
@@ -563,8 +578,11 @@ def test_compact_inplace_strided_view_and_bad_indices(b, ref):
 
 # ------------------------------------------------------------------------------ ragged batches
 def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=torch.float32, cap=None,
-               tight_new=True):
-    """One ragged step on the GPU and in the oracle; compares everything the step writes."""
+               tight_new=True, new_cap=None):
+    """One ragged step on the GPU and in the oracle; compares everything the step writes.  cap / new_cap: the
+    bounds on n_cand[s] / n_new[s] promised to the library when they are lower than what the streams hold; a
+    stream beyond either, or with a negative n_held, must come back flagged with nothing of its kept list or
+    K/V touched."""
     n_held, n_new = np.asarray(n_held), np.asarray(n_new)
     n_cand = n_held + n_new
     max_cand = int(n_cand.max()) if cap is None else cap
@@ -577,7 +595,7 @@ def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=
     tok = torch.randint(0, V, (total,), generator=g0, device=DEV, dtype=torch.int32)
     scores = torch.full((S, max_cand + 2), -3.0, device=DEV)
     for s in range(S):
-        fill = min(int(n_held[s]), max_cand + 2)          # a stream beyond the promised bound only fills what exists
+        fill = max(0, min(int(n_held[s]), max_cand + 2))  # a stream beyond the promised bound only fills what exists
         scores[s, :fill] = torch.randint(0, 50, (fill,), generator=g0, device=DEV) / 7.0
     k = torch.randn((S, L, H, max_cand + 1, D), generator=g0, device=DEV).to(kv_dt)
     v = torch.randn((S, L, H, max_cand + 1, D), generator=g0, device=DEV).to(kv_dt)
@@ -589,6 +607,10 @@ def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=
     cu = torch.from_numpy(np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)).to(DEV)
     hs, hk, hv = to_np(scores).copy(), to_np(k).copy(), to_np(v).copy()
     max_new = min(int(n_new.max()), max_cand) if tight_new else None
+    if new_cap is not None:
+        max_new = new_cap
+    bound_new = max_new if max_new is not None else min(total, max_cand)
+    fits_all = (n_held >= 0) & (n_new <= bound_new) & (n_cand <= max_cand)
     b.sirllm_step_ragged(z, tok, V, scores, held_dev, cu, total, max_cand, pol, k, v, kept, out, n_keep_dev,
                          max_new=max_new)
     torch.cuda.synchronize()
@@ -599,19 +621,22 @@ def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=
         e = ref.score(to_np(z), to_np(tok), vocab=V)
         r0 = 0
         for s in range(S):
-            if n_cand[s] <= max_cand:
+            if fits_all[s]:
                 want_scores[s, n_held[s]:n_cand[s]] = e[r0:r0 + n_new[s]]
             r0 += n_new[s]
     for s in range(S):
-        fits = n_cand[s] <= max_cand
-        if not fits:
-            assert gkeep[s] == -1
-            np.testing.assert_array_equal(gs[s], hs[s])       # flagged and left alone
+        if not fits_all[s]:
+            assert gkeep[s] == -1                             # flagged ...
+            assert (to_np(kept)[s] == -7).all()               # ... and its kept list left alone (K/V: compared below)
+            if n_cand[s] > max_cand and n_held[s] >= max_cand + 2:
+                np.testing.assert_array_equal(gs[s], hs[s])   # no place for its new scores: nothing written at all
+            else:
+                np.testing.assert_array_equal(gs[s, :max(0, n_held[s])], hs[s, :max(0, n_held[s])])   # held scores intact
             continue
         assert_scores_close(gs[s, n_held[s]:n_cand[s]], want_scores[s, n_held[s]:n_cand[s]])
         np.testing.assert_array_equal(gs[s, :n_held[s]], hs[s, :n_held[s]])
         np.testing.assert_array_equal(gs[s, n_cand[s]:], hs[s, n_cand[s]:])
-    ok = [s for s in range(S) if n_cand[s] <= max_cand]
+    ok = [s for s in range(S) if fits_all[s]]
     forced = gs.copy()
     # the oracle recomputes the new scores itself; overwrite them with the GPU's afterwards by calling the pieces
     for s in ok:
@@ -641,6 +666,13 @@ def test_step_ragged_matches_oracle(b, ref):
                L=1, H=2, D=64, kv_dt=torch.bfloat16)
     # a stream larger than the promised bound is flagged and left alone
     run_ragged(b, ref, rng, 3, pol, 100, torch.float32, [10, 60, 20], [5, 30, 5], cap=40, tight_new=False)
+    # so is a stream with more new tokens than promised, or with a negative slot count, although each has more
+    # slots than the budget and fewer than the bound (its K/V must not be compacted from a stale kept list);
+    # with the tight bound scoring and selection share a launch, with the loose one they do not
+    run_ragged(b, ref, rng, 4, pol, 100, torch.float32, [40, 30, 50, 45], [5, 20, 8, 3], new_cap=8)
+    run_ragged(b, ref, rng, 4, pol, 100, torch.float32, [40, 30, 50, 45], [5, 20, 8, 3], new_cap=12)
+    run_ragged(b, ref, rng, 4, pol, 100, torch.bfloat16, [40, -3, 50, -40], [5, 60, 8, 90], cap=100, new_cap=90)
+    run_ragged(b, ref, rng, 3, b.Policy(4, 20, 64, 0.9), 100, torch.float32, [90, -3, 100], [5, 60, 8], cap=200, new_cap=64)
     # every stream's new tokens fit the recent window: scoring and selection share a launch
     run_ragged(b, ref, rng, 5, pol, 300, torch.float32, [0, 30, 24, 100, 3], [8, 2, 8, 7, 0])
     run_ragged(b, ref, rng, 3, b.Policy(4, 3068, 1024, 0.85), 2000, torch.bfloat16, [7168, 100, 4000], [1024, 1000, 96],
@@ -652,6 +684,23 @@ def test_step_ragged_matches_oracle(b, ref):
         run_ragged(b, ref, rng, S, b.Policy(int(rng.integers(0, 5)), int(rng.integers(0, 60)), int(rng.integers(0, 20)), 0.7),
                    int(rng.integers(2, 900)), torch.float32 if rng.integers(2) else torch.bfloat16,
                    rng.integers(0, 150, S), rng.integers(0, 40, S))
+
+
+@pytest.mark.parametrize("tight_new", [True, False])
+@pytest.mark.parametrize("held,new,pol_t", [
+    # bound on n_cand in 8193..16384: sixteen slots per thread (select_ragged_kernel<1024, 16>)
+    ([11000, 9000, 300, 12000, 8150], [1000, 700, 1000, 0, 43], (4, 6000, 1000, 0.9)),
+    ([11800, 2000, 11000], [200, 64, 1000], (4, 4092, 0, 0.8)),                  # no recent window
+    # bound in 16385..32768: thirty-two slots per thread (select_ragged_kernel<1024, 32>)
+    ([30000, 500, 20000, 32000], [2000, 2000, 100, 768], (4, 16000, 2048, 0.9)),
+    ([32768 - 54, 17000], [54, 54], (4, 1020, 0, 0.7)),                          # the documented limit of the call
+])
+def test_step_ragged_large_caches(b, ref, held, new, pol_t, tight_new):
+    """Ragged steps whose largest stream holds 8193..32768 slots: the selecting workgroup then keeps 16 or 32
+    slots per thread.  Streams of very different fill share the batch; tight and loose bounds on the new tokens."""
+    rng = np.random.default_rng(len(held) * 1000 + held[0])
+    run_ragged(b, ref, rng, len(held), b.Policy(*pol_t), 300, torch.bfloat16, held, new, L=1, H=2, D=64,
+               kv_dt=torch.bfloat16, tight_new=tight_new)
 
 
 # ------------------------------------------------------------- scoring from chunks of columns
