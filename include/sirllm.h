@@ -186,6 +186,29 @@ int sirllm_decay_select(const float* scores, int64_t scores_stride,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * sirllm_decay_select for callers that cannot allocate device memory or size a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and limits as
+ * sirllm_decay_select, minus the workspace: the scratch of the multi-workgroup selection (more than 32768 slots
+ * per stream) lives in a static device array of SIRLLM_STATIC_SCRATCH_BYTES inside the library, which every GPU
+ * the library runs on holds until the process ends.  The call allocates nothing and frees nothing.
+ *   - Sizes whose scratch does not fit (sirllm_workspace_bytes(n_streams, n_cand, 0, 0) >
+ *     SIRLLM_STATIC_SCRATCH_BYTES, e.g. more than 240 streams of 131072 slots, or more than 51 streams of
+ *     SIRLLM_MAX_CAND slots) return SIRLLM_ERR_UNSUPPORTED; nothing is launched.
+ *   - All calls on one GPU share that GPU's array.  The call clears what it needs itself (with a kernel), so
+ *     nothing carries over from one call to the next; but two calls that overlap in time on one GPU (two streams,
+ *     two host threads) race on it.  Order them on one stream, or use sirllm_decay_select with workspaces of
+ *     their own.  Up to 32768 slots per stream no scratch is used and nothing is shared.
+ *   - The address of the array is looked up (hipGetSymbolAddress) the first time the call needs it on a device;
+ *     make one call outside any graph capture first.
+ */
+#define SIRLLM_STATIC_SCRATCH_BYTES 1048576
+int sirllm_decay_select_static(const float* scores, int64_t scores_stride,
+                               int32_t n_streams, int32_t n_held, int32_t n_new,
+                               const sirllm_policy* policy,
+                               int32_t* kept_idx, int64_t idx_stride,
+                               float* scores_out, int64_t out_stride, void* hip_stream);
+
+/*
  * KV compaction (Sec. 3.3: KV_cache <- KV_cache[Id], for the keys and the values of every
  * layer and head).  Out of place:
  *     dst(s, l, h, j, :) = src(s, l, h, kept_idx[s*idx_stride + j], :),   0 <= j < n_keep

@@ -43,7 +43,9 @@ class sirllm_kv_layout(C.Structure):
 
 SIRLLM_BASELINE_STREAM, SIRLLM_BASELINE_INTERVAL, SIRLLM_BASELINE_RANDOM = 0, 1, 2
 
-EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step", "sirllm_baseline_select",
+SIRLLM_STATIC_SCRATCH_BYTES = 1048576
+
+EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_decay_select_static", "sirllm_compact_kv", "sirllm_step", "sirllm_baseline_select",
            "sirllm_compact_kv_inplace", "sirllm_step_ragged", "sirllm_score_partial",
            "sirllm_score_merge", "sirllm_lmhead_score", "sirllm_lmhead_workspace_bytes",
            "sirllm_step_lmhead", "sirllm_step_lmhead_workspace_bytes", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
@@ -52,6 +54,8 @@ _vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
 _PP, _LP = C.POINTER(sirllm_policy), C.POINTER(sirllm_kv_layout)
 _lib.sirllm_score.argtypes = [_vp, C.c_int, _i64, _i32, _i64, _vp, _vp, _vp, _sz, _vp]
 _lib.sirllm_decay_select.argtypes = [_vp, _i64, _i32, _i32, _i32, _PP, _vp, _i64, _vp, _i64, _vp, _sz, _vp]
+_lib.sirllm_decay_select_static.argtypes = [_vp, _i64, _i32, _i32, _i32, _PP, _vp, _i64, _vp, _i64, _vp]
+_lib.sirllm_decay_select_static.restype = C.c_int
 _lib.sirllm_compact_kv.argtypes = [_vp, _vp, _LP, _i32, _vp, _vp, _LP, _vp, _i64, _i32, _i32, _vp]
 _lib.sirllm_step.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _i32, _i32, _PP,
                              _vp, _vp, _LP, _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _sz, _vp]
@@ -226,6 +230,23 @@ def sirllm_decay_select(scores: torch.Tensor, n_held: int, n_new: int, policy, k
     _check(_lib.sirllm_decay_select(_ptr(scores), _row_stride(scores), n_streams, n_held, n_new, C.byref(p),
                                     _ptr(kept_idx), _row_stride(kept_idx), _ptr(scores_out), _row_stride(scores_out),
                                     wp, wb, _stream(stream)), "sirllm_decay_select")
+    return kept_idx, scores_out
+
+
+def sirllm_decay_select_static(scores: torch.Tensor, n_held: int, n_new: int, policy, kept_idx: torch.Tensor,
+                               scores_out: torch.Tensor, stream=None):
+    """sirllm_decay_select without a workspace: the library's static device scratch serves large caches."""
+    _on_device(scores, kept_idx, scores_out)
+    for t, dt in ((scores, torch.float32), (kept_idx, torch.int32), (scores_out, torch.float32)):
+        if t.dim() != 2 or t.dtype != dt or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise ValueError("scores / kept_idx / scores_out must be 2-D with contiguous rows (f32 / i32 / f32)")
+    n_streams = scores.shape[0]
+    if kept_idx.shape[0] != n_streams or scores_out.shape[0] != n_streams:
+        raise ValueError("one row per stream in every array")
+    p = _policy(policy)
+    _check(_lib.sirllm_decay_select_static(_ptr(scores), _row_stride(scores), n_streams, n_held, n_new, C.byref(p),
+                                           _ptr(kept_idx), _row_stride(kept_idx), _ptr(scores_out),
+                                           _row_stride(scores_out), _stream(stream)), "sirllm_decay_select_static")
     return kept_idx, scores_out
 
 

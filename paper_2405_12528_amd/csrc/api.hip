@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "common.h"
 #include "tuning.h"
@@ -185,6 +186,38 @@ int hip_status(hipError_t e) { return e == hipSuccess ? SIRLLM_OK : SIRLLM_ERR_H
 }  // namespace
 }  // namespace sirllm
 
+// ---- scratch of sirllm_decay_select_static ---------------------------------------------------
+// Device memory that lives in the library's code object: every GPU the library runs on holds its own
+// copy, at its own address, from module load until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; the address it returns for the current device is what kernels,
+// and everything else on the host, are given.
+static __device__ __align__(256) uint32_t sirllm_static_scratch[SIRLLM_STATIC_SCRATCH_BYTES / sizeof(uint32_t)];
+
+namespace sirllm {
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};        // per device, resolved on the first call made with that device current
+
+int static_scratch_of_current_device(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return SIRLLM_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return SIRLLM_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(sirllm_static_scratch)) != hipSuccess || !p) return SIRLLM_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SIRLLM_OK;
+}
+
+}  // namespace
+}  // namespace sirllm
+
 using namespace sirllm;
 
 extern "C" {
@@ -326,6 +359,28 @@ int sirllm_decay_select(const float* scores, int64_t scores_stride, int32_t n_st
     if ((int64_t)n_cand <= budget_of(policy)) return hip_status(launch_keep_all(a, (hipStream_t)hip_stream));
     if (n_cand > SIRLLM_SINGLE_WG_CAND) return hip_status(launch_select_large(a, workspace, (hipStream_t)hip_stream));
     return hip_status(launch_select(a, (hipStream_t)hip_stream));
+}
+
+int sirllm_decay_select_static(const float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held,
+                               int32_t n_new, const sirllm_policy* policy, int32_t* kept_idx, int64_t idx_stride,
+                               float* scores_out, int64_t out_stride, void* hip_stream)
+{
+    int rc = validate_select(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx, idx_stride,
+                             scores_out, out_stride);
+    if (rc) return rc;
+    const int32_t n_cand = n_held + n_new;
+    if (n_streams == 0 || n_cand == 0) return SIRLLM_OK;
+    const SelectArgs a = make_select_args(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx,
+                                          idx_stride, scores_out, out_stride);
+    if ((int64_t)n_cand <= budget_of(policy)) return hip_status(launch_keep_all(a, (hipStream_t)hip_stream));
+    if (n_cand <= SIRLLM_SINGLE_WG_CAND) return hip_status(launch_select(a, (hipStream_t)hip_stream));
+    // the multi-workgroup selection: its histograms and per-tile counts go into the static array, which the
+    // first launch of the call clears (a kernel, not a memset)
+    if (select_large_scratch_bytes(n_streams, n_cand) > (size_t)SIRLLM_STATIC_SCRATCH_BYTES) return SIRLLM_ERR_UNSUPPORTED;
+    void* scratch = nullptr;
+    rc = static_scratch_of_current_device(&scratch);
+    if (rc) return rc;
+    return hip_status(launch_select_large(a, scratch, (hipStream_t)hip_stream));
 }
 
 int sirllm_baseline_select(sirllm_baseline kind, int32_t n_streams, int32_t n_cand, const sirllm_policy* policy,

@@ -63,6 +63,27 @@ def test_score_argument_errors(b):
     assert L.sirllm_score(None, 0, 0, 10, 10, None, None, None, 0, None) == b.SIRLLM_OK                 # empty
 
 
+def test_decay_select_static_rejects_on_the_host(b):
+    """The entry point without a workspace validates like sirllm_decay_select and refuses, before anything is
+    launched, sizes whose scratch exceeds its static array."""
+    L = b.raw()
+    p = b.sirllm_policy(4, 20000, 512, 0.9)
+
+    def call(n_streams, n_held, n_new, scores=FAKE):
+        n_cand = n_held + n_new
+        return L.sirllm_decay_select_static(scores, n_cand, n_streams, n_held, n_new, C.byref(p), FAKE + (1 << 40), 20516,
+                                            FAKE + (1 << 41), 20516, None)
+    assert call(300, 39000, 1000) == b.SIRLLM_ERR_UNSUPPORTED          # 300 x 4352 bytes > 1 MiB
+    assert call(52, 16777216 - 4096, 4096) == b.SIRLLM_ERR_UNSUPPORTED  # 52 x 20480 bytes > 1 MiB
+    assert call(1, 16777216, 1) == b.SIRLLM_ERR_UNSUPPORTED             # above SIRLLM_MAX_CAND
+    assert call(1, -1, 5) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(1, 39000, 1000, scores=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(0, 39000, 1000) == b.SIRLLM_OK                          # no streams: nothing to do
+    assert b.SIRLLM_STATIC_SCRATCH_BYTES == 1048576
+    text = open(os.path.join(ROOT, "include", "sirllm.h")).read()
+    assert re.search(r"#define\s+SIRLLM_STATIC_SCRATCH_BYTES\s+1048576\b", text)
+
+
 def test_decay_select_argument_errors(b):
     L = b.raw()
     p = b.sirllm_policy(4, 20, 8, 0.9)
