@@ -6,8 +6,14 @@ sink + top-k + recent, compact every layer's K/V.  Inputs are seeded synthetic t
 resident in HBM when the timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama3_8b] [--no-cpu-baseline]
+
+The headline measurement (value, ms_per_step, roofline, cpu_baseline) is the workload named by
+--workload.  After it, outside its timed region, the default run also times the step on the other
+workloads ("workloads" in the JSON line: min / median / max over repetitions) and three plain
+streaming kernels ("ceilings": what this GPU gives a read-only scan, a fill and a copy of 1 GiB).
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -18,10 +24,161 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E peak
+OTHER_WORKLOADS = ("llama2_7b", "mistral_7b", "batched_dialogue", "rps_dialogue")
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def time_launches(torch, fn, n, group=8):
+    """Average, median and minimum duration (ms) of one launch: n groups of `group` back-to-back
+    launches, each group bracketed by two events on the stream the kernels run on."""
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    for e0, e1 in evs:
+        e0.record()
+        for _ in range(group):
+            fn()
+        e1.record()
+    torch.cuda.synchronize()
+    ts = sorted(e0.elapsed_time(e1) / group for e0, e1 in evs)
+    return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
+
+
+class StepBench:
+    """Inputs and outputs of one workload's step, resident in HBM, and the calls that are timed."""
+
+    def __init__(self, torch, b, synth, w, dev):
+        self.torch, self.b, self.w, self.dev = torch, b, w, dev
+        S, n_held, n_new, n_cand, n_keep = w.n_streams, w.n_held, w.n_new, w.n_cand, w.n_keep
+        self.pol = b.Policy(w.n_sink, w.n_topk, w.n_recent, w.decay)
+        # Logits smaller than the 256 MB Infinity Cache would be served from it if one buffer were reused step
+        # after step: rotate among enough distinct sets that at least 600 MB of logits pass between two uses of
+        # the same set.  (The K/V sets are above 1.5 GB in every large workload and need no rotation.)
+        logit_bytes = S * n_new * w.vocab * w.logit_bytes
+        self.n_sets = 1 if logit_bytes >= 600e6 or w.name == "tiny" else min(32, -(-int(600e6) // logit_bytes))
+        self.logit_sets = [synth.make_logits(w, turn=1 + i, device=dev) for i in range(self.n_sets)]
+        self.tok_sets = [synth.make_token_ids(w, turn=1 + i, device=dev) for i in range(self.n_sets)]
+        self.logit_bytes = logit_bytes
+        self.scores = torch.zeros((S, n_cand), device=dev)
+        self.scores[:, :n_held] = synth.make_held_scores(w, device=dev)
+        self.k_src = synth.make_kv(w, device=dev, which="k")
+        self.v_src = synth.make_kv(w, device=dev, which="v")
+        dst_shape = (S, w.n_layers, w.n_kv_heads, n_keep, w.head_dim)
+        self.k_dst = torch.zeros(dst_shape, dtype=self.k_src.dtype, device=dev)
+        self.v_dst = torch.zeros(dst_shape, dtype=self.k_src.dtype, device=dev)
+        self.kept = torch.zeros((S, n_keep), dtype=torch.int32, device=dev)
+        self.scores_out = torch.zeros((S, n_keep), device=dev)
+        self.new_scores = torch.zeros(S * n_new, device=dev)
+        ws_bytes = b.sirllm_workspace_bytes(S, n_cand, S * n_new, w.vocab)
+        self.ws = torch.zeros(max(ws_bytes, 256), dtype=torch.uint8, device=dev) if ws_bytes else None
+        self.turn = 0
+        torch.cuda.synchronize()
+
+    def _next_set(self):
+        i = self.turn % self.n_sets
+        self.turn += 1
+        return self.logit_sets[i], self.tok_sets[i]
+
+    def step(self):
+        w = self.w
+        z, t = self._next_set()
+        self.b.sirllm_step(z, t, w.vocab, self.scores, w.n_held, w.n_new, self.pol, self.k_src, self.v_src,
+                           self.k_dst, self.v_dst, self.kept, self.scores_out, workspace=self.ws)
+
+    def gather(self, kept=None):
+        self.b.sirllm_compact_kv(self.k_src, self.v_src, self.k_dst, self.v_dst, self.kept if kept is None else kept,
+                                 self.w.n_keep, n_src=self.w.n_cand)
+
+    def score(self):
+        z, t = self._next_set()
+        self.b.sirllm_score(z, t, self.new_scores, vocab=self.w.vocab, workspace=self.ws)
+
+    def select(self):
+        self.b.sirllm_decay_select(self.scores, self.w.n_held, self.w.n_new, self.pol, self.kept, self.scores_out,
+                                   workspace=self.ws)
+
+    def time_steps(self, steps, warmup):
+        """ms per step: `steps` back-to-back steps between two events, after `warmup` untimed ones."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(steps):
+            self.step()
+        ev1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        return ev0.elapsed_time(ev1) / steps, wall_ms / steps
+
+
+def measure_other_workload(torch, b, synth, name, dev, reps=5):
+    """The step on one of the non-headline workloads: `reps` repetitions of a timed run of several steps; the
+    spread between repetitions is part of the result."""
+    w = synth.WORKLOADS[name]
+    sb = StepBench(torch, b, synth, w, dev)
+    bytes_ = w.algorithmic_bytes()
+    est_ms = max(bytes_["total"] / 6.0e12 * 1e3, 0.03)
+    steps = int(max(4, min(60, 40.0 / est_ms)))                # about 40 ms of GPU time per repetition
+    runs = sorted(sb.time_steps(steps, warmup=2 if i else 10)[0] for i in range(reps))
+    med = runs[len(runs) // 2]
+    n_k = 6
+    g_avg, _, g_min = time_launches(torch, sb.gather, n_k, group=4)
+    out = {"ms_per_step": {"min": round(runs[0], 5), "median": round(med, 5), "max": round(runs[-1], 5)},
+           "reps": reps, "steps_per_rep": steps, "algorithmic_bytes": bytes_["total"],
+           "hbm_gbps": round(bytes_["total"] / (med * 1e-3) / 1e9, 1),
+           "frac": round(bytes_["total"] / (med * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+           "frac_range": [round(bytes_["total"] / (runs[-1] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                          round(bytes_["total"] / (runs[0] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)],
+           "tokens_per_s": round(w.n_streams * w.n_new / (med * 1e-3), 1),
+           "gather_us": round(g_avg * 1e3, 2),
+           "gather_gbps": round(bytes_["compact"] / (g_avg * 1e-3) / 1e9, 1),
+           "config": {"n_streams": w.n_streams, "n_new": w.n_new, "n_cand": w.n_cand, "budget": w.budget, "vocab": w.vocab,
+                      "logits_dtype": w.logits_dtype, "kv": f"{w.n_layers}x{w.n_kv_heads}x{w.head_dim} {w.kv_dtype}"}}
+    log(f"[bench] {name}: {runs[0]*1e3:.1f} / {med*1e3:.1f} / {runs[-1]*1e3:.1f} us per step (min / median / max of {reps} x "
+        f"{steps} steps) -> {out['hbm_gbps']:.0f} GB/s = {100*out['frac']:.1f} % of peak; gather alone {g_avg*1e3:.1f} us")
+    del sb
+    torch.cuda.empty_cache()
+    return out
+
+
+def measure_ceilings(torch, dev):
+    """Plain streaming kernels over 1 GiB (libmembench.so): what the memory system gives a read-only scan, a fill
+    and a copy with 16-byte non-temporal accesses, in this very run."""
+    path = os.path.join(ROOT, "paper_2405_12528_amd", "libmembench.so")
+    if not os.path.exists(path):
+        log("[bench] libmembench.so is not built: no ceilings")
+        return None
+    mb = ctypes.CDLL(path)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    mb.membench_read.argtypes = [vp, sz, vp, vp]
+    mb.membench_write.argtypes = [vp, sz, vp]
+    mb.membench_copy.argtypes = [vp, vp, sz, vp]
+    n = 1 << 30
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def must(rc):
+        if rc != 0:
+            raise RuntimeError(f"membench call failed with {rc}")
+
+    r_avg, _, r_min = time_launches(torch, lambda: must(mb.membench_read(src.data_ptr(), n, sink.data_ptr(), stream)), 5, group=4)
+    w_avg, _, w_min = time_launches(torch, lambda: must(mb.membench_write(dst.data_ptr(), n, stream)), 5, group=4)
+    c_avg, _, c_min = time_launches(torch, lambda: must(mb.membench_copy(dst.data_ptr(), src.data_ptr(), n, stream)), 5, group=4)
+    out = {"bytes": n, "read_gbps": round(n / (r_avg * 1e-3) / 1e9, 1), "write_gbps": round(n / (w_avg * 1e-3) / 1e9, 1),
+           "copy_gbps": round(2 * n / (c_avg * 1e-3) / 1e9, 1),
+           "note": "1 GiB, 16-byte non-temporal accesses, 512-thread workgroups; copy counts bytes read + bytes written"}
+    log(f"[bench] streaming ceilings over 1 GiB: read {out['read_gbps']:.0f} GB/s, write {out['write_gbps']:.0f} GB/s, "
+        f"copy {out['copy_gbps']:.0f} GB/s (read + written)")
+    return out
 
 
 def main():
@@ -31,6 +188,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama3_8b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the 'workloads' and 'ceilings' records (the step on the four other workloads and the "
+                         "plain streaming kernels), e.g. under a profiler")
     ap.add_argument("--ragged-inplace", action="store_true",
                     help="also time sirllm_step_ragged (per-stream sizes in device memory, in-place compaction) on "
                          "the same shapes; reported under 'ragged_inplace' in the JSON line")
@@ -56,55 +216,19 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
-    pol = b.Policy(w.n_sink, w.n_topk, w.n_recent, w.decay)
     S, n_held, n_new, n_cand, n_keep = w.n_streams, w.n_held, w.n_new, w.n_cand, w.n_keep
     log(f"[bench] {synth.describe(w)}")
 
     # ---- inputs, resident in HBM ---------------------------------------------------------
-    # Logits smaller than the 256 MB Infinity Cache would be served from it if one buffer were reused step
-    # after step: rotate among enough distinct sets that at least 600 MB of logits pass between two uses of
-    # the same set.  (The K/V sets are above 1.5 GB in every large workload and need no rotation.)
-    logit_bytes = S * n_new * w.vocab * w.logit_bytes
-    n_sets = 1 if logit_bytes >= 600e6 or w.name == "tiny" else min(32, -(-int(600e6) // logit_bytes))
-    logit_sets = [synth.make_logits(w, turn=1 + i, device=dev) for i in range(n_sets)]
-    tok_sets = [synth.make_token_ids(w, turn=1 + i, device=dev) for i in range(n_sets)]
-    logits, tok = logit_sets[0], tok_sets[0]
-    log(f"[bench] rotating among {n_sets} logits set(s) of {logit_bytes / 1e6:.1f} MB")
-    scores = torch.zeros((S, n_cand), device=dev)
-    scores[:, :n_held] = synth.make_held_scores(w, device=dev)
-    k_src = synth.make_kv(w, device=dev, which="k")
-    v_src = synth.make_kv(w, device=dev, which="v")
-    dst_shape = (S, w.n_layers, w.n_kv_heads, n_keep, w.head_dim)
-    k_dst = torch.zeros(dst_shape, dtype=k_src.dtype, device=dev)
-    v_dst = torch.zeros(dst_shape, dtype=k_src.dtype, device=dev)
-    kept = torch.zeros((S, n_keep), dtype=torch.int32, device=dev)
-    scores_out = torch.zeros((S, n_keep), device=dev)
-    ws_bytes = b.sirllm_workspace_bytes(S, n_cand, S * n_new, w.vocab)
-    ws = torch.zeros(max(ws_bytes, 256), dtype=torch.uint8, device=dev) if ws_bytes else None
-    torch.cuda.synchronize()
-
-    turn = [0]
-
-    def step():
-        i = turn[0] % n_sets
-        turn[0] += 1
-        b.sirllm_step(logit_sets[i], tok_sets[i], w.vocab, scores, n_held, n_new, pol, k_src, v_src, k_dst, v_dst,
-                      kept, scores_out, workspace=ws)
+    sb = StepBench(torch, b, synth, w, dev)
+    pol, scores, kept, scores_out, ws = sb.pol, sb.scores, sb.kept, sb.scores_out, sb.ws
+    k_src, v_src, k_dst, v_dst, new_scores = sb.k_src, sb.v_src, sb.k_dst, sb.v_dst, sb.new_scores
+    logits, tok = sb.logit_sets[0], sb.tok_sets[0]
+    log(f"[bench] rotating among {sb.n_sets} logits set(s) of {sb.logit_bytes / 1e6:.1f} MB")
 
     # ---- the timed region: exactly K steps between two synchronisations ------------------
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
-        step()
-    ev1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    ms_per_step = ev0.elapsed_time(ev1) / args.steps
-    log(f"[bench] {args.steps} steps: {ms_per_step * 1e3:.1f} us/step by events, {wall_ms / args.steps * 1e3:.1f} us/step by host clock")
+    ms_per_step, wall_ms_per_step = sb.time_steps(args.steps, args.warmup)
+    log(f"[bench] {args.steps} steps: {ms_per_step * 1e3:.1f} us/step by events, {wall_ms_per_step * 1e3:.1f} us/step by host clock")
 
     bytes_ = w.algorithmic_bytes()
     tokens_per_s = S * n_new / (ms_per_step * 1e-3)
@@ -112,34 +236,10 @@ def main():
 
     # ---- the dominant kernel (the K/V gather), timed launch by launch with events on the
     #      stream it runs on, in the launch configuration the step uses ---------------------
-    def time_launches(fn, n, group=8):
-        """Average, median and minimum duration of one launch: n groups of `group` back-to-back
-        launches, each group bracketed by two events on the stream the kernels run on."""
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        for e0, e1 in evs:
-            e0.record()
-            for _ in range(group):
-                fn()
-            e1.record()
-        torch.cuda.synchronize()
-        ts = sorted(e0.elapsed_time(e1) / group for e0, e1 in evs)
-        return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
-
     n_k = max(5, min(args.steps, 20))
-    gather_avg, gather_med, gather_min = time_launches(
-        lambda: b.sirllm_compact_kv(k_src, v_src, k_dst, v_dst, kept, n_keep, n_src=n_cand), n_k)
-    new_scores = torch.zeros(S * n_new, device=dev)
-    def score_only():
-        i = turn[0] % n_sets
-        turn[0] += 1
-        b.sirllm_score(logit_sets[i], tok_sets[i], new_scores, vocab=w.vocab, workspace=ws)
-
-    score_avg, score_med, score_min = time_launches(score_only, n_k)
-    sel_avg, sel_med, sel_min = time_launches(
-        lambda: b.sirllm_decay_select(scores, n_held, n_new, pol, kept, scores_out, workspace=ws), n_k)
+    gather_avg, gather_med, gather_min = time_launches(torch, sb.gather, n_k)
+    score_avg, score_med, score_min = time_launches(torch, sb.score, n_k)
+    sel_avg, sel_med, sel_min = time_launches(torch, sb.select, n_k)
     log(f"[bench] per launch (avg/median/min us): gather {gather_avg*1e3:.1f}/{gather_med*1e3:.1f}/{gather_min*1e3:.1f}  "
         f"score {score_avg*1e3:.1f}/{score_med*1e3:.1f}/{score_min*1e3:.1f}  "
         f"decay_select {sel_avg*1e3:.1f}/{sel_med*1e3:.1f}/{sel_min*1e3:.1f}")
@@ -147,32 +247,31 @@ def main():
     # command holds its own calibration kernel for FETCH_SIZE / WRITE_SIZE
     calib_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     calib_dst = torch.empty_like(calib_src)
-    copy_avg, _, _ = time_launches(lambda: calib_dst.copy_(calib_src), 3, group=2)
+    copy_avg, _, _ = time_launches(torch, lambda: calib_dst.copy_(calib_src), 3, group=2)
     copy_gbps = 2 * (1 << 30) / (copy_avg * 1e-3) / 1e9
-    log(f"[bench] plain 1 GiB device copy (torch): {copy_avg*1e3:.1f} us -> {copy_gbps:.0f} GB/s")
+    log(f"[bench] calibration copy of 1 GiB (torch's own kernel): {copy_avg*1e3:.1f} us -> {copy_gbps:.0f} GB/s")
     del calib_src, calib_dst
     # the same gather on the identity list 0..n_keep-1: a contiguous copy of the same size through the same kernel
     ident = torch.arange(n_keep, dtype=torch.int32, device=dev).repeat(S, 1).contiguous()
-    ident_avg, _, _ = time_launches(
-        lambda: b.sirllm_compact_kv(k_src, v_src, k_dst, v_dst, ident, n_keep, n_src=n_cand), max(3, n_k // 2))
+    ident_avg, _, _ = time_launches(torch, lambda: sb.gather(ident), max(3, n_k // 2))
     ident_gbps = bytes_["compact"] / (ident_avg * 1e-3) / 1e9
-    b.sirllm_compact_kv(k_src, v_src, k_dst, v_dst, kept, n_keep, n_src=n_cand)       # leave the step's own result behind
+    sb.gather()                                                                        # leave the step's own result behind
     log(f"[bench] the gather on the identity list (contiguous copy, same kernel): {ident_avg*1e3:.1f} us -> {ident_gbps:.0f} GB/s")
     if bytes_["compact"] >= bytes_["score"]:
         dom, dom_bytes, dom_ms = "gather_rows_kernel", bytes_["compact"], gather_avg
     else:
         dom, dom_bytes, dom_ms = "score_rows_kernel", bytes_["score"], score_avg
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
-    traffic = committed_traffic(dom, w.name)
+    traffic, traffic_source = committed_traffic(dom, w.name)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_source": traffic_source,
                 "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_ms * 1e3, 2),
                 "step": {"algorithmic_bytes": bytes_["total"], "achieved": round(step_gbps, 1),
                          "frac": round(step_gbps / HBM_PEAK_GBPS, 4)},
                 "kernels_us": {"gather": round(gather_avg * 1e3, 2), "score": round(score_avg * 1e3, 2),
                                "decay_select": round(sel_avg * 1e3, 2)},
                 "score_gbps": round(bytes_["score"] / (score_avg * 1e-3) / 1e9, 1),
-                "plain_copy_gbps": round(copy_gbps, 1), "identity_gather_gbps": round(ident_gbps, 1)}
+                "calibration_copy_gbps": round(copy_gbps, 1), "identity_gather_gbps": round(ident_gbps, 1)}
 
     # ---- optional: the ragged in-place step on the same shapes --------------------------------
     ragged = None
@@ -181,16 +280,28 @@ def main():
         cu_dev = torch.arange(0, (S + 1) * n_new, n_new, dtype=torch.int32, device=dev)
         keep_dev = torch.zeros(S, dtype=torch.int32, device=dev)
 
-        def ragged_step():      # repeated in place on the same buffers: the data changes, the traffic does not
-            i = turn[0] % n_sets
-            turn[0] += 1
-            b.sirllm_step_ragged(logit_sets[i], tok_sets[i], w.vocab, scores, held_dev, cu_dev, S * n_new, n_cand, pol,
-                                 k_src, v_src, kept, scores_out, keep_dev, max_new=n_new, workspace=ws)
+        ip_ws = torch.zeros(b.SIRLLM_INPLACE_WORKSPACE_BYTES, dtype=torch.uint8, device=dev)
 
-        r_avg, r_med, r_min = time_launches(ragged_step, n_k, group=4)
+        def ragged_step(scratch=ip_ws):      # repeated in place on the same buffers: the data changes, the traffic does not
+            z, t = sb._next_set()
+            b.sirllm_step_ragged(z, t, w.vocab, scores, held_dev, cu_dev, S * n_new, n_cand, pol,
+                                 k_src, v_src, kept, scores_out, keep_dev, max_new=n_new, workspace=scratch)
+
+        r_avg, r_med, r_min = time_launches(torch, ragged_step, n_k, group=4)
         ragged = {"ms_per_step": round(r_avg, 5), "hbm_gbps": round(bytes_["total"] / (r_avg * 1e-3) / 1e9, 1),
-                  "frac": round(bytes_["total"] / (r_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
-        log(f"[bench] ragged in-place step: {r_avg*1e3:.1f} us -> {ragged['hbm_gbps']:.0f} GB/s")
+                  "frac": round(bytes_["total"] / (r_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                  "vs_uniform_step": round(r_avg / ms_per_step, 4)}
+        rw_avg, _, _ = time_launches(torch, lambda: ragged_step(None), n_k, group=4)
+        ragged["ms_per_step_without_workspace"] = round(rw_avg, 5)
+        for label, scratch in (("inplace_gather", ip_ws), ("inplace_gather_without_workspace", None)):
+            ip_avg, _, _ = time_launches(
+                torch, lambda: b.sirllm_compact_kv_inplace(k_src, v_src, kept, n_keep, n_src=n_cand, workspace=scratch), n_k, group=4)
+            ragged[label + "_us"] = round(ip_avg * 1e3, 2)
+            ragged[label + "_gbps"] = round(bytes_["compact"] / (ip_avg * 1e-3) / 1e9, 1)
+        log(f"[bench] ragged in-place step: {r_avg*1e3:.1f} us -> {ragged['hbm_gbps']:.0f} GB/s ({rw_avg*1e3:.1f} us without a "
+            f"workspace); in-place gather alone {ragged['inplace_gather_us']:.1f} us -> {ragged['inplace_gather_gbps']:.0f} GB/s "
+            f"(planes by ticket), {ragged['inplace_gather_without_workspace_us']:.1f} us -> "
+            f"{ragged['inplace_gather_without_workspace_gbps']:.0f} GB/s (planes by block index)")
 
     # ---- optional: the step replayed from a captured graph ----------------------------------------------
     graph_ms = None
@@ -198,14 +309,14 @@ def main():
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
-            step()                                       # warm-up on the capture stream
+            sb.step()                                    # warm-up on the capture stream
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
         reps = 20
         hgraph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(hgraph):
             for _ in range(reps):                        # back-to-back steps in one graph, sets rotating as above
-                step()
+                sb.step()
         hgraph.replay()
         torch.cuda.synchronize()
         g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -223,7 +334,7 @@ def main():
         hid, wmat = synth.make_lmhead(w, turn=1, device=dev)
         lm_ws = torch.empty(b.sirllm_lmhead_workspace_bytes(hid.shape[0], w.vocab), dtype=torch.uint8, device=dev)
         lm_avg, lm_med, lm_min = time_launches(
-            lambda: b.sirllm_lmhead_score(hid, wmat, tok, new_scores, lm_ws), n_k, group=2)
+            torch, lambda: b.sirllm_lmhead_score(hid, wmat, tok, new_scores, lm_ws), n_k, group=2)
         flops = 2.0 * hid.shape[0] * w.vocab * w.d_model
         tfl = flops / (lm_avg * 1e-3) / 1e12
         lmhead = {"bound": "mfma", "kernel": "lmhead_score_kernel", "dtype": "bf16", "achieved": round(tfl, 1),
@@ -234,13 +345,14 @@ def main():
         st_ws = torch.empty(max(b.sirllm_step_lmhead_workspace_bytes(S, n_cand, hid.shape[0], w.vocab), 256),
                             dtype=torch.uint8, device=dev)
         st_avg, _, _ = time_launches(
-            lambda: b.sirllm_step_lmhead(hid, wmat, tok, scores, n_held, n_new, pol, k_src, v_src, k_dst, v_dst, kept,
-                                         scores_out, st_ws), n_k, group=2)
+            torch, lambda: b.sirllm_step_lmhead(hid, wmat, tok, scores, n_held, n_new, pol, k_src, v_src, k_dst, v_dst,
+                                                kept, scores_out, st_ws), n_k, group=2)
         lmhead["step_ms"] = round(st_avg, 4)
         lmhead["step_tokens_per_s"] = round(hid.shape[0] / (st_avg * 1e-3), 1)
         log(f"[bench] step with the scores from the LM head: {st_avg*1e3:.1f} us")
         log(f"[bench] lmhead_score {hid.shape[0]} x {w.d_model} x {w.vocab}: {lm_avg*1e3:.1f}/{lm_med*1e3:.1f}/{lm_min*1e3:.1f} us "
             f"(avg/median/min) -> {tfl:.0f} TFLOP/s = {100 * tfl / 2500:.1f} % of 2.5 PFLOP/s")
+        del hid, wmat, lm_ws, st_ws
 
     # ---- the oracle on the host cores, same bytes, as a reported baseline ----------------
     cpu = None
@@ -264,20 +376,28 @@ def main():
         out["lmhead"] = lmhead
     if graph_ms is not None:
         out["graph_ms_per_step"] = round(graph_ms, 5)
+
+    # ---- after the headline measurement: the other workloads and the streaming ceilings -------------
+    if not args.no_other_workloads and args.workload == "llama3_8b":
+        del sb, pol, scores, kept, scores_out, ws, k_src, v_src, k_dst, v_dst, new_scores, logits, tok, ident
+        torch.cuda.empty_cache()
+        out["ceilings"] = measure_ceilings(torch, dev)
+        out["workloads"] = {name: measure_other_workload(torch, b, synth, name, dev) for name in OTHER_WORKLOADS}
     print(json.dumps(out), flush=True)
 
 
 def committed_traffic(kernel, workload):
     """HBM bytes per launch of `kernel` as measured by the rocprofv3 FETCH_SIZE / WRITE_SIZE counter
-    runs of this command; the figure is kept in the committed summary under profiles/ (a counter
-    run cannot be made from inside the timed process).  None when no summary covers the workload."""
+    runs of this command, and the file that holds the figure: the committed summary under profiles/
+    (a counter run cannot be made from inside the timed process).  (None, None) when no summary
+    covers the workload."""
     import re
-    path = os.path.join(ROOT, "profiles", f"{kernel}__{workload}.md")
+    rel = os.path.join("profiles", f"{kernel}__{workload}.md")
     try:
-        m = re.search(r"^traffic_bytes_per_launch\s*=\s*(\d+)", open(path).read(), flags=re.M)
+        m = re.search(r"^traffic_bytes_per_launch\s*=\s*(\d+)", open(os.path.join(ROOT, rel)).read(), flags=re.M)
     except OSError:
-        return None
-    return int(m.group(1)) if m else None
+        return None, None
+    return (int(m.group(1)), rel) if m else (None, None)
 
 
 def cpu_baseline(w, args, logits, tok, scores, k_src, v_src):

@@ -44,6 +44,7 @@ class sirllm_kv_layout(C.Structure):
 SIRLLM_BASELINE_STREAM, SIRLLM_BASELINE_INTERVAL, SIRLLM_BASELINE_RANDOM = 0, 1, 2
 
 SIRLLM_STATIC_SCRATCH_BYTES = 1048576
+SIRLLM_INPLACE_WORKSPACE_BYTES = 256
 
 EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_decay_select_static", "sirllm_compact_kv", "sirllm_step", "sirllm_baseline_select",
            "sirllm_compact_kv_inplace", "sirllm_step_ragged", "sirllm_score_partial",
@@ -62,7 +63,7 @@ _lib.sirllm_step.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _i3
 _lib.sirllm_baseline_select.argtypes = [C.c_int, _i32, _i32, _PP, C.c_uint64, C.c_uint64, _vp, _i64,
                                         C.POINTER(C.c_int32), _vp]
 _lib.sirllm_baseline_select.restype = C.c_int
-_lib.sirllm_compact_kv_inplace.argtypes = [_vp, _vp, _LP, _i32, _vp, _i64, _i32, _i32, _vp]
+_lib.sirllm_compact_kv_inplace.argtypes = [_vp, _vp, _LP, _i32, _vp, _i64, _i32, _i32, _vp, _sz, _vp]
 _lib.sirllm_compact_kv_inplace.restype = C.c_int
 _lib.sirllm_step_ragged.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _vp, _vp, _i64, _i32, _i32, _PP,
                                     _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _vp]
@@ -290,9 +291,9 @@ def sirllm_compact_kv(k_src: torch.Tensor, v_src, k_dst: torch.Tensor, v_dst, ke
 
 
 def sirllm_compact_kv_inplace(k: torch.Tensor, v, kept_idx: torch.Tensor, n_keep: int, n_src: int | None = None,
-                              stream=None):
+                              workspace: torch.Tensor | None = None, stream=None):
     """k[s, l, h, j, :] = k[s, l, h, kept_idx[s, j], :] for j < n_keep, in place (kept_idx strictly ascending)."""
-    _on_device(k, v, kept_idx)
+    _on_device(k, v, kept_idx, workspace)
     if kept_idx.dim() != 2 or kept_idx.dtype != torch.int32 or (kept_idx.shape[1] > 1 and kept_idx.stride(1) != 1):
         raise ValueError("kept_idx must be [n_streams, >= n_keep] int32 with contiguous rows")
     lay = kv_layout(k)
@@ -301,8 +302,9 @@ def sirllm_compact_kv_inplace(k: torch.Tensor, v, kept_idx: torch.Tensor, n_keep
     n_src = k.shape[3] if n_src is None else int(n_src)
     if k.shape[3] < n_src or kept_idx.shape[0] != k.shape[0]:
         raise ValueError("cache has fewer than n_src slots, or stream counts differ")
+    wp, wb = _ws(workspace)
     _check(_lib.sirllm_compact_kv_inplace(_ptr(k), _ptr(v), C.byref(lay), n_src, _ptr(kept_idx),
-                                          _row_stride(kept_idx), k.shape[0], int(n_keep), _stream(stream)),
+                                          _row_stride(kept_idx), k.shape[0], int(n_keep), wp, wb, _stream(stream)),
            "sirllm_compact_kv_inplace")
     return k, v
 

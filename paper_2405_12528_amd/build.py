@@ -63,6 +63,23 @@ def build(verbose: bool = False, incremental: bool = False, jobs: int | None = N
     return LIB
 
 
+MEMBENCH_LIB = os.path.join(HERE, "libmembench.so")
+
+
+def build_membench() -> str:
+    """Compile membench/membench.hip (streaming read / write / copy reference kernels for bench.py)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, f"--offload-arch={ARCH}", "-O3", "-std=c++17", "-fPIC", "-shared", "-Xclang", "-target-feature",
+           "-Xclang", "-packed-fp32-ops", os.path.join(HERE, "membench", "membench.hip"), "-o", MEMBENCH_LIB]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    err = "\n".join(l for l in r.stderr.splitlines() if "is not a recognized feature for this target" not in l)
+    if err.strip():
+        print(err, file=sys.stderr, flush=True)
+    if r.returncode != 0:
+        raise subprocess.CalledProcessError(r.returncode, cmd)
+    return MEMBENCH_LIB
+
+
 def build_example() -> str:
     """Compile examples/step_example.c (plain C, HIP runtime + libsirllm only) next to its source."""
     src = os.path.join(ROOT, "examples", "step_example.c")
@@ -77,4 +94,5 @@ def build_example() -> str:
 
 if __name__ == "__main__":
     print(build(verbose=True, incremental="--incremental" in sys.argv))
+    print(build_membench())
     print(build_example())

@@ -127,7 +127,9 @@ class RaggedRetentiveCache:
         self.kept_idx = torch.zeros((n_streams, self.capacity), dtype=torch.int32, device=device)
         self._cur = 0
         self.n_held = [0] * n_streams                  # host mirror
-        nbytes = b.sirllm_workspace_bytes(n_streams, self.capacity, n_streams * max_new, 1 << 20)
+        # the in-place compaction's ticket counter lives in the workspace
+        nbytes = max(b.sirllm_workspace_bytes(n_streams, self.capacity, n_streams * max_new, 1 << 20),
+                     b.SIRLLM_INPLACE_WORKSPACE_BYTES)
         self._ws = torch.zeros(nbytes, dtype=torch.uint8, device=device) if nbytes else None
 
     @property

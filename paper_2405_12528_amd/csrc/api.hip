@@ -431,7 +431,7 @@ int sirllm_compact_kv(const void* k_src, const void* v_src, const sirllm_kv_layo
 
 int sirllm_compact_kv_inplace(void* k, void* v, const sirllm_kv_layout* layout, int32_t n_src,
                               const int32_t* kept_idx, int64_t idx_stride, int32_t n_streams, int32_t n_keep,
-                              void* hip_stream)
+                              void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!layout_ok(layout)) return SIRLLM_ERR_INVALID_ARG;
     if (n_streams < 0 || n_keep < 0 || n_src < 0 || n_keep > n_src) return SIRLLM_ERR_INVALID_ARG;
@@ -442,8 +442,9 @@ int sirllm_compact_kv_inplace(void* k, void* v, const sirllm_kv_layout* layout, 
     if (((uintptr_t)k & em) || ((uintptr_t)v & em)) return SIRLLM_ERR_INVALID_ARG;
     if (ranges_overlap(k, extent_bytes(layout, n_streams, n_src), v, extent_bytes(layout, n_streams, n_src)))
         return SIRLLM_ERR_INVALID_ARG;
+    if (workspace && ((uintptr_t)workspace & (kWorkspaceAlign - 1)) != 0) return SIRLLM_ERR_WORKSPACE;
     const GatherArgs g = make_gather_args(k, v, layout, n_src, k, v, layout, kept_idx, idx_stride, n_streams, n_keep);
-    return hip_status(launch_gather_inplace(g, (hipStream_t)hip_stream));
+    return hip_status(launch_gather_inplace(g, workspace, workspace ? workspace_bytes : 0, (hipStream_t)hip_stream));
 }
 
 int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
@@ -586,6 +587,7 @@ int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64
     }
     rc = workspace_check(workspace, workspace_bytes, sirllm_workspace_bytes(n_streams, max_cand, total_new, vocab));
     if (rc) return rc;
+    if (workspace && ((uintptr_t)workspace & (kWorkspaceAlign - 1)) != 0) return SIRLLM_ERR_WORKSPACE;
     hipStream_t stream = (hipStream_t)hip_stream;
 
     ScoreArgs a;
@@ -611,7 +613,9 @@ int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64
     if (rc || !may_evict) return rc;
     const GatherArgs g = make_gather_args(k, v, layout, max_cand, k, v, layout, kept_idx, idx_stride, n_streams,
                                           (int32_t)budget);
-    return hip_status(launch_gather_inplace_ragged(g, n_held, cu_new, n_keep_out, (int32_t)budget, stream));
+    // with a workspace the compacting workgroups take their planes in ticket order
+    return hip_status(launch_gather_inplace_ragged(g, n_held, cu_new, n_keep_out, (int32_t)budget, workspace,
+                                                   workspace ? workspace_bytes : 0, stream));
 }
 
 }  // extern "C"

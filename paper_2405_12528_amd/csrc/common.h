@@ -110,13 +110,16 @@ struct GatherArgs {
 hipError_t launch_gather(const GatherArgs& a, int row_begin, int row_end, hipStream_t stream);
 
 // ---- gather_inplace.hip -----------------------------------------------------------------
-// src and dst of `a` are the same buffers and layouts; kept_idx must be strictly ascending.
-hipError_t launch_gather_inplace(const GatherArgs& a, hipStream_t stream);
+// src and dst of `a` are the same buffers and layouts; kept_idx must be strictly ascending.  `scratch` is optional:
+// with at least SIRLLM_INPLACE_WORKSPACE_BYTES of device memory the workgroups take their planes in ticket order
+// (the call clears the counter itself), without it by block index.
+hipError_t launch_gather_inplace(const GatherArgs& a, void* scratch, size_t scratch_bytes, hipStream_t stream);
 // Ragged batches: stream s holds held_dev[s] + (cu_new_dev[s+1] - cu_new_dev[s]) slots and is compacted
 // to `budget` slots only when it holds more and the selection did not flag it (n_keep_dev[s] >= 0); a.n_keep and
 // a.n_src are upper bounds.
 hipError_t launch_gather_inplace_ragged(const GatherArgs& a, const int32_t* held_dev, const int32_t* cu_new_dev,
-                                        const int32_t* n_keep_dev, int32_t budget, hipStream_t stream);
+                                        const int32_t* n_keep_dev, int32_t budget, void* scratch, size_t scratch_bytes,
+                                        hipStream_t stream);
 
 // ---- baseline.hip -----------------------------------------------------------------------
 // kept_idx of the score-free policies; n_topk of `a` is the number of middle slots to keep.

@@ -184,8 +184,8 @@ def test_baseline_select_argument_errors(b):
 def test_inplace_and_ragged_argument_errors(b):
     L = b.raw()
     lay = b.sirllm_kv_layout(2, 2, 16, 4, 2 * 2 * 128 * 16, 2 * 128 * 16, 128 * 16, 16)
-    def inplace(k=0x10000000, v=None, l=lay, n_src=100, idx=0x5000000, istr=32, n_streams=1, n_keep=32):
-        return L.sirllm_compact_kv_inplace(k, v, C.byref(l) if l else None, n_src, idx, istr, n_streams, n_keep, None)
+    def inplace(k=0x10000000, v=None, l=lay, n_src=100, idx=0x5000000, istr=32, n_streams=1, n_keep=32, ws=None, ws_bytes=0):
+        return L.sirllm_compact_kv_inplace(k, v, C.byref(l) if l else None, n_src, idx, istr, n_streams, n_keep, ws, ws_bytes, None)
     assert inplace(l=None) == b.SIRLLM_ERR_INVALID_ARG
     assert inplace(k=None) == b.SIRLLM_ERR_INVALID_ARG
     assert inplace(idx=None) == b.SIRLLM_ERR_INVALID_ARG
@@ -194,6 +194,9 @@ def test_inplace_and_ragged_argument_errors(b):
     assert inplace(v=0x10000000 + 64) == b.SIRLLM_ERR_INVALID_ARG     # K and V overlap
     assert inplace(k=0x10000002) == b.SIRLLM_ERR_INVALID_ARG
     assert inplace(n_keep=0) == b.SIRLLM_OK and inplace(n_streams=0) == b.SIRLLM_OK
+    assert inplace(ws=0x30000001, ws_bytes=1 << 20) == b.SIRLLM_ERR_WORKSPACE      # not 256-byte aligned
+    text = open(os.path.join(ROOT, "include", "sirllm.h")).read()
+    assert re.search(r"#define\s+SIRLLM_INPLACE_WORKSPACE_BYTES\s+256\b", text) and b.SIRLLM_INPLACE_WORKSPACE_BYTES == 256
     p = b.sirllm_policy(4, 20, 8, 0.9)
     def ragged(logits=0x1000, dt=0, vocab=1000, ld=1000, tok=0x2000000, scores=0x3000000, sstr=128, n_streams=2,
                held=0x7000000, cu=0x7100000, total=64, max_cand=100, max_new=64, pol=p, k=0x10000000, v=0x20000000,

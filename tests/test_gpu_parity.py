@@ -487,6 +487,12 @@ def test_step_random_shapes(b, ref):
 
 
 # ------------------------------------------------------------------------ in-place compaction
+def inplace_scratch(b, dirty=0x5A):
+    """A workspace for the in-place compaction's ticket counter (dirty on purpose: the call clears it itself)."""
+    return torch.full((b.SIRLLM_INPLACE_WORKSPACE_BYTES,), dirty, dtype=torch.uint8, device=DEV)
+
+
+@pytest.mark.parametrize("ticket", [False, True], ids=["by block index", "by ticket"])
 @pytest.mark.parametrize("S,L,H,P,D,dtype,frac", [
     (1, 2, 2, 96, 16, torch.float32, 0.33),
     (2, 3, 2, 300, 128, torch.bfloat16, 0.6),
@@ -497,7 +503,8 @@ def test_step_random_shapes(b, ref):
     (1, 2, 2, 4096, 128, torch.bfloat16, 0.97),   # almost everything kept: short moves
     (1, 2, 2, 1078, 128, torch.bfloat16, 0.95),
 ])
-def test_compact_inplace_matches_oracle(b, ref, S, L, H, P, D, dtype, frac):
+def test_compact_inplace_matches_oracle(b, ref, S, L, H, P, D, dtype, frac, ticket):
+    """Without a workspace the workgroups take their planes by block index, with one by ticket."""
     rng = np.random.default_rng(P * 7 + D)
     mod = 251 if dtype == torch.uint8 else (32749 if dtype in (torch.int16, torch.bfloat16) else 1 << 31)
     k = (synth.tagged_kv(S, L, H, P, D, 0) % mod).to(dtype).to(DEV)
@@ -510,7 +517,8 @@ def test_compact_inplace_matches_oracle(b, ref, S, L, H, P, D, dtype, frac):
         kept[0] = np.sort(rng.choice(P, n_keep, replace=False))
     hk, hv = to_np(k).copy(), to_np(v).copy()
     ref.compact_kv_inplace(hk, hv, kept)
-    b.sirllm_compact_kv_inplace(k, v, torch.from_numpy(kept).to(DEV), n_keep)
+    ws = inplace_scratch(b) if ticket else None
+    b.sirllm_compact_kv_inplace(k, v, torch.from_numpy(kept).to(DEV), n_keep, workspace=ws)
     torch.cuda.synchronize()
     assert np.array_equal(to_np(k), hk), "K differs (kept rows or the untouched tail)"
     assert np.array_equal(to_np(v), hv), "V differs"
@@ -519,9 +527,34 @@ def test_compact_inplace_matches_oracle(b, ref, S, L, H, P, D, dtype, frac):
     chain = np.arange(1, P, dtype=np.int32)[None, :].repeat(S, 0)
     h2 = to_np(k2).copy()
     ref.compact_kv_inplace(h2, None, chain)
-    b.sirllm_compact_kv_inplace(k2, None, torch.from_numpy(chain).to(DEV), P - 1)
+    ws = inplace_scratch(b) if ticket else None
+    b.sirllm_compact_kv_inplace(k2, None, torch.from_numpy(chain).to(DEV), P - 1, workspace=ws)
     torch.cuda.synchronize()
     assert np.array_equal(to_np(k2), h2)
+
+
+@pytest.mark.parametrize("ticket", [False, True], ids=["by block index", "by ticket"])
+@pytest.mark.parametrize("dtype,D", [(torch.float32, 4), (torch.int16, 4), (torch.int16, 2), (torch.int16, 1), (torch.uint8, 1),
+                                     (torch.bfloat16, 128)])
+def test_compact_inplace_chunk_boundaries(b, ref, dtype, D, ticket):
+    """Planes of 1, CH - 1, CH, CH + 1 and 2 CH + 1 vectors for every vector width the kernels use (16, 8, 4, 2, 1
+    bytes), at the default launch shape: CH = 4096 vectors is one chunk of the walk, whose counted wait must also
+    hold when a chunk is ragged or the look-ahead chunk lies wholly past the end of the plane."""
+    row_vecs = 16 if D == 128 else 1                                  # vectors per row: rows of 256 bytes, else one vector
+    for ch in (4096,):
+        for n_vec in (1, ch - 1, ch, ch + 1, 2 * ch - 1, 2 * ch, 2 * ch + 1, 3 * ch + 1):
+            n_keep = max(1, n_vec // row_vecs)
+            P = n_keep + 1 + n_keep // 3
+            rng = np.random.default_rng(n_vec + D)
+            mod = 251 if dtype == torch.uint8 else (32749 if dtype in (torch.int16, torch.bfloat16) else 1 << 31)
+            k = (synth.tagged_kv(1, 1, 2, P, D, 0) % mod).to(dtype).to(DEV)
+            kept = np.sort(rng.choice(P, n_keep, replace=False)).astype(np.int32)[None, :]
+            hk = to_np(k).copy()
+            ref.compact_kv_inplace(hk, None, kept)
+            ws = inplace_scratch(b) if ticket else None
+            b.sirllm_compact_kv_inplace(k, None, torch.from_numpy(kept).to(DEV), n_keep, workspace=ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_np(k), hk), f"{n_vec} vectors of {k.element_size() * D} bytes"
 
 
 @pytest.mark.parametrize("order", ["SLPHD", "SPLHD", "SLPHD_padded", "SLHPD"])
@@ -560,9 +593,36 @@ def test_compact_slot_major_layouts(b, ref, order, dtype, D):
     kept[1] = np.sort(rng.choice(P, n_keep, replace=False))          # in place needs a strictly ascending list
     hk, hv = to_np(k).copy(), to_np(v).copy()
     ref.compact_kv_inplace(hk, hv, kept)
-    b.sirllm_compact_kv_inplace(k, v, torch.from_numpy(kept).to(DEV), n_keep)
+    b.sirllm_compact_kv_inplace(k, v, torch.from_numpy(kept).to(DEV), n_keep, workspace=inplace_scratch(b))
     torch.cuda.synchronize()
     assert np.array_equal(to_np(k), hk) and np.array_equal(to_np(v), hv)
+
+
+@pytest.mark.parametrize("ticket", [False, True], ids=["by block index", "by ticket"])
+def test_compact_inplace_with_unusable_lists(b, ref, ticket):
+    """Lists the header calls unspecified -- not ascending, repeated entries, entries with no source slot -- must
+    still leave everything outside the first n_keep slots alone."""
+    S, L, H, P, D = 1, 1, 2, 20000, 128
+    rng = np.random.default_rng(3)
+    n_keep = 15000
+    for kind in ("shuffled", "all the same", "descending", "mostly out of range"):
+        k = (synth.tagged_kv(S, L, H, P, D, 0) % 32749).to(torch.bfloat16).to(DEV)
+        before = to_np(k).copy()
+        if kind == "shuffled":
+            kept = rng.permutation(P)[:n_keep]
+        elif kind == "all the same":
+            kept = np.full(n_keep, P - 1)
+        elif kind == "descending":
+            kept = np.arange(P - 1, P - 1 - n_keep, -1)
+        else:
+            kept = np.sort(rng.choice(P, n_keep, replace=False))
+            kept[::3] = 2 ** 31 - 5
+        kept = kept.astype(np.int32)[None, :]
+        ws = inplace_scratch(b) if ticket else None
+        b.sirllm_compact_kv_inplace(k, None, torch.from_numpy(kept).to(DEV), n_keep, workspace=ws)
+        torch.cuda.synchronize()
+        after = to_np(k)
+        assert np.array_equal(after[:, :, :, n_keep:], before[:, :, :, n_keep:]), kind     # the tail is never written
 
 
 def test_compact_inplace_strided_view_and_bad_indices(b, ref):
@@ -606,13 +666,14 @@ def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=
     held_dev = torch.from_numpy(n_held.astype(np.int32)).to(DEV)
     cu = torch.from_numpy(np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)).to(DEV)
     hs, hk, hv = to_np(scores).copy(), to_np(k).copy(), to_np(v).copy()
+    ws = inplace_scratch(b) if rng.integers(2) else None
     max_new = min(int(n_new.max()), max_cand) if tight_new else None
     if new_cap is not None:
         max_new = new_cap
     bound_new = max_new if max_new is not None else min(total, max_cand)
     fits_all = (n_held >= 0) & (n_new <= bound_new) & (n_cand <= max_cand)
     b.sirllm_step_ragged(z, tok, V, scores, held_dev, cu, total, max_cand, pol, k, v, kept, out, n_keep_dev,
-                         max_new=max_new)
+                         max_new=max_new, workspace=ws)
     torch.cuda.synchronize()
     gs, gkeep = to_np(scores), to_np(n_keep_dev)
     # scores: tolerance; then teacher-force the oracle with the GPU's scores for everything exact

@@ -17,7 +17,7 @@ from paper_2405_12528_amd import binding as b, synth        # noqa: E402
 DEV = "cuda:0"
 KNOBS = ("SIRLLM_SCORE_BLOCK", "SIRLLM_SCORE_NT", "SIRLLM_GATHER_BLOCK", "SIRLLM_GATHER_UNROLL", "SIRLLM_GATHER_NT",
          "SIRLLM_FUSE_SELECT", "SIRLLM_INPLACE_BLOCK", "SIRLLM_INPLACE_UNROLL", "SIRLLM_INPLACE_PARTS",
-         "SIRLLM_INPLACE_NT")
+         "SIRLLM_INPLACE_NT", "SIRLLM_INPLACE_TICKET")
 
 
 def set_knobs(**kw):
@@ -77,7 +77,7 @@ def check_gather(label):
         assert bool((kd[:, :, :, n_keep:] == 77).all())
 
 
-def check_inplace(label):
+def check_inplace(label, scratch=False):
     rng = np.random.default_rng(6)
     for (S, L, H, P, D, dtype, n_keep) in ((2, 2, 2, 9000, 128, torch.bfloat16, 4500), (1, 1, 2, 4300, 128, torch.bfloat16, 4100),
                                            (1, 2, 2, 700, 100, torch.bfloat16, 300), (1, 1, 2, 90, 7, torch.int16, 41)):
@@ -85,7 +85,8 @@ def check_inplace(label):
         kept = kept_list(rng, S, P, n_keep)
         hk, hv = to_np(k).copy(), to_np(v).copy()
         ref.compact_kv_inplace(hk, hv, kept)
-        b.sirllm_compact_kv_inplace(k, v, torch.from_numpy(kept).to(DEV), n_keep)
+        ws = torch.full((b.SIRLLM_INPLACE_WORKSPACE_BYTES,), 0x33, dtype=torch.uint8, device=DEV) if scratch else None
+        b.sirllm_compact_kv_inplace(k, v, torch.from_numpy(kept).to(DEV), n_keep, workspace=ws)
         torch.cuda.synchronize()
         assert np.array_equal(to_np(k), hk) and np.array_equal(to_np(v), hv), f"in-place {P}x{D} under {label}"
 
@@ -138,10 +139,13 @@ def main():
         for un in (2, 4, 8):
             for parts, nt in ((1, 1), (2, 1), (4, 0), (1, 0)):
                 label = set_knobs(INPLACE_BLOCK=blk, INPLACE_UNROLL=un, INPLACE_PARTS=parts, INPLACE_NT=nt)
-                check_inplace(label); n += 1
+                check_inplace(label); check_inplace(label, scratch=True); n += 1
                 print("ok", label, flush=True)
+    label = set_knobs(INPLACE_TICKET=0)                        # a workspace is given, the ticket order switched off
+    check_inplace(label, scratch=True); n += 1
+    print("ok", label, flush=True)
     label = set_knobs()
-    check_score(label); check_gather(label); check_inplace(label); check_step(label)
+    check_score(label); check_gather(label); check_inplace(label); check_inplace(label, scratch=True); check_step(label)
     print(f"ALL OK: {n} override settings", flush=True)
 
 
