@@ -13,6 +13,39 @@ constexpr int kWave = 64;                    // CDNA wavefront width
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// ---- cross-lane moves inside a wavefront ------------------------------------------------
+// Data-parallel-primitive (DPP) moves run on the vector ALU, without the round trip through the LDS crossbar that a
+// general lane shuffle takes; the reductions at the end of every latency-bound kernel here are chains of them.
+// A wave is four rows of 16 lanes.  dpp_move<CTRL, ROW_MASK>(v, fill): every lane of the rows enabled in ROW_MASK
+// receives v from the lane CTRL names, or `fill` when that lane does not exist or its own row is not enabled.
+constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;   // lane i <- lane i - n of its row
+constexpr int kDppRowBcast15 = 0x142;   // lane 15 of each row -> every lane of the next row
+constexpr int kDppRowBcast31 = 0x143;   // lane 31 -> every lane of rows 2 and 3
+
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ uint32_t dpp_move(uint32_t v, uint32_t fill)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)fill, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+
+// Inclusive prefix sum over the 64 lanes: Hillis-Steele inside each row, then the row totals carried forward.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
+{
+    v += dpp_move<kDppRowShr1>(v, 0u);
+    v += dpp_move<kDppRowShr2>(v, 0u);
+    v += dpp_move<kDppRowShr4>(v, 0u);
+    v += dpp_move<kDppRowShr8>(v, 0u);
+    v += dpp_move<kDppRowBcast15, 0xa>(v, 0u);
+    v += dpp_move<kDppRowBcast31, 0xc>(v, 0u);
+    return v;
+}
+
+// Sum over the 64 lanes, the same value in every lane.
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_sum(v), kWave - 1);
+}
+
 // ---- score.hip --------------------------------------------------------------------------
 // Token entropy of n_rows rows.  Row `row` belongs to stream row / rows_per_stream, token
 // t = row % rows_per_stream; its score goes to out_a[stream*stride_a + t] and, when out_b is

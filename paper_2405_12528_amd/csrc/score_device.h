@@ -29,6 +29,35 @@ __device__ __forceinline__ MS merge(MS a, MS b)
     return {m, a.s * fa + b.s * fb};
 }
 
+// One step of a cross-lane reduction: every lane merges in the (m, s) of the lane CTRL names (the empty element
+// where there is none).
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ MS merge_from(MS a)
+{
+    const MS o = {__uint_as_float(dpp_move<CTRL, ROW_MASK>(__float_as_uint(a.m), kNegInfBits)),
+                  __uint_as_float(dpp_move<CTRL, ROW_MASK>(__float_as_uint(a.s), 0u))};
+    return merge(a, o);
+}
+
+// Lane 16*r + 15 ends up with the merge of row r's sixteen lanes (rows are the wave's four groups of 16 lanes).
+__device__ __forceinline__ MS row_reduce(MS a)
+{
+    a = merge_from<kDppRowShr1>(a);
+    a = merge_from<kDppRowShr2>(a);
+    a = merge_from<kDppRowShr4>(a);
+    a = merge_from<kDppRowShr8>(a);
+    return a;
+}
+
+// Lane 63 ends up with the merge of all 64 lanes.
+__device__ __forceinline__ MS wave_reduce(MS a)
+{
+    a = row_reduce(a);
+    a = merge_from<kDppRowBcast15, 0xa>(a);
+    a = merge_from<kDppRowBcast31, 0xc>(a);
+    return a;
+}
+
 template <int N>
 __device__ __forceinline__ void accumulate(const float (&z)[N], MS& acc)
 {
@@ -139,6 +168,15 @@ __device__ __forceinline__ void score_row(const ScoreArgs& a, int64_t row, Score
     const int nvec = (V - head) / VEC;
     const int tail0 = head + nvec * VEC;
 
+    // The token's own logit is fetched now, by the lane that finishes the row, so that its two dependent loads (the
+    // id, then the logit) are over long before the reduction is: at the end of a short row they would be the
+    // longest thing left.
+    float z_tok = __uint_as_float(0x7fc00000u);            // NaN: no such token (or not in this chunk of columns)
+    if (tid == 0) {
+        const int64_t local = (int64_t)a.token_ids[row] - (a.partial ? a.v_begin : 0);
+        if (local >= 0 && local < V) z_tok = E::load1(rowp, (int)local);
+    }
+
     MS acc = {-INFINITY, 0.0f};
     {   // at most 2*(VEC-1) scalar elements, one per thread
         int e = -1;
@@ -174,44 +212,35 @@ __device__ __forceinline__ void score_row(const ScoreArgs& a, int64_t row, Score
         accumulate<UNROLL * VEC>(z, acc);
     }
 
-    // lanes -> wave
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        MS o = {__shfl_xor(acc.m, off, kWave), __shfl_xor(acc.s, off, kWave)};
-        acc = merge(acc, o);
-    }
+    // lanes -> wave (lane 63 holds the wave's result)
+    acc = wave_reduce(acc);
     // waves -> workgroup
     constexpr int NW = BLOCK / kWave;
+    static_assert(NW <= 16, "the second stage reduces one row of sixteen lanes");
     if constexpr (NW > 1) {
-        if ((tid & (kWave - 1)) == 0) { sm.m[tid / kWave] = acc.m; sm.s[tid / kWave] = acc.s; }
+        if ((tid & (kWave - 1)) == kWave - 1) { sm.m[tid / kWave] = acc.m; sm.s[tid / kWave] = acc.s; }
         __syncthreads();
         if (tid < kWave) {
             acc = (tid < NW) ? MS{sm.m[tid], sm.s[tid]} : MS{-INFINITY, 0.0f};
-#pragma unroll
-            for (int off = NW / 2; off > 0; off >>= 1) {
-                MS o = {__shfl_xor(acc.m, off, kWave), __shfl_xor(acc.s, off, kWave)};
-                acc = merge(acc, o);
-            }
+            acc = row_reduce(acc);                                     // lanes 0..15 hold the waves: lane 15 has it all
+            acc.m = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(acc.m), 15));
+            acc.s = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(acc.s), 15));
         }
+    } else {
+        acc.m = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(acc.m), kWave - 1));
+        acc.s = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(acc.s), kWave - 1));
     }
     if (tid == 0 && a.partial) {
         // a chunk of columns [v_begin, v_begin + V) of a longer row: leave the monoid element and, if the
         // token's column is in this chunk, its logit (NaN says "not in this chunk")
-        const int64_t local = (int64_t)a.token_ids[row] - a.v_begin;
         a.partial[3 * row + 0] = acc.m;
         a.partial[3 * row + 1] = acc.s;
-        a.partial[3 * row + 2] = (local >= 0 && local < V) ? E::load1(rowp, (int)local) : __uint_as_float(0x7fc00000u);
+        a.partial[3 * row + 2] = z_tok;
         return;
     }
     if (tid == 0) {
-        const int32_t tok = a.token_ids[row];
-        float e;
-        if (tok < 0 || tok >= V) {
-            e = __uint_as_float(0x7fc00000u);          // no such token: quiet NaN
-        } else {
-            const float zt = E::load1(rowp, tok);
-            e = (acc.m - zt) + logf(acc.s);
-        }
+        // a token id outside [0, V) left z_tok = NaN, and so is the score
+        const float e = (acc.m - z_tok) + logf(acc.s);
         if (a.cu_rows) {
             // ragged batch: the stream whose row range holds `row` (largest s with cu_rows[s] <= row)
             int lo = 0, hi = a.n_streams_r;

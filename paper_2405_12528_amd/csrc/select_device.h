@@ -1,14 +1,18 @@
 // Device code of decay, Top_k selection and index build (paper Sec. 3.3: E <- E*eta,
 // Id_entropy = Top_k(E), E <- E[Id]; Sec. 3.1: Id_sink, Id_recent) for ONE dialogue stream by
 // one workgroup.  Every thread owns KPT consecutive candidate slots in registers.  The k-th
-// largest key of the middle region is found by an MSB-first radix select (four 8-bit digits,
-// LDS histograms), which yields the threshold key and how many slots equal to it may still be
+// largest key of the middle region is found by an MSB-first radix select (four 8-bit digits, one
+// LDS histogram, two barriers per digit), which yields the threshold key and how many slots equal to it may still be
 // taken (lowest slots first); one block-wide prefix sum over (greater, equal) counts then
 // gives every kept slot its in-cache position, so the kept list comes out in ascending slot
 // order without sorting anything.  Latency bound: a few tens of KB per stream.
 #pragma once
 
 #include "common.h"
+
+#ifndef SIRLLM_TSTAMP
+#define SIRLLM_TSTAMP(k)
+#endif
 
 namespace sirllm {
 namespace select_dev {
@@ -22,16 +26,7 @@ __device__ __forceinline__ uint32_t order_key(float x)
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
-{
-    const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t o = __shfl_up(v, off, kWave);
-        if (lane >= off) v += o;
-    }
-    return v;
-}
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) { return wave_inclusive_sum(v); }
 
 template <int BLOCK>
 struct SelectSmem {
@@ -81,20 +76,47 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, S
 
     // E <- E * eta for the held slots (one rounded multiply; never fused with anything)
     float val[KPT];
+    if constexpr (RANDOM_KEYS) {
 #pragma unroll
-    for (int q = 0; q < KPT; ++q) {
-        const int i = i0 + q;
-        float e = 0.0f;
-        if constexpr (RANDOM_KEYS) {
+        for (int q = 0; q < KPT; ++q) {
+            const int i = i0 + q;
+            float e = 0.0f;
             if (i >= mid_lo && i < mid_hi)
                 e = __uint_as_float(philox4x32_10_word0((uint32_t)i, (uint32_t)stream, a.turn_lo, a.turn_hi,
                                                         a.seed_lo, a.seed_hi));
-        } else if (i < n_read) {
-            e = E[i];
-            if (i < a.n_held) e = __fmul_rn(e, a.decay);
+            val[q] = e;
         }
-        val[q] = e;
+    } else {
+        // a lane's KPT consecutive scores in 16-byte pieces when the row allows it (uniform over the workgroup),
+        // else one by one
+        bool wide = false;
+        if constexpr (KPT % 4 == 0) wide = (((uintptr_t)E) & 15) == 0;
+        if (wide) {
+            if constexpr (KPT % 4 == 0) {
+#pragma unroll
+                for (int q4 = 0; q4 < KPT; q4 += 4) {
+                    const int i = i0 + q4;
+                    u32x4 x = {0u, 0u, 0u, 0u};
+                    if (i + 3 < n_read) {
+                        x = *(const u32x4*)(E + i);
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (i + t < n_read) x[t] = __float_as_uint(E[i + t]);
+                    }
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) val[q4 + t] = __uint_as_float(x[t]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < KPT; ++q) val[q] = (i0 + q < n_read) ? E[i0 + q] : 0.0f;
+        }
+#pragma unroll
+        for (int q = 0; q < KPT; ++q)
+            if (i0 + q < a.n_held && i0 + q < n_read) val[q] = __fmul_rn(val[q], a.decay);
     }
+    SIRLLM_TSTAMP(1);
     auto key_of = [](float v) -> uint32_t {
         if constexpr (RANDOM_KEYS) return __float_as_uint(v);
         else return order_key(v);
@@ -105,13 +127,15 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, S
     uint32_t k_rem = 0;
     if (a.n_topk > 0) {
         prefix = 0u; mask = 0u; k_rem = (uint32_t)a.n_topk;
+        if (tid < 256) sm.hist[tid] = 0u;
+        __syncthreads();
         for (int shift = 24; shift >= 0; shift -= 8) {
-            if (tid < 256) sm.hist[tid] = 0u;
-            __syncthreads();
             // A lane first folds its own slots: those whose digit equals the digit of its first live slot
             // go into the histogram with one add.  In the first pass (sign and high exponent bits, nearly
-            // the same for every score) that is all of them, which takes the pile-up on one or two bins
-            // down by a factor KPT; in later passes digits differ and most slots add on their own.
+            // the same for every score) that is all of them; the wave then folds its lanes the same way: when
+            // every live lane holds the same digit, one lane adds the wave's count.  That takes the pile-up on
+            // one or two bins from one add per slot down to one per wave.  In later passes digits differ and
+            // most slots add on their own.
             {
                 uint32_t d0 = 0xffffffffu, n0 = 0u;
 #pragma unroll
@@ -127,26 +151,38 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, S
                         }
                     }
                 }
-                if (n0) atomicAdd(&sm.hist[d0], n0);
-            }
-            __syncthreads();
-            // the digit d with  #(digit > d) < k_rem <= #(digit >= d)
-            const uint32_t c = (tid < 256) ? sm.hist[tid] : 0u;
-            const uint32_t inc = wave_inclusive_scan(c);
-            if (lane == kWave - 1) sm.wave_tot[wave] = inc;
-            __syncthreads();
-            if (tid < 256) {
-                uint32_t below_waves = 0u, total = 0u;
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const uint32_t t = sm.wave_tot[w];
-                    if (w < wave) below_waves += t;
-                    total += t;
+                const unsigned long long live = __ballot(n0 != 0u);
+                if (live != 0ull) {
+                    const int first = __ffsll((long long)live) - 1;
+                    const uint32_t ref = (uint32_t)__builtin_amdgcn_readlane((int)d0, first);
+                    if (__ballot(n0 != 0u && d0 != ref) == 0ull) {
+                        const uint32_t tot = wave_sum(n0);
+                        if (lane == first) atomicAdd(&sm.hist[ref], tot);
+                    } else if (n0) {
+                        atomicAdd(&sm.hist[d0], n0);
+                    }
                 }
-                const uint32_t above = total - (inc + below_waves);
-                if (above < k_rem && k_rem <= above + c) { sm.sel_digit = (uint32_t)tid; sm.sel_above = above; }
             }
             __syncthreads();
+            // One wave finds the digit d with  #(digit > d) < k_rem <= #(digit >= d):  lane l owns bins 4l .. 4l+3,
+            // a wave scan of the lanes' sums gives the count above each lane's bins.  It clears the bins for the next
+            // pass on the way (every other wave is past its adds and waits at the barrier below).
+            if (wave == 0) {
+                uint32_t c[4];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) { c[b] = sm.hist[4 * lane + b]; sm.hist[4 * lane + b] = 0u; }
+                const uint32_t mine = (c[0] + c[1]) + (c[2] + c[3]);
+                const uint32_t inc = wave_inclusive_scan(mine);
+                const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)inc, kWave - 1);
+                uint32_t above = total - inc;                       // slots in bins above this lane's four
+#pragma unroll
+                for (int b = 3; b >= 0; --b) {
+                    if (above < k_rem && k_rem <= above + c[b]) { sm.sel_digit = (uint32_t)(4 * lane + b); sm.sel_above = above; }
+                    above += c[b];
+                }
+            }
+            __syncthreads();
+            SIRLLM_TSTAMP(2 + (24 - shift) / 8);
             prefix |= sm.sel_digit << shift;
             mask |= 255u << shift;
             k_rem -= sm.sel_above;
@@ -167,7 +203,6 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, S
         }
     }
     const uint32_t inc = wave_inclusive_scan(mine);
-    __syncthreads();                   // wave_tot is reused
     if (lane == kWave - 1) sm.wave_tot[wave] = inc;
     __syncthreads();
     uint32_t before = inc - mine;
@@ -175,6 +210,7 @@ __device__ __forceinline__ void select_stream(const SelectArgs& a, int stream, S
     for (int w = 0; w < NW; ++w)
         if (w < wave) before += sm.wave_tot[w];
     uint32_t g = before & 0xffffu, eq = before >> 16;
+    SIRLLM_TSTAMP(6);
 
     // ---- index build: kept slot i goes to in-cache position pos; E_out[pos] = E[i] ------------
     int32_t* idx = a.kept_idx + (int64_t)stream * a.idx_stride;

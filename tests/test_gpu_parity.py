@@ -395,6 +395,32 @@ def test_step_small_shapes(b, ref, n_streams, n_held, n_new, pol):
     check_step_against_oracle(b, ref, w2, z, tok, held, k_c, v_c, g, pol=pol)
 
 
+@pytest.mark.parametrize("S,L,H,n_held,n_new,pol,D,kv_dt", [
+    (2, 4, 4, 2400, 600, (4, 1396, 600, 0.9), 128, torch.bfloat16),     # the recent window is exactly this turn's tokens
+    (1, 8, 4, 3000, 500, (4, 1000, 1100, 0.8), 128, torch.bfloat16),    # the window holds held slots as well as the new ones
+    (3, 2, 8, 2000, 700, (0, 500, 700, 1.0), 64, torch.float32),        # no sinks, 4-byte elements
+    (2, 4, 4, 2400, 600, (4, 1396, 600, 0.9), 120, torch.bfloat16),     # 240-byte rows: 15 vectors, not a power of two
+    (2, 4, 4, 2400, 600, (4, 1396, 600, 0.9), 100, torch.bfloat16),     # 200-byte rows: 8-byte vectors
+])
+def test_step_mid_sizes(b, ref, S, L, H, n_held, n_new, pol, D, kv_dt):
+    """Whole steps between the small shapes and the benchmark's: a few thousand slots, tens of planes, rows of 256,
+    240 and 200 bytes (16-byte vectors with a power-of-two and an odd count per row, 8-byte vectors), self-identifying
+    K/V payloads; scoring and selection share a launch (no new token can compete in Top_k)."""
+    import dataclasses
+    V = 2000
+    w2 = dataclasses.replace(synth.WORKLOADS["tiny"], vocab=V)
+    pol = b.Policy(*pol)
+    g0 = torch.Generator(device=DEV).manual_seed(n_held + D)
+    z = (torch.randn((S * n_new, V), generator=g0, device=DEV) * 3).to(torch.bfloat16)
+    tok = torch.randint(0, V, (S * n_new,), generator=g0, device=DEV, dtype=torch.int32)
+    held = torch.rand((S, n_held), generator=g0, device=DEV) * 6
+    n_cand = n_held + n_new
+    k_c = (synth.tagged_kv(S, L, H, n_cand, D, 0) % 32749).to(kv_dt).to(DEV)
+    v_c = (synth.tagged_kv(S, L, H, n_cand, D, 1) % 32719).to(kv_dt).to(DEV)
+    g = gpu_step(b, w2, z, tok, held, k_c, v_c, pol=pol)
+    check_step_against_oracle(b, ref, w2, z, tok, held, k_c, v_c, g, pol=pol)
+
+
 # ------------------------------------------------------------------------- baseline policies
 BASELINE_CASES = [
     # n_streams, n_cand, n_sink, k, n_recent
