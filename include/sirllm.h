@@ -18,8 +18,22 @@
  *     is current when the call is made.  Policy and layout structs are HOST pointers and are
  *     read before the call returns.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
- *     enqueue work on it and return without synchronising.  The library allocates nothing,
- *     creates no streams and keeps no state between calls.
+ *     enqueue work on it and return without synchronising.  The library allocates nothing and
+ *     creates no streams.  Nothing a call computes depends on an earlier call; what the process keeps
+ *     is bookkeeping only: per kernel and device, that the runtime has been told once about its LDS
+ *     size; per device, the address of the static scratch of sirllm_decay_select_static; and whether
+ *     the launch-shape overrides below are switched on.
+ *   - Launch-shape overrides, for sweeps.  If the environment variable SIRLLM_TUNE is set to a non-empty
+ *     value when the process makes its first call into the library, every launch reads the following
+ *     variables (integers; unset = the default in brackets) -- otherwise none of them is ever read:
+ *       SIRLLM_SCORE_BLOCK [by row length: 1024, 512 or 256]  threads per scored row
+ *       SIRLLM_SCORE_NT [1], SIRLLM_GATHER_NT [1], SIRLLM_INPLACE_NT [1]   non-temporal (1) or cached (0) accesses
+ *       SIRLLM_GATHER_BLOCK [512] (or 256), SIRLLM_GATHER_UNROLL [1] (or 2)   threads and 16-byte vectors per lane of a gather tile
+ *       SIRLLM_FUSE_SELECT [1]   0: score and select in separate launches even when they are independent
+ *       SIRLLM_INPLACE_BLOCK [1024] (512, 256), SIRLLM_INPLACE_UNROLL [4] (2, 8), SIRLLM_INPLACE_PARTS [by plane count]
+ *                                threads, vectors per lane and column parts of the in-place walk
+ *       SIRLLM_INPLACE_TICKET [1]   0: planes by block index even when a workspace is given
+ *     Results do not depend on any of them (every setting is tested against the oracle); timings do.
  *   - All shapes are host integers and are uniform over the `n_streams` independent dialogue
  *     streams of a call.
  *   - Return value: SIRLLM_OK (0) or a negative sirllm_status.  Arguments are validated on

@@ -10,6 +10,8 @@
 //   The result block D[vocab i][token j] leaves lane l with token j = l % 32 and the 16 vocabulary rows
 //   i = 8 * (r / 4) + 4 * (l / 32) + r % 4, r = 0..15: the reduction over the vocabulary is lane-local but
 //   for one exchange between the two half waves.
+#include <atomic>
+
 #include "common.h"
 #include "score_device.h"
 
@@ -466,6 +468,19 @@ void tile_shape(int64_t n_rows, int32_t vocab, int& bv, int& bt)
     else { bv = 256; bt = 256; }
 }
 
+// A kernel that uses more than 64 KB of dynamic LDS has to be told so once per device; `done` (one bit per device,
+// owned by the calling launcher, i.e. one per kernel) remembers where that has happened, so that the launch path of
+// a small turn does not pay for the runtime call every time.
+inline hipError_t allow_dynamic_lds(const void* fn, int bytes, std::atomic<uint64_t>& done)
+{
+    int dev = -1;
+    const bool known = hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64;
+    if (known && (done.load(std::memory_order_acquire) >> dev & 1ull)) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && known) done.fetch_or(1ull << dev, std::memory_order_release);
+    return e;
+}
+
 template <int DT, int NVB, int NTB, int RING, bool PIN, bool WARM>
 hipError_t launch_fast(const LmHeadArgs& a, hipStream_t stream)
 {
@@ -473,7 +488,8 @@ hipError_t launch_fast(const LmHeadArgs& a, hipStream_t stream)
     const int64_t groups = (int64_t)((a.n_vtiles + 7) / 8) * a.n_ttiles * 8;
     if (groups > 0x7fffffff) return hipErrorInvalidValue;
     auto fn = lmhead_score_kernel<DT, NVB, NTB, RING, PIN, WARM>;
-    hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLds);
+    static std::atomic<uint64_t> lds_allowed{0};
+    const hipError_t e = allow_dynamic_lds((const void*)fn, Cfg::kLds, lds_allowed);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(fn, dim3((unsigned)groups), dim3(256), Cfg::kLds, stream, a);
     return hipGetLastError();
@@ -485,7 +501,8 @@ hipError_t launch_general(const LmHeadArgs& a, hipStream_t stream)
     const int64_t groups = (int64_t)((a.n_vtiles + 7) / 8) * a.n_ttiles * 8;
     if (groups > 0x7fffffff) return hipErrorInvalidValue;
     auto fn = lmhead_score_general_kernel<DT>;
-    hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    static std::atomic<uint64_t> lds_allowed{0};
+    const hipError_t e = allow_dynamic_lds((const void*)fn, kLdsBytes, lds_allowed);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(fn, dim3((unsigned)groups), dim3(256), kLdsBytes, stream, a);
     return hipGetLastError();

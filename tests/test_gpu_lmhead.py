@@ -1,12 +1,14 @@
 """Parity of sirllm_lmhead_score (token entropy straight from hidden states and the output embedding
 matrix, paper Sec. 3.2) with the CPU oracle, through the C ABI, on one MI355X.
 
-Tolerance: |gpu - ref| <= 1e-4 + 1e-5*|ref|.  The kernel's products of two bf16 / f16 numbers are exact in
+Tolerance: |gpu - ref| <= 2e-5 + 1e-5*|ref|.  The kernel's products of two bf16 / f16 numbers are exact in
 binary32; a logit is their sum over d_model terms taken 16 at a time into a binary32 accumulator, i.e.
-d_model/16 roundings of at most 2^-24 * |partial sum| each.  With errors adding like a random walk
-(sqrt(d_model/16) * 2^-24 * max |partial sum|; d_model = 4096, partial sums below ~45 on these inputs) a logit
-is within ~4e-5 of its exact value, and the score, a difference of the token's logit and a weighted mean
-of logits, within twice that; the softmax reduction itself adds the ~1e-6 of the logits path.
+d_model/16 roundings, each off by at most 2^-24 * |partial sum| and by 2^-24 * |partial sum| / sqrt(3) in the root
+mean square.  Adding like a random walk over the 256 roundings of d_model = 4096, with partial sums of order 10 on
+these inputs, that is ~6e-6 per logit in the root mean square; the score is the token's logit minus a weighted mean
+of logits (whose errors average out), plus the ~1e-6 of the softmax reduction.  Worst case seen over the 268
+oracle-checked rows of the Llama-3-8B-shaped workload: 2.1e-5 (about three standard deviations), on scores of
+5 to 15, where the bound is 7e-5 to 1.7e-4.  The relative term is the one the logits path uses.
 """
 import numpy as np
 import pytest
@@ -32,7 +34,7 @@ def assert_close(gpu: np.ndarray, want: np.ndarray):
     np.testing.assert_array_equal(nan_g, nan_w)
     ok = ~nan_w
     err = np.abs(gpu[ok].astype(np.float64) - want[ok].astype(np.float64))
-    tol = 1e-4 + 1e-5 * np.abs(want[ok].astype(np.float64))
+    tol = 2e-5 + 1e-5 * np.abs(want[ok].astype(np.float64))
     bad = err > tol
     assert not bad.any(), f"{bad.sum()} scores off; worst {err.max():.3e} (tolerance {tol[err.argmax()]:.3e})"
     return float(err.max()) if err.size else 0.0
@@ -192,9 +194,12 @@ def test_lmhead_agrees_with_scoring_the_materialised_logits(b):
     assert_close(got, to_np(out))
 
 
-def test_lmhead_llama3_shape_sampled_rows_against_the_oracle(b, ref):
-    """2048 x 4096 hidden states against a 128256 x 4096 output embedding (the Llama-3-8B-shaped workload):
-    every row is checked against the logits route, 12 sampled rows against the oracle."""
+@pytest.mark.timeout(600)
+def test_lmhead_llama3_shape_a_whole_token_tile_against_the_oracle(b, ref):
+    """2048 x 4096 hidden states against a 128256 x 4096 output embedding (the Llama-3-8B-shaped workload): one whole
+    256-row token tile (rows 256..511: every lane, wave and accumulator block of a workgroup, against all 501
+    vocabulary tiles) and 12 rows sampled from the other tiles are checked against the oracle's double-precision
+    product; every row is also checked against the logits route."""
     w_ = synth.WORKLOADS["llama3_8b"]
     h, W = synth.make_lmhead(w_, turn=1, device=DEV)
     tok = synth.make_token_ids(w_, turn=1, device=DEV)
@@ -210,12 +215,12 @@ def test_lmhead_llama3_shape_sampled_rows_against_the_oracle(b, ref):
         b.sirllm_score(z, tok[r0:r0 + 256], other[r0:r0 + 256])
     torch.cuda.synchronize()
     assert_close(got, to_np(other))
-    rows = np.random.default_rng(0).choice(n, 12, replace=False)
+    rows = np.concatenate([np.arange(256, 512), np.random.default_rng(0).choice(np.r_[0:256, 512:n], 12, replace=False)])
     rows.sort()
     ref.set_threads(16)
     want = ref.lmhead_score(to_np(h[torch.from_numpy(rows).to(DEV)]), to_np(W), to_np(tok)[rows])
     worst = assert_close(got[rows], want)
-    print(f"llama3 shape: worst |gpu - oracle| over 12 sampled rows = {worst:.2e}")
+    print(f"llama3 shape: worst |gpu - oracle| over {len(rows)} rows (one whole token tile + 12 sampled) = {worst:.2e}")
 
 
 # ------------------------------------------------------------------ the whole step, scores from the LM head
