@@ -32,7 +32,7 @@
  *       SIRLLM_FUSE_SELECT [1]   0: score and select in separate launches even when they are independent
  *       SIRLLM_INPLACE_BLOCK [1024] (512, 256), SIRLLM_INPLACE_UNROLL [4] (2, 8), SIRLLM_INPLACE_PARTS [by plane count]
  *                                threads, vectors per lane and column parts of the in-place walk
- *       SIRLLM_INPLACE_TICKET [1]   0: planes by block index even when a workspace is given
+ *       SIRLLM_INPLACE_TICKET [1 from 8192 planes on, else 0]   planes by ticket (1) or by block index (0) when a workspace is given
  *     Results do not depend on any of them (every setting is tested against the oracle); timings do.
  *   - All shapes are host integers and are uniform over the `n_streams` independent dialogue
  *     streams of a call.
@@ -253,8 +253,9 @@ int sirllm_compact_kv(const void* k_src, const void* v_src, const sirllm_kv_layo
  *               SIRLLM_INPLACE_WORKSPACE_BYTES the workgroups that compact the (stream, layer, tensor, head) planes
  *               take their planes in the order in which they start (a ticket counter in the scratch, cleared by the
  *               call itself) instead of by block index, which keeps the planes in flight next to each other in
- *               memory: up to 7 % faster on batches of tens of thousands of planes, no difference on small ones.
- *               NULL or smaller: ignored.  Results are identical either way.  Calls that share a workspace must be
+ *               memory: up to 7 % faster on batches of tens of thousands of planes.  The library does so from 8192
+ *               planes on (streams x layers x tensors x heads); below that, and with NULL or a smaller workspace,
+ *               planes go by block index.  Results are identical either way.  Calls that share a workspace must be
  *               ordered on one stream.
  */
 #define SIRLLM_INPLACE_WORKSPACE_BYTES 256

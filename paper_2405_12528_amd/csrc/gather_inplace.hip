@@ -15,7 +15,7 @@
 // through its share at its own pace; over a batch of tens of thousands of planes the dies drift apart and the
 // workgroups in flight end up walking planes that lie gigabytes apart.  With tickets the planes being walked at any
 // moment are always neighbours, which the memory system serves faster (32 streams x 2048 planes: 5.6 -> 6.0 TB/s;
-// no difference for a few thousand planes).
+// no difference for a few thousand planes, so the launcher uses tickets from 8192 planes on).
 #include "common.h"
 #include "gather_device.h"
 #include "tuning.h"
@@ -218,9 +218,13 @@ hipError_t launch_any(const GatherArgs& a, const Ragged& rg, void* scratch, size
 {
     if (a.n_keep <= 0 || a.n_streams <= 0 || a.row_bytes <= 0 || a.n_layers <= 0 || a.n_heads <= 0)
         return hipSuccess;
+    // Ticket order pays once the batch has so many planes that the dies drift apart while they work through them; for
+    // a few thousand planes it changes nothing and the launch that clears the counter would only cost its 2-4 us.
+    constexpr int64_t kTicketPlanes = 8192;
+    const int64_t planes_total = (int64_t)a.n_streams * a.n_tensors * a.n_layers * a.n_heads;
     int32_t* ticket = nullptr;
-    if (scratch && scratch_bytes >= (size_t)SIRLLM_INPLACE_WORKSPACE_BYTES && tuning::get("SIRLLM_INPLACE_TICKET", 1) != 0)
-        ticket = (int32_t*)scratch;
+    const int want = tuning::get("SIRLLM_INPLACE_TICKET", planes_total >= kTicketPlanes ? 1 : 0);
+    if (scratch && scratch_bytes >= (size_t)SIRLLM_INPLACE_WORKSPACE_BYTES && want != 0) ticket = (int32_t*)scratch;
     switch (gather_dev::vector_bytes(a)) {
     case 16: return launch_vec<u32x4>(a, rg, ticket, stream);
     case 8:  return launch_vec<u32x2>(a, rg, ticket, stream);

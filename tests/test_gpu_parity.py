@@ -528,6 +528,8 @@ def inplace_scratch(b, dirty=0x5A):
     (2, 2, 2, 5000, 64, torch.float32, 0.5),      # many chunks per plane
     (1, 2, 2, 4096, 128, torch.bfloat16, 0.97),   # almost everything kept: short moves
     (1, 2, 2, 1078, 128, torch.bfloat16, 0.95),
+    (4, 32, 32, 40, 8, torch.int16, 0.6),         # 8192 planes: from here on a workspace switches the ticket order on
+    (3, 48, 32, 70, 64, torch.bfloat16, 0.8),     # 9216 planes of 128-byte rows
 ])
 def test_compact_inplace_matches_oracle(b, ref, S, L, H, P, D, dtype, frac, ticket):
     """Without a workspace the workgroups take their planes by block index, with one by ticket."""
@@ -766,6 +768,11 @@ def test_step_ragged_matches_oracle(b, ref):
                L=1, H=2, D=64, kv_dt=torch.bfloat16)
     # the same shapes with a loose bound on the new tokens: three launches
     run_ragged(b, ref, rng, 5, pol, 300, torch.float32, [0, 30, 24, 100, 3], [8, 2, 8, 7, 0], tight_new=False)
+    # 5 x 32 x 32 x 2 = 10240 planes: with a workspace the compaction takes its planes by ticket (one stream under
+    # budget and one flagged among them: their workgroups draw tickets too and return)
+    for _ in range(2):
+        run_ragged(b, ref, rng, 5, pol, 200, torch.bfloat16, [40, 10, 90, 33, 60], [8, 5, 3, 8, 20], L=32, H=32, D=8,
+                   kv_dt=torch.bfloat16, new_cap=8)
     for _ in range(10):
         S = int(rng.integers(1, 9))
         run_ragged(b, ref, rng, S, b.Policy(int(rng.integers(0, 5)), int(rng.integers(0, 60)), int(rng.integers(0, 20)), 0.7),

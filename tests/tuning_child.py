@@ -138,12 +138,14 @@ def main():
     for blk in (256, 512, 1024):
         for un in (2, 4, 8):
             for parts, nt in ((1, 1), (2, 1), (4, 0), (1, 0)):
-                label = set_knobs(INPLACE_BLOCK=blk, INPLACE_UNROLL=un, INPLACE_PARTS=parts, INPLACE_NT=nt)
-                check_inplace(label); check_inplace(label, scratch=True); n += 1
+                label = set_knobs(INPLACE_BLOCK=blk, INPLACE_UNROLL=un, INPLACE_PARTS=parts, INPLACE_NT=nt, INPLACE_TICKET=(blk // 256 + un) % 2)
+                check_inplace(label, scratch=True)
+                check_inplace(label); n += 1
                 print("ok", label, flush=True)
-    label = set_knobs(INPLACE_TICKET=0)                        # a workspace is given, the ticket order switched off
-    check_inplace(label, scratch=True); n += 1
-    print("ok", label, flush=True)
+    for t in (0, 1):                                           # a workspace is given; ticket order forced off / on at any size
+        label = set_knobs(INPLACE_TICKET=t)
+        check_inplace(label, scratch=True); n += 1
+        print("ok", label, flush=True)
     label = set_knobs()
     check_score(label); check_gather(label); check_inplace(label); check_inplace(label, scratch=True); check_step(label)
     print(f"ALL OK: {n} override settings", flush=True)
