@@ -222,7 +222,18 @@ __device__ __forceinline__ void load_to_lds(const char* g, char* lds_block)
 constexpr int FK = 32;
 constexpr int kFastRow = FK * 2;                       // 64 bytes per tile row
 
-// wait for all but the n youngest vector-memory operations and for every LDS operation, then barrier
+// Wait until at most N vector-memory operations of this wave are outstanding and every LDS operation is done, then
+// barrier.  What the callers rely on, and what an edit must keep:
+//  * vmcnt counts every vector-memory instruction of the wave (tile loads into LDS, the warm-up touches, stores) and
+//    loads complete in issue order, so "at most N outstanding" means "everything but the N youngest has landed".
+//  * N is therefore the number of vector-memory instructions the wave has issued AFTER the last load of the stage
+//    it is about to read.  Every wave issues exactly kLpw tile loads per stage, unconditionally (rows past the end
+//    of a tile load a clamped address), so that number is a compile-time constant.
+//  * An extra instruction issued in between (the warm-up touch is one) makes the wait stricter by one, never
+//    weaker: it is always safe to add one.  Dropping a load, or making one conditional per wave, is not: the
+//    constant would then let a needed load count among the "youngest N" while still in flight.
+//  * The barrier sits behind the wait, so a wave passes it only after its own share of the stage has landed, and
+//    all waves have passed it before any reads the stage.
 template <int N>
 __device__ __forceinline__ void wait_barrier()
 {
@@ -348,6 +359,7 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
         for (int j = 0; j < Cfg::kLpw; ++j) issue_load(st, st, j);
 #pragma unroll
     for (int j = 0; j < Cfg::kLpw - kHalf; ++j) issue_load(RING - 1, RING - 1, j);
+    // issued so far: RING * kLpw - kHalf loads, stage 0's kLpw first: all but the rest may stay in flight
     wait_barrier<(RING - 1) * Cfg::kLpw - kHalf>();        // stage 0 landed (the others may be in flight)
 #pragma unroll
     for (int i = 0; i < NVB + NTB; ++i) read_frag(lds, 0, 0, i);
@@ -388,6 +400,8 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
         const char* cur = lds + bcur * Cfg::kStage;
         const char* nxt = lds + bnext * Cfg::kStage;
         slice(0, cur, 1, ks + RING - 1, blast, Cfg::kLpw - kHalf, kHalf);
+        // issued after stage ks + 1: stages ks + 2 .. ks + RING - 1 whole = (RING - 2) * kLpw loads (plus, for one
+        // wave in four iterations, the touch below: a stricter wait, see wait_barrier)
         wait_barrier<(RING - 2) * Cfg::kLpw>();            // stage ks + 1 landed; all reads of stage ks done
         // (right after a wait: the touch has three stages to come back before a younger load is waited for)
         if (WARM && kstart == 0 && (ks & 3) == 0 && ((ks >> 2) & 3) == swave) warm(ks + 12);

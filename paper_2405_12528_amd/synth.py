@@ -64,10 +64,11 @@ class Workload:
         return 4 if self.kv_dtype == "f32" else 2
 
     def algorithmic_bytes(self) -> dict:
-        """Bytes one step must move: each logit read once, ids and scores touched once, each
-        kept K/V row read once and written once (nothing for the rows that are dropped)."""
+        """Bytes one step must move: each logit read once, one 4-byte score per new token, the held scores
+        read once, index and score of every kept slot written once, each kept K/V row read once and written
+        once (nothing for the rows that are dropped).  The 4-byte token ids are not counted."""
         rows = self.n_streams * self.n_new
-        score = rows * self.vocab * self.logit_bytes + 8 * rows
+        score = rows * self.vocab * self.logit_bytes + 4 * rows
         select = self.n_streams * (4 * self.n_held + 8 * self.n_keep)
         per_slot = self.n_layers * 2 * self.n_kv_heads * self.head_dim * self.kv_elem_bytes
         compact = 2 * self.n_streams * self.n_keep * per_slot if self.n_cand > self.budget else 0
