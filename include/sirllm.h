@@ -328,10 +328,13 @@ size_t sirllm_step_lmhead_workspace_bytes(int32_t n_streams, int32_t n_cand, int
  *                                Top_k, and scoring and selection share one launch.
  *   k, v, layout                 caches holding n_cand[s] slots of stream s (new tokens already appended);
  *                                rewritten in place as by sirllm_compact_kv_inplace.  v may be NULL.
- * scores_stride >= max_cand; idx_stride, out_stride >= min(max_cand, budget).  max_cand <= 32768 (every stream is
- * selected by one workgroup), else SIRLLM_ERR_UNSUPPORTED.
- * workspace: optional (NULL accepted), 256-byte aligned.  With at least SIRLLM_INPLACE_WORKSPACE_BYTES the
- * compaction takes its planes in ticket order, as described at sirllm_compact_kv_inplace.
+ * scores_stride >= max_cand; idx_stride, out_stride >= min(max_cand, budget).  max_cand <= SIRLLM_MAX_CAND, else
+ * SIRLLM_ERR_UNSUPPORTED.
+ * workspace: 256-byte aligned.  Up to max_cand = 32768 every stream is selected by one workgroup and the workspace
+ * is optional (NULL accepted); with at least SIRLLM_INPLACE_WORKSPACE_BYTES the compaction takes its planes in
+ * ticket order, as described at sirllm_compact_kv_inplace.  Above 32768 the streams are selected by the
+ * multi-workgroup kernels and sirllm_workspace_bytes(n_streams, max_cand, 0, 0) bytes are required
+ * (SIRLLM_ERR_WORKSPACE otherwise); the compaction reuses them for its ticket.
  */
 int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld,
                        const int32_t* token_ids,
@@ -343,6 +346,28 @@ int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64
                        int32_t* kept_idx, int64_t idx_stride,
                        float* scores_out, int64_t out_stride, int32_t* n_keep_out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * sirllm_step_ragged with its scores taken straight from the LM head (Alg. 1 per stream; Sec. 3.2): the rows of
+ * `hidden` / `token_ids` of stream s are [cu_new[s], cu_new[s+1]), the score of its token t is written to
+ * scores[s*scores_stride + n_held[s] + t], and everything behind the scores is sirllm_step_ragged's.  Operands
+ * and their limits as for sirllm_lmhead_score; sizes, bounds, flags and in-place compaction as for
+ * sirllm_step_ragged.  workspace: required, 256-byte aligned, at least
+ * sirllm_step_lmhead_ragged_workspace_bytes(n_streams, max_cand, total_new, vocab) bytes (the LM head's per-tile
+ * triples, then the selection's scratch or the compaction's ticket).
+ */
+int sirllm_step_lmhead_ragged(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w,
+                              sirllm_dtype dt, int32_t d_model, int32_t vocab, const int32_t* token_ids,
+                              float* scores, int64_t scores_stride,
+                              int32_t n_streams, const int32_t* n_held, const int32_t* cu_new,
+                              int64_t total_new, int32_t max_cand, int32_t max_new,
+                              const sirllm_policy* policy,
+                              void* k, void* v, const sirllm_kv_layout* layout,
+                              int32_t* kept_idx, int64_t idx_stride,
+                              float* scores_out, int64_t out_stride, int32_t* n_keep_out,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t sirllm_step_lmhead_ragged_workspace_bytes(int32_t n_streams, int32_t max_cand, int64_t total_new,
+                                                 int32_t vocab);
 
 /*
  * Baseline retention policies on the same compaction path (Sec. 4.1 "Baselines"): they pick the
@@ -362,7 +387,10 @@ int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64
  *                             and the n_topk largest keys are kept (equal keys: lower slot).
  * When n_cand <= the kept count nothing is evicted: kept_idx = 0..n_cand-1.
  * Returns, through *n_keep_out (host pointer, may be NULL), the number of kept slots per stream.
- * Limits as for sirllm_decay_select; SIRLLM_BASELINE_RANDOM takes at most 32768 slots per stream.
+ * Limits as for sirllm_decay_select.  workspace: only SIRLLM_BASELINE_RANDOM with more than 32768 slots per
+ * stream uses it (the multi-workgroup selection on the generator's draws) and then needs
+ * sirllm_workspace_bytes(n_streams, n_cand, 0, 0) bytes, 256-byte aligned (SIRLLM_ERR_WORKSPACE otherwise);
+ * everywhere else NULL / 0 is accepted.
  */
 typedef enum {
     SIRLLM_BASELINE_STREAM   = 0,
@@ -373,7 +401,7 @@ typedef enum {
 int sirllm_baseline_select(sirllm_baseline kind, int32_t n_streams, int32_t n_cand,
                            const sirllm_policy* policy, uint64_t seed, uint64_t turn,
                            int32_t* kept_idx, int64_t idx_stride, int32_t* n_keep_out,
-                           void* hip_stream);
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Bytes of device workspace the calls above need for these sizes (pass 0 for the sizes a
  * call does not have): 0 unless n_cand exceeds 32768, then about 4 KB + n_cand/1024 bytes per stream.

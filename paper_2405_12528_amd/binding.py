@@ -49,7 +49,8 @@ SIRLLM_INPLACE_WORKSPACE_BYTES = 256
 EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_decay_select_static", "sirllm_compact_kv", "sirllm_step", "sirllm_baseline_select",
            "sirllm_compact_kv_inplace", "sirllm_step_ragged", "sirllm_score_partial",
            "sirllm_score_merge", "sirllm_lmhead_score", "sirllm_lmhead_workspace_bytes",
-           "sirllm_step_lmhead", "sirllm_step_lmhead_workspace_bytes", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
+           "sirllm_step_lmhead", "sirllm_step_lmhead_workspace_bytes", "sirllm_step_lmhead_ragged",
+           "sirllm_step_lmhead_ragged_workspace_bytes", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
 
 _vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
 _PP, _LP = C.POINTER(sirllm_policy), C.POINTER(sirllm_kv_layout)
@@ -61,7 +62,7 @@ _lib.sirllm_compact_kv.argtypes = [_vp, _vp, _LP, _i32, _vp, _vp, _LP, _vp, _i64
 _lib.sirllm_step.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _i32, _i32, _PP,
                              _vp, _vp, _LP, _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _sz, _vp]
 _lib.sirllm_baseline_select.argtypes = [C.c_int, _i32, _i32, _PP, C.c_uint64, C.c_uint64, _vp, _i64,
-                                        C.POINTER(C.c_int32), _vp]
+                                        C.POINTER(C.c_int32), _vp, _sz, _vp]
 _lib.sirllm_baseline_select.restype = C.c_int
 _lib.sirllm_compact_kv_inplace.argtypes = [_vp, _vp, _LP, _i32, _vp, _i64, _i32, _i32, _vp, _sz, _vp]
 _lib.sirllm_compact_kv_inplace.restype = C.c_int
@@ -81,6 +82,11 @@ _lib.sirllm_step_lmhead.argtypes = [_vp, _i64, _vp, _i64, C.c_int, _i32, _i32, _
 _lib.sirllm_step_lmhead.restype = C.c_int
 _lib.sirllm_step_lmhead_workspace_bytes.argtypes = [_i32, _i32, _i64, _i32]
 _lib.sirllm_step_lmhead_workspace_bytes.restype = _sz
+_lib.sirllm_step_lmhead_ragged.argtypes = [_vp, _i64, _vp, _i64, C.c_int, _i32, _i32, _vp, _vp, _i64, _i32, _vp, _vp, _i64,
+                                           _i32, _i32, _PP, _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _vp]
+_lib.sirllm_step_lmhead_ragged.restype = C.c_int
+_lib.sirllm_step_lmhead_ragged_workspace_bytes.argtypes = [_i32, _i32, _i64, _i32]
+_lib.sirllm_step_lmhead_ragged_workspace_bytes.restype = _sz
 for _n in ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step"):
     getattr(_lib, _n).restype = C.c_int
 _lib.sirllm_workspace_bytes.argtypes = [_i32, _i32, _i64, _i32]
@@ -252,15 +258,17 @@ def sirllm_decay_select_static(scores: torch.Tensor, n_held: int, n_new: int, po
 
 
 def sirllm_baseline_select(kind: int, n_cand: int, policy, kept_idx: torch.Tensor, seed: int = 0, turn: int = 0,
-                           stream=None) -> int:
-    """Kept slots of a score-free baseline policy for n_streams = kept_idx.shape[0] streams; returns n_keep."""
-    _on_device(kept_idx)
+                           workspace: torch.Tensor | None = None, stream=None) -> int:
+    """Kept slots of a score-free baseline policy for n_streams = kept_idx.shape[0] streams; returns n_keep.
+    workspace: only the random policy above 32768 slots per stream needs one (sirllm_workspace_bytes)."""
+    _on_device(kept_idx, workspace)
     if kept_idx.dim() != 2 or kept_idx.dtype != torch.int32 or (kept_idx.shape[1] > 1 and kept_idx.stride(1) != 1):
         raise ValueError("kept_idx must be [n_streams, >= n_keep] int32 with contiguous rows")
     p = _policy(policy)
     n_keep = C.c_int32(-1)
     _check(_lib.sirllm_baseline_select(int(kind), kept_idx.shape[0], int(n_cand), C.byref(p), int(seed), int(turn),
-                                       _ptr(kept_idx), _row_stride(kept_idx), C.byref(n_keep), _stream(stream)),
+                                       _ptr(kept_idx), _row_stride(kept_idx), C.byref(n_keep), *_ws(workspace),
+                                       _stream(stream)),
            "sirllm_baseline_select")
     return n_keep.value
 
@@ -447,6 +455,55 @@ def sirllm_step_ragged(logits: torch.Tensor, token_ids: torch.Tensor, vocab: int
                                    _ptr(k), _ptr(v), C.byref(lay), _ptr(kept_idx), _row_stride(kept_idx),
                                    _ptr(scores_out), _row_stride(scores_out), _ptr(n_keep_out), wp, wb,
                                    _stream(stream)), "sirllm_step_ragged")
+
+
+def sirllm_step_lmhead_ragged_workspace_bytes(n_streams: int, max_cand: int, total_new: int, vocab: int) -> int:
+    return int(_lib.sirllm_step_lmhead_ragged_workspace_bytes(n_streams, max_cand, total_new, vocab))
+
+
+def sirllm_step_lmhead_ragged(hidden: torch.Tensor, weight: torch.Tensor, token_ids: torch.Tensor, scores: torch.Tensor,
+                              n_held: torch.Tensor, cu_new: torch.Tensor, total_new: int, max_cand: int, policy,
+                              k: torch.Tensor, v, kept_idx: torch.Tensor, scores_out: torch.Tensor,
+                              n_keep_out: torch.Tensor, workspace: torch.Tensor, max_new: int | None = None,
+                              d_model: int | None = None, vocab: int | None = None, stream=None) -> None:
+    """sirllm_step_ragged with the scores taken from hidden [total_new, ld_h] and weight [>= vocab, ld_w] (bf16 or
+    f16) instead of stored logits."""
+    _on_device(hidden, weight, token_ids, scores, n_held, cu_new, k, v, kept_idx, scores_out, n_keep_out, workspace)
+    n_streams = scores.shape[0]
+    for t, n in ((n_held, n_streams), (cu_new, n_streams + 1), (n_keep_out, n_streams)):
+        if t.dtype != torch.int32 or t.dim() != 1 or t.numel() != n or not t.is_contiguous():
+            raise ValueError("n_held [S], cu_new [S+1], n_keep_out [S] must be contiguous int32 device vectors")
+    for t in (hidden, weight):
+        if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise ValueError("hidden / weight must be 2-D with contiguous rows")
+    if hidden.dtype != weight.dtype:
+        raise TypeError("hidden and weight must have the same element type")
+    if hidden.shape[0] != total_new or token_ids.numel() != total_new:
+        raise ValueError("one hidden-state row and one token id per new token")
+    if token_ids.dtype != torch.int32 or not token_ids.is_contiguous():
+        raise TypeError("token_ids must be contiguous int32")
+    for t, dt in ((scores, torch.float32), (kept_idx, torch.int32), (scores_out, torch.float32)):
+        if t.dim() != 2 or t.dtype != dt or (t.shape[1] > 1 and t.stride(1) != 1) or t.shape[0] != n_streams:
+            raise ValueError("scores / kept_idx / scores_out must be [n_streams, n] with contiguous rows")
+    d_model = min(hidden.shape[1], weight.shape[1]) if d_model is None else int(d_model)
+    vocab = weight.shape[0] if vocab is None else int(vocab)
+    if vocab > weight.shape[0] or d_model > hidden.shape[1] or d_model > weight.shape[1]:
+        raise ValueError("vocab / d_model exceed the arrays")
+    lay = kv_layout(k)
+    if v is not None and kv_layout_tuple(v) != kv_layout_tuple(k):
+        raise ValueError("K and V must share one layout")
+    if k.shape[0] != n_streams or k.shape[3] < max_cand:
+        raise ValueError("the cache must hold max_cand slots for every stream")
+    p = _policy(policy)
+    wp, wb = _ws(workspace)
+    _check(_lib.sirllm_step_lmhead_ragged(_ptr(hidden) if total_new else None, _row_stride(hidden), _ptr(weight),
+                                          _row_stride(weight), _dtype_code(hidden), d_model, vocab,
+                                          _ptr(token_ids) if total_new else None, _ptr(scores), _row_stride(scores),
+                                          n_streams, _ptr(n_held), _ptr(cu_new), int(total_new), int(max_cand),
+                                          int(min(total_new, max_cand) if max_new is None else max_new), C.byref(p),
+                                          _ptr(k), _ptr(v), C.byref(lay), _ptr(kept_idx), _row_stride(kept_idx),
+                                          _ptr(scores_out), _row_stride(scores_out), _ptr(n_keep_out), wp, wb,
+                                          _stream(stream)), "sirllm_step_lmhead_ragged")
 
 
 def sirllm_score_partial(logits_chunk: torch.Tensor, v_begin: int, token_ids: torch.Tensor, partial: torch.Tensor,

@@ -115,9 +115,6 @@ class RaggedRetentiveCache:
         self.policy = b.Policy(*policy)
         self.budget = self.policy.n_sink + self.policy.n_topk + self.policy.n_recent
         self.capacity = self.budget + max_new
-        if self.capacity > b.SIRLLM_SINGLE_WG_CAND:
-            raise ValueError(f"budget + max_new = {self.capacity} exceeds the ragged path's limit of "
-                             f"{b.SIRLLM_SINGLE_WG_CAND} slots per stream")
         self.n_streams, self.max_new, self.device = n_streams, max_new, device
         shape = (n_streams, n_layers, n_kv_heads, self.capacity, head_dim)
         self.k = torch.zeros(shape, dtype=kv_dtype, device=device)
@@ -127,10 +124,12 @@ class RaggedRetentiveCache:
         self.kept_idx = torch.zeros((n_streams, self.capacity), dtype=torch.int32, device=device)
         self._cur = 0
         self.n_held = [0] * n_streams                  # host mirror
-        # the in-place compaction's ticket counter lives in the workspace
+        # the multi-workgroup selection's scratch (above 32768 slots per stream) and the in-place compaction's
+        # ticket counter live in the workspace
         nbytes = max(b.sirllm_workspace_bytes(n_streams, self.capacity, n_streams * max_new, 1 << 20),
                      b.SIRLLM_INPLACE_WORKSPACE_BYTES)
         self._ws = torch.zeros(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+        self._lm_ws = None                             # sized on the first step_from_hidden
 
     @property
     def scores(self) -> torch.Tensor:
@@ -158,6 +157,28 @@ class RaggedRetentiveCache:
                              max_cand, self.policy, self.k, self.v, self.kept_idx, self._scores[oth],
                              self._held_dev[oth], max_new=max(int(n) for n in n_new), workspace=self._ws,
                              stream=stream)
+        self._cur = oth
+        evicted = [h + int(n) > self.budget for h, n in zip(self.n_held, n_new)]
+        self.n_held = [min(h + int(n), self.budget) for h, n in zip(self.n_held, n_new)]
+        return evicted
+
+    def step_from_hidden(self, hidden: torch.Tensor, weight: torch.Tensor, token_ids: torch.Tensor, n_new, stream=None):
+        """step() with the scores taken straight from the final hidden states [sum(n_new), d_model] (rows concatenated
+        stream by stream) and the output embedding matrix [vocab, d_model] (bf16 or f16): no logits are stored."""
+        if len(n_new) != self.n_streams or max(n_new) > self.max_new or min(n_new) < 0:
+            raise ValueError("n_new must give 0..max_new tokens for every stream")
+        cu = [0]
+        for n in n_new:
+            cu.append(cu[-1] + int(n))
+        cu_dev = torch.tensor(cu, dtype=torch.int32, device=self.device)
+        max_cand = max(h + int(n) for h, n in zip(self.n_held, n_new))
+        need = b.sirllm_step_lmhead_ragged_workspace_bytes(self.n_streams, max_cand, cu[-1], weight.shape[0])
+        if self._lm_ws is None or self._lm_ws.numel() < need:
+            self._lm_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        cur, oth = self._cur, 1 - self._cur
+        b.sirllm_step_lmhead_ragged(hidden, weight, token_ids, self._scores[cur], self._held_dev[cur], cu_dev, cu[-1],
+                                    max_cand, self.policy, self.k, self.v, self.kept_idx, self._scores[oth],
+                                    self._held_dev[oth], self._lm_ws, max_new=max(int(n) for n in n_new), stream=stream)
         self._cur = oth
         evicted = [h + int(n) > self.budget for h, n in zip(self.n_held, n_new)]
         self.n_held = [min(h + int(n), self.budget) for h, n in zip(self.n_held, n_new)]

@@ -385,7 +385,7 @@ int sirllm_decay_select_static(const float* scores, int64_t scores_stride, int32
 
 int sirllm_baseline_select(sirllm_baseline kind, int32_t n_streams, int32_t n_cand, const sirllm_policy* policy,
                            uint64_t seed, uint64_t turn, int32_t* kept_idx, int64_t idx_stride,
-                           int32_t* n_keep_out, void* hip_stream)
+                           int32_t* n_keep_out, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (kind != SIRLLM_BASELINE_STREAM && kind != SIRLLM_BASELINE_INTERVAL && kind != SIRLLM_BASELINE_RANDOM)
         return SIRLLM_ERR_UNSUPPORTED;
@@ -406,8 +406,11 @@ int sirllm_baseline_select(sirllm_baseline kind, int32_t n_streams, int32_t n_ca
     hipStream_t stream = (hipStream_t)hip_stream;
     if ((int64_t)n_cand <= budget) return hip_status(launch_baseline_comb(a, 0, stream));
     if (kind == SIRLLM_BASELINE_RANDOM && p.n_topk > 0) {
-        if (n_cand > SIRLLM_SINGLE_WG_CAND) return SIRLLM_ERR_UNSUPPORTED;   // the random subset is drawn by one workgroup
-        return hip_status(launch_baseline_random(a, stream));
+        if (n_cand <= SIRLLM_SINGLE_WG_CAND) return hip_status(launch_baseline_random(a, stream));
+        // more slots than one workgroup holds: the multi-workgroup selection on the generator's draws
+        const int rc = workspace_check(workspace, workspace_bytes, sirllm_workspace_bytes(n_streams, n_cand, 0, 0));
+        if (rc) return rc;
+        return hip_status(launch_select_large(a, workspace, stream, true));
     }
     int interval = 1;
     if (p.n_topk > 0) {
@@ -555,19 +558,17 @@ int sirllm_step_lmhead(const void* hidden, int64_t ld_h, const void* weight, int
     return hip_status(launch_gather(g, 0, n_keep, stream));
 }
 
-int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
-                       float* scores, int64_t scores_stride, int32_t n_streams, const int32_t* n_held,
-                       const int32_t* cu_new, int64_t total_new, int32_t max_cand, int32_t max_new,
-                       const sirllm_policy* policy,
-                       void* k, void* v, const sirllm_kv_layout* layout, int32_t* kept_idx, int64_t idx_stride,
-                       float* scores_out, int64_t out_stride, int32_t* n_keep_out, void* workspace,
-                       size_t workspace_bytes, void* hip_stream)
+namespace {
+
+// What sirllm_step_ragged and sirllm_step_lmhead_ragged share: the checks of everything but the scoring operands ...
+int validate_ragged(float* scores, int64_t scores_stride, int32_t n_streams, const int32_t* n_held,
+                    const int32_t* cu_new, int64_t total_new, int32_t max_cand, int32_t max_new,
+                    const sirllm_policy* policy, void* k, void* v, const sirllm_kv_layout* layout, int32_t* kept_idx,
+                    int64_t idx_stride, float* scores_out, int64_t out_stride, int32_t* n_keep_out)
 {
     if (n_streams < 0 || total_new < 0 || max_cand < 0 || max_new < 0 || max_new > max_cand) return SIRLLM_ERR_INVALID_ARG;
-    int rc = validate_score(logits, dt, total_new, vocab, ld, token_ids);
-    if (rc) return rc;
     if (!policy_ok(policy)) return SIRLLM_ERR_INVALID_ARG;
-    if (max_cand > SIRLLM_SINGLE_WG_CAND) return SIRLLM_ERR_UNSUPPORTED;   // ragged streams are selected by one workgroup each
+    if (max_cand > SIRLLM_MAX_CAND) return SIRLLM_ERR_UNSUPPORTED;
     if (n_streams == 0) return SIRLLM_OK;
     if (!n_held || !cu_new || !n_keep_out || !scores || !kept_idx || !scores_out) return SIRLLM_ERR_INVALID_ARG;
     const int64_t budget = budget_of(policy);
@@ -576,8 +577,7 @@ int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64
     if (ranges_overlap(scores, ((int64_t)(n_streams - 1) * scores_stride + max_cand) * 4,
                        scores_out, ((int64_t)(n_streams - 1) * out_stride + keep_bound) * 4))
         return SIRLLM_ERR_INVALID_ARG;
-    const bool may_evict = max_cand > budget;
-    if (may_evict) {
+    if (max_cand > budget) {
         if (!layout_ok(layout) || !k) return SIRLLM_ERR_INVALID_ARG;
         if ((int64_t)layout->head_dim * layout->elem_bytes * budget > 0x7fff0000LL) return SIRLLM_ERR_UNSUPPORTED;
         const uintptr_t em = (uintptr_t)layout->elem_bytes - 1;
@@ -585,10 +585,58 @@ int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64
         if (ranges_overlap(k, extent_bytes(layout, n_streams, max_cand), v, extent_bytes(layout, n_streams, max_cand)))
             return SIRLLM_ERR_INVALID_ARG;
     }
+    return SIRLLM_OK;
+}
+
+SelectArgs make_ragged_select_args(float* scores, int64_t scores_stride, int32_t n_streams, const int32_t* n_held,
+                                   const int32_t* cu_new, int32_t max_cand, int32_t max_new, const sirllm_policy* policy,
+                                   int32_t* kept_idx, int64_t idx_stride, float* scores_out, int64_t out_stride,
+                                   int32_t* n_keep_out)
+{
+    SelectArgs s = make_select_args(scores, scores_stride, n_streams, 0, max_cand, policy, kept_idx, idx_stride,
+                                    scores_out, out_stride);
+    s.held_dev = n_held; s.cu_new_dev = cu_new; s.n_keep_dev = n_keep_out; s.max_new = max_new;
+    return s;
+}
+
+// ... and the part behind the scores: E <- E * eta, Id, E <- E[Id] per stream, then KV <- KV[Id] in place.
+// `scratch` is the selection's scratch when a stream may hold more slots than one workgroup selects (then required
+// and already checked), and the in-place compaction's ticket afterwards (stream order keeps the two uses apart).
+int ragged_select_compact(const SelectArgs& s, int32_t max_cand, const sirllm_policy* policy, void* k, void* v,
+                          const sirllm_kv_layout* layout, void* scratch, size_t scratch_bytes, hipStream_t stream)
+{
+    int rc = hip_status(max_cand > SIRLLM_SINGLE_WG_CAND ? launch_select_large(s, scratch, stream)
+                                                          : launch_select_ragged(s, stream));
+    const int64_t budget = budget_of(policy);
+    if (rc || max_cand <= budget) return rc;
+    const GatherArgs g = make_gather_args(k, v, layout, max_cand, k, v, layout, s.kept_idx, s.idx_stride, s.n_streams,
+                                          (int32_t)budget);
+    // with a workspace the compacting workgroups take their planes in ticket order
+    return hip_status(launch_gather_inplace_ragged(g, s.held_dev, s.cu_new_dev, s.n_keep_dev, (int32_t)budget, scratch,
+                                                   scratch ? scratch_bytes : 0, stream));
+}
+
+}  // namespace
+
+int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
+                       float* scores, int64_t scores_stride, int32_t n_streams, const int32_t* n_held,
+                       const int32_t* cu_new, int64_t total_new, int32_t max_cand, int32_t max_new,
+                       const sirllm_policy* policy,
+                       void* k, void* v, const sirllm_kv_layout* layout, int32_t* kept_idx, int64_t idx_stride,
+                       float* scores_out, int64_t out_stride, int32_t* n_keep_out, void* workspace,
+                       size_t workspace_bytes, void* hip_stream)
+{
+    if (total_new < 0) return SIRLLM_ERR_INVALID_ARG;
+    int rc = validate_score(logits, dt, total_new, vocab, ld, token_ids);
+    if (rc) return rc;
+    rc = validate_ragged(scores, scores_stride, n_streams, n_held, cu_new, total_new, max_cand, max_new, policy, k, v,
+                         layout, kept_idx, idx_stride, scores_out, out_stride, n_keep_out);
+    if (rc || n_streams == 0) return rc;
     rc = workspace_check(workspace, workspace_bytes, sirllm_workspace_bytes(n_streams, max_cand, total_new, vocab));
     if (rc) return rc;
     if (workspace && ((uintptr_t)workspace & (kWorkspaceAlign - 1)) != 0) return SIRLLM_ERR_WORKSPACE;
     hipStream_t stream = (hipStream_t)hip_stream;
+    const int64_t budget = budget_of(policy);
 
     ScoreArgs a;
     a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
@@ -596,26 +644,63 @@ int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64
     a.out_a = scores; a.stride_a = scores_stride; a.out_b = nullptr; a.stride_b = 0;
     a.partial = nullptr; a.v_begin = 0;
     a.cu_rows = cu_new; a.held_dev = n_held; a.n_streams_r = n_streams; a.budget_r = (int32_t)(budget < 0x7fffffff ? budget : 0x7fffffff);
-    SelectArgs s = make_select_args(scores, scores_stride, n_streams, 0, max_cand, policy, kept_idx, idx_stride,
-                                    scores_out, out_stride);
-    s.held_dev = n_held; s.cu_new_dev = cu_new; s.n_keep_dev = n_keep_out; s.max_new = max_new;
+    const SelectArgs s = make_ragged_select_args(scores, scores_stride, n_streams, n_held, cu_new, max_cand, max_new,
+                                                 policy, kept_idx, idx_stride, scores_out, out_stride, n_keep_out);
     if (score_select_ragged_fusable(a, s)) {
         // no stream brings more new tokens than the recent window holds: score and select in one launch
         a.out_b = scores_out; a.stride_b = out_stride;
         rc = hip_status(launch_score_select_ragged(a, s, dt, stream));
-    } else {
-        if (total_new > 0) {
-            rc = hip_status(launch_score(a, dt, stream));
-            if (rc) return rc;
-        }
-        rc = hip_status(launch_select_ragged(s, stream));
+        if (rc || max_cand <= budget) return rc;
+        const GatherArgs g = make_gather_args(k, v, layout, max_cand, k, v, layout, kept_idx, idx_stride, n_streams,
+                                              (int32_t)budget);
+        return hip_status(launch_gather_inplace_ragged(g, n_held, cu_new, n_keep_out, (int32_t)budget, workspace,
+                                                       workspace ? workspace_bytes : 0, stream));
     }
-    if (rc || !may_evict) return rc;
-    const GatherArgs g = make_gather_args(k, v, layout, max_cand, k, v, layout, kept_idx, idx_stride, n_streams,
-                                          (int32_t)budget);
-    // with a workspace the compacting workgroups take their planes in ticket order
-    return hip_status(launch_gather_inplace_ragged(g, n_held, cu_new, n_keep_out, (int32_t)budget, workspace,
-                                                   workspace ? workspace_bytes : 0, stream));
+    if (total_new > 0) {
+        rc = hip_status(launch_score(a, dt, stream));
+        if (rc) return rc;
+    }
+    return ragged_select_compact(s, max_cand, policy, k, v, layout, workspace, workspace_bytes, stream);
+}
+
+size_t sirllm_step_lmhead_ragged_workspace_bytes(int32_t n_streams, int32_t max_cand, int64_t total_new, int32_t vocab)
+{
+    const size_t sel = sirllm_workspace_bytes(n_streams, max_cand, 0, 0);
+    return sirllm_lmhead_workspace_bytes(total_new, vocab) +
+           (sel > (size_t)SIRLLM_INPLACE_WORKSPACE_BYTES ? sel : (size_t)SIRLLM_INPLACE_WORKSPACE_BYTES);
+}
+
+int sirllm_step_lmhead_ragged(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, sirllm_dtype dt,
+                              int32_t d_model, int32_t vocab, const int32_t* token_ids,
+                              float* scores, int64_t scores_stride, int32_t n_streams, const int32_t* n_held,
+                              const int32_t* cu_new, int64_t total_new, int32_t max_cand, int32_t max_new,
+                              const sirllm_policy* policy, void* k, void* v, const sirllm_kv_layout* layout,
+                              int32_t* kept_idx, int64_t idx_stride, float* scores_out, int64_t out_stride,
+                              int32_t* n_keep_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (total_new < 0) return SIRLLM_ERR_INVALID_ARG;
+    int rc = validate_lmhead(hidden, ld_h, weight, ld_w, dt, d_model, total_new, vocab, token_ids);
+    if (rc) return rc;
+    rc = validate_ragged(scores, scores_stride, n_streams, n_held, cu_new, total_new, max_cand, max_new, policy, k, v,
+                         layout, kept_idx, idx_stride, scores_out, out_stride, n_keep_out);
+    if (rc || n_streams == 0) return rc;
+    rc = workspace_check(workspace, workspace_bytes,
+                         sirllm_step_lmhead_ragged_workspace_bytes(n_streams, max_cand, total_new, vocab));
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const size_t lm_bytes = sirllm_lmhead_workspace_bytes(total_new, vocab);
+
+    // E_t = Entropy(new tokens) from z = h W^T; token t of stream s lands behind that stream's held scores
+    if (total_new > 0) {
+        const LmHeadArgs a = make_lmhead_args(hidden, ld_h, weight, ld_w, d_model, total_new, vocab, token_ids, workspace);
+        const LmHeadRagged rg = {cu_new, n_held, n_streams};
+        rc = hip_status(launch_lmhead_score(a, dt, scores, 1, scores_stride, stream, &rg));
+        if (rc) return rc;
+    }
+    const SelectArgs s = make_ragged_select_args(scores, scores_stride, n_streams, n_held, cu_new, max_cand, max_new,
+                                                 policy, kept_idx, idx_stride, scores_out, out_stride, n_keep_out);
+    return ragged_select_compact(s, max_cand, policy, k, v, layout, (char*)workspace + lm_bytes,
+                                 workspace_bytes - lm_bytes, stream);
 }
 
 }  // extern "C"

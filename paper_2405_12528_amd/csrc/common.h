@@ -91,9 +91,17 @@ struct LmHeadArgs {
 };
 // Upper bound on the number of vocabulary tiles (sets of triples in the scratch) for these sizes.
 int lmhead_tiles_vocab(int64_t n_rows, int32_t vocab);
+// Ragged batches: stream s owns rows [cu_rows[s], cu_rows[s+1]) and holds held_dev[s] slots already.
+struct LmHeadRagged {
+    const int32_t* cu_rows;   // device [n_streams + 1]
+    const int32_t* held_dev;  // device [n_streams]
+    int32_t n_streams;
+};
 // Row r is token r % rows_per_stream of stream r / rows_per_stream; its score goes to out[stream*out_stride + token].
+// With `ragged`, row r is token t = r - cu_rows[s] of the stream s that owns it and goes to
+// out[s*out_stride + held_dev[s] + t] (dropped when that lies outside [0, out_stride)).
 hipError_t launch_lmhead_score(const LmHeadArgs& a, sirllm_dtype dt, float* out, int64_t rows_per_stream,
-                               int64_t out_stride, hipStream_t stream);
+                               int64_t out_stride, hipStream_t stream, const LmHeadRagged* ragged = nullptr);
 
 // ---- select.hip -------------------------------------------------------------------------
 struct SelectArgs {
@@ -125,7 +133,9 @@ hipError_t launch_select_ragged(const SelectArgs& a, hipStream_t stream);
 // through the multi-workgroup path, which needs scratch.
 #define SIRLLM_SINGLE_WG_CAND 32768
 size_t select_large_scratch_bytes(int32_t n_streams, int32_t n_cand);
-hipError_t launch_select_large(const SelectArgs& a, void* scratch, hipStream_t stream);
+// Serves ragged batches too (a.held_dev set: per-stream sizes, a.n_cand the bound, a.n_keep_dev written), and with
+// random_keys the RandomLLM baseline (no score read or written).
+hipError_t launch_select_large(const SelectArgs& a, void* scratch, hipStream_t stream, bool random_keys = false);
 
 // ---- gather.hip -------------------------------------------------------------------------
 struct GatherArgs {

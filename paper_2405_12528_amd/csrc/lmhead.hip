@@ -415,10 +415,11 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
 // Folds the n_parts triples of every row: 4 rows per workgroup, 64 lanes per row striding over the parts (the
 // chain of dependent merges is n_parts / 64 long, then a shuffle tree inside each wave and one exchange through LDS).
 // Row `row` belongs to stream row / rows_per_stream and is its token t = row % rows_per_stream; the score goes
-// to out[stream * out_stride + t].
+// to out[stream * out_stride + t].  Ragged batches (rg.cu_rows not null): stream s owns rows
+// [cu_rows[s], cu_rows[s+1]) and its token t goes to out[s * out_stride + held_dev[s] + t].
 __global__ __launch_bounds__(256) void lmhead_merge_kernel(const float* partials, int n_parts, int64_t part_stride,
                                                            int64_t n_rows, float* out, int64_t rows_per_stream,
-                                                           int64_t out_stride)
+                                                           int64_t out_stride, LmHeadRagged rg)
 {
     constexpr int R = 4, PL = 256 / R;           // rows per workgroup, part lanes per row
     __shared__ float sm[4][R][3];
@@ -463,8 +464,20 @@ __global__ __launch_bounds__(256) void lmhead_merge_kernel(const float* partials
             const float z = sm[i][r][2];
             if (zt != zt && z == z) zt = z;
         }
-        const int64_t stream = row / rows_per_stream;
-        out[stream * out_stride + (row - stream * rows_per_stream)] = (acc.m - zt) + logf(acc.s);
+        const float e = (acc.m - zt) + logf(acc.s);
+        if (rg.cu_rows) {
+            int lo = 0, hi = rg.n_streams;                 // largest s with cu_rows[s] <= row
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if ((int64_t)rg.cu_rows[mid] <= row) lo = mid; else hi = mid;
+            }
+            const int64_t pos = (int64_t)rg.held_dev[lo] + (row - rg.cu_rows[lo]);
+            if (pos >= 0 && pos < out_stride)              // sizes the caller did not promise are dropped, not written
+                out[lo * out_stride + pos] = e;
+        } else {
+            const int64_t stream = row / rows_per_stream;
+            out[stream * out_stride + (row - stream * rows_per_stream)] = e;
+        }
     }
 }
 
@@ -551,14 +564,16 @@ int lmhead_tiles_vocab(int64_t n_rows, int32_t vocab)
 }
 
 hipError_t launch_lmhead_score(const LmHeadArgs& args, sirllm_dtype dt, float* out, int64_t rows_per_stream,
-                               int64_t out_stride, hipStream_t stream)
+                               int64_t out_stride, hipStream_t stream, const LmHeadRagged* ragged)
 {
+    LmHeadRagged rg = {nullptr, nullptr, 0};
+    if (ragged) rg = *ragged;
     if (args.n_rows <= 0) return hipSuccess;
     LmHeadArgs a = args;
     hipError_t e = dt == SIRLLM_BF16 ? launch_dtype<SIRLLM_BF16>(a, stream) : launch_dtype<SIRLLM_F16>(a, stream);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(lmhead_merge_kernel, dim3((unsigned)((a.n_rows + 3) / 4)), dim3(256), 0, stream,
-                       a.partial, a.n_vtiles, a.part_stride, a.n_rows, out, rows_per_stream > 0 ? rows_per_stream : 1, out_stride);
+                       a.partial, a.n_vtiles, a.part_stride, a.n_rows, out, rows_per_stream > 0 ? rows_per_stream : 1, out_stride, rg);
     return hipGetLastError();
 }
 

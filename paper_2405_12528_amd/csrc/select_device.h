@@ -249,14 +249,15 @@ template <int BLOCK, int KPT, bool NEW_ELSEWHERE>
 __device__ __forceinline__ void select_ragged_stream(const SelectArgs& a, int s, SelectSmem<BLOCK>& sm)
 {
     SelectArgs b = a;
-    b.n_held = a.held_dev[s];
-    const int n_new = a.cu_new_dev[s + 1] - a.cu_new_dev[s];
-    b.n_cand = b.n_held + n_new;
+    const int64_t held = a.held_dev[s];
+    const int64_t n_new = (int64_t)a.cu_new_dev[s + 1] - (int64_t)a.cu_new_dev[s];
+    const int64_t cand = held + n_new;                      // 64-bit: sizes that are garbage must not wrap into range
     const int budget = a.n_sink + a.n_topk + a.n_recent;
-    const bool fits = b.n_held >= 0 && n_new >= 0 && n_new <= a.max_new && b.n_cand <= a.n_cand &&
-                      b.n_cand <= BLOCK * KPT;
-    if (threadIdx.x == 0) a.n_keep_dev[s] = !fits ? -1 : (b.n_cand < budget ? b.n_cand : budget);
+    const bool fits = held >= 0 && n_new >= 0 && n_new <= a.max_new && cand <= a.n_cand && cand <= BLOCK * KPT;
+    if (threadIdx.x == 0) a.n_keep_dev[s] = !fits ? -1 : (int)(cand < budget ? cand : budget);
     if (!fits) return;                      // flagged, nothing written (uniform over the workgroup)
+    b.n_held = (int)held;
+    b.n_cand = (int)cand;
     if (b.n_cand <= budget) {
         const int n_read = NEW_ELSEWHERE ? b.n_held : b.n_cand;
         for (int i = threadIdx.x; i < b.n_cand; i += BLOCK) {

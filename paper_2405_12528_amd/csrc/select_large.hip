@@ -9,6 +9,9 @@
 //   scatter   prefix over the tiles before it + the in-tile prefix of the one-workgroup kernel give
 //             every kept slot its in-cache position
 // Kernel boundaries order the phases; nothing spins.  Latency bound (seven small launches).
+// The same launches serve ragged batches (every stream's own sizes are read from device memory; a stream within
+// its budget is only decayed, a stream beyond the promised bounds is flagged and left alone: Alg. 1 per stream) and
+// the RandomLLM baseline of Sec. 4.1 (the keys are then draws of Philox4x32-10, no score is read or written).
 #include "common.h"
 #include "select_device.h"
 
@@ -27,7 +30,29 @@ struct LargeArgs {
     uint32_t* ws;          // per stream: [4][256] histograms, then n_tiles x {greater, equal}
     int64_t ws_stride;     // uint32 words per stream
     int32_t n_tiles;
+    int32_t random_keys;   // keys are generator draws, not scores
 };
+
+// What a workgroup does for its stream.  Uniform batches: always the selection on the launch's sizes.
+enum StreamMode { kSelect = 0, kKeepAll = 1, kFlagged = 2 };
+struct StreamDims {
+    int n_held, n_cand, mode;
+};
+
+__device__ __forceinline__ StreamDims dims_of(const SelectArgs& a, int s)
+{
+    StreamDims d = {a.n_held, a.n_cand, kSelect};
+    if (a.held_dev) {
+        const int64_t held = a.held_dev[s];
+        const int64_t n_new = (int64_t)a.cu_new_dev[s + 1] - (int64_t)a.cu_new_dev[s];
+        const int64_t cand = held + n_new;
+        const bool fits = held >= 0 && n_new >= 0 && n_new <= a.max_new && cand <= a.n_cand;
+        d.n_held = fits ? (int)held : 0;
+        d.n_cand = fits ? (int)cand : 0;
+        d.mode = !fits ? kFlagged : (cand <= (int64_t)a.n_sink + a.n_topk + a.n_recent ? kKeepAll : kSelect);
+    }
+    return d;
+}
 
 struct ScanSmem {
     uint32_t wave_tot[kBlock / kWave];
@@ -66,11 +91,18 @@ __device__ __forceinline__ void derive_prefix(const uint32_t* hist, int n_passes
     }
 }
 
-__device__ __forceinline__ float decayed(const SelectArgs& a, const float* E, int i)
+// Slot i of a stream: its value (the decayed score; 0 for the random policy) and the key it is ranked by.
+__device__ __forceinline__ uint32_t slot_key(const LargeArgs& g, const float* E, int i, int n_held, int stream, float& val)
 {
+    if (g.random_keys) {
+        val = 0.0f;
+        return select_dev::philox4x32_10_word0((uint32_t)i, (uint32_t)stream, g.a.turn_lo, g.a.turn_hi, g.a.seed_lo,
+                                               g.a.seed_hi);
+    }
     float e = E[i];
-    if (i < a.n_held) e = __fmul_rn(e, a.decay);           // one rounded multiply, never fused
-    return e;
+    if (i < n_held) e = __fmul_rn(e, g.a.decay);           // one rounded multiply, never fused
+    val = e;
+    return order_key(e);
 }
 
 __global__ __launch_bounds__(256) void zero_kernel(LargeArgs g)
@@ -85,19 +117,22 @@ __global__ __launch_bounds__(kBlock) void hist_kernel(LargeArgs g, int pass)
     __shared__ uint32_t lh[256];
     const SelectArgs& a = g.a;
     const int tid = threadIdx.x, tile = blockIdx.x, stream = blockIdx.y;
+    const StreamDims d = dims_of(a, stream);
+    if (d.mode != kSelect || tile * kTile >= d.n_cand) return;      // uniform over the workgroup
     uint32_t* hist = g.ws + stream * g.ws_stride;
     uint32_t prefix, mask, k_rem;
     derive_prefix(hist, pass, (uint32_t)a.n_topk, sm, prefix, mask, k_rem);
     if (tid < 256) lh[tid] = 0u;
     __syncthreads();
     const float* E = a.scores + (int64_t)stream * a.scores_stride;
-    const int mid_lo = a.n_sink, mid_hi = a.n_cand - a.n_recent;
+    const int mid_lo = a.n_sink, mid_hi = d.n_cand - a.n_recent;
     const int shift = 24 - 8 * pass;
 #pragma unroll
     for (int q = 0; q < kKpt; ++q) {
         const int i = tile * kTile + q * kBlock + tid;     // coalesced: order does not matter for counting
         if (i >= mid_lo && i < mid_hi) {
-            const uint32_t key = order_key(decayed(a, E, i));
+            float val;
+            const uint32_t key = slot_key(g, E, i, d.n_held, stream, val);
             if ((key & mask) == prefix) atomicAdd(&lh[(key >> shift) & 255u], 1u);
         }
     }
@@ -112,17 +147,20 @@ __global__ __launch_bounds__(kBlock) void count_kernel(LargeArgs g)
     const SelectArgs& a = g.a;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int tile = blockIdx.x, stream = blockIdx.y;
+    const StreamDims d = dims_of(a, stream);
+    if (d.mode != kSelect || tile * kTile >= d.n_cand) return;      // its counts stay zero
     uint32_t* hist = g.ws + stream * g.ws_stride;
     uint32_t tau, mask, quota;
     derive_prefix(hist, 4, (uint32_t)a.n_topk, sm, tau, mask, quota);
     const float* E = a.scores + (int64_t)stream * a.scores_stride;
-    const int mid_lo = a.n_sink, mid_hi = a.n_cand - a.n_recent;
+    const int mid_lo = a.n_sink, mid_hi = d.n_cand - a.n_recent;
     uint32_t gt = 0u, eq = 0u;
 #pragma unroll
     for (int q = 0; q < kKpt; ++q) {
         const int i = tile * kTile + q * kBlock + tid;
         if (i >= mid_lo && i < mid_hi) {
-            const uint32_t key = order_key(decayed(a, E, i));
+            float val;
+            const uint32_t key = slot_key(g, E, i, d.n_held, stream, val);
             gt += key > tau;
             eq += key == tau;
         }
@@ -150,6 +188,22 @@ __global__ __launch_bounds__(kBlock) void scatter_kernel(LargeArgs g)
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     constexpr int NW = kBlock / kWave;
     const int tile = blockIdx.x, stream = blockIdx.y;
+    const StreamDims d = dims_of(a, stream);
+    const int budget = a.n_sink + a.n_topk + a.n_recent;
+    if (a.n_keep_dev && tile == 0 && tid == 0)
+        a.n_keep_dev[stream] = d.mode == kFlagged ? -1 : (d.n_cand < budget ? d.n_cand : budget);
+    if (d.mode == kFlagged || tile * kTile >= d.n_cand) return;
+    if (d.mode == kKeepAll) {                              // within the budget: identity list, E <- E * eta
+        for (int i = tile * kTile + tid; i < min(d.n_cand, (tile + 1) * kTile); i += kBlock) {
+            a.kept_idx[(int64_t)stream * a.idx_stride + i] = i;
+            if (!g.random_keys) {
+                float val;
+                slot_key(g, a.scores + (int64_t)stream * a.scores_stride, i, d.n_held, stream, val);
+                a.scores_out[(int64_t)stream * a.out_stride + i] = val;
+            }
+        }
+        return;
+    }
     uint32_t* hist = g.ws + stream * g.ws_stride;
     uint32_t tau, mask, quota;
     if (a.n_topk > 0) {
@@ -173,20 +227,22 @@ __global__ __launch_bounds__(kBlock) void scatter_kernel(LargeArgs g)
     __syncthreads();                                       // red is reused below
 
     // this tile: every lane owns kKpt consecutive slots, as in the one-workgroup kernel
-    const int n_cand = a.n_cand, mid_lo = a.n_sink, mid_hi = n_cand - a.n_recent;
-    const int n_keep = a.n_sink + a.n_topk + a.n_recent;
+    const int n_cand = d.n_cand, mid_lo = a.n_sink, mid_hi = n_cand - a.n_recent;
+    const int n_keep = budget;
     const float* E = a.scores + (int64_t)stream * a.scores_stride;
     const int i0 = tile * kTile + tid * kKpt;
     float val[kKpt];
+    uint32_t key[kKpt];
     uint32_t mg = 0u, me = 0u;
 #pragma unroll
     for (int q = 0; q < kKpt; ++q) {
         const int i = i0 + q;
-        val[q] = i < n_cand ? decayed(a, E, i) : 0.0f;
+        val[q] = 0.0f;
+        key[q] = 0u;
+        if (i < n_cand && (!g.random_keys || (i >= mid_lo && i < mid_hi))) key[q] = slot_key(g, E, i, d.n_held, stream, val[q]);
         if (i >= mid_lo && i < mid_hi) {
-            const uint32_t key = order_key(val[q]);
-            mg += key > tau;
-            me += key == tau;
+            mg += key[q] > tau;
+            me += key[q] == tau;
         }
     }
     const uint32_t ig = wave_inclusive_scan(mg), ie = wave_inclusive_scan(me);
@@ -209,16 +265,18 @@ __global__ __launch_bounds__(kBlock) void scatter_kernel(LargeArgs g)
         } else if (i >= mid_hi) {
             pos = n_keep - (n_cand - i);                        // Id_recent
         } else {
-            const uint32_t key = order_key(val[q]);
-            if (key > tau) {
+            if (key[q] > tau) {
                 pos = mid_lo + (int)(gt + (eq < quota ? eq : quota));
                 ++gt;
-            } else if (key == tau) {
+            } else if (key[q] == tau) {
                 if (eq < quota) pos = mid_lo + (int)(gt + eq);  // Id_entropy, ties to the lower slot
                 ++eq;
             }
         }
-        if (pos >= 0 && pos < n_keep) { idx[pos] = i; Eo[pos] = val[q]; }
+        if (pos >= 0 && pos < n_keep) {
+            idx[pos] = i;
+            if (!g.random_keys) Eo[pos] = val[q];
+        }
     }
 }
 
@@ -232,7 +290,7 @@ size_t select_large_scratch_bytes(int32_t n_streams, int32_t n_cand)
     return (size_t)(words * 4 * n_streams);
 }
 
-hipError_t launch_select_large(const SelectArgs& a, void* scratch, hipStream_t stream)
+hipError_t launch_select_large(const SelectArgs& a, void* scratch, hipStream_t stream, bool random_keys)
 {
     if (a.n_streams <= 0 || a.n_cand <= 0) return hipSuccess;
     LargeArgs g;
@@ -240,6 +298,7 @@ hipError_t launch_select_large(const SelectArgs& a, void* scratch, hipStream_t s
     g.n_tiles = (a.n_cand + kTile - 1) / kTile;
     g.ws = (uint32_t*)scratch;
     g.ws_stride = (1024 + 2 * (int64_t)g.n_tiles + 63) / 64 * 64;
+    g.random_keys = random_keys ? 1 : 0;
     if (g.n_tiles > 65535 || a.n_streams > 65535) return hipErrorInvalidValue;
     const dim3 grid((unsigned)g.n_tiles, (unsigned)a.n_streams), block(kBlock);
     hipLaunchKernelGGL(zero_kernel, dim3((unsigned)min((int64_t)1024, (a.n_streams * g.ws_stride + 255) / 256)), dim3(256), 0, stream, g);

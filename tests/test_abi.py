@@ -164,15 +164,20 @@ def test_baseline_select_argument_errors(b):
     L = b.raw()
     p = b.sirllm_policy(4, 20, 8, 0.0)
     n_keep = C.c_int32(-5)
-    def call(kind=1, n_streams=1, n_cand=100, pol=p, idx=FAKE, istr=32, out=n_keep):
+    def call(kind=1, n_streams=1, n_cand=100, pol=p, idx=FAKE, istr=32, out=n_keep, ws=None, ws_bytes=0):
         return L.sirllm_baseline_select(kind, n_streams, n_cand, C.byref(pol) if pol else None, 1, 2, idx, istr,
-                                        C.byref(out) if out is not None else None, None)
+                                        C.byref(out) if out is not None else None, ws, ws_bytes, None)
     assert call(kind=3) == b.SIRLLM_ERR_UNSUPPORTED
     assert call(pol=None) == b.SIRLLM_ERR_INVALID_ARG
     assert call(pol=b.sirllm_policy(4, -1, 8, 0.0)) == b.SIRLLM_ERR_INVALID_ARG
     assert call(n_cand=-1) == b.SIRLLM_ERR_INVALID_ARG
     assert call(n_cand=b.SIRLLM_MAX_CAND + 1) == b.SIRLLM_ERR_UNSUPPORTED
-    assert call(kind=2, n_cand=40000, istr=40000) == b.SIRLLM_ERR_UNSUPPORTED      # random subsets: one workgroup only
+    # random subsets of more slots than one workgroup holds need the selection's scratch
+    need = b.sirllm_workspace_bytes(1, 40000, 0, 0)
+    assert need > 0
+    assert call(kind=2, n_cand=40000, istr=40000) == b.SIRLLM_ERR_WORKSPACE
+    assert call(kind=2, n_cand=40000, istr=40000, ws=0x30000000, ws_bytes=need - 1) == b.SIRLLM_ERR_WORKSPACE
+    assert call(kind=2, n_cand=40000, istr=40000, ws=0x30000010, ws_bytes=need) == b.SIRLLM_ERR_WORKSPACE
     assert call(idx=None) == b.SIRLLM_ERR_INVALID_ARG
     assert call(istr=31) == b.SIRLLM_ERR_INVALID_ARG
     assert call(n_streams=0) == b.SIRLLM_OK and n_keep.value == 32       # the kept count is host arithmetic
@@ -200,15 +205,19 @@ def test_inplace_and_ragged_argument_errors(b):
     p = b.sirllm_policy(4, 20, 8, 0.9)
     def ragged(logits=0x1000, dt=0, vocab=1000, ld=1000, tok=0x2000000, scores=0x3000000, sstr=128, n_streams=2,
                held=0x7000000, cu=0x7100000, total=64, max_cand=100, max_new=64, pol=p, k=0x10000000, v=0x20000000,
-               l=lay, idx=0x5000000, istr=32, out=0x6000000, ostr=32, keep=0x7200000):
+               l=lay, idx=0x5000000, istr=32, out=0x6000000, ostr=32, keep=0x7200000, ws=None, ws_bytes=0):
         return L.sirllm_step_ragged(logits, dt, vocab, ld, tok, scores, sstr, n_streams, held, cu, total, max_cand,
                                     max_new, C.byref(pol) if pol else None, k, v, C.byref(l) if l else None, idx, istr, out,
-                                    ostr, keep, None, 0, None)
+                                    ostr, keep, ws, ws_bytes, None)
     assert ragged(dt=9) == b.SIRLLM_ERR_UNSUPPORTED
     assert ragged(total=-1) == b.SIRLLM_ERR_INVALID_ARG
     assert ragged(logits=None) == b.SIRLLM_ERR_INVALID_ARG
     assert ragged(pol=None) == b.SIRLLM_ERR_INVALID_ARG
-    assert ragged(max_cand=40000) == b.SIRLLM_ERR_UNSUPPORTED
+    assert ragged(max_cand=b.SIRLLM_MAX_CAND + 1, sstr=1 << 25) == b.SIRLLM_ERR_UNSUPPORTED
+    # above 32768 slots per stream the selection needs its scratch
+    assert ragged(max_cand=40000, sstr=40000) == b.SIRLLM_ERR_WORKSPACE
+    assert ragged(max_cand=40000, sstr=40000, ws=0x30000000, ws_bytes=b.sirllm_workspace_bytes(2, 40000, 0, 0) - 1) == b.SIRLLM_ERR_WORKSPACE
+    assert ragged(ws=0x30000001, ws_bytes=4096) == b.SIRLLM_ERR_WORKSPACE          # optional, but aligned when given
     assert ragged(max_new=-1) == b.SIRLLM_ERR_INVALID_ARG
     assert ragged(max_new=101) == b.SIRLLM_ERR_INVALID_ARG              # more new tokens than candidates
     assert ragged(held=None) == b.SIRLLM_ERR_INVALID_ARG
@@ -219,6 +228,32 @@ def test_inplace_and_ragged_argument_errors(b):
     assert ragged(k=None) == b.SIRLLM_ERR_INVALID_ARG                  # max_cand > budget: a cache is needed
     assert ragged(l=None) == b.SIRLLM_ERR_INVALID_ARG
     assert ragged(n_streams=0) == b.SIRLLM_OK
+
+    def lm_ragged(hidden=0x1000, ld_h=64, weight=0x8000000, ld_w=64, dt=1, d_model=64, vocab=1000, tok=0x2000000,
+                  scores=0x3000000, sstr=128, n_streams=2, held=0x7000000, cu=0x7100000, total=64, max_cand=100,
+                  max_new=64, pol=p, k=0x10000000, v=0x20000000, l=lay, idx=0x5000000, istr=32, out=0x6000000, ostr=32,
+                  keep=0x7200000, ws=0x30000000, ws_bytes=1 << 30):
+        return L.sirllm_step_lmhead_ragged(hidden, ld_h, weight, ld_w, dt, d_model, vocab, tok, scores, sstr, n_streams,
+                                           held, cu, total, max_cand, max_new, C.byref(pol) if pol else None, k, v,
+                                           C.byref(l) if l else None, idx, istr, out, ostr, keep, ws, ws_bytes, None)
+    need = b.sirllm_step_lmhead_ragged_workspace_bytes(2, 100, 64, 1000)
+    assert need == b.sirllm_lmhead_workspace_bytes(64, 1000) + b.SIRLLM_INPLACE_WORKSPACE_BYTES
+    assert b.sirllm_step_lmhead_ragged_workspace_bytes(2, 40000, 64, 1000) == \
+        b.sirllm_lmhead_workspace_bytes(64, 1000) + b.sirllm_workspace_bytes(2, 40000, 0, 0)
+    assert lm_ragged(dt=0) == b.SIRLLM_ERR_UNSUPPORTED                   # f32 operands
+    assert lm_ragged(d_model=60) == b.SIRLLM_ERR_UNSUPPORTED
+    assert lm_ragged(hidden=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged(total=-1) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged(pol=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged(max_new=101) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged(held=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged(keep=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged(sstr=99) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged(k=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged(ws=None) == b.SIRLLM_ERR_WORKSPACE
+    assert lm_ragged(ws_bytes=need - 1) == b.SIRLLM_ERR_WORKSPACE
+    assert lm_ragged(ws=0x30000010) == b.SIRLLM_ERR_WORKSPACE
+    assert lm_ragged(n_streams=0) == b.SIRLLM_OK
 
 
 def test_score_chunk_argument_errors(b):

@@ -23,14 +23,16 @@ def b():
     return binding
 
 
-def assert_scores_close(gpu: np.ndarray, want: np.ndarray):
+def assert_scores_close(gpu: np.ndarray, want: np.ndarray, atol: float = 1e-6):
+    """atol: 1e-6 for scores from stored logits; 2e-5 for scores from the LM head, whose logits are binary32 sums of
+    d_model products (derivation at the top of test_gpu_lmhead.py)."""
     nan_w, nan_g = np.isnan(want), np.isnan(gpu)
     np.testing.assert_array_equal(nan_g, nan_w)
     inf_w = np.isinf(want)
     np.testing.assert_array_equal(gpu[inf_w], want[inf_w])
     ok = ~(nan_w | inf_w)
     err = np.abs(gpu[ok].astype(np.float64) - want[ok].astype(np.float64))
-    tol = 1e-6 + 1e-5 * np.abs(want[ok].astype(np.float64))
+    tol = atol + 1e-5 * np.abs(want[ok].astype(np.float64))
     bad = err > tol
     assert not bad.any(), f"{bad.sum()} scores off; worst {err.max():.3e} (tolerance {tol[err.argmax()]:.3e})"
 
@@ -431,6 +433,10 @@ BASELINE_CASES = [
     # instance, 16385..32768 the 32-slot one
     (1, 8193, 4, 4000, 193), (2, 12000, 4, 6000, 500), (1, 16384, 4, 1, 0), (2, 12345, 0, 12000, 45),
     (1, 16385, 4, 8000, 384), (2, 26000, 4, 13000, 1000),
+    # above 32768 slots per stream the random policy goes through the multi-workgroup selection (tiles of 8192 slots):
+    # one slot past the limit, a ragged last tile, several streams, a 128K-slot cache, all-but-one and one kept
+    (1, 32769, 4, 16000, 68), (3, 40000, 4, 20000, 1000), (2, 133120, 4, 129020, 2048), (1, 50000, 0, 49999, 0),
+    (2, 70001, 4, 1, 0), (1, 65536, 4, 0, 100),
 ]
 
 
@@ -443,7 +449,11 @@ def test_baseline_select_matches_oracle(b, ref, kind, case):
     want = ref.baseline_select(kind, n_streams, n_cand, ref.Policy(*pol), seed=seed, turn=turn)
     n_keep = want.shape[1]
     idx = torch.full((n_streams, n_keep + 3), -7, dtype=torch.int32, device=DEV)
-    got_keep = b.sirllm_baseline_select(kind, n_cand, pol, idx, seed=seed, turn=turn)
+    # scratch is asked for above 32768 slots only; it arrives dirty, the call clears what it uses
+    nbytes = b.sirllm_workspace_bytes(n_streams, n_cand, 0, 0)
+    assert (nbytes > 0) == (n_cand > 32768)
+    ws = torch.full((nbytes,), 0x5a, dtype=torch.uint8, device=DEV) if nbytes else None
+    got_keep = b.sirllm_baseline_select(kind, n_cand, pol, idx, seed=seed, turn=turn, workspace=ws)
     torch.cuda.synchronize()
     assert got_keep == n_keep
     got = to_np(idx)
@@ -666,20 +676,25 @@ def test_compact_inplace_strided_view_and_bad_indices(b, ref):
 
 # ------------------------------------------------------------------------------ ragged batches
 def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=torch.float32, cap=None,
-               tight_new=True, new_cap=None):
+               tight_new=True, new_cap=None, lmhead_d=None):
     """One ragged step on the GPU and in the oracle; compares everything the step writes.  cap / new_cap: the
     bounds on n_cand[s] / n_new[s] promised to the library when they are lower than what the streams hold; a
     stream beyond either, or with a negative n_held, must come back flagged with nothing of its kept list or
-    K/V touched."""
+    K/V touched.  lmhead_d: the scores come from hidden states of that width and an output embedding matrix
+    (sirllm_step_lmhead_ragged) instead of stored logits."""
     n_held, n_new = np.asarray(n_held), np.asarray(n_new)
     n_cand = n_held + n_new
     max_cand = int(n_cand.max()) if cap is None else cap
     budget = pol.n_sink + pol.n_topk + pol.n_recent
     total = int(n_new.sum())
     g0 = torch.Generator(device=DEV).manual_seed(int(rng.integers(1 << 30)))
-    z = (torch.randn((total, V + 3), generator=g0, device=DEV) * 3).to(dt)
-    if total:
-        z[:, V:] = 1.0e4
+    if lmhead_d is None:
+        z = (torch.randn((total, V + 3), generator=g0, device=DEV) * 3).to(dt)
+        if total:
+            z[:, V:] = 1.0e4
+    else:
+        hid = (torch.randn((total, lmhead_d + 8), generator=g0, device=DEV) + 0.5).to(dt)[:, :lmhead_d]
+        emb = (torch.randn((V + 2, lmhead_d), generator=g0, device=DEV) * (3.0 / lmhead_d ** 0.5)).to(dt)
     tok = torch.randint(0, V, (total,), generator=g0, device=DEV, dtype=torch.int32)
     scores = torch.full((S, max_cand + 2), -3.0, device=DEV)
     for s in range(S):
@@ -695,19 +710,28 @@ def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=
     cu = torch.from_numpy(np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)).to(DEV)
     hs, hk, hv = to_np(scores).copy(), to_np(k).copy(), to_np(v).copy()
     ws = inplace_scratch(b) if rng.integers(2) else None
+    if max_cand > 32768:        # the multi-workgroup selection's scratch is required there; it arrives dirty
+        ws = torch.full((b.sirllm_workspace_bytes(S, max_cand, 0, 0),), 0x5a, dtype=torch.uint8, device=DEV)
     max_new = min(int(n_new.max()), max_cand) if tight_new else None
     if new_cap is not None:
         max_new = new_cap
     bound_new = max_new if max_new is not None else min(total, max_cand)
     fits_all = (n_held >= 0) & (n_new <= bound_new) & (n_cand <= max_cand)
-    b.sirllm_step_ragged(z, tok, V, scores, held_dev, cu, total, max_cand, pol, k, v, kept, out, n_keep_dev,
-                         max_new=max_new, workspace=ws)
+    if lmhead_d is None:
+        b.sirllm_step_ragged(z, tok, V, scores, held_dev, cu, total, max_cand, pol, k, v, kept, out, n_keep_dev,
+                             max_new=max_new, workspace=ws)
+    else:
+        ws = torch.full((b.sirllm_step_lmhead_ragged_workspace_bytes(S, max_cand, total, V),), 0x5a, dtype=torch.uint8,
+                        device=DEV)
+        b.sirllm_step_lmhead_ragged(hid, emb, tok, scores, held_dev, cu, total, max_cand, pol, k, v, kept, out,
+                                    n_keep_dev, ws, max_new=max_new, vocab=V)
     torch.cuda.synchronize()
     gs, gkeep = to_np(scores), to_np(n_keep_dev)
     # scores: tolerance; then teacher-force the oracle with the GPU's scores for everything exact
     want_scores = hs.copy()
     if total:
-        e = ref.score(to_np(z), to_np(tok), vocab=V)
+        e = ref.score(to_np(z), to_np(tok), vocab=V) if lmhead_d is None else \
+            ref.lmhead_score(np.ascontiguousarray(to_np(hid)), to_np(emb)[:V], to_np(tok))
         r0 = 0
         for s in range(S):
             if fits_all[s]:
@@ -722,7 +746,8 @@ def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=
             else:
                 np.testing.assert_array_equal(gs[s, :max(0, n_held[s])], hs[s, :max(0, n_held[s])])   # held scores intact
             continue
-        assert_scores_close(gs[s, n_held[s]:n_cand[s]], want_scores[s, n_held[s]:n_cand[s]])
+        assert_scores_close(gs[s, n_held[s]:n_cand[s]], want_scores[s, n_held[s]:n_cand[s]],
+                            atol=1e-6 if lmhead_d is None else 2e-5)
         np.testing.assert_array_equal(gs[s, :n_held[s]], hs[s, :n_held[s]])
         np.testing.assert_array_equal(gs[s, n_cand[s]:], hs[s, n_cand[s]:])
     ok = [s for s in range(S) if fits_all[s]]
@@ -795,6 +820,49 @@ def test_step_ragged_large_caches(b, ref, held, new, pol_t, tight_new):
     rng = np.random.default_rng(len(held) * 1000 + held[0])
     run_ragged(b, ref, rng, len(held), b.Policy(*pol_t), 300, torch.bfloat16, held, new, L=1, H=2, D=64,
                kv_dt=torch.bfloat16, tight_new=tight_new)
+
+
+@pytest.mark.parametrize("held,new,pol_t,kw", [
+    # one slot past what one workgroup selects; a stream within its budget and an empty one in the same batch
+    ([32768 - 53, 100, 0], [54, 54, 0], (4, 1020, 0, 0.7), {}),
+    # streams above and below 32768 slots, one within the budget (only decayed), ragged last tiles
+    ([39000, 20000, 33000, 8191], [800, 100, 1000, 1], (4, 30000, 1000, 0.9), {}),
+    # no top-k part, and a top-k part that takes all but one middle slot
+    ([50000, 100], [77, 5], (4, 0, 128, 0.9), {}),
+    ([40000, 35000], [50, 1], (4, 40000, 45, 0.8), {}),
+    # streams beyond the promised bounds (slots, new tokens, negative fill) are flagged and left alone
+    ([39000, 60000, 36000, -5, 34000], [800, 10, 3000, 10, 100], (4, 30000, 1000, 0.9), {"cap": 41000, "new_cap": 1000}),
+    # a 128K-slot budget with a ragged tail
+    ([131072, 131000], [2048, 100], (4, 129020, 2048, 0.9), {}),
+])
+def test_step_ragged_above_one_workgroup(b, ref, held, new, pol_t, kw):
+    """Ragged steps whose bound on the slots per stream exceeds 32768: every stream is then selected by the
+    multi-workgroup kernels on its own sizes (Alg. 1 per stream), whatever it holds itself."""
+    rng = np.random.default_rng(len(held) * 977 + abs(held[0]))
+    run_ragged(b, ref, rng, len(held), b.Policy(*pol_t), 300, torch.bfloat16, held, new, L=1, H=2, D=16,
+               kv_dt=torch.bfloat16, **kw)
+
+
+@pytest.mark.parametrize("dt", [torch.bfloat16, torch.float16])
+def test_step_lmhead_ragged_matches_oracle(b, ref, dt):
+    """The ragged step fed with hidden states and the output embedding matrix (Sec. 3.2; Alg. 1 per stream): scores
+    against the oracle's double-precision product, everything behind them bit exact given the scores."""
+    rng = np.random.default_rng(4242)
+    pol = b.Policy(4, 20, 8, 0.9)                       # budget 32
+    # streams under, at and over the budget, empty streams, streams without new tokens; 1 to 3 token tiles
+    run_ragged(b, ref, rng, 6, pol, 500, dt, [0, 10, 24, 40, 90, 0], [5, 22, 8, 0, 17, 0], lmhead_d=64)
+    run_ragged(b, ref, rng, 3, pol, 777, dt, [100, 31, 0], [1, 1, 64], kv_dt=torch.bfloat16, D=128, lmhead_d=72)
+    run_ragged(b, ref, rng, 1, pol, 64, dt, [200], [0], lmhead_d=64)
+    run_ragged(b, ref, rng, 4, b.Policy(4, 1020, 0, 0.8), 1000, dt, [1024, 1000, 500, 1024], [54, 54, 54, 1],
+               L=1, H=2, D=64, kv_dt=torch.bfloat16, lmhead_d=256)
+    run_ragged(b, ref, rng, 3, b.Policy(4, 3068, 1024, 0.85), 2000, dt, [7168, 100, 4000], [300, 257, 96],
+               L=1, H=2, D=64, kv_dt=torch.bfloat16, lmhead_d=128)
+    # flagged streams: too many slots, too many new tokens, a negative slot count
+    run_ragged(b, ref, rng, 3, pol, 100, dt, [10, 60, 20], [5, 30, 5], cap=40, tight_new=False, lmhead_d=64)
+    run_ragged(b, ref, rng, 4, pol, 100, dt, [40, -3, 50, -40], [5, 60, 8, 90], cap=100, new_cap=90, lmhead_d=64)
+    # a bound above 32768 slots per stream: the multi-workgroup selection behind the LM-head scores
+    run_ragged(b, ref, rng, 3, b.Policy(4, 30000, 1000, 0.9), 300, dt, [39000, 20000, 33000], [80, 100, 130],
+               L=1, H=2, D=16, kv_dt=torch.bfloat16, lmhead_d=64)
 
 
 # ------------------------------------------------------------- scoring from chunks of columns

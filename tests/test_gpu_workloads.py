@@ -263,16 +263,20 @@ def test_step_replays_from_a_captured_graph(b, ref):
             assert torch.equal(cap[name], eager[name]), f"replay {rep}: {name} differs from the eager run"
 
 
-def test_ragged_dialogues_of_unequal_length(b, ref):
+@pytest.mark.parametrize("from_hidden", [False, True], ids=["logits", "hidden states"])
+def test_ragged_dialogues_of_unequal_length(b, ref, from_hidden):
     """Six dialogues in one serving batch, each with its own arrival turn and its own number of tokens per
-    turn (some turns idle), stepped together by sirllm_step_ragged with in-place compaction; the oracle
-    replays every stream on its own and every turn is compared in full."""
+    turn (some turns idle), stepped together by sirllm_step_ragged (or, fed with hidden states and the output
+    embedding matrix, by sirllm_step_lmhead_ragged) with in-place compaction; the oracle replays every stream on
+    its own and every turn is compared in full."""
     from paper_2405_12528_amd.cache import RaggedRetentiveCache
     S, L, H, D, V = 6, 2, 2, 16, 400
     pol = (4, 20, 8, 0.9)
     rng = np.random.default_rng(11)
     cache = RaggedRetentiveCache(S, L, H, D, pol, max_new=40, kv_dtype=torch.float32, device=DEV)
     g0 = torch.Generator(device=DEV).manual_seed(3)
+    d_model = 64
+    emb = (torch.randn((V, d_model), generator=g0, device=DEV) * (2.5 / d_model ** 0.5)).to(torch.bfloat16)
     # oracle state per stream
     oE = [np.zeros((1, 0), np.float32) for _ in range(S)]
     oK = [np.zeros((1, L, H, 0, D), np.float32) for _ in range(S)]
@@ -285,6 +289,7 @@ def test_ragged_dialogues_of_unequal_length(b, ref):
             oE[2], oK[2], oV[2] = oE[2][:, :0], oK[2][:, :, :, :0], oV[2][:, :, :, :0]
         total = sum(n_new)
         z = torch.randn((total, V), generator=g0, device=DEV) * 2.5
+        hid = (torch.randn((total, d_model), generator=g0, device=DEV) + 0.5).to(torch.bfloat16)
         tok = torch.randint(0, V, (total,), generator=g0, device=DEV, dtype=torch.int32)
         new_kv = []
         for s in range(S):
@@ -294,7 +299,7 @@ def test_ragged_dialogues_of_unequal_length(b, ref):
             new_kv.append((to_np(ks)[None], to_np(vs)[None]))
         held_before = list(cache.n_held)
         pre_scores = cache.scores                                   # new scores are appended to this array
-        evicted = cache.step(z, tok, V, n_new)
+        evicted = cache.step_from_hidden(hid, emb, tok, n_new) if from_hidden else cache.step(z, tok, V, n_new)
         torch.cuda.synchronize()
         zs, ts = to_np(z), to_np(tok)
         r0 = 0
@@ -307,7 +312,10 @@ def test_ragged_dialogues_of_unequal_length(b, ref):
                 continue
             # scores within tolerance, then the oracle's selection and gather on the GPU's scores
             g_new = to_np(pre_scores[s, h:h + n])
-            if n:
+            if n and from_hidden:
+                assert_scores_close(g_new, ref.lmhead_score(np.ascontiguousarray(to_np(hid)[r0:r0 + n]), to_np(emb),
+                                                            ts[r0:r0 + n]), atol=2e-5)
+            elif n:
                 assert_scores_close(g_new, ref.score(np.ascontiguousarray(zs[r0:r0 + n]), ts[r0:r0 + n], vocab=V))
             r0 += n
             cand = np.concatenate([oE[s], g_new[None]], axis=1)
