@@ -128,8 +128,7 @@ def measure_other_workload(torch, b, synth, name, dev, reps=5):
     steps = int(max(4, min(60, 40.0 / est_ms)))                # about 40 ms of GPU time per repetition
     runs = sorted(sb.time_steps(steps, warmup=2 if i else 10)[0] for i in range(reps))
     med = runs[len(runs) // 2]
-    n_k = 6
-    g_avg, _, g_min = time_launches(torch, sb.gather, n_k, group=4)
+    g_avg, _, g_min = time_launches(torch, sb.gather, 4, group=8)
     out = {"ms_per_step": {"min": round(runs[0], 5), "median": round(med, 5), "max": round(runs[-1], 5)},
            "reps": reps, "steps_per_rep": steps, "algorithmic_bytes": bytes_["total"],
            "hbm_gbps": round(bytes_["total"] / (med * 1e-3) / 1e9, 1),
@@ -275,12 +274,16 @@ def main():
 
     # ---- optional: the ragged in-place step on the same shapes --------------------------------
     ragged = None
-    if args.ragged_inplace and n_cand <= b.SIRLLM_SINGLE_WG_CAND:
+    if args.ragged_inplace:
         held_dev = torch.full((S,), n_held, dtype=torch.int32, device=dev)
         cu_dev = torch.arange(0, (S + 1) * n_new, n_new, dtype=torch.int32, device=dev)
         keep_dev = torch.zeros(S, dtype=torch.int32, device=dev)
 
-        ip_ws = torch.zeros(b.SIRLLM_INPLACE_WORKSPACE_BYTES, dtype=torch.uint8, device=dev)
+        # above 32768 slots per stream the selection's scratch is required; below, the workspace only carries the
+        # in-place compaction's ticket and the step also runs without one
+        large = n_cand > b.SIRLLM_SINGLE_WG_CAND
+        ip_ws = torch.zeros(max(b.SIRLLM_INPLACE_WORKSPACE_BYTES, b.sirllm_workspace_bytes(S, n_cand, 0, 0)),
+                            dtype=torch.uint8, device=dev)
 
         def ragged_step(scratch=ip_ws):      # repeated in place on the same buffers: the data changes, the traffic does not
             z, t = sb._next_set()
@@ -291,8 +294,8 @@ def main():
         ragged = {"ms_per_step": round(r_avg, 5), "hbm_gbps": round(bytes_["total"] / (r_avg * 1e-3) / 1e9, 1),
                   "frac": round(bytes_["total"] / (r_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                   "vs_uniform_step": round(r_avg / ms_per_step, 4)}
-        rw_avg, _, _ = time_launches(torch, lambda: ragged_step(None), n_k, group=4)
-        ragged["ms_per_step_without_workspace"] = round(rw_avg, 5)
+        rw_avg = r_avg if large else time_launches(torch, lambda: ragged_step(None), n_k, group=4)[0]
+        ragged["ms_per_step_without_workspace"] = None if large else round(rw_avg, 5)
         for label, scratch in (("inplace_gather", ip_ws), ("inplace_gather_without_workspace", None)):
             ip_avg, _, _ = time_launches(
                 torch, lambda: b.sirllm_compact_kv_inplace(k_src, v_src, kept, n_keep, n_src=n_cand, workspace=scratch), n_k, group=4)

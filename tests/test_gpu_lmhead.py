@@ -271,6 +271,7 @@ def check_step_lmhead(ref, pol, h, W, tok, held, k_c, v_c, g):
     (2, 10, 12, (4, 20, 8, 0.9), 72, 300),       # under budget; d_model on the general kernel
     (2, 90, 0, (4, 20, 8, 0.9), 64, 300),        # no new tokens
     (1, 0, 50, (4, 20, 8, 0.9), 64, 300),        # empty cache
+    (2, 33000, 100, (4, 30000, 200, 0.9), 64, 300),   # above 32768 slots: the selection's scratch sits behind the LM head's
 ])
 def test_step_lmhead_small_shapes(b, ref, n_streams, n_held, n_new, pol, d, V):
     pol = b.Policy(*pol)
