@@ -203,15 +203,15 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (every stream, the whole step); --gpus must be 1. "
-                 "Sharding across GPUs (by stream, or by KV head with a replicated selection) is a design note "
-                 "in DESIGN.md, not code.")
+                 "Sharding across GPUs (by stream, or by KV head with a replicated selection) is described in the "
+                 "design notes, not built.")
 
     import torch
     from paper_2405_12528_amd import binding as b
     from paper_2405_12528_amd import synth
 
     if not torch.cuda.is_available():
-        sys.exit("bench.py needs a GPU (run it under gpurun)")
+        sys.exit("bench.py needs a GPU")
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]

@@ -9,7 +9,7 @@ if ROOT not in sys.path:
 
 
 def pytest_configure(config):
-    config.addinivalue_line("markers", "gpu: needs a real MI355X (run under gpurun); everything else runs on CPU")
+    config.addinivalue_line("markers", "gpu: needs a real MI355X; everything else runs on CPU")
 
 
 @pytest.fixture(scope="session")
