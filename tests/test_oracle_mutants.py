@@ -9,6 +9,7 @@ import sys
 
 import pytest
 
+import test_oracle_baselines as t_bl
 import test_oracle_compact_step as t_cs
 import test_oracle_lmhead as t_lm
 import test_oracle_score as t_sc
@@ -64,6 +65,30 @@ MUTANTS = [
      "h[k] = logit_at(hidden, dtype, 0 * ld_h + k);", [lambda r: t_lm.test_matches_float64_library_matmul_and_logsumexp(r, "bf16")]),
     ("step_compacts_even_under_budget_wrong_count", "(int32_t)budget);", "(int32_t)budget - 1);",
      [t_cs.test_step_is_score_then_decay_select_then_gather]),
+    # the baseline policies (Sec. 4.1) and their generator
+    ("philox_nine_rounds", "for (int round = 0; round < 10; ++round) {", "for (int round = 0; round < 9; ++round) {",
+     [t_bl.test_philox_known_answers]),
+    ("philox_multipliers_swapped", "const uint64_t p0 = (uint64_t)0xD2511F53u * c0;\n        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;",
+     "const uint64_t p0 = (uint64_t)0xCD9E8D57u * c0;\n        const uint64_t p1 = (uint64_t)0xD2511F53u * c2;",
+     [t_bl.test_philox_known_answers]),
+    ("philox_key_schedule_words_swapped", "k0 += 0x9E3779B9u;\n        k1 += 0xBB67AE85u;",
+     "k0 += 0xBB67AE85u;\n        k1 += 0x9E3779B9u;", [t_bl.test_philox_known_answers]),
+    ("philox_high_halves_not_crossed", "const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;",
+     "const uint32_t n0 = (uint32_t)(p0 >> 32) ^ c1 ^ k0;", [t_bl.test_philox_known_answers]),
+    ("interval_comb_anchored_at_oldest_slot", "keep[mid_hi - 1 - j * interval] = 1;", "keep[mid_lo + j * interval] = 1;",
+     [t_bl.test_interval_comb_by_hand]),
+    ("interval_rounded_up", "int64_t interval = M / k;", "int64_t interval = (M + k - 1) / k;",
+     [t_bl.test_interval_comb_by_hand]),
+    ("random_keeps_smallest_draws", "if (a->key != b->key) return a->key > b->key ? -1 : 1;",
+     "if (a->key != b->key) return a->key > b->key ? 1 : -1;", [t_bl.test_random_subset_follows_the_published_generator]),
+    ("random_ignores_the_stream", "(uint32_t)(mid_lo + i), (uint32_t)s, (uint32_t)turn,", "(uint32_t)(mid_lo + i), 0u, (uint32_t)turn,",
+     [t_bl.test_random_subset_properties, t_bl.test_random_subset_follows_the_published_generator]),
+    ("random_drops_the_turns_high_word", "(uint32_t)turn, (uint32_t)(turn >> 32)};", "(uint32_t)turn, 0u};",
+     [t_bl.test_random_subset_properties]),
+    ("random_counter_is_middle_relative", "const uint32_t ctr[4] = {(uint32_t)(mid_lo + i),", "const uint32_t ctr[4] = {(uint32_t)(i),",
+     [t_bl.test_random_subset_follows_the_published_generator]),
+    ("stream_policy_keeps_topk_slots_too", "const int64_t k = kind == 0 ? 0 : policy->n_topk;", "const int64_t k = policy->n_topk;",
+     [t_bl.test_stream_policy_is_sink_plus_recent]),
 ]
 
 
