@@ -10,6 +10,8 @@
 
 #include "common.h"
 
+// Phase marks: a file that includes this header to time the selection's phases defines SIRLLM_TSTAMP(k) beforehand
+// (e.g. to store the cycle counter into slot k of a buffer); in the library it expands to nothing.
 #ifndef SIRLLM_TSTAMP
 #define SIRLLM_TSTAMP(k)
 #endif
