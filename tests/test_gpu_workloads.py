@@ -379,6 +379,57 @@ def test_ragged_dialogues_of_unequal_length(b, ref, from_hidden):
             oE[s], oK[s], oV[s] = so, rk, rv
 
 
+def test_ragged_cache_beyond_one_workgroups_slots(b, ref):
+    """RaggedRetentiveCache with a budget of 33000 slots: once a stream may hold more than 32768 slots the batch is
+    selected by the multi-workgroup kernels (workspace from the cache).  Two streams fill at different speeds, so
+    early steps keep everything, later ones evict in one stream only, then in both; the oracle replays every step."""
+    from paper_2405_12528_amd.cache import RaggedRetentiveCache
+    S, L, H, D, V = 2, 1, 2, 8, 200
+    pol = (4, 32000, 996, 0.9)
+    rng = np.random.default_rng(33)
+    cache = RaggedRetentiveCache(S, L, H, D, pol, max_new=3000, kv_dtype=torch.float32, device=DEV)
+    g0 = torch.Generator(device=DEV).manual_seed(9)
+    oE = [np.zeros((1, 0), np.float32) for _ in range(S)]
+    oK = [np.zeros((1, L, H, 0, D), np.float32) for _ in range(S)]
+    oV = [np.zeros((1, L, H, 0, D), np.float32) for _ in range(S)]
+    seen_evictions = [0, 0]
+    for turn in range(1, 21):
+        n_new = [3000, int(rng.integers(1500, 2600))]
+        total = sum(n_new)
+        z = torch.randn((total, V), generator=g0, device=DEV) * 2.5
+        tok = torch.randint(0, V, (total,), generator=g0, device=DEV, dtype=torch.int32)
+        new_kv = []
+        for s in range(S):
+            ks, vs = cache.new_kv_slots(s, n_new[s])
+            ks.copy_(torch.randn(ks.shape, generator=g0, device=DEV))
+            vs.copy_(torch.randn(vs.shape, generator=g0, device=DEV))
+            new_kv.append((to_np(ks)[None], to_np(vs)[None]))
+        held_before = list(cache.n_held)
+        pre_scores = cache.scores
+        evicted = cache.step(z, tok, V, n_new)
+        torch.cuda.synchronize()
+        zs, ts = to_np(z), to_np(tok)
+        r0 = 0
+        for s in range(S):
+            h, n = held_before[s], n_new[s]
+            Kc = np.concatenate([oK[s], new_kv[s][0]], axis=3)
+            Vc = np.concatenate([oV[s], new_kv[s][1]], axis=3)
+            g_new = to_np(pre_scores[s, h:h + n])
+            assert_scores_close(g_new, ref.score(np.ascontiguousarray(zs[r0:r0 + n]), ts[r0:r0 + n], vocab=V))
+            r0 += n
+            ki, so = ref.decay_select(np.concatenate([oE[s], g_new[None]], axis=1), h, n, ref.Policy(*pol))
+            n_keep = ki.shape[1]
+            assert cache.n_held[s] == n_keep and evicted[s] == (h + n > 33000)
+            seen_evictions[s] += int(evicted[s])
+            np.testing.assert_array_equal(to_np(cache.kept_idx[s, :n_keep]), ki[0])
+            np.testing.assert_array_equal(to_np(cache.scores[s, :n_keep]).view(np.uint32), so[0].view(np.uint32))
+            rk, rv = ref.compact_kv(Kc, Vc, ki)
+            assert np.array_equal(to_np(cache.k[s:s + 1, :, :, :n_keep]), rk), f"turn {turn} stream {s}: K differs"
+            assert np.array_equal(to_np(cache.v[s:s + 1, :, :, :n_keep]), rv), f"turn {turn} stream {s}: V differs"
+            oE[s], oK[s], oV[s] = so, rk, rv
+    assert seen_evictions[0] >= 8 and 1 <= seen_evictions[1] < seen_evictions[0]
+
+
 def test_c_example_runs_without_torch():
     """examples/step_example.c: the C ABI driven from plain C with the HIP runtime only."""
     import os
