@@ -14,6 +14,10 @@ namespace sirllm {
 namespace {
 
 constexpr int kBlock = 1024;
+// Most slots per lane of a selecting workgroup inside the shared launch: with 16 the kernel still fits 64 registers,
+// so two workgroups of 1024 threads share a CU as in the scoring kernel proper; 32 slots per lane need 128 registers
+// (one workgroup per CU, and spills), so caches above 16384 slots take the three launches.
+constexpr int kMaxKpt = 16;
 
 template <int DT, int KPT, bool NT>
 __global__ __launch_bounds__(kBlock) void score_select_kernel(ScoreArgs sa, SelectArgs se)
@@ -60,7 +64,8 @@ hipError_t launch_ragged_esize(const ScoreArgs& sa, const SelectArgs& se, hipStr
 {
     const int need = (se.n_cand + kBlock - 1) / kBlock;
     if (need <= 2) return launch_ragged_kpt<DT, 2>(sa, se, stream);
-    return launch_ragged_kpt<DT, 8>(sa, se, stream);
+    if (need <= 8) return launch_ragged_kpt<DT, 8>(sa, se, stream);
+    return launch_ragged_kpt<DT, 16>(sa, se, stream);
 }
 
 template <int DT, int KPT>
@@ -79,7 +84,8 @@ hipError_t launch_esize(const ScoreArgs& sa, const SelectArgs& se, hipStream_t s
 {
     const int need = (se.n_cand + kBlock - 1) / kBlock;
     if (need <= 2) return launch_kpt<DT, 2>(sa, se, stream);
-    return launch_kpt<DT, 8>(sa, se, stream);
+    if (need <= 8) return launch_kpt<DT, 8>(sa, se, stream);
+    return launch_kpt<DT, 16>(sa, se, stream);
 }
 
 }  // namespace
@@ -88,15 +94,14 @@ bool score_select_fusable(const ScoreArgs& sa, const SelectArgs& se)
 {
     if (tuning::get("SIRLLM_FUSE_SELECT", 1) == 0) return false;
     const int n_new = se.n_cand - se.n_held;
-    // more than 8 slots per lane in the selecting workgroup would cost the scorers their occupancy
-    return sa.n_rows > 0 && n_new <= se.n_recent && se.n_cand <= kBlock * 8 &&
+    return sa.n_rows > 0 && n_new <= se.n_recent && se.n_cand <= kBlock * kMaxKpt &&
            sa.n_rows + se.n_streams <= 0x7fffffffLL;
 }
 
 bool score_select_ragged_fusable(const ScoreArgs& sa, const SelectArgs& se)
 {
     if (tuning::get("SIRLLM_FUSE_SELECT", 1) == 0) return false;
-    return sa.n_rows > 0 && se.max_new <= se.n_recent && se.n_cand <= kBlock * 8 &&
+    return sa.n_rows > 0 && se.max_new <= se.n_recent && se.n_cand <= kBlock * kMaxKpt &&
            sa.n_rows + se.n_streams <= 0x7fffffffLL;
 }
 

@@ -108,6 +108,10 @@ WORKLOADS = {
     # A long-context cache: the Llama-3-8B shape with a 128K-slot budget (the pre-training length of its
     # long-context variants), 2048 new tokens per turn.  35 GB of K/V in flight per step; the selection runs
     # over 133120 candidate slots, beyond what one workgroup holds.
+    # The Llama-3-8B shape with twice the budget: 10240 candidate slots, ten per lane of the selecting workgroup.
+    "llama3_8k_budget": Workload("llama3_8k_budget", vocab=128256, n_new=2048, logits_dtype="f32", sigma=4.0, zipf_a=1.05,
+                                 spike=0.0, spike_frac=0.0, n_sink=4, n_topk=6140, n_recent=2048, decay=0.9,
+                                 n_layers=32, n_kv_heads=8, head_dim=128, kv_dtype="bf16", n_cand=10240),
     "llama3_128k": Workload("llama3_128k", vocab=128256, n_new=2048, logits_dtype="f32", sigma=4.0, zipf_a=1.05,
                             spike=0.0, spike_frac=0.0, n_sink=4, n_topk=129020, n_recent=2048, decay=0.9,
                             n_layers=32, n_kv_heads=8, head_dim=128, kv_dtype="bf16", n_cand=133120),

@@ -403,11 +403,16 @@ def test_step_small_shapes(b, ref, n_streams, n_held, n_new, pol):
     (3, 2, 8, 2000, 700, (0, 500, 700, 1.0), 64, torch.float32),        # no sinks, 4-byte elements
     (2, 4, 4, 2400, 600, (4, 1396, 600, 0.9), 120, torch.bfloat16),     # 240-byte rows: 15 vectors, not a power of two
     (2, 4, 4, 2400, 600, (4, 1396, 600, 0.9), 100, torch.bfloat16),     # 200-byte rows: 8-byte vectors
+    # 8193..16384 candidate slots with the new tokens inside the recent window: scoring and selection still share a
+    # launch, the selecting workgroup with sixteen slots per lane; at 16385 slots they do not any more
+    (1, 2, 2, 9000, 1000, (4, 5000, 1500, 0.9), 64, torch.bfloat16),
+    (2, 1, 2, 15000, 1384, (4, 8000, 1384, 0.8), 32, torch.float32),
+    (1, 1, 2, 15001, 1384, (4, 8000, 1384, 0.8), 32, torch.float32),
 ])
 def test_step_mid_sizes(b, ref, S, L, H, n_held, n_new, pol, D, kv_dt):
     """Whole steps between the small shapes and the benchmark's: a few thousand slots, tens of planes, rows of 256,
     240 and 200 bytes (16-byte vectors with a power-of-two and an odd count per row, 8-byte vectors), self-identifying
-    K/V payloads; scoring and selection share a launch (no new token can compete in Top_k)."""
+    K/V payloads; scoring and selection share a launch (no new token can compete in Top_k) up to 16384 slots."""
     import dataclasses
     V = 2000
     w2 = dataclasses.replace(synth.WORKLOADS["tiny"], vocab=V)
