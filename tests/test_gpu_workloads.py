@@ -27,7 +27,7 @@ def b():
 
 
 @pytest.mark.timeout(300)
-@pytest.mark.parametrize("name", ["llama2_7b", "mistral_7b", "llama3_8b"])
+@pytest.mark.parametrize("name", ["llama2_7b", "mistral_7b", "llama3_8b", "llama3_8k_budget"])
 def test_full_size_step(b, ref, name):
     w = synth.WORKLOADS[name]
     ref.set_threads(16)
