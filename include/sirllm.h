@@ -241,6 +241,20 @@ int sirllm_compact_kv(const void* k_src, const void* v_src, const sirllm_kv_layo
                       int32_t n_streams, int32_t n_keep, void* hip_stream);
 
 /*
+ * The same compaction (Sec. 3.3) for a cache held as one K and one V buffer PER LAYER, the usual shape of a model's
+ * past keys and values: k_src[l], v_src[l], k_dst[l], v_dst[l] are device pointers to layer l's buffers, and the four
+ * arrays of src->n_layers pointers themselves are HOST memory (they travel in the kernels' arguments, 32 layers per
+ * launch; nothing is staged in device memory and the call can be captured).  `src` and `dst` describe ONE layer:
+ * stride_stream, stride_head, stride_pos as in sirllm_kv_layout, stride_layer is ignored, n_layers is the number of
+ * entries of the arrays.  v_src and v_dst may both be NULL.  Everything else as for sirllm_compact_kv; no destination
+ * buffer may overlap a source buffer or another destination buffer (SIRLLM_ERR_INVALID_ARG).
+ */
+int sirllm_compact_kv_layers(const void* const* k_src, const void* const* v_src, const sirllm_kv_layout* src,
+                             int32_t n_src, void* const* k_dst, void* const* v_dst, const sirllm_kv_layout* dst,
+                             const int32_t* kept_idx, int64_t idx_stride,
+                             int32_t n_streams, int32_t n_keep, void* hip_stream);
+
+/*
  * The same compaction, written back into the buffer it reads (Sec. 3.3): after the call slots
  * [0, n_keep) of every plane hold the rows kept_idx[0 : n_keep), slots >= n_keep keep whatever
  * they held.  Needs kept_idx strictly ascending per stream with entries in [0, n_src) -- which is

@@ -46,7 +46,8 @@ SIRLLM_BASELINE_STREAM, SIRLLM_BASELINE_INTERVAL, SIRLLM_BASELINE_RANDOM = 0, 1,
 SIRLLM_STATIC_SCRATCH_BYTES = 1048576
 SIRLLM_INPLACE_WORKSPACE_BYTES = 256
 
-EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_decay_select_static", "sirllm_compact_kv", "sirllm_step", "sirllm_baseline_select",
+EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_decay_select_static", "sirllm_compact_kv", "sirllm_compact_kv_layers",
+           "sirllm_step", "sirllm_baseline_select",
            "sirllm_compact_kv_inplace", "sirllm_step_ragged", "sirllm_score_partial",
            "sirllm_score_merge", "sirllm_lmhead_score", "sirllm_lmhead_workspace_bytes",
            "sirllm_step_lmhead", "sirllm_step_lmhead_workspace_bytes", "sirllm_step_lmhead_ragged",
@@ -59,6 +60,8 @@ _lib.sirllm_decay_select.argtypes = [_vp, _i64, _i32, _i32, _i32, _PP, _vp, _i64
 _lib.sirllm_decay_select_static.argtypes = [_vp, _i64, _i32, _i32, _i32, _PP, _vp, _i64, _vp, _i64, _vp]
 _lib.sirllm_decay_select_static.restype = C.c_int
 _lib.sirllm_compact_kv.argtypes = [_vp, _vp, _LP, _i32, _vp, _vp, _LP, _vp, _i64, _i32, _i32, _vp]
+_lib.sirllm_compact_kv_layers.argtypes = [_vp, _vp, _LP, _i32, _vp, _vp, _LP, _vp, _i64, _i32, _i32, _vp]
+_lib.sirllm_compact_kv_layers.restype = C.c_int
 _lib.sirllm_step.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _i32, _i32, _PP,
                              _vp, _vp, _LP, _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _sz, _vp]
 _lib.sirllm_baseline_select.argtypes = [C.c_int, _i32, _i32, _PP, C.c_uint64, C.c_uint64, _vp, _i64,
@@ -295,6 +298,51 @@ def sirllm_compact_kv(k_src: torch.Tensor, v_src, k_dst: torch.Tensor, v_dst, ke
     _check(_lib.sirllm_compact_kv(_ptr(k_src), _ptr(v_src), C.byref(ls), n_src, _ptr(k_dst), _ptr(v_dst),
                                   C.byref(ld), _ptr(kept_idx), _row_stride(kept_idx), n_streams, int(n_keep),
                                   _stream(stream)), "sirllm_compact_kv")
+    return k_dst, v_dst
+
+
+def layer_layout(t: torch.Tensor, n_layers: int) -> sirllm_kv_layout:
+    """Layout struct of ONE layer's [streams, kv_heads, slots, head_dim] tensor (any strides, last axis contiguous)."""
+    if t.dim() != 4:
+        raise ValueError("per-layer K/V tensors are [streams, kv_heads, slots, head_dim]")
+    if t.shape[3] > 1 and t.stride(3) != 1:
+        raise ValueError("head_dim must be contiguous")
+    return sirllm_kv_layout(n_layers, t.shape[1], t.shape[3], t.element_size(), t.stride(0), 0, t.stride(1), t.stride(2))
+
+
+def sirllm_compact_kv_layers(k_src, v_src, k_dst, v_dst, kept_idx: torch.Tensor, n_keep: int, n_src: int | None = None,
+                             stream=None):
+    """sirllm_compact_kv for a cache held as one tensor per layer: k_src, v_src, k_dst, v_dst are sequences of
+    [streams, kv_heads, slots, head_dim] tensors (v_src and v_dst may both be None); all layers of one side share
+    shape, strides and dtype."""
+    sides = [list(k_src), None if v_src is None else list(v_src), list(k_dst), None if v_dst is None else list(v_dst)]
+    n_layers = len(sides[0])
+    if (sides[1] is None) != (sides[3] is None) or any(x is not None and len(x) != n_layers for x in sides):
+        raise ValueError("one tensor per layer on every side; V on both sides or on neither")
+    _on_device(kept_idx, *[t for x in sides if x is not None for t in x])
+    if kept_idx.dim() != 2 or kept_idx.dtype != torch.int32 or (kept_idx.shape[1] > 1 and kept_idx.stride(1) != 1):
+        raise ValueError("kept_idx must be [n_streams, >= n_keep] int32 with contiguous rows")
+    if n_layers == 0:
+        return k_dst, v_dst
+
+    def same(ts):
+        first = (ts[0].shape, ts[0].stride(), ts[0].dtype)
+        return all((t.shape, t.stride(), t.dtype) == first for t in ts)
+    if not all(same(x) for x in sides if x is not None):
+        raise ValueError("the layers of one side must share shape, strides and dtype")
+    if sides[1] is not None and ((sides[1][0].shape, sides[1][0].stride()) != (sides[0][0].shape, sides[0][0].stride())
+                                 or (sides[3][0].shape, sides[3][0].stride()) != (sides[2][0].shape, sides[2][0].stride())):
+        raise ValueError("K and V must share one layout")
+    ls, ld = layer_layout(sides[0][0], n_layers), layer_layout(sides[2][0], n_layers)
+    n_streams = sides[0][0].shape[0]
+    n_src = sides[0][0].shape[2] if n_src is None else int(n_src)
+    if sides[2][0].shape[2] < n_keep or sides[0][0].shape[2] < n_src or kept_idx.shape[0] != n_streams \
+            or sides[2][0].shape[0] != n_streams:
+        raise ValueError("destination has fewer than n_keep slots, or stream counts differ")
+    arrays = [None if x is None else (C.c_void_p * n_layers)(*[t.data_ptr() for t in x]) for x in sides]
+    _check(_lib.sirllm_compact_kv_layers(arrays[0], arrays[1], C.byref(ls), n_src, arrays[2], arrays[3], C.byref(ld),
+                                         _ptr(kept_idx), _row_stride(kept_idx), n_streams, int(n_keep), _stream(stream)),
+           "sirllm_compact_kv_layers")
     return k_dst, v_dst
 
 

@@ -432,6 +432,64 @@ int sirllm_compact_kv(const void* k_src, const void* v_src, const sirllm_kv_layo
     return hip_status(launch_gather(g, 0, n_keep, (hipStream_t)hip_stream));
 }
 
+int sirllm_compact_kv_layers(const void* const* k_src, const void* const* v_src, const sirllm_kv_layout* src,
+                             int32_t n_src, void* const* k_dst, void* const* v_dst, const sirllm_kv_layout* dst,
+                             const int32_t* kept_idx, int64_t idx_stride, int32_t n_streams, int32_t n_keep,
+                             void* hip_stream)
+{
+    if (!layout_ok(src) || !layout_ok(dst)) return SIRLLM_ERR_INVALID_ARG;
+    if (src->n_layers != dst->n_layers || src->n_kv_heads != dst->n_kv_heads || src->head_dim != dst->head_dim ||
+        src->elem_bytes != dst->elem_bytes)
+        return SIRLLM_ERR_INVALID_ARG;
+    if (n_streams < 0 || n_keep < 0 || n_src < 0) return SIRLLM_ERR_INVALID_ARG;
+    const int32_t n_layers = src->n_layers;
+    if (n_streams == 0 || n_keep == 0 || n_layers == 0) return SIRLLM_OK;
+    if (!k_src || !k_dst || !kept_idx || idx_stride < n_keep) return SIRLLM_ERR_INVALID_ARG;
+    if ((v_src == nullptr) != (v_dst == nullptr)) return SIRLLM_ERR_INVALID_ARG;
+    if ((int64_t)src->head_dim * src->elem_bytes * n_keep > 0x7fff0000LL) return SIRLLM_ERR_UNSUPPORTED;
+    // one layer of either side: the layouts with the layer dimension taken out
+    sirllm_kv_layout s1 = *src, d1 = *dst;
+    s1.n_layers = d1.n_layers = 1;
+    s1.stride_layer = d1.stride_layer = 0;
+    const int64_t sb = extent_bytes(&s1, n_streams, n_src), db = extent_bytes(&d1, n_streams, n_keep);
+    const uintptr_t em = (uintptr_t)src->elem_bytes - 1;
+    const int n_tensors = v_src ? 2 : 1;
+    const void* const* srcs[2] = {k_src, v_src};
+    void* const* dsts[2] = {k_dst, v_dst};
+    for (int x = 0; x < n_tensors; ++x)
+        for (int l = 0; l < n_layers; ++l) {
+            if (!srcs[x][l] || !dsts[x][l]) return SIRLLM_ERR_INVALID_ARG;
+            if (((uintptr_t)srcs[x][l] & em) || ((uintptr_t)dsts[x][l] & em)) return SIRLLM_ERR_INVALID_ARG;
+        }
+    // no destination buffer may overlap a source buffer or another destination buffer
+    for (int x = 0; x < n_tensors; ++x)
+        for (int l = 0; l < n_layers; ++l)
+            for (int y = 0; y < n_tensors; ++y)
+                for (int m = 0; m < n_layers; ++m) {
+                    if (ranges_overlap(dsts[x][l], db, srcs[y][m], sb)) return SIRLLM_ERR_INVALID_ARG;
+                    if ((x != y || l != m) && ranges_overlap(dsts[x][l], db, dsts[y][m], db)) return SIRLLM_ERR_INVALID_ARG;
+                }
+    // the layers go into the kernel's arguments kLayerTable at a time
+    for (int l0 = 0; l0 < n_layers; l0 += kLayerTable) {
+        const int nl = n_layers - l0 < kLayerTable ? n_layers - l0 : kLayerTable;
+        s1.n_layers = d1.n_layers = nl;
+        GatherArgs g = make_gather_args(k_src[l0], v_src ? v_src[l0] : nullptr, &s1, n_src, k_dst[l0],
+                                        v_dst ? v_dst[l0] : nullptr, &d1, kept_idx, idx_stride, n_streams, n_keep);
+        g.src[0] = g.src[1] = nullptr;                       // the table below is what the kernel reads
+        g.dst[0] = g.dst[1] = nullptr;
+        LayerTable t;
+        for (int x = 0; x < 2; ++x)
+            for (int l = 0; l < kLayerTable; ++l) {
+                const bool live = x < n_tensors && l < nl;
+                t.src[x][l] = live ? (const char*)srcs[x][l0 + l] : nullptr;
+                t.dst[x][l] = live ? (char*)dsts[x][l0 + l] : nullptr;
+            }
+        const int rc = hip_status(launch_gather_layers(g, t, (hipStream_t)hip_stream));
+        if (rc) return rc;
+    }
+    return SIRLLM_OK;
+}
+
 int sirllm_compact_kv_inplace(void* k, void* v, const sirllm_kv_layout* layout, int32_t n_src,
                               const int32_t* kept_idx, int64_t idx_stride, int32_t n_streams, int32_t n_keep,
                               void* workspace, size_t workspace_bytes, void* hip_stream)

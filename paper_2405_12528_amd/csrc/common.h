@@ -151,6 +151,15 @@ struct GatherArgs {
 };
 // Copies destination rows [row_begin, row_end) of every plane.
 hipError_t launch_gather(const GatherArgs& a, int row_begin, int row_end, hipStream_t stream);
+// The same for a cache held as one buffer per layer and tensor: a.src / a.dst and the layer strides of `a` are not
+// used, layer l of tensor x starts at t.src[x][l] / t.dst[x][l]; a.n_layers <= kLayerTable.  The table travels in the
+// kernel arguments (1 KB), so nothing has to be staged in device memory.
+constexpr int kLayerTable = 32;
+struct LayerTable {
+    const char* src[2][kLayerTable];
+    char* dst[2][kLayerTable];
+};
+hipError_t launch_gather_layers(const GatherArgs& a, const LayerTable& t, hipStream_t stream);
 
 // ---- gather_inplace.hip -----------------------------------------------------------------
 // src and dst of `a` are the same buffers and layouts; kept_idx must be strictly ascending.  `scratch` is optional:

@@ -17,6 +17,13 @@ __global__ __launch_bounds__(BLOCK) void gather_rows_kernel(GatherLaunch g)
         g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z);
 }
 
+template <typename VecT, bool POW2, bool OFF64>
+__global__ __launch_bounds__(512) void gather_rows_layers_kernel(GatherLaunch g, LayerTable t)
+{
+    gather_dev::gather_tile_layers<VecT, 512, 1, true, POW2, OFF64>(g, t, (int)blockIdx.x, g.plane0 + (int)blockIdx.y,
+                                                                   g.stream0 + (int)blockIdx.z);
+}
+
 template <typename VecT, int BLOCK, int UNROLL, bool NT>
 void launch_shape(const GatherLaunch& g, dim3 grid, bool pow2, bool off64, hipStream_t stream)
 {
@@ -64,7 +71,55 @@ hipError_t launch_vec(const GatherArgs& a, int row_begin, int row_end, hipStream
     return hipSuccess;
 }
 
+// Per-layer buffers: the default launch shape only (512 threads, one vector per lane, non-temporal accesses).
+template <typename VecT>
+hipError_t launch_vec_layers(const GatherArgs& a, const LayerTable& t, hipStream_t stream)
+{
+    GatherLaunch g;
+    bool pow2, off64;
+    if (!gather_dev::fill_launch<VecT>(g, a, 0, a.n_keep, &pow2, &off64)) return hipErrorInvalidValue;
+    const int64_t n_items = (int64_t)a.n_keep * g.vpr;
+    const unsigned n_tiles = (unsigned)((n_items + 511) / 512);
+    const int planes = a.n_tensors * g.lh;            // at most 2 * 32 * n_heads
+    constexpr int kMaxDim = 65535;
+    const dim3 block(512);
+    for (int s0 = 0; s0 < a.n_streams; s0 += kMaxDim) {
+        for (int p0 = 0; p0 < planes; p0 += kMaxDim) {
+            g.stream0 = s0;
+            g.plane0 = p0;
+            const dim3 grid(n_tiles, (unsigned)min(kMaxDim, planes - p0), (unsigned)min(kMaxDim, a.n_streams - s0));
+            if (pow2) {
+                if (off64) hipLaunchKernelGGL((gather_rows_layers_kernel<VecT, true, true>), grid, block, 0, stream, g, t);
+                else       hipLaunchKernelGGL((gather_rows_layers_kernel<VecT, true, false>), grid, block, 0, stream, g, t);
+            } else {
+                if (off64) hipLaunchKernelGGL((gather_rows_layers_kernel<VecT, false, true>), grid, block, 0, stream, g, t);
+                else       hipLaunchKernelGGL((gather_rows_layers_kernel<VecT, false, false>), grid, block, 0, stream, g, t);
+            }
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+
 }  // namespace
+
+hipError_t launch_gather_layers(const GatherArgs& a, const LayerTable& t, hipStream_t stream)
+{
+    if (a.n_keep <= 0 || a.n_streams <= 0 || a.row_bytes <= 0 || a.n_layers <= 0 || a.n_heads <= 0) return hipSuccess;
+    if (a.n_layers > kLayerTable) return hipErrorInvalidValue;
+    // the widest access every address of the call is a multiple of: strides and row size, and every layer's pointers
+    uint64_t bits = (uint64_t)gather_dev::vector_bytes(a, false);
+    for (int x = 0; x < a.n_tensors; ++x)
+        for (int l = 0; l < a.n_layers; ++l) bits |= (uint64_t)(uintptr_t)t.src[x][l] | (uint64_t)(uintptr_t)t.dst[x][l];
+    switch (gather_dev::widest_access(bits)) {
+    case 16: return launch_vec_layers<u32x4>(a, t, stream);
+    case 8:  return launch_vec_layers<u32x2>(a, t, stream);
+    case 4:  return launch_vec_layers<uint32_t>(a, t, stream);
+    case 2:  return launch_vec_layers<uint16_t>(a, t, stream);
+    default: return launch_vec_layers<uint8_t>(a, t, stream);
+    }
+}
 
 hipError_t launch_gather(const GatherArgs& a, int row_begin, int row_end, hipStream_t stream)
 {

@@ -38,27 +38,13 @@ struct GatherLaunch {
     int32_t uniform;      // 1: s_layer == n_heads*s_head and d_layer == n_heads*d_head
 };
 
+// One tile of destination rows of the plane that starts at sp (source) / dp (destination) and belongs to `stream`.
 // POW2: vpr is a power of two.  OFF64: offsets inside a plane need more than 32 bits.
 template <typename VecT, int BLOCK, int UNROLL, bool NT, bool POW2, bool OFF64>
-__device__ __forceinline__ void gather_tile(const GatherLaunch& g, int tile, int plane, int stream)
+__device__ __forceinline__ void gather_tile_at(const GatherLaunch& g, int tile, const char* sp, char* dp, int stream)
 {
     const GatherArgs& a = g.a;
     using off_t = typename std::conditional<OFF64, int64_t, uint32_t>::type;
-
-    // plane -> base pointers (uniform over the workgroup: scalar arithmetic)
-    const int tensor = plane >= g.lh ? 1 : 0;
-    const int ph = plane - tensor * g.lh;
-    int64_t so, dof;
-    if (g.uniform) {
-        so = ph * a.s_head;
-        dof = ph * a.d_head;
-    } else {
-        const int l = ph / a.n_heads, h = ph - l * a.n_heads;
-        so = l * a.s_layer + h * a.s_head;
-        dof = l * a.d_layer + h * a.d_head;
-    }
-    const char* sp = a.src[tensor] + stream * a.s_stream + so;
-    char* dp = a.dst[tensor] + stream * a.d_stream + dof;
     const int32_t* idx = a.kept_idx + stream * a.idx_stride;
 
     const int n_items = (g.row_end - g.row_begin) * g.vpr;
@@ -88,6 +74,40 @@ __device__ __forceinline__ void gather_tile(const GatherLaunch& g, int tile, int
         if (live[u]) st<VecT, NT>(dp + doff[u], v[u]);
 }
 
+// The cache is one buffer per tensor: plane -> base pointers by the layout's strides (uniform over the workgroup:
+// scalar arithmetic).
+template <typename VecT, int BLOCK, int UNROLL, bool NT, bool POW2, bool OFF64>
+__device__ __forceinline__ void gather_tile(const GatherLaunch& g, int tile, int plane, int stream)
+{
+    const GatherArgs& a = g.a;
+    const int tensor = plane >= g.lh ? 1 : 0;
+    const int ph = plane - tensor * g.lh;
+    int64_t so, dof;
+    if (g.uniform) {
+        so = ph * a.s_head;
+        dof = ph * a.d_head;
+    } else {
+        const int l = ph / a.n_heads, h = ph - l * a.n_heads;
+        so = l * a.s_layer + h * a.s_head;
+        dof = l * a.d_layer + h * a.d_head;
+    }
+    gather_tile_at<VecT, BLOCK, UNROLL, NT, POW2, OFF64>(g, tile, a.src[tensor] + stream * a.s_stream + so,
+                                                         a.dst[tensor] + stream * a.d_stream + dof, stream);
+}
+
+// The cache is one buffer per layer and tensor (the table rides in the kernel arguments): plane -> (tensor, layer,
+// head), base pointer of that layer's buffer, then the stream and head strides.
+template <typename VecT, int BLOCK, int UNROLL, bool NT, bool POW2, bool OFF64>
+__device__ __forceinline__ void gather_tile_layers(const GatherLaunch& g, const LayerTable& t, int tile, int plane, int stream)
+{
+    const GatherArgs& a = g.a;
+    const int tensor = plane >= g.lh ? 1 : 0;
+    const int ph = plane - tensor * g.lh;
+    const int l = ph / a.n_heads, h = ph - l * a.n_heads;
+    gather_tile_at<VecT, BLOCK, UNROLL, NT, POW2, OFF64>(g, tile, t.src[tensor][l] + stream * a.s_stream + h * a.s_head,
+                                                         t.dst[tensor][l] + stream * a.d_stream + h * a.d_head, stream);
+}
+
 // Host side: fills everything of a GatherLaunch that depends on the vector width.
 template <typename VecT>
 inline bool fill_launch(GatherLaunch& g, const GatherArgs& a, int row_begin, int row_end, bool* pow2, bool* off64)
@@ -110,18 +130,26 @@ inline bool fill_launch(GatherLaunch& g, const GatherArgs& a, int row_begin, int
     return true;
 }
 
-// Widest power-of-two access (<= 16 bytes) that every address of the call is a multiple of.
-inline int vector_bytes(const GatherArgs& a)
+// Widest power-of-two access (<= 16 bytes) that every number OR-ed into `bits` is a multiple of.
+inline int widest_access(uint64_t bits)
 {
-    uint64_t bits = (uint64_t)a.row_bytes | (uint64_t)a.s_stream | (uint64_t)a.s_layer | (uint64_t)a.s_head |
-                    (uint64_t)a.s_pos | (uint64_t)a.d_stream | (uint64_t)a.d_layer | (uint64_t)a.d_head |
-                    (uint64_t)a.d_pos;
-    for (int t = 0; t < a.n_tensors; ++t) bits |= (uint64_t)(uintptr_t)a.src[t] | (uint64_t)(uintptr_t)a.dst[t];
     if ((bits & 15) == 0) return 16;
     if ((bits & 7) == 0) return 8;
     if ((bits & 3) == 0) return 4;
     if ((bits & 1) == 0) return 2;
     return 1;
+}
+
+// ... that every address of the call is a multiple of (with_layer_stride = false: the layers are separate buffers).
+inline int vector_bytes(const GatherArgs& a, bool with_layer_stride = true)
+{
+    uint64_t bits = (uint64_t)a.row_bytes | (uint64_t)a.s_stream | (uint64_t)a.s_head | (uint64_t)a.s_pos |
+                    (uint64_t)a.d_stream | (uint64_t)a.d_head | (uint64_t)a.d_pos;
+    if (with_layer_stride) {
+        bits |= (uint64_t)a.s_layer | (uint64_t)a.d_layer;
+        for (int t = 0; t < a.n_tensors; ++t) bits |= (uint64_t)(uintptr_t)a.src[t] | (uint64_t)(uintptr_t)a.dst[t];
+    }
+    return widest_access(bits);
 }
 
 }  // namespace gather_dev

@@ -140,6 +140,38 @@ def test_compact_kv_argument_errors(b):
     assert call(n_streams=0) == b.SIRLLM_OK
 
 
+def test_compact_kv_layers_argument_errors(b):
+    L = b.raw()
+    lay = lambda **kw: b.sirllm_kv_layout(**{**dict(n_layers=3, n_kv_heads=2, head_dim=16, elem_bytes=4,
+                                                    stride_stream=2 * 64 * 16, stride_layer=12345, stride_head=64 * 16,
+                                                    stride_pos=16), **kw})
+    one = 2 * 64 * 16 * 4                                # bytes of one layer's buffer (one stream)
+    arr = lambda *ptrs: (C.c_void_p * len(ptrs))(*ptrs)
+    ksrc, kdst = arr(0x100000, 0x200000, 0x300000), arr(0x900000, 0xa00000, 0xb00000)
+    vsrc, vdst = arr(0x400000, 0x500000, 0x600000), arr(0xc00000, 0xd00000, 0xe00000)
+    def call(ks=ksrc, vs=None, s=lay(), n_src=64, kd=kdst, vd=None, d=lay(), ix=0x50000, istr=32, n_streams=1, n_keep=32):
+        return L.sirllm_compact_kv_layers(ks, vs, C.byref(s) if s else None, n_src, kd, vd, C.byref(d) if d else None,
+                                          ix, istr, n_streams, n_keep, None)
+    assert call(s=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(d=lay(n_layers=2)) == b.SIRLLM_ERR_INVALID_ARG                     # layer counts disagree
+    assert call(d=lay(head_dim=8)) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(ks=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(kd=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(ix=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(istr=31) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(vs=vsrc) == b.SIRLLM_ERR_INVALID_ARG                               # V source without V destination
+    assert call(ks=arr(0x100000, 0, 0x300000)) == b.SIRLLM_ERR_INVALID_ARG         # a layer without a buffer
+    assert call(ks=arr(0x100000, 0x200002, 0x300000)) == b.SIRLLM_ERR_INVALID_ARG  # 4-byte elements at an odd address
+    assert call(kd=arr(0x900000, 0x200000 + 64, 0xb00000)) == b.SIRLLM_ERR_INVALID_ARG   # a destination inside a source
+    assert call(kd=arr(0x900000, 0x900000 + one // 2, 0xb00000)) == b.SIRLLM_ERR_INVALID_ARG   # two destinations overlap
+    assert call(vs=vsrc, vd=arr(0xc00000, 0xd00000, 0x900000)) == b.SIRLLM_ERR_INVALID_ARG    # V destination on a K destination
+    assert call(n_keep=-1) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(n_keep=0) == b.SIRLLM_OK and call(n_streams=0) == b.SIRLLM_OK
+    assert call(s=lay(n_layers=0), d=lay(n_layers=0)) == b.SIRLLM_OK
+    # stride_layer is ignored: adjacent one-layer buffers are fine whatever it says
+    assert one == 0x2000
+
+
 def test_step_argument_errors(b):
     L = b.raw()
     p = b.sirllm_policy(4, 20, 8, 0.9)

@@ -257,6 +257,44 @@ def run_compact(b, ref, k_src, v_src, kept, n_src=None):
         assert bool((v_dst[:, :, :, n_keep:] == 77).all())
 
 
+@pytest.mark.parametrize("S,L,H,P,D,dtype,with_v", [
+    (2, 3, 2, 300, 128, torch.bfloat16, True),      # 256-byte rows, three layers
+    (1, 40, 2, 70, 64, torch.float32, True),        # more layers than one launch carries in its arguments (32)
+    (1, 33, 1, 50, 16, torch.float16, False),       # K only; one head per layer
+    (2, 2, 3, 41, 100, torch.bfloat16, True),       # 200-byte rows: 8-byte vectors
+    (1, 2, 2, 33, 5, torch.int16, True),            # 10-byte rows: 2-byte vectors
+    (1, 4, 8, 2000, 128, torch.bfloat16, True),     # several tiles per plane
+])
+def test_compact_per_layer_tensors_matches_oracle(b, ref, S, L, H, P, D, dtype, with_v):
+    """sirllm_compact_kv_layers: the cache as one [streams, heads, slots, head_dim] tensor per layer, sources and
+    destinations allocated separately (and destinations as views with padded slots), against the oracle layer by
+    layer; slots past n_keep and the padding stay untouched."""
+    rng = np.random.default_rng(S * 1000 + L * 10 + D)
+    g0 = torch.Generator(device=DEV).manual_seed(L * 7 + D)
+    def make(n):
+        t = torch.randint(-30000, 30000, (S, H, n, D), generator=g0, device=DEV, dtype=torch.int32)
+        return t.to(dtype) if dtype.is_floating_point else t.to(dtype)
+    ks = [make(P) for _ in range(L)]
+    vs = [make(P) for _ in range(L)] if with_v else None
+    n_keep = max(1, int(P * 0.6))
+    kept = np.stack([np.sort(rng.choice(P, n_keep, replace=False)) for _ in range(S)]).astype(np.int32)
+    kept[0, -1] = P + 5 if P > 40 else kept[0, -1]                   # an index with no source slot: a zero row
+    pad = 3
+    kd_full = [torch.full((S, H, n_keep + pad, D + 8), 77, dtype=dtype, device=DEV) for _ in range(L)]
+    vd_full = [torch.full((S, H, n_keep + pad, D + 8), 77, dtype=dtype, device=DEV) for _ in range(L)] if with_v else None
+    kd = [t[:, :, :, :D] for t in kd_full]
+    vd = [t[:, :, :, :D] for t in vd_full] if with_v else None
+    b.sirllm_compact_kv_layers(ks, vs, kd, vd, torch.from_numpy(kept).to(DEV), n_keep)
+    torch.cuda.synchronize()
+    for l in range(L):
+        rk, rv = ref.compact_kv(to_np(ks[l])[:, None], to_np(vs[l])[:, None] if with_v else None, kept)
+        np.testing.assert_array_equal(to_np(kd_full[l])[:, :, :n_keep, :D], rk[:, 0])
+        if with_v:
+            np.testing.assert_array_equal(to_np(vd_full[l])[:, :, :n_keep, :D], rv[:, 0])
+        for full in ([kd_full[l]] + ([vd_full[l]] if with_v else [])):
+            assert bool((full[:, :, n_keep:] == 77).all()) and bool((full[:, :, :, D:] == 77).all())
+
+
 def to_np_strided(t):
     """Host copy of a possibly strided device view, as a contiguous array (the oracle takes any strides itself)."""
     return to_np(t)
