@@ -279,6 +279,16 @@ int sirllm_compact_kv_inplace(void* k, void* v, const sirllm_kv_layout* layout, 
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * sirllm_compact_kv_inplace for a cache held as one K and one V buffer per layer: k[l], v[l] are device pointers to
+ * layer l's buffers, the two arrays of layout->n_layers pointers are HOST memory (see sirllm_compact_kv_layers); `layout`
+ * describes one layer, stride_layer is ignored.  v may be NULL.  No two buffers may overlap.
+ */
+int sirllm_compact_kv_inplace_layers(void* const* k, void* const* v, const sirllm_kv_layout* layout, int32_t n_src,
+                                     const int32_t* kept_idx, int64_t idx_stride,
+                                     int32_t n_streams, int32_t n_keep,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * One whole retention step (Alg. 1 with the loop rotated so that a call is
  * score -> decay held -> select -> compact; multiplying every candidate by the same
  * eta > 0 cannot change a comparison, so the kept sets equal those of the printed order).

@@ -47,7 +47,7 @@ SIRLLM_STATIC_SCRATCH_BYTES = 1048576
 SIRLLM_INPLACE_WORKSPACE_BYTES = 256
 
 EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_decay_select_static", "sirllm_compact_kv", "sirllm_compact_kv_layers",
-           "sirllm_step", "sirllm_baseline_select",
+           "sirllm_compact_kv_inplace_layers", "sirllm_step", "sirllm_baseline_select",
            "sirllm_compact_kv_inplace", "sirllm_step_ragged", "sirllm_score_partial",
            "sirllm_score_merge", "sirllm_lmhead_score", "sirllm_lmhead_workspace_bytes",
            "sirllm_step_lmhead", "sirllm_step_lmhead_workspace_bytes", "sirllm_step_lmhead_ragged",
@@ -62,6 +62,8 @@ _lib.sirllm_decay_select_static.restype = C.c_int
 _lib.sirllm_compact_kv.argtypes = [_vp, _vp, _LP, _i32, _vp, _vp, _LP, _vp, _i64, _i32, _i32, _vp]
 _lib.sirllm_compact_kv_layers.argtypes = [_vp, _vp, _LP, _i32, _vp, _vp, _LP, _vp, _i64, _i32, _i32, _vp]
 _lib.sirllm_compact_kv_layers.restype = C.c_int
+_lib.sirllm_compact_kv_inplace_layers.argtypes = [_vp, _vp, _LP, _i32, _vp, _i64, _i32, _i32, _vp, _sz, _vp]
+_lib.sirllm_compact_kv_inplace_layers.restype = C.c_int
 _lib.sirllm_step.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _i32, _i32, _PP,
                              _vp, _vp, _LP, _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _sz, _vp]
 _lib.sirllm_baseline_select.argtypes = [C.c_int, _i32, _i32, _PP, C.c_uint64, C.c_uint64, _vp, _i64,
@@ -344,6 +346,36 @@ def sirllm_compact_kv_layers(k_src, v_src, k_dst, v_dst, kept_idx: torch.Tensor,
                                          _ptr(kept_idx), _row_stride(kept_idx), n_streams, int(n_keep), _stream(stream)),
            "sirllm_compact_kv_layers")
     return k_dst, v_dst
+
+
+def sirllm_compact_kv_inplace_layers(k, v, kept_idx: torch.Tensor, n_keep: int, n_src: int | None = None,
+                                     workspace: torch.Tensor | None = None, stream=None):
+    """sirllm_compact_kv_inplace for a cache held as one [streams, kv_heads, slots, head_dim] tensor per layer: k and v
+    (v may be None) are sequences of such tensors sharing shape, strides and dtype."""
+    k = list(k)
+    v = None if v is None else list(v)
+    n_layers = len(k)
+    if v is not None and len(v) != n_layers:
+        raise ValueError("one K and one V tensor per layer")
+    _on_device(kept_idx, workspace, *k, *(v or []))
+    if kept_idx.dim() != 2 or kept_idx.dtype != torch.int32 or (kept_idx.shape[1] > 1 and kept_idx.stride(1) != 1):
+        raise ValueError("kept_idx must be [n_streams, >= n_keep] int32 with contiguous rows")
+    if n_layers == 0:
+        return k, v
+    first = (k[0].shape, k[0].stride(), k[0].dtype)
+    if any((t.shape, t.stride(), t.dtype) != first for t in k + (v or [])):
+        raise ValueError("all layers, K and V alike, must share shape, strides and dtype")
+    lay = layer_layout(k[0], n_layers)
+    n_src = k[0].shape[2] if n_src is None else int(n_src)
+    if k[0].shape[2] < n_src or kept_idx.shape[0] != k[0].shape[0]:
+        raise ValueError("cache has fewer than n_src slots, or stream counts differ")
+    ka = (C.c_void_p * n_layers)(*[t.data_ptr() for t in k])
+    va = None if v is None else (C.c_void_p * n_layers)(*[t.data_ptr() for t in v])
+    wp, wb = _ws(workspace)
+    _check(_lib.sirllm_compact_kv_inplace_layers(ka, va, C.byref(lay), n_src, _ptr(kept_idx), _row_stride(kept_idx),
+                                                 k[0].shape[0], int(n_keep), wp, wb, _stream(stream)),
+           "sirllm_compact_kv_inplace_layers")
+    return k, v
 
 
 def sirllm_compact_kv_inplace(k: torch.Tensor, v, kept_idx: torch.Tensor, n_keep: int, n_src: int | None = None,

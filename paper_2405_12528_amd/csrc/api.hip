@@ -508,6 +508,52 @@ int sirllm_compact_kv_inplace(void* k, void* v, const sirllm_kv_layout* layout, 
     return hip_status(launch_gather_inplace(g, workspace, workspace ? workspace_bytes : 0, (hipStream_t)hip_stream));
 }
 
+int sirllm_compact_kv_inplace_layers(void* const* k, void* const* v, const sirllm_kv_layout* layout, int32_t n_src,
+                                     const int32_t* kept_idx, int64_t idx_stride, int32_t n_streams, int32_t n_keep,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!layout_ok(layout)) return SIRLLM_ERR_INVALID_ARG;
+    if (n_streams < 0 || n_keep < 0 || n_src < 0 || n_keep > n_src) return SIRLLM_ERR_INVALID_ARG;
+    const int32_t n_layers = layout->n_layers;
+    if (n_streams == 0 || n_keep == 0 || n_layers == 0) return SIRLLM_OK;
+    if (!k || !kept_idx || idx_stride < n_keep) return SIRLLM_ERR_INVALID_ARG;
+    if ((int64_t)layout->head_dim * layout->elem_bytes * n_keep > 0x7fff0000LL) return SIRLLM_ERR_UNSUPPORTED;
+    if (workspace && ((uintptr_t)workspace & (kWorkspaceAlign - 1)) != 0) return SIRLLM_ERR_WORKSPACE;
+    sirllm_kv_layout one = *layout;                          // one layer: the layout with the layer dimension taken out
+    one.n_layers = 1;
+    one.stride_layer = 0;
+    const int64_t bytes = extent_bytes(&one, n_streams, n_src);
+    const uintptr_t em = (uintptr_t)layout->elem_bytes - 1;
+    const int n_tensors = v ? 2 : 1;
+    void* const* bufs[2] = {k, v};
+    for (int x = 0; x < n_tensors; ++x)
+        for (int l = 0; l < n_layers; ++l) {
+            if (!bufs[x][l] || ((uintptr_t)bufs[x][l] & em)) return SIRLLM_ERR_INVALID_ARG;
+            for (int y = 0; y <= x; ++y)
+                for (int m = 0; m < (y == x ? l : n_layers); ++m)
+                    if (ranges_overlap(bufs[x][l], bytes, bufs[y][m], bytes)) return SIRLLM_ERR_INVALID_ARG;
+        }
+    for (int l0 = 0; l0 < n_layers; l0 += kLayerTable) {
+        const int nl = n_layers - l0 < kLayerTable ? n_layers - l0 : kLayerTable;
+        one.n_layers = nl;
+        GatherArgs g = make_gather_args(k[l0], v ? v[l0] : nullptr, &one, n_src, k[l0], v ? v[l0] : nullptr, &one, kept_idx,
+                                        idx_stride, n_streams, n_keep);
+        g.src[0] = g.src[1] = nullptr;                       // the table below is what the kernel reads
+        g.dst[0] = g.dst[1] = nullptr;
+        LayerTable t;
+        for (int x = 0; x < 2; ++x)
+            for (int l = 0; l < kLayerTable; ++l) {
+                char* p = (x < n_tensors && l < nl) ? (char*)bufs[x][l0 + l] : nullptr;
+                t.src[x][l] = p;
+                t.dst[x][l] = p;
+            }
+        const int rc = hip_status(launch_gather_inplace_layers(g, t, workspace, workspace ? workspace_bytes : 0,
+                                                               (hipStream_t)hip_stream));
+        if (rc) return rc;
+    }
+    return SIRLLM_OK;
+}
+
 int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
                 float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held, int32_t n_new,
                 const sirllm_policy* policy, const void* k_src, const void* v_src, const sirllm_kv_layout* src,

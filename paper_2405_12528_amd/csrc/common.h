@@ -166,6 +166,9 @@ hipError_t launch_gather_layers(const GatherArgs& a, const LayerTable& t, hipStr
 // with at least SIRLLM_INPLACE_WORKSPACE_BYTES of device memory the workgroups take their planes in ticket order
 // (the call clears the counter itself), without it by block index.
 hipError_t launch_gather_inplace(const GatherArgs& a, void* scratch, size_t scratch_bytes, hipStream_t stream);
+// The same for a cache held as one buffer per layer and tensor (t.dst; a.n_layers <= kLayerTable).
+hipError_t launch_gather_inplace_layers(const GatherArgs& a, const LayerTable& t, void* scratch, size_t scratch_bytes,
+                                        hipStream_t stream);
 // Ragged batches: stream s holds held_dev[s] + (cu_new_dev[s+1] - cu_new_dev[s]) slots and is compacted
 // to `budget` slots only when it holds more and the selection did not flag it (n_keep_dev[s] >= 0); a.n_keep and
 // a.n_src are upper bounds.

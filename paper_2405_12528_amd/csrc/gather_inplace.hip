@@ -61,8 +61,10 @@ __device__ __forceinline__ char* plane_base(const GatherLaunch& g, int plane, in
 // A kernel, not a memset: the call may be recorded into a HIP graph.
 __global__ void ticket_clear_kernel(int32_t* ticket) { *ticket = 0; }
 
-template <typename VecT, int BLOCK, int UNROLL, bool NT, bool POW2, bool OFF64>
-__global__ __launch_bounds__(BLOCK) void gather_inplace_kernel(GatherLaunch g, Ragged rg, int32_t* ticket)
+// The walk of one plane by one workgroup.  base_of(plane, stream) is where that plane starts: by the layout's strides
+// when the cache is one buffer per tensor, from a table of pointers when it is one buffer per layer.
+template <typename VecT, int BLOCK, int UNROLL, bool NT, bool POW2, bool OFF64, typename BaseOf>
+__device__ __forceinline__ void inplace_walk(GatherLaunch g, const Ragged& rg, int32_t* ticket, BaseOf base_of)
 {
     // Which plane: by block index, or -- with a ticket counter -- the next one in the order in which workgroups
     // actually start, so that the workgroups in flight always walk neighbouring planes.  Every ticket below the
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(BLOCK) void gather_inplace_kernel(GatherLaunch g, R
     using off_t = typename std::conditional<OFF64, int64_t, uint32_t>::type;
     const int stream = g.stream0 + by;
     // bz picks one column part of the rows: parts never share a byte, so they need no ordering
-    char* base = plane_base(g, g.plane0 + bx, stream) + (int64_t)bz * (g.vpr * (int)sizeof(VecT));
+    char* base = base_of(g.plane0 + bx, stream) + (int64_t)bz * (g.vpr * (int)sizeof(VecT));
     const int32_t* idx = a.kept_idx + stream * a.idx_stride;
 
     const int n_items = (g.row_end - g.row_begin) * g.vpr;
@@ -156,6 +158,26 @@ __global__ __launch_bounds__(BLOCK) void gather_inplace_kernel(GatherLaunch g, R
     }
 }
 
+template <typename VecT, int BLOCK, int UNROLL, bool NT, bool POW2, bool OFF64>
+__global__ __launch_bounds__(BLOCK) void gather_inplace_kernel(GatherLaunch g, Ragged rg, int32_t* ticket)
+{
+    inplace_walk<VecT, BLOCK, UNROLL, NT, POW2, OFF64>(g, rg, ticket,
+                                                      [&](int plane, int stream) { return plane_base(g, plane, stream); });
+}
+
+// One buffer per layer and tensor: the default launch shape only; the table of base pointers rides in the kernel
+// arguments (t.dst; t.src is not used, source and destination are the same buffers).
+template <typename VecT, bool POW2, bool OFF64>
+__global__ __launch_bounds__(1024) void gather_inplace_layers_kernel(GatherLaunch g, Ragged rg, int32_t* ticket, LayerTable t)
+{
+    inplace_walk<VecT, 1024, 4, true, POW2, OFF64>(g, rg, ticket, [&](int plane, int stream) {
+        const int tensor = plane >= g.lh ? 1 : 0;
+        const int ph = plane - tensor * g.lh;
+        const int l = ph / g.a.n_heads, h = ph - l * g.a.n_heads;
+        return t.dst[tensor][l] + stream * g.a.s_stream + h * g.a.s_head;
+    });
+}
+
 template <typename VecT, int BLOCK, int UNROLL>
 void launch_shape(const GatherLaunch& g, const Ragged& rg, dim3 grid, bool pow2, bool off64, int32_t* ticket, hipStream_t stream)
 {
@@ -175,7 +197,7 @@ void launch_shape(const GatherLaunch& g, const Ragged& rg, dim3 grid, bool pow2,
 }
 
 template <typename VecT>
-hipError_t launch_vec(const GatherArgs& a, const Ragged& rg, int32_t* ticket, hipStream_t stream)
+hipError_t launch_vec(const GatherArgs& a, const Ragged& rg, int32_t* ticket, const LayerTable* layers, hipStream_t stream)
 {
     GatherLaunch g;
     bool pow2, off64;
@@ -199,7 +221,15 @@ hipError_t launch_vec(const GatherArgs& a, const Ragged& rg, int32_t* ticket, hi
         g.plane0 = 0;
         const dim3 grid((unsigned)planes, (unsigned)min(kMaxDim, a.n_streams - s0), (unsigned)parts);
         if (ticket) hipLaunchKernelGGL(ticket_clear_kernel, dim3(1), dim3(1), 0, stream, ticket);
-        if (block == 1024) {
+        if (layers) {
+            const dim3 blk(1024);
+            if (pow2) {
+                if (off64) hipLaunchKernelGGL((gather_inplace_layers_kernel<VecT, true, true>), grid, blk, 0, stream, g, rg, ticket, *layers);
+                else       hipLaunchKernelGGL((gather_inplace_layers_kernel<VecT, true, false>), grid, blk, 0, stream, g, rg, ticket, *layers);
+            } else {
+                hipLaunchKernelGGL((gather_inplace_layers_kernel<VecT, false, true>), grid, blk, 0, stream, g, rg, ticket, *layers);
+            }
+        } else if (block == 1024) {
             if (unroll == 2)      launch_shape<VecT, 1024, 2>(g, rg, grid, pow2, off64, ticket, stream);
             else if (unroll == 8) launch_shape<VecT, 1024, 8>(g, rg, grid, pow2, off64, ticket, stream);
             else                  launch_shape<VecT, 1024, 4>(g, rg, grid, pow2, off64, ticket, stream);
@@ -218,7 +248,8 @@ hipError_t launch_vec(const GatherArgs& a, const Ragged& rg, int32_t* ticket, hi
     return hipSuccess;
 }
 
-hipError_t launch_any(const GatherArgs& a, const Ragged& rg, void* scratch, size_t scratch_bytes, hipStream_t stream)
+hipError_t launch_any(const GatherArgs& a, const Ragged& rg, void* scratch, size_t scratch_bytes, const LayerTable* layers,
+                      hipStream_t stream)
 {
     if (a.n_keep <= 0 || a.n_streams <= 0 || a.row_bytes <= 0 || a.n_layers <= 0 || a.n_heads <= 0)
         return hipSuccess;
@@ -229,12 +260,19 @@ hipError_t launch_any(const GatherArgs& a, const Ragged& rg, void* scratch, size
     int32_t* ticket = nullptr;
     const int want = tuning::get("SIRLLM_INPLACE_TICKET", planes_total >= kTicketPlanes ? 1 : 0);
     if (scratch && scratch_bytes >= (size_t)SIRLLM_INPLACE_WORKSPACE_BYTES && want != 0) ticket = (int32_t*)scratch;
-    switch (gather_dev::vector_bytes(a)) {
-    case 16: return launch_vec<u32x4>(a, rg, ticket, stream);
-    case 8:  return launch_vec<u32x2>(a, rg, ticket, stream);
-    case 4:  return launch_vec<uint32_t>(a, rg, ticket, stream);
-    case 2:  return launch_vec<uint16_t>(a, rg, ticket, stream);
-    default: return launch_vec<uint8_t>(a, rg, ticket, stream);
+    int width = gather_dev::vector_bytes(a, layers == nullptr);
+    if (layers) {
+        uint64_t bits = (uint64_t)width;
+        for (int x = 0; x < a.n_tensors; ++x)
+            for (int l = 0; l < a.n_layers; ++l) bits |= (uint64_t)(uintptr_t)layers->dst[x][l];
+        width = gather_dev::widest_access(bits);
+    }
+    switch (width) {
+    case 16: return launch_vec<u32x4>(a, rg, ticket, layers, stream);
+    case 8:  return launch_vec<u32x2>(a, rg, ticket, layers, stream);
+    case 4:  return launch_vec<uint32_t>(a, rg, ticket, layers, stream);
+    case 2:  return launch_vec<uint16_t>(a, rg, ticket, layers, stream);
+    default: return launch_vec<uint8_t>(a, rg, ticket, layers, stream);
     }
 }
 
@@ -243,14 +281,23 @@ hipError_t launch_any(const GatherArgs& a, const Ragged& rg, void* scratch, size
 // a.src and a.dst name the same buffers; the s_* strides are used for both sides.
 hipError_t launch_gather_inplace(const GatherArgs& a, void* scratch, size_t scratch_bytes, hipStream_t stream)
 {
-    return launch_any(a, Ragged{nullptr, nullptr, nullptr, 0}, scratch, scratch_bytes, stream);
+    return launch_any(a, Ragged{nullptr, nullptr, nullptr, 0}, scratch, scratch_bytes, nullptr, stream);
+}
+
+// One buffer per layer and tensor: t.dst[x][l] is layer l of tensor x (a.src / a.dst and the layer stride of `a` are
+// not used; a.n_layers <= kLayerTable).
+hipError_t launch_gather_inplace_layers(const GatherArgs& a, const LayerTable& t, void* scratch, size_t scratch_bytes,
+                                        hipStream_t stream)
+{
+    if (a.n_layers > kLayerTable) return hipErrorInvalidValue;
+    return launch_any(a, Ragged{nullptr, nullptr, nullptr, 0}, scratch, scratch_bytes, &t, stream);
 }
 
 hipError_t launch_gather_inplace_ragged(const GatherArgs& a, const int32_t* held_dev, const int32_t* cu_new_dev,
                                         const int32_t* n_keep_dev, int32_t budget, void* scratch, size_t scratch_bytes,
                                         hipStream_t stream)
 {
-    return launch_any(a, Ragged{held_dev, cu_new_dev, n_keep_dev, budget}, scratch, scratch_bytes, stream);
+    return launch_any(a, Ragged{held_dev, cu_new_dev, n_keep_dev, budget}, scratch, scratch_bytes, nullptr, stream);
 }
 
 }  // namespace sirllm

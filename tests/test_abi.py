@@ -172,6 +172,30 @@ def test_compact_kv_layers_argument_errors(b):
     assert one == 0x2000
 
 
+def test_compact_kv_inplace_layers_argument_errors(b):
+    L = b.raw()
+    lay = lambda **kw: b.sirllm_kv_layout(**{**dict(n_layers=3, n_kv_heads=2, head_dim=16, elem_bytes=4,
+                                                    stride_stream=2 * 64 * 16, stride_layer=999, stride_head=64 * 16,
+                                                    stride_pos=16), **kw})
+    arr = lambda *ptrs: (C.c_void_p * len(ptrs))(*ptrs)
+    ks = arr(0x100000, 0x200000, 0x300000)
+    def call(k=ks, v=None, l=lay(), n_src=64, ix=0x50000, istr=32, n_streams=1, n_keep=32, ws=None, ws_bytes=0):
+        return L.sirllm_compact_kv_inplace_layers(k, v, C.byref(l) if l else None, n_src, ix, istr, n_streams, n_keep,
+                                                  ws, ws_bytes, None)
+    assert call(l=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(k=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(ix=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(n_keep=65) == b.SIRLLM_ERR_INVALID_ARG                             # cannot keep more than there is
+    assert call(istr=31) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(k=arr(0x100000, 0, 0x300000)) == b.SIRLLM_ERR_INVALID_ARG          # a layer without a buffer
+    assert call(k=arr(0x100000, 0x200002, 0x300000)) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(k=arr(0x100000, 0x100000 + 64, 0x300000)) == b.SIRLLM_ERR_INVALID_ARG   # two layers overlap
+    assert call(v=arr(0x400000, 0x300000, 0x600000)) == b.SIRLLM_ERR_INVALID_ARG        # a V buffer on a K buffer
+    assert call(ws=0x30000001, ws_bytes=1 << 20) == b.SIRLLM_ERR_WORKSPACE
+    assert call(n_keep=0) == b.SIRLLM_OK and call(n_streams=0) == b.SIRLLM_OK
+    assert call(l=lay(n_layers=0)) == b.SIRLLM_OK
+
+
 def test_step_argument_errors(b):
     L = b.raw()
     p = b.sirllm_policy(4, 20, 8, 0.9)

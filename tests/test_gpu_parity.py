@@ -615,6 +615,36 @@ def test_compact_inplace_matches_oracle(b, ref, S, L, H, P, D, dtype, frac, tick
 
 
 @pytest.mark.parametrize("ticket", [False, True], ids=["by block index", "by ticket"])
+@pytest.mark.parametrize("S,L,H,P,D,dtype,frac,with_v", [
+    (2, 3, 2, 300, 128, torch.bfloat16, 0.6, True),
+    (1, 40, 2, 5000, 64, torch.float32, 0.5, True),     # more layers than one launch carries (32); many chunks per plane
+    (1, 33, 1, 50, 16, torch.float16, 0.9, False),      # K only, one head per layer
+    (1, 2, 2, 33, 5, torch.int16, 0.7, True),           # 2-byte vectors
+    (2, 34, 64, 40, 8, torch.int16, 0.6, True),         # 8704 planes: ticket order with a workspace
+])
+def test_compact_inplace_per_layer_tensors_matches_oracle(b, ref, S, L, H, P, D, dtype, frac, with_v, ticket):
+    """sirllm_compact_kv_inplace_layers: one [streams, heads, slots, head_dim] tensor per layer, compacted in place,
+    against the oracle's in-place compaction layer by layer (kept rows and the untouched tail alike)."""
+    rng = np.random.default_rng(P * 11 + D + L)
+    mod = 32749 if dtype in (torch.int16, torch.bfloat16, torch.float16) else 1 << 31
+    k = [(synth.tagged_kv(S, 1, H, P, D, 2 * l) % mod).to(dtype)[:, 0].contiguous().to(DEV) for l in range(L)]
+    v = [(synth.tagged_kv(S, 1, H, P, D, 2 * l + 1) % mod).to(dtype)[:, 0].contiguous().to(DEV) for l in range(L)] if with_v else None
+    n_keep = max(1, int(P * frac))
+    kept = np.stack([np.sort(rng.choice(P, n_keep, replace=False)) for _ in range(S)]).astype(np.int32)
+    want_k = [to_np(t)[:, None].copy() for t in k]
+    want_v = [to_np(t)[:, None].copy() for t in v] if with_v else None
+    for l in range(L):
+        ref.compact_kv_inplace(want_k[l], want_v[l] if with_v else None, kept)
+    ws = inplace_scratch(b) if ticket else None
+    b.sirllm_compact_kv_inplace_layers(k, v, torch.from_numpy(kept).to(DEV), n_keep, workspace=ws)
+    torch.cuda.synchronize()
+    for l in range(L):
+        assert np.array_equal(to_np(k[l]), want_k[l][:, 0]), f"layer {l}: K differs"
+        if with_v:
+            assert np.array_equal(to_np(v[l]), want_v[l][:, 0]), f"layer {l}: V differs"
+
+
+@pytest.mark.parametrize("ticket", [False, True], ids=["by block index", "by ticket"])
 @pytest.mark.parametrize("dtype,D", [(torch.float32, 4), (torch.int16, 4), (torch.int16, 2), (torch.int16, 1), (torch.uint8, 1),
                                      (torch.bfloat16, 128)])
 def test_compact_inplace_chunk_boundaries(b, ref, dtype, D, ticket):
