@@ -315,6 +315,21 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The step without its K/V movement (Alg. 1: the entropy, decay and selection lines): exactly what sirllm_step does in
+ * front of its compaction, including the shared launch of scoring and selection when no new token can compete in
+ * Top_k.  For callers that move their caches themselves -- per-layer tensors through sirllm_compact_kv_layers or
+ * sirllm_compact_kv_inplace_layers, paged caches, a cache on another device.  Arguments, limits and workspace as for
+ * sirllm_step.  kept_idx / scores_out hold min(n_cand, budget) entries per stream afterwards.
+ */
+int sirllm_score_select(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld,
+                        const int32_t* token_ids,
+                        float* scores, int64_t scores_stride,
+                        int32_t n_streams, int32_t n_held, int32_t n_new,
+                        const sirllm_policy* policy,
+                        int32_t* kept_idx, int64_t idx_stride, float* scores_out, int64_t out_stride,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * One dialogue turn with the scores taken straight from the language-model head: sirllm_step with its first
  * stage replaced by sirllm_lmhead_score (Alg. 1, one loop iteration; Sec. 3.2 for the score).  hidden holds
  * n_streams * n_new rows, stream s owning rows [s*n_new, (s+1)*n_new); every other argument, the results and the

@@ -47,7 +47,7 @@ SIRLLM_STATIC_SCRATCH_BYTES = 1048576
 SIRLLM_INPLACE_WORKSPACE_BYTES = 256
 
 EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_decay_select_static", "sirllm_compact_kv", "sirllm_compact_kv_layers",
-           "sirllm_compact_kv_inplace_layers", "sirllm_step", "sirllm_baseline_select",
+           "sirllm_compact_kv_inplace_layers", "sirllm_step", "sirllm_score_select", "sirllm_baseline_select",
            "sirllm_compact_kv_inplace", "sirllm_step_ragged", "sirllm_score_partial",
            "sirllm_score_merge", "sirllm_lmhead_score", "sirllm_lmhead_workspace_bytes",
            "sirllm_step_lmhead", "sirllm_step_lmhead_workspace_bytes", "sirllm_step_lmhead_ragged",
@@ -66,6 +66,9 @@ _lib.sirllm_compact_kv_inplace_layers.argtypes = [_vp, _vp, _LP, _i32, _vp, _i64
 _lib.sirllm_compact_kv_inplace_layers.restype = C.c_int
 _lib.sirllm_step.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _i32, _i32, _PP,
                              _vp, _vp, _LP, _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _sz, _vp]
+_lib.sirllm_score_select.argtypes = [_vp, C.c_int, _i32, _i64, _vp, _vp, _i64, _i32, _i32, _i32, _PP,
+                                     _vp, _i64, _vp, _i64, _vp, _sz, _vp]
+_lib.sirllm_score_select.restype = C.c_int
 _lib.sirllm_baseline_select.argtypes = [C.c_int, _i32, _i32, _PP, C.c_uint64, C.c_uint64, _vp, _i64,
                                         C.POINTER(C.c_int32), _vp, _sz, _vp]
 _lib.sirllm_baseline_select.restype = C.c_int
@@ -400,6 +403,34 @@ def sirllm_compact_kv_inplace(k: torch.Tensor, v, kept_idx: torch.Tensor, n_keep
 def kv_layout_tuple(t):
     L = kv_layout(t)
     return tuple(getattr(L, f) for f, _ in sirllm_kv_layout._fields_)
+
+
+def sirllm_score_select(logits: torch.Tensor, token_ids: torch.Tensor, vocab: int, scores: torch.Tensor, n_held: int,
+                        n_new: int, policy, kept_idx: torch.Tensor, scores_out: torch.Tensor,
+                        workspace: torch.Tensor | None = None, stream=None) -> int:
+    """The step without its K/V movement: scores the new tokens, decays, selects; returns n_keep.  Shapes as in
+    sirllm_step."""
+    _on_device(logits, token_ids, scores, kept_idx, scores_out, workspace)
+    n_streams = scores.shape[0]
+    if logits.dim() != 2 or (logits.shape[1] > 1 and logits.stride(1) != 1):
+        raise ValueError("logits must be [n_streams*n_new, ld] with contiguous rows")
+    if logits.shape[0] != n_streams * n_new or token_ids.numel() != n_streams * n_new:
+        raise ValueError("one logits row and one token id per new token")
+    if token_ids.dtype != torch.int32 or not token_ids.is_contiguous():
+        raise TypeError("token_ids must be contiguous int32")
+    for t, dt in ((scores, torch.float32), (kept_idx, torch.int32), (scores_out, torch.float32)):
+        if t.dim() != 2 or t.dtype != dt or (t.shape[1] > 1 and t.stride(1) != 1) or t.shape[0] != n_streams:
+            raise ValueError("scores / kept_idx / scores_out must be [n_streams, n] with contiguous rows")
+    ld = logits.stride(0) if logits.shape[0] > 1 else logits.shape[1]
+    p = _policy(policy)
+    wp, wb = _ws(workspace)
+    dtc = _dtype_code(logits) if n_new > 0 else SIRLLM_F32
+    _check(_lib.sirllm_score_select(_ptr(logits) if n_new else None, dtc, int(vocab), ld,
+                                    _ptr(token_ids) if n_new else None, _ptr(scores), _row_stride(scores), n_streams,
+                                    int(n_held), int(n_new), C.byref(p), _ptr(kept_idx), _row_stride(kept_idx),
+                                    _ptr(scores_out), _row_stride(scores_out), wp, wb, _stream(stream)),
+           "sirllm_score_select")
+    return min(n_held + n_new, p.n_sink + p.n_topk + p.n_recent)
 
 
 def sirllm_step(logits: torch.Tensor, token_ids: torch.Tensor, vocab: int, scores: torch.Tensor, n_held: int,

@@ -104,6 +104,63 @@ class RetentiveCache:
         self.n_held = 0
 
 
+class LayeredRetentiveCache:
+    """The same state with K and V held as one [streams, kv_heads, capacity, head_dim] tensor PER LAYER, the way model
+    code usually keeps its past keys and values; compacted in place.  A step is sirllm_score_select followed by
+    sirllm_compact_kv_inplace_layers."""
+
+    def __init__(self, n_streams: int, n_layers: int, n_kv_heads: int, head_dim: int, policy, max_new: int,
+                 kv_dtype=torch.bfloat16, device="cuda:0"):
+        self.policy = b.Policy(*policy)
+        self.budget = self.policy.n_sink + self.policy.n_topk + self.policy.n_recent
+        self.capacity = self.budget + max_new
+        self.n_streams, self.max_new, self.device = n_streams, max_new, device
+        shape = (n_streams, n_kv_heads, self.capacity, head_dim)
+        self.k = [torch.zeros(shape, dtype=kv_dtype, device=device) for _ in range(n_layers)]
+        self.v = [torch.zeros(shape, dtype=kv_dtype, device=device) for _ in range(n_layers)]
+        self._scores = [torch.zeros((n_streams, self.capacity), device=device) for _ in range(2)]
+        self.kept_idx = torch.zeros((n_streams, self.capacity), dtype=torch.int32, device=device)
+        self._cur = 0
+        self.n_held = 0
+        nbytes = max(b.sirllm_workspace_bytes(n_streams, self.capacity, n_streams * max_new, 1 << 20),
+                     b.SIRLLM_INPLACE_WORKSPACE_BYTES)
+        self._ws = torch.zeros(nbytes, dtype=torch.uint8, device=device)
+
+    @property
+    def scores(self) -> torch.Tensor:
+        """[streams, capacity]; entries [0, n_held) are the (decayed) token entropies of the live slots."""
+        return self._scores[self._cur]
+
+    def new_kv_slots(self, layer: int, n_new: int):
+        """The K and V views of one layer that the model writes this turn's n_new tokens into, before step()."""
+        if n_new > self.max_new or self.n_held + n_new > self.capacity:
+            raise ValueError("more new tokens than the cache was sized for")
+        s = slice(self.n_held, self.n_held + n_new)
+        return self.k[layer][:, :, s, :], self.v[layer][:, :, s, :]
+
+    def step(self, logits: torch.Tensor, token_ids: torch.Tensor, vocab: int, stream=None) -> bool:
+        """Score the n_new = logits.shape[0] / n_streams tokens at slots [n_held, n_held + n_new), decay, select and
+        compact every layer in place.  Returns True when slots were evicted."""
+        n_new = logits.shape[0] // self.n_streams
+        if n_new * self.n_streams != logits.shape[0] or n_new > self.max_new:
+            raise ValueError("logits must hold n_streams * n_new rows with n_new <= max_new")
+        cur, oth = self._cur, 1 - self._cur
+        n_cand = self.n_held + n_new
+        n_keep = b.sirllm_score_select(logits, token_ids, vocab, self._scores[cur], self.n_held, n_new, self.policy,
+                                       self.kept_idx, self._scores[oth], workspace=self._ws, stream=stream)
+        evicted = n_cand > n_keep
+        if evicted:
+            b.sirllm_compact_kv_inplace_layers(self.k, self.v, self.kept_idx, n_keep, n_src=n_cand, workspace=self._ws,
+                                               stream=stream)
+        self._cur = oth
+        self.n_held = n_keep
+        return evicted
+
+    def reset(self):
+        """Start a new dialogue: forget every slot (buffers are reused as they are)."""
+        self.n_held = 0
+
+
 class RaggedRetentiveCache:
     """The same state for a serving batch whose streams are at different turns: every stream has its
     own slot count and takes its own number of new tokens per step; K/V are compacted in place, so

@@ -554,6 +554,61 @@ int sirllm_compact_kv_inplace_layers(void* const* k, void* const* v, const sirll
     return SIRLLM_OK;
 }
 
+namespace {
+
+// The part of a step in front of the K/V movement: E_t = Entropy(new tokens) behind the held scores, E <- E * eta on
+// the held part, Id = sink + Top_k + recent, E <- E[Id].  All arguments are validated by the caller.
+int score_and_select(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
+                     float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held, int32_t n_new,
+                     const sirllm_policy* policy, int32_t* kept_idx, int64_t idx_stride, float* scores_out,
+                     int64_t out_stride, void* workspace, hipStream_t stream)
+{
+    const int64_t n_rows = (int64_t)n_streams * n_new;
+    const int32_t n_cand = n_held + n_new;
+    const bool evict = (int64_t)n_cand > budget_of(policy);
+    const int32_t n_keep = evict ? (int32_t)budget_of(policy) : n_cand;
+    ScoreArgs a;
+    a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
+    a.n_rows = n_rows; a.rows_per_stream = n_new > 0 ? n_new : 1;
+    a.out_a = scores + n_held; a.stride_a = scores_stride; a.out_b = nullptr; a.stride_b = 0;
+    a.partial = nullptr; a.v_begin = 0; a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0; a.budget_r = 0;
+    const SelectArgs s = make_select_args(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx,
+                                          idx_stride, scores_out, out_stride);
+    if (evict && score_select_fusable(a, s)) {
+        // The new tokens all sit in the recent window: Top_k does not look at this turn's scores, so
+        // one launch scores the rows and selects at the same time.  New token t of a stream ends up
+        // at in-cache position n_keep - n_new + t; the scoring workgroups write it there themselves.
+        a.out_b = scores_out + (n_keep - n_new); a.stride_b = out_stride;
+        return hip_status(launch_score_select(a, s, dt, stream));
+    }
+    if (n_rows > 0) {
+        const int rc = hip_status(launch_score(a, dt, stream));
+        if (rc) return rc;
+    }
+    if (!evict) return hip_status(launch_keep_all(s, stream));
+    return hip_status(n_cand > SIRLLM_SINGLE_WG_CAND ? launch_select_large(s, workspace, stream) : launch_select(s, stream));
+}
+
+}  // namespace
+
+int sirllm_score_select(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
+                        float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held, int32_t n_new,
+                        const sirllm_policy* policy, int32_t* kept_idx, int64_t idx_stride,
+                        float* scores_out, int64_t out_stride, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (n_streams < 0 || n_held < 0 || n_new < 0) return SIRLLM_ERR_INVALID_ARG;
+    int rc = validate_score(logits, dt, (int64_t)n_streams * n_new, vocab, ld, token_ids);
+    if (rc) return rc;
+    rc = validate_select(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx, idx_stride,
+                         scores_out, out_stride);
+    if (rc) return rc;
+    if (n_streams == 0 || n_held + n_new == 0) return SIRLLM_OK;
+    rc = workspace_check(workspace, workspace_bytes, sirllm_workspace_bytes(n_streams, n_held + n_new, 0, 0));
+    if (rc) return rc;
+    return score_and_select(logits, dt, vocab, ld, token_ids, scores, scores_stride, n_streams, n_held, n_new, policy,
+                            kept_idx, idx_stride, scores_out, out_stride, workspace, (hipStream_t)hip_stream);
+}
+
 int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
                 float* scores, int64_t scores_stride, int32_t n_streams, int32_t n_held, int32_t n_new,
                 const sirllm_policy* policy, const void* k_src, const void* v_src, const sirllm_kv_layout* src,
@@ -578,33 +633,9 @@ int sirllm_step(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, 
     rc = workspace_check(workspace, workspace_bytes, sirllm_workspace_bytes(n_streams, n_cand, n_rows, vocab));
     if (rc) return rc;
     hipStream_t stream = (hipStream_t)hip_stream;
-
-    ScoreArgs a;
-    a.logits = logits; a.ld = ld; a.vocab = vocab; a.token_ids = token_ids;
-    a.n_rows = n_rows; a.rows_per_stream = n_new > 0 ? n_new : 1;
-    a.out_a = scores + n_held; a.stride_a = scores_stride; a.out_b = nullptr; a.stride_b = 0;
-    a.partial = nullptr; a.v_begin = 0; a.cu_rows = nullptr; a.held_dev = nullptr; a.n_streams_r = 0; a.budget_r = 0;
-    const SelectArgs s = make_select_args(scores, scores_stride, n_streams, n_held, n_new, policy, kept_idx,
-                                          idx_stride, scores_out, out_stride);
-    if (evict && score_select_fusable(a, s)) {
-        // The new tokens all sit in the recent window: Top_k does not look at this turn's scores, so
-        // one launch scores the rows and selects at the same time.  New token t of a stream ends up
-        // at in-cache position n_keep - n_new + t; the scoring workgroups write it there themselves.
-        a.out_b = scores_out + (n_keep - n_new); a.stride_b = out_stride;
-        rc = hip_status(launch_score_select(a, s, dt, stream));
-        if (rc) return rc;
-    } else {
-        // E_t = Entropy(new tokens), appended behind the held scores
-        if (n_rows > 0) {
-            rc = hip_status(launch_score(a, dt, stream));
-            if (rc) return rc;
-        }
-        // E <- E * eta on the held part; Id = sink + Top_k + recent; E <- E[Id]
-        if (!evict) return hip_status(launch_keep_all(s, stream));
-        rc = hip_status(n_cand > SIRLLM_SINGLE_WG_CAND ? launch_select_large(s, workspace, stream)
-                                                         : launch_select(s, stream));
-        if (rc) return rc;
-    }
+    rc = score_and_select(logits, dt, vocab, ld, token_ids, scores, scores_stride, n_streams, n_held, n_new, policy,
+                          kept_idx, idx_stride, scores_out, out_stride, workspace, stream);
+    if (rc || !evict) return rc;
     // KV <- KV[Id]
     const GatherArgs g = make_gather_args(k_src, v_src, src, n_cand, k_dst, v_dst, dst, kept_idx, idx_stride,
                                           n_streams, n_keep);

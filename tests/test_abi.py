@@ -196,6 +196,29 @@ def test_compact_kv_inplace_layers_argument_errors(b):
     assert call(l=lay(n_layers=0)) == b.SIRLLM_OK
 
 
+def test_score_select_argument_errors(b):
+    L = b.raw()
+    p = b.sirllm_policy(4, 20, 8, 0.9)
+    def call(logits=0x1000, dt=0, vocab=1000, ld=1000, tok=0x2000000, scores=0x3000000, sstr=128, n_streams=1, n_held=32,
+             n_new=64, pol=p, idx=0x5000000, istr=32, out=0x6000000, ostr=32, ws=None, ws_bytes=0):
+        return L.sirllm_score_select(logits, dt, vocab, ld, tok, scores, sstr, n_streams, n_held, n_new,
+                                     C.byref(pol) if pol else None, idx, istr, out, ostr, ws, ws_bytes, None)
+    assert call(dt=7) == b.SIRLLM_ERR_UNSUPPORTED
+    assert call(logits=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(tok=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(ld=999) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(pol=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(scores=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(sstr=95) == b.SIRLLM_ERR_INVALID_ARG                    # scores_stride < n_cand
+    assert call(idx=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(istr=31) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(out=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(n_new=-1) == b.SIRLLM_ERR_INVALID_ARG
+    assert call(n_held=40000, n_new=64, sstr=40064) == b.SIRLLM_ERR_WORKSPACE   # above 32768 slots the selection needs scratch
+    assert call(n_streams=0) == b.SIRLLM_OK
+    assert call(n_held=0, n_new=0, logits=None, tok=None) == b.SIRLLM_OK
+
+
 def test_step_argument_errors(b):
     L = b.raw()
     p = b.sirllm_policy(4, 20, 8, 0.9)

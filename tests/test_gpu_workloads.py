@@ -264,6 +264,52 @@ def test_dailydialog_shaped_dialogues_with_resets(b, ref):
     assert 4 <= outgrew <= 16, outgrew
 
 
+def test_per_layer_cache_dialogues(b, ref):
+    """LayeredRetentiveCache: K and V as one tensor per layer, stepped by sirllm_score_select and compacted in place
+    by sirllm_compact_kv_inplace_layers.  Eight synthetic dialogues with resets in between (budget 512 = 4 + 380 +
+    128: some turns fit the recent window and share a launch for scoring and selection, some do not); every turn is
+    checked against the oracle fed the GPU's scores, layer by layer."""
+    from paper_2405_12528_amd.cache import LayeredRetentiveCache
+    V, L, H, D, S = 5000, 3, 2, 64, 2
+    pol = (4, 380, 128, 0.7)
+    rng = np.random.default_rng(99)
+    g0 = torch.Generator(device=DEV).manual_seed(17)
+    cache = LayeredRetentiveCache(S, L, H, D, pol, max_new=300, device=DEV)
+    evictions = 0
+    for dialogue in range(8):
+        cache.reset()
+        for n_new in (int(x) for x in rng.integers(20, 300, size=int(rng.integers(3, 7)))):
+            z = (torch.randn((S * n_new, V), generator=g0, device=DEV) * 3.0).to(torch.bfloat16)
+            tok = torch.randint(0, V, (S * n_new,), generator=g0, device=DEV, dtype=torch.int32)
+            for l in range(L):
+                k_new, v_new = cache.new_kv_slots(l, n_new)
+                k_new.copy_(torch.randn(k_new.shape, generator=g0, device=DEV).to(k_new.dtype))
+                v_new.copy_(torch.randn(v_new.shape, generator=g0, device=DEV).to(v_new.dtype))
+            n_held = cache.n_held
+            n_cand = n_held + n_new
+            held = cache.scores[:, :n_held].clone()
+            k_pre = [to_np(t[:, :, :n_cand])[:, None].copy() for t in cache.k]
+            v_pre = [to_np(t[:, :, :n_cand])[:, None].copy() for t in cache.v]
+            s_pre = cache.scores
+            evicted = cache.step(z, tok, V)
+            torch.cuda.synchronize()
+            evictions += int(evicted)
+            assert evicted == (n_cand > 512) and cache.n_held == min(n_cand, 512)
+            n_keep = cache.n_held
+            Eg = to_np(s_pre[:, :n_cand])
+            assert_scores_close(Eg[:, n_held:].reshape(-1), ref.score(to_np(z), to_np(tok), vocab=V))
+            np.testing.assert_array_equal(Eg[:, :n_held].view(np.uint32), to_np(held).view(np.uint32))
+            ri, ro = ref.decay_select(Eg, n_held, n_new, ref.Policy(*pol))
+            np.testing.assert_array_equal(to_np(cache.kept_idx[:, :n_keep]), ri)
+            np.testing.assert_array_equal(to_np(cache.scores[:, :n_keep]).view(np.uint32), ro.view(np.uint32))
+            for l in range(L):
+                if evicted:
+                    ref.compact_kv_inplace(k_pre[l], v_pre[l], ri, n_src=n_cand)
+                assert np.array_equal(to_np(cache.k[l][:, :, :n_cand]), k_pre[l][:, 0]), f"layer {l}: K differs"
+                assert np.array_equal(to_np(cache.v[l][:, :, :n_cand]), v_pre[l][:, 0]), f"layer {l}: V differs"
+    assert evictions >= 5
+
+
 def test_step_replays_from_a_captured_graph(b, ref):
     """sirllm_step allocates nothing, synchronises nothing and clears nothing with memset nodes, so it
     can be captured into a HIP graph; every replay must reproduce the eager result, also with eager
