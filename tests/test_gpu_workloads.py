@@ -358,6 +358,56 @@ def test_step_replays_from_a_captured_graph(b, ref):
             assert torch.equal(cap[name], eager[name]), f"replay {rep}: {name} differs from the eager run"
 
 
+def test_per_layer_step_replays_from_a_captured_graph(b):
+    """sirllm_score_select + sirllm_compact_kv_layers (the per-layer pointer table travels in the kernel arguments, so
+    nothing is staged or allocated) captured into a HIP graph: every replay reproduces the eager result."""
+    pol = b.Policy(4, 22, 8, 0.8)
+    S, L, H, D, n_held, n_new, V, n_keep = 2, 3, 2, 16, 60, 40, 777, 34
+    g0 = torch.Generator(device=DEV).manual_seed(6)
+    z = torch.randn((S * n_new, V), generator=g0, device=DEV) * 2
+    tok = torch.randint(0, V, (S * n_new,), generator=g0, device=DEV, dtype=torch.int32)
+    held = torch.rand((S, n_held), generator=g0, device=DEV) * 6
+    k_c = [torch.randn((S, H, n_held + n_new, D), generator=g0, device=DEV) for _ in range(L)]
+    v_c = [torch.randn((S, H, n_held + n_new, D), generator=g0, device=DEV) for _ in range(L)]
+
+    def fresh():
+        E = torch.zeros((S, n_held + n_new), device=DEV)
+        E[:, :n_held] = held
+        t = dict(E=E, idx=torch.zeros((S, n_keep), dtype=torch.int32, device=DEV), out=torch.zeros((S, n_keep), device=DEV))
+        for l in range(L):
+            t[f"k{l}"] = torch.zeros((S, H, n_keep, D), device=DEV)
+            t[f"v{l}"] = torch.zeros((S, H, n_keep, D), device=DEV)
+        return t
+
+    def run(t):
+        assert b.sirllm_score_select(z, tok, V, t["E"], n_held, n_new, pol, t["idx"], t["out"]) == n_keep
+        b.sirllm_compact_kv_layers(k_c, v_c, [t[f"k{l}"] for l in range(L)], [t[f"v{l}"] for l in range(L)], t["idx"], n_keep,
+                                   n_src=n_held + n_new)
+
+    eager = fresh()
+    run(eager)
+    torch.cuda.synchronize()
+    cap = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(cap)                                         # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(cap)
+    for rep in range(3):
+        for name, t in cap.items():                      # eager work between replays: wipe every output
+            t.zero_() if name != "E" else t[:, n_held:].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in eager:
+            assert torch.equal(cap[name], eager[name]), f"replay {rep}: {name} differs from the eager run"
+    assert eager["k0"].abs().sum() > 0
+
+
 @pytest.mark.parametrize("from_hidden", [False, True], ids=["logits", "hidden states"])
 def test_ragged_dialogues_of_unequal_length(b, ref, from_hidden):
     """Six dialogues in one serving batch, each with its own arrival turn and its own number of tokens per
