@@ -18,9 +18,9 @@ __global__ __launch_bounds__(BLOCK) void gather_rows_kernel(GatherLaunch g)
 }
 
 template <typename VecT, bool POW2, bool OFF64>
-__global__ __launch_bounds__(512) void gather_rows_layers_kernel(GatherLaunch g, LayerTable t)
+__global__ __launch_bounds__(128) void gather_rows_layers_kernel(GatherLaunch g, LayerTable t)
 {
-    gather_dev::gather_tile_layers<VecT, 512, 1, true, POW2, OFF64>(g, t, (int)blockIdx.x, g.plane0 + (int)blockIdx.y,
+    gather_dev::gather_tile_layers<VecT, 128, 1, true, POW2, OFF64>(g, t, (int)blockIdx.x, g.plane0 + (int)blockIdx.y,
                                                                    g.stream0 + (int)blockIdx.z);
 }
 
@@ -45,9 +45,14 @@ hipError_t launch_vec(const GatherArgs& a, int row_begin, int row_end, hipStream
     if (!gather_dev::fill_launch<VecT>(g, a, row_begin, row_end, &pow2, &off64)) return hipErrorInvalidValue;
     const int64_t n_items = (int64_t)(row_end - row_begin) * g.vpr;
 
-    const int block = tuning::get("SIRLLM_GATHER_BLOCK", 512);
-    const int unroll = tuning::get("SIRLLM_GATHER_UNROLL", 1);
-    const bool nt = tuning::get("SIRLLM_GATHER_NT", 1) != 0;
+    // Small workgroups: a workgroup's wave slots come free only when its slowest wave is done, and a tile of two waves
+    // (8 rows of 256 bytes) wastes fewer of them than one of eight.  Measured on the seven workloads of bench.py against
+    // 512 threads: 1 to 6.5 % less time at 128, never more; 64 threads gain another 1 to 4 % on five of them but lose 9 %
+    // on long contiguous runs (a kept list that is one run), so 128 it is.
+    int block = tuning::get("SIRLLM_GATHER_BLOCK", 128);
+    if (block != 64 && block != 256 && block != 512) block = 128;
+    const int unroll = block == 64 ? 1 : (tuning::get("SIRLLM_GATHER_UNROLL", 1) == 2 ? 2 : 1);
+    const bool nt = block == 64 || tuning::get("SIRLLM_GATHER_NT", 1) != 0;
     const int per_block = block * unroll;
     const unsigned n_tiles = (unsigned)((n_items + per_block - 1) / per_block);
     const int planes = a.n_tensors * g.lh;
@@ -57,12 +62,17 @@ hipError_t launch_vec(const GatherArgs& a, int row_begin, int row_end, hipStream
             g.stream0 = s0;
             g.plane0 = p0;
             const dim3 grid(n_tiles, (unsigned)min(kMaxDim, planes - p0), (unsigned)min(kMaxDim, a.n_streams - s0));
-            if (block == 256) {
+            if (block == 64) {
+                launch_shape<VecT, 64, 1, true>(g, grid, pow2, off64, stream);
+            } else if (block == 256) {
                 if (unroll == 2) { if (nt) launch_shape<VecT, 256, 2, true>(g, grid, pow2, off64, stream); else launch_shape<VecT, 256, 2, false>(g, grid, pow2, off64, stream); }
                 else             { if (nt) launch_shape<VecT, 256, 1, true>(g, grid, pow2, off64, stream); else launch_shape<VecT, 256, 1, false>(g, grid, pow2, off64, stream); }
-            } else {
+            } else if (block == 512) {
                 if (unroll == 2) { if (nt) launch_shape<VecT, 512, 2, true>(g, grid, pow2, off64, stream); else launch_shape<VecT, 512, 2, false>(g, grid, pow2, off64, stream); }
                 else             { if (nt) launch_shape<VecT, 512, 1, true>(g, grid, pow2, off64, stream); else launch_shape<VecT, 512, 1, false>(g, grid, pow2, off64, stream); }
+            } else {
+                if (unroll == 2) { if (nt) launch_shape<VecT, 128, 2, true>(g, grid, pow2, off64, stream); else launch_shape<VecT, 128, 2, false>(g, grid, pow2, off64, stream); }
+                else             { if (nt) launch_shape<VecT, 128, 1, true>(g, grid, pow2, off64, stream); else launch_shape<VecT, 128, 1, false>(g, grid, pow2, off64, stream); }
             }
             const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
@@ -71,7 +81,7 @@ hipError_t launch_vec(const GatherArgs& a, int row_begin, int row_end, hipStream
     return hipSuccess;
 }
 
-// Per-layer buffers: the default launch shape only (512 threads, one vector per lane, non-temporal accesses).
+// Per-layer buffers: the default launch shape only (128 threads, one vector per lane, non-temporal accesses).
 template <typename VecT>
 hipError_t launch_vec_layers(const GatherArgs& a, const LayerTable& t, hipStream_t stream)
 {
@@ -79,10 +89,10 @@ hipError_t launch_vec_layers(const GatherArgs& a, const LayerTable& t, hipStream
     bool pow2, off64;
     if (!gather_dev::fill_launch<VecT>(g, a, 0, a.n_keep, &pow2, &off64)) return hipErrorInvalidValue;
     const int64_t n_items = (int64_t)a.n_keep * g.vpr;
-    const unsigned n_tiles = (unsigned)((n_items + 511) / 512);
+    const unsigned n_tiles = (unsigned)((n_items + 127) / 128);
     const int planes = a.n_tensors * g.lh;            // at most 2 * 32 * n_heads
     constexpr int kMaxDim = 65535;
-    const dim3 block(512);
+    const dim3 block(128);
     for (int s0 = 0; s0 < a.n_streams; s0 += kMaxDim) {
         for (int p0 = 0; p0 < planes; p0 += kMaxDim) {
             g.stream0 = s0;

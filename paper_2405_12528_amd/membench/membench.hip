@@ -1,18 +1,17 @@
 // Plain streaming kernels that measure what this GPU's memory system gives a read-only scan, a write-only
 // fill and a copy, with the same access shape the library's kernels use (one 16-byte non-temporal vector per
-// lane per step).  They are measurement references for bench.py, not part of the retention path: the score
-// scan is compared with the read stream, the K/V gather with the copy.
+// lane per step), in workgroups of 128 or of 512 threads.  They are measurement references for bench.py, not part
+// of the retention path: the score scan is compared with the read stream, the K/V gather with the copy.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-constexpr int kBlock = 512;
 
 // Every lane reads `per_lane` vectors a whole workgroup sweep apart; the XOR of what it read is stored only if
 // it equals a value that random data never produces, so the loads cannot be dropped.
-template <int UNROLL>
+template <int kBlock, int UNROLL>
 __global__ __launch_bounds__(kBlock) void read_kernel(const u32x4* src, uint64_t n_vec, uint32_t* sink)
 {
     const uint64_t base = (uint64_t)blockIdx.x * (kBlock * UNROLL) + threadIdx.x;
@@ -25,6 +24,7 @@ __global__ __launch_bounds__(kBlock) void read_kernel(const u32x4* src, uint64_t
     if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u && acc.x == 0x7f4a7c15u) sink[0] = acc.y;
 }
 
+template <int kBlock>
 __global__ __launch_bounds__(kBlock) void write_kernel(u32x4* dst, uint64_t n_vec, uint32_t value)
 {
     const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -32,49 +32,61 @@ __global__ __launch_bounds__(kBlock) void write_kernel(u32x4* dst, uint64_t n_ve
     if (i < n_vec) __builtin_nontemporal_store(v, dst + i);
 }
 
+template <int kBlock>
 __global__ __launch_bounds__(kBlock) void copy_kernel(u32x4* dst, const u32x4* src, uint64_t n_vec)
 {
     const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i < n_vec) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+bool shape_ok(int threads) { return threads == 128 || threads == 512; }
 bool aligned(const void* p, size_t bytes) { return ((uintptr_t)p & 15) == 0 && (bytes & 15) == 0 && bytes > 0 && bytes <= ((size_t)1 << 40); }
 
 }  // namespace
 
 extern "C" {
 
-// All three: device pointers, 16-byte aligned, `bytes` a multiple of 16; enqueue on `stream` and return at once.
-// Return 0, or -1 for bad arguments, -2 when the launch was refused.
-int membench_read(const void* src, size_t bytes, void* sink, void* stream)
+// All three: device pointers, 16-byte aligned, `bytes` a multiple of 16, `threads` (per workgroup) 128 or 512; enqueue on
+// `stream` and return at once.  Return 0, or -1 for bad arguments, -2 when the launch was refused.
+int membench_read(const void* src, size_t bytes, void* sink, int threads, void* stream)
 {
-    if (!src || !sink || !aligned(src, bytes)) return -1;
+    if (!src || !sink || !aligned(src, bytes) || !shape_ok(threads)) return -1;
     const uint64_t n_vec = bytes / 16;
     constexpr int UNROLL = 4;
-    const uint64_t blocks = (n_vec + kBlock * UNROLL - 1) / (kBlock * UNROLL);
+    const uint64_t blocks = (n_vec + (uint64_t)threads * UNROLL - 1) / ((uint64_t)threads * UNROLL);
     if (blocks > 0x7fffffffull) return -1;
-    hipLaunchKernelGGL(read_kernel<UNROLL>, dim3((unsigned)blocks), dim3(kBlock), 0, (hipStream_t)stream,
-                       (const u32x4*)src, n_vec, (uint32_t*)sink);
+    if (threads == 128)
+        hipLaunchKernelGGL((read_kernel<128, UNROLL>), dim3((unsigned)blocks), dim3(128), 0, (hipStream_t)stream,
+                           (const u32x4*)src, n_vec, (uint32_t*)sink);
+    else
+        hipLaunchKernelGGL((read_kernel<512, UNROLL>), dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream,
+                           (const u32x4*)src, n_vec, (uint32_t*)sink);
     return hipGetLastError() == hipSuccess ? 0 : -2;
 }
 
-int membench_write(void* dst, size_t bytes, void* stream)
+int membench_write(void* dst, size_t bytes, int threads, void* stream)
 {
-    if (!dst || !aligned(dst, bytes)) return -1;
+    if (!dst || !aligned(dst, bytes) || !shape_ok(threads)) return -1;
     const uint64_t n_vec = bytes / 16;
-    const uint64_t blocks = (n_vec + kBlock - 1) / kBlock;
+    const uint64_t blocks = (n_vec + threads - 1) / threads;
     if (blocks > 0x7fffffffull) return -1;
-    hipLaunchKernelGGL(write_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, (hipStream_t)stream, (u32x4*)dst, n_vec, 0x01020304u);
+    if (threads == 128)
+        hipLaunchKernelGGL(write_kernel<128>, dim3((unsigned)blocks), dim3(128), 0, (hipStream_t)stream, (u32x4*)dst, n_vec, 0x01020304u);
+    else
+        hipLaunchKernelGGL(write_kernel<512>, dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream, (u32x4*)dst, n_vec, 0x01020304u);
     return hipGetLastError() == hipSuccess ? 0 : -2;
 }
 
-int membench_copy(void* dst, const void* src, size_t bytes, void* stream)
+int membench_copy(void* dst, const void* src, size_t bytes, int threads, void* stream)
 {
-    if (!dst || !src || !aligned(dst, bytes) || !aligned(src, bytes)) return -1;
+    if (!dst || !src || !aligned(dst, bytes) || !aligned(src, bytes) || !shape_ok(threads)) return -1;
     const uint64_t n_vec = bytes / 16;
-    const uint64_t blocks = (n_vec + kBlock - 1) / kBlock;
+    const uint64_t blocks = (n_vec + threads - 1) / threads;
     if (blocks > 0x7fffffffull) return -1;
-    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, (hipStream_t)stream, (u32x4*)dst, (const u32x4*)src, n_vec);
+    if (threads == 128)
+        hipLaunchKernelGGL(copy_kernel<128>, dim3((unsigned)blocks), dim3(128), 0, (hipStream_t)stream, (u32x4*)dst, (const u32x4*)src, n_vec);
+    else
+        hipLaunchKernelGGL(copy_kernel<512>, dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream, (u32x4*)dst, (const u32x4*)src, n_vec);
     return hipGetLastError() == hipSuccess ? 0 : -2;
 }
 

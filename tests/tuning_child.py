@@ -125,7 +125,7 @@ def main():
             label = set_knobs(SCORE_BLOCK=blk, SCORE_NT=nt)
             check_score(label); check_step(label); n += 1
             print("ok", label, flush=True)
-    for blk in (256, 512):
+    for blk in (64, 128, 256, 512):
         for un in (1, 2):
             for nt in (0, 1):
                 label = set_knobs(GATHER_BLOCK=blk, GATHER_UNROLL=un, GATHER_NT=nt)
