@@ -362,6 +362,24 @@ def main():
         lmhead["step_ms"] = round(st_avg, 4)
         lmhead["step_tokens_per_s"] = round(hid.shape[0] / (st_avg * 1e-3), 1)
         log(f"[bench] step with the scores from the LM head: {st_avg*1e3:.1f} us")
+        # context, not the product path: the same product by the library GEMM torch ships (logits stored in the hidden
+        # states' type), alone and followed by this library's scan of those logits
+        lib_logits = torch.empty((hid.shape[0], w.vocab), dtype=hid.dtype, device=dev)
+        lib_scores = torch.empty(hid.shape[0], device=dev)
+        wt = wmat[:w.vocab].t()
+        mm_avg, _, _ = time_launches(torch, lambda: torch.mm(hid, wt, out=lib_logits), n_k, group=2)
+
+        def library_route():
+            torch.mm(hid, wt, out=lib_logits)
+            b.sirllm_score(lib_logits, tok, lib_scores, vocab=w.vocab, workspace=ws)
+
+        lr_avg, _, _ = time_launches(torch, library_route, n_k, group=2)
+        lmhead["library_gemm_ms"] = round(mm_avg, 4)
+        lmhead["library_gemm_tflops"] = round(flops / (mm_avg * 1e-3) / 1e12, 1)
+        lmhead["library_gemm_then_scan_ms"] = round(lr_avg, 4)
+        log(f"[bench] for comparison, torch.mm of the same operands (logits written out): {mm_avg*1e3:.1f} us -> "
+            f"{lmhead['library_gemm_tflops']:.0f} TFLOP/s; followed by sirllm_score on them: {lr_avg*1e3:.1f} us")
+        del lib_logits, lib_scores
         log(f"[bench] lmhead_score {hid.shape[0]} x {w.d_model} x {w.vocab}: {lm_avg*1e3:.1f}/{lm_med*1e3:.1f}/{lm_min*1e3:.1f} us "
             f"(avg/median/min) -> {tfl:.0f} TFLOP/s = {100 * tfl / 2500:.1f} % of 2.5 PFLOP/s")
         del hid, wmat, lm_ws, st_ws
