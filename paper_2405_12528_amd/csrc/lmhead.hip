@@ -65,24 +65,46 @@ __device__ __forceinline__ void tile_epilogue(const LmHeadArgs& a, f32x16 (&acc)
 {
     constexpr int TILE_T = 64 * NTB;
     const int frag_row = lane & 31, khalf = lane >> 5;
+    const int v_wave = v0 + wv * (32 * NVB);           // first vocabulary row of this wave's blocks
+    // Only the last vocabulary tile can hold rows past the end of the vocabulary: they are set to -inf in place, in
+    // a pass of their own that every other tile jumps over (wave-uniform).
+    if (v_wave + 32 * NVB > a.vocab) {
+#pragma unroll
+        for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int v = v_wave + vb * 32 + 8 * (r >> 2) + 4 * khalf + (r & 3);
+                if (v >= a.vocab) {
+#pragma unroll
+                    for (int tb = 0; tb < NTB; ++tb) acc[vb][tb][r] = -INFINITY;
+                }
+            }
+    }
 #pragma unroll
     for (int tb = 0; tb < NTB; ++tb) {
         const int T = wt * (32 * NTB) + tb * 32 + frag_row;
         const int64_t row = t0 + T;
         int32_t tok = (row < a.n_rows) ? a.token_ids[row] : -1;
         if (tok >= a.vocab) tok = -1;
-        float z[16 * NVB];
+        // The token's logit: lane l holds vocabulary rows v_wave + 32 vb + 8 (r / 4) + 4 (l / 32) + r % 4, so the token
+        // sits in this lane iff d = tok - v_wave is in [0, 32 NVB) and bit 2 of d is l / 32.  Few waves hold any of their
+        // 32 tokens' logits in a given tile; the others skip the search (wave-uniform).
+        const int d = tok - v_wave;
+        const bool mine = tok >= 0 && d >= 0 && d < 32 * NVB && ((d >> 2) & 1) == khalf;
         float zt = __uint_as_float(0x7fc00000u);
+        if (__builtin_amdgcn_ballot_w64(mine) != 0ull) {
+            const int e = mine ? (d >> 5) * 16 + ((d >> 3) & 3) * 4 + (d & 3) : -1;
+#pragma unroll
+            for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (e == vb * 16 + r) zt = acc[vb][tb][r];
+        }
+        float z[16 * NVB];
 #pragma unroll
         for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int v = v0 + wv * (32 * NVB) + vb * 32 + 8 * (r >> 2) + 4 * khalf + (r & 3);
-                float x = acc[vb][tb][r];
-                if (v >= a.vocab) x = -INFINITY;
-                if (v == tok) zt = x;
-                z[vb * 16 + r] = x;
-            }
+            for (int r = 0; r < 16; ++r) z[vb * 16 + r] = acc[vb][tb][r];
         score_dev::MS ms = {-INFINITY, 0.0f};
         score_dev::accumulate<16 * NVB>(z, ms);
         const score_dev::MS o = {__shfl_xor(ms.m, 32, kWave), __shfl_xor(ms.s, 32, kWave)};
