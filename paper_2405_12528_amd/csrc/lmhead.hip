@@ -47,14 +47,36 @@ __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c)
 __device__ __forceinline__ int tile_offset(int r, int c) { return r * kRowBytes + ((c ^ ((r >> 1) & 7)) << 4); }
 
 // Tile coordinates of a workgroup.  Workgroups are dealt to the 8 XCDs round robin; an XCD takes every 8th
-// vocabulary tile and walks all token tiles of it back to back, so a weight tile is fetched into one L2 only
-// and the (small) hidden-state matrix is what the XCDs share.
+// vocabulary tile, so a weight tile is fetched into one L2 only.  Token tiles come in groups of at most kTokenGroup:
+// an XCD walks, group after group, all its vocabulary tiles and for each the token tiles of the group back to back.
+// The 32 workgroups it runs at a time are then 4 vocabulary tiles x 8 token tiles, whose 12 operand tiles per stage
+// fit its 4 MB L2 with a ring's worth of stages to spare; without the grouping 32 token tiles of one vocabulary tile
+// would be in flight (33 operand tiles per stage, and every generation of workgroups pulls in all of h again).
+constexpr int kTokenGroup = 8;
+__host__ __device__ __forceinline__ int token_group(int n_ttiles) { return n_ttiles < kTokenGroup ? n_ttiles : kTokenGroup; }
+// workgroups per XCD and token group
+__host__ __device__ __forceinline__ int tiles_per_group(const LmHeadArgs& a) { return ((a.n_vtiles + 7) / 8) * token_group(a.n_ttiles); }
+
+// q-th workgroup of XCD `xcd` -> tile; false when it falls off the ragged end of either axis
+__device__ __forceinline__ bool tile_of(const LmHeadArgs& a, int q, int xcd, int& vt, int& tt)
+{
+    const int tg = token_group(a.n_ttiles), per = tiles_per_group(a);
+    const int grp = q / per, r = q - grp * per;
+    vt = (r / tg) * 8 + xcd;
+    tt = grp * tg + r % tg;
+    return vt < a.n_vtiles && tt < a.n_ttiles;
+}
+
 __device__ __forceinline__ bool tile_of_block(const LmHeadArgs& a, int& vt, int& tt)
 {
-    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
-    tt = q % a.n_ttiles;
-    vt = (q / a.n_ttiles) * 8 + xcd;
-    return vt < a.n_vtiles;
+    return tile_of(a, (int)(blockIdx.x >> 3), (int)(blockIdx.x & 7), vt, tt);
+}
+
+// Workgroups of a launch: 8 XCDs x token groups x (vocabulary tiles per XCD x token tiles per group).
+inline int64_t lmhead_grid(const LmHeadArgs& a)
+{
+    const int tg = token_group(a.n_ttiles);
+    return (int64_t)8 * ((a.n_ttiles + tg - 1) / tg) * tiles_per_group(a);
 }
 
 // Reduces a wave's (32 NVB) x (32 NTB) block of logits (vocabulary x tokens) to per-token softmax statistics,
@@ -392,15 +414,13 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
     // workgroups that share a W tile (same vocabulary tile, consecutive token tiles, resident together on one XCD)
     // split its rows.  Past the end of K the lines of the tile this CU will take next are touched.
     const int swave = __builtin_amdgcn_readfirstlane(wave);
-    const int ns = (a.n_ttiles & 7) == 0 ? 8 : (a.n_ttiles & 3) == 0 ? 4 : (a.n_ttiles & 1) == 0 ? 2 : 1;
+    const int tgs = token_group(a.n_ttiles);   // the workgroups that share a W tile: the token tiles of one group
+    const int ns = (tgs & 7) == 0 ? 8 : (tgs & 3) == 0 ? 4 : (tgs & 1) == 0 ? 2 : 1;
     auto warm = [&](int stage) {
         int vt2 = vt, tt2 = tt;
         if (stage >= nk) {
             stage -= nk;
-            const int q2 = (int)(blockIdx.x >> 3) + 32;
-            vt2 = (q2 / a.n_ttiles) * 8 + (int)(blockIdx.x & 7);
-            tt2 = q2 % a.n_ttiles;
-            if (vt2 >= a.n_vtiles || stage >= nk) return;
+            if (!tile_of(a, (int)(blockIdx.x >> 3) + 32, (int)(blockIdx.x & 7), vt2, tt2) || stage >= nk) return;
         }
         const int rows_per = Cfg::kBV / ns;
         const int rows_left = a.vocab - vt2 * Cfg::kBV;
@@ -534,7 +554,7 @@ template <int DT, int NVB, int NTB, int RING, bool PIN, bool WARM>
 hipError_t launch_fast(const LmHeadArgs& a, hipStream_t stream)
 {
     using Cfg = FastCfg<NVB, NTB, RING>;
-    const int64_t groups = (int64_t)((a.n_vtiles + 7) / 8) * a.n_ttiles * 8;
+    const int64_t groups = lmhead_grid(a);
     if (groups > 0x7fffffff) return hipErrorInvalidValue;
     auto fn = lmhead_score_kernel<DT, NVB, NTB, RING, PIN, WARM>;
     static std::atomic<uint64_t> lds_allowed{0};
@@ -547,7 +567,7 @@ hipError_t launch_fast(const LmHeadArgs& a, hipStream_t stream)
 template <int DT>
 hipError_t launch_general(const LmHeadArgs& a, hipStream_t stream)
 {
-    const int64_t groups = (int64_t)((a.n_vtiles + 7) / 8) * a.n_ttiles * 8;
+    const int64_t groups = lmhead_grid(a);
     if (groups > 0x7fffffff) return hipErrorInvalidValue;
     auto fn = lmhead_score_general_kernel<DT>;
     static std::atomic<uint64_t> lds_allowed{0};
