@@ -373,17 +373,38 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
     // MFMA at most one read or one load (a matrix instruction keeps its pipe busy for 32 cycles, and one read or
     // load issues within that time); otherwise the compiler orders them (small tiles are not MFMA bound).
     auto slice = [&](int use, const char* rs, int rkk, int ls, int lbuf, int lj0, int ln) {
-        int extra = 0;                                     // reads, then loads, handed out one per MFMA
+        if constexpr (PIN) {
+            // reads and loads one per MFMA, a load behind every fourth MFMA: the four waves run in step, and four 1 KB
+            // loads in a row from each of them would queue up in the CU's one address unit faster than it drains
+            int ri = 0, li = 0;
+#pragma unroll
+            for (int g = 0; g < NVB; ++g)
+#pragma unroll
+                for (int i = 0; i < NTB; ++i) {
+                    const int e = g * NTB + i;
+                    acc[g][i] = mfma<DT>(af[use][g], bf[use][i], acc[g][i]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if ((e & 3) == 1 && li < ln) { issue_load(ls, lbuf, lj0 + li); ++li; }
+                    else if (ri < NVB + NTB) { read_frag(rs, rkk, use ^ 1, ri); ++ri; }
+                    else if (li < ln) { issue_load(ls, lbuf, lj0 + li); ++li; }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+            for (; ri < NVB + NTB; ++ri) read_frag(rs, rkk, use ^ 1, ri);
+#pragma unroll
+            for (; li < Cfg::kLpw; ++li)
+                if (li < ln) issue_load(ls, lbuf, lj0 + li);
+            return;
+        }
+        int extra = 0;                                     // reads, then loads, one behind each MFMA; the compiler reorders
 #pragma unroll
         for (int g = 0; g < NVB; ++g)
 #pragma unroll
             for (int i = 0; i < NTB; ++i) {
                 acc[g][i] = mfma<DT>(af[use][g], bf[use][i], acc[g][i]);
-                if (PIN) __builtin_amdgcn_sched_barrier(0);
                 if (extra < NVB + NTB) read_frag(rs, rkk, use ^ 1, extra);
                 else if (extra - (NVB + NTB) < ln) issue_load(ls, lbuf, lj0 + extra - (NVB + NTB));
                 ++extra;
-                if (PIN) __builtin_amdgcn_sched_barrier(0);
             }
         // what did not fit behind an MFMA (tiles with fewer MFMAs than reads + loads)
 #pragma unroll
