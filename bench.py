@@ -171,7 +171,7 @@ def measure_ceilings(torch, dev):
             raise RuntimeError(f"membench call failed with {rc}")
 
     by_threads = {}
-    for threads in (128, 512):
+    for threads in (64, 128, 512):
         r_avg, _, _ = time_launches(torch, lambda: must(mb.membench_read(src.data_ptr(), n, sink.data_ptr(), threads, stream)), 5, group=4)
         w_avg, _, _ = time_launches(torch, lambda: must(mb.membench_write(dst.data_ptr(), n, threads, stream)), 5, group=4)
         c_avg, _, _ = time_launches(torch, lambda: must(mb.membench_copy(dst.data_ptr(), src.data_ptr(), n, threads, stream)), 5, group=4)
@@ -183,7 +183,7 @@ def measure_ceilings(torch, dev):
     for k in ("read_gbps", "write_gbps", "copy_gbps"):
         out[k] = max(v[k] for v in by_threads.values())
     out["by_workgroup_threads"] = {str(t): v for t, v in by_threads.items()}
-    out["note"] = ("1 GiB, 16-byte non-temporal accesses; the better of 128- and 512-thread workgroups for each; "
+    out["note"] = ("1 GiB, 16-byte non-temporal accesses; the best of 64-, 128- and 512-thread workgroups for each; "
                    "copy counts bytes read + bytes written")
     log(f"[bench] streaming ceilings over 1 GiB: read {out['read_gbps']:.0f} GB/s, write {out['write_gbps']:.0f} GB/s, "
         f"copy {out['copy_gbps']:.0f} GB/s (read + written)")

@@ -28,7 +28,11 @@
  *     variables (integers; unset = the default in brackets) -- otherwise none of them is ever read:
  *       SIRLLM_SCORE_BLOCK [by row length: 1024, 512 or 256]  threads per scored row
  *       SIRLLM_SCORE_NT [1], SIRLLM_GATHER_NT [1], SIRLLM_INPLACE_NT [1]   non-temporal (1) or cached (0) accesses
- *       SIRLLM_GATHER_BLOCK [128] (or 64, 256, 512), SIRLLM_GATHER_UNROLL [1] (or 2; 64 threads: 1, non-temporal only)   threads and 16-byte vectors per lane of a gather tile
+ *       SIRLLM_GATHER_BLOCK [64 for rows of 256 bytes, else 128] (or 64, 128, 256, 512), SIRLLM_GATHER_UNROLL [1] (or 2; 64 threads:
+ *                                1, non-temporal only)   threads and 16-byte vectors per lane of a gather tile
+ *       SIRLLM_GATHER_SCALAR_IDX [1], SIRLLM_GATHER_ROTATE [1 when the source planes lie a power of two apart, else 0]
+ *                                rows of 256 bytes in tiles of 64 or 128 threads: kept indices by scalar loads (1) or per lane (0);
+ *                                tiles of each group of eight exchanged by the plane index (1) or not (0)
  *       SIRLLM_FUSE_SELECT [1]   0: score and select in separate launches even when they are independent
  *       SIRLLM_INPLACE_BLOCK [1024] (512, 256), SIRLLM_INPLACE_UNROLL [4] (2, 8), SIRLLM_INPLACE_PARTS [by plane count]
  *                                threads, vectors per lane and column parts of the in-place walk

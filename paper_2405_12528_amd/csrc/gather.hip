@@ -17,6 +17,13 @@ __global__ __launch_bounds__(BLOCK) void gather_rows_kernel(GatherLaunch g)
         g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z);
 }
 
+// Rows of sixteen 16-byte vectors, one vector per lane: the kept indices come through the scalar cache.
+template <int BLOCK, bool OFF64>
+__global__ __launch_bounds__(BLOCK) void gather_rows16_kernel(GatherLaunch g)
+{
+    gather_dev::gather_tile_rows16<BLOCK, true, OFF64>(g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z);
+}
+
 template <typename VecT, bool POW2, bool OFF64>
 __global__ __launch_bounds__(128) void gather_rows_layers_kernel(GatherLaunch g, LayerTable t)
 {
@@ -45,14 +52,20 @@ hipError_t launch_vec(const GatherArgs& a, int row_begin, int row_end, hipStream
     if (!gather_dev::fill_launch<VecT>(g, a, row_begin, row_end, &pow2, &off64)) return hipErrorInvalidValue;
     const int64_t n_items = (int64_t)(row_end - row_begin) * g.vpr;
 
-    // Small workgroups: a workgroup's wave slots come free only when its slowest wave is done, and a tile of two waves
-    // (8 rows of 256 bytes) wastes fewer of them than one of eight.  Measured on the seven workloads of bench.py against
-    // 512 threads: 1 to 6.5 % less time at 128, never more; 64 threads gain another 1 to 4 % on five of them but lose 9 %
-    // on long contiguous runs (a kept list that is one run), so 128 it is.
-    int block = tuning::get("SIRLLM_GATHER_BLOCK", 128);
+    // Small workgroups: a workgroup's wave slots come free only when its slowest wave is done, and a tile of one or two
+    // waves wastes fewer of them than one of eight (128 threads against 512 on the workloads of bench.py: 1 to 6.5 %
+    // less time, never more).  Rows of 256 bytes (sixteen vectors) have a kernel of their own that fetches the kept
+    // indices by scalar loads; it runs best as single waves (64 threads: another 2 to 6 % on all but one workload).
+    const bool rows16_shape = sizeof(VecT) == 16 && g.vpr == 16;
+    int block = tuning::get("SIRLLM_GATHER_BLOCK", rows16_shape ? 64 : 128);
     if (block != 64 && block != 256 && block != 512) block = 128;
     const int unroll = block == 64 ? 1 : (tuning::get("SIRLLM_GATHER_UNROLL", 1) == 2 ? 2 : 1);
     const bool nt = block == 64 || tuning::get("SIRLLM_GATHER_NT", 1) != 0;
+    const bool rows16 = rows16_shape && unroll == 1 && nt && (block == 64 || block == 128) &&
+                        tuning::get("SIRLLM_GATHER_SCALAR_IDX", 1) != 0;
+    // source planes a power of two apart: see gather_tile_rows16
+    const bool pow2_planes = a.s_head > 0 && (a.s_head & (a.s_head - 1)) == 0;
+    g.rotate = tuning::get("SIRLLM_GATHER_ROTATE", pow2_planes ? 1 : 0) != 0 ? 1 : 0;
     const int per_block = block * unroll;
     const unsigned n_tiles = (unsigned)((n_items + per_block - 1) / per_block);
     const int planes = a.n_tensors * g.lh;
@@ -62,7 +75,15 @@ hipError_t launch_vec(const GatherArgs& a, int row_begin, int row_end, hipStream
             g.stream0 = s0;
             g.plane0 = p0;
             const dim3 grid(n_tiles, (unsigned)min(kMaxDim, planes - p0), (unsigned)min(kMaxDim, a.n_streams - s0));
-            if (block == 64) {
+            if (rows16) {
+                if (block == 64) {
+                    if (off64) hipLaunchKernelGGL((gather_rows16_kernel<64, true>), grid, dim3(64), 0, stream, g);
+                    else       hipLaunchKernelGGL((gather_rows16_kernel<64, false>), grid, dim3(64), 0, stream, g);
+                } else {
+                    if (off64) hipLaunchKernelGGL((gather_rows16_kernel<128, true>), grid, dim3(128), 0, stream, g);
+                    else       hipLaunchKernelGGL((gather_rows16_kernel<128, false>), grid, dim3(128), 0, stream, g);
+                }
+            } else if (block == 64) {
                 launch_shape<VecT, 64, 1, true>(g, grid, pow2, off64, stream);
             } else if (block == 256) {
                 if (unroll == 2) { if (nt) launch_shape<VecT, 256, 2, true>(g, grid, pow2, off64, stream); else launch_shape<VecT, 256, 2, false>(g, grid, pow2, off64, stream); }

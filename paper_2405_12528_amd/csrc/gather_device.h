@@ -36,6 +36,7 @@ struct GatherLaunch {
     int32_t stream0;      // first stream of this launch
     int32_t lh;           // n_layers * n_heads
     int32_t uniform;      // 1: s_layer == n_heads*s_head and d_layer == n_heads*d_head
+    int32_t rotate;       // rows-of-16-vectors kernel: exchange tiles inside groups of eight, differently from plane to plane
 };
 
 // One tile of destination rows of the plane that starts at sp (source) / dp (destination) and belongs to `stream`.
@@ -72,6 +73,84 @@ __device__ __forceinline__ void gather_tile_at(const GatherLaunch& g, int tile, 
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
         if (live[u]) st<VecT, NT>(dp + doff[u], v[u]);
+}
+
+// A tile for rows of exactly 16 vectors (256 bytes: 128 two-byte channels, the common head) and one vector per lane.
+// A wave covers four whole rows, so their four kept indices are wave-uniform and come through the scalar cache (four
+// scalar loads from clamped positions) instead of one vector load per lane; each lane then picks its row's index.
+// Every kernel argument the wave needs is requested in one batch at its start, the indices in a second one: two
+// scalar round trips, then the wave's first vector memory operation is the row load itself.  The kept list must not
+// be written while the launch runs (it is read through the constant address space), which every caller of the
+// compaction already guarantees: destination buffers and kept list may not overlap.
+template <int BLOCK, bool NT, bool OFF64>
+__device__ __forceinline__ void gather_tile_rows16(const GatherLaunch& g, int tile, int plane, int stream)
+{
+    static_assert(BLOCK % 64 == 0, "four rows of sixteen 16-byte vectors per wave");
+    using VecT = u32x4;
+    using off_t = typename std::conditional<OFF64, int64_t, uint32_t>::type;
+    typedef const __attribute__((address_space(4))) int32_t* const_idx_t;     // read-only for the whole launch: scalar loads
+    typedef const __attribute__((address_space(1))) char* gsrc_t;
+    typedef __attribute__((address_space(1))) char* gdst_t;
+    const GatherArgs& a = g.a;
+    // one batch of scalar loads from the argument block (addresses as integers, so that the batch can be pinned here)
+    uint64_t idx_base = (uint64_t)(uintptr_t)a.kept_idx;
+    int64_t idx_stride = a.idx_stride;
+    int row_begin = g.row_begin, row_end = g.row_end, lh = g.lh, uniform = g.uniform, n_heads = a.n_heads, n_src = a.n_src;
+    uint64_t src0 = (uint64_t)(uintptr_t)a.src[0], src1 = (uint64_t)(uintptr_t)a.src[1];
+    uint64_t dst0 = (uint64_t)(uintptr_t)a.dst[0], dst1 = (uint64_t)(uintptr_t)a.dst[1];
+    int64_t s_stream = a.s_stream, d_stream = a.d_stream, s_head = a.s_head, d_head = a.d_head, s_layer = a.s_layer,
+            d_layer = a.d_layer, s_pos = a.s_pos, d_pos = a.d_pos;
+    asm volatile("" : "+s"(idx_base), "+s"(idx_stride), "+s"(row_begin), "+s"(row_end), "+s"(lh), "+s"(uniform), "+s"(n_heads),
+                      "+s"(n_src));
+    asm volatile("" : "+s"(src0), "+s"(src1), "+s"(dst0), "+s"(dst1), "+s"(s_stream), "+s"(d_stream), "+s"(s_head), "+s"(d_head));
+    asm volatile("" : "+s"(s_layer), "+s"(d_layer), "+s"(s_pos), "+s"(d_pos));
+
+    const int n_rows = row_end - row_begin;
+    const int lane = (int)threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    // Workgroups are dealt to the eight XCDs round robin and a plane holds a multiple of eight tiles, so XCD x would
+    // copy tile 8 m + x of EVERY plane: one fixed eighth of the addresses modulo eight tiles.  When the planes also lie
+    // a power of two apart, an XCD's traffic then keeps falling on the same few channels (measured: 5.2-5.9 instead of
+    // 6.5 TB/s on long runs of kept slots).  Exchanging the tiles of each group of eight by the plane index gives every
+    // XCD every residue in turn.  It costs 3-7 % where nothing needs curing (many planes, strides that are no power of
+    // two), so the launcher asks for it only where it pays.
+    if (g.rotate && tile < ((int)gridDim.x & ~7)) tile ^= plane & 7;
+    const int r0 = (tile * (BLOCK / 64) + wave) * 4;                 // first of the wave's four rows (relative to row_begin)
+    if (r0 >= n_rows) return;                                        // wave-uniform
+    const int last = n_rows - 1;
+    const_idx_t idx = (const_idx_t)(idx_base + (uint64_t)((stream * idx_stride + row_begin) * 4));
+    int32_t i0 = idx[r0];
+    int32_t i1 = idx[min(r0 + 1, last)];
+    int32_t i2 = idx[min(r0 + 2, last)];
+    int32_t i3 = idx[min(r0 + 3, last)];
+    asm volatile("" : "+s"(i0), "+s"(i1), "+s"(i2), "+s"(i3));       // all four requested before any is looked at
+
+    const int tensor = plane >= lh ? 1 : 0;
+    const int ph = plane - tensor * lh;
+    int64_t so, dof;
+    if (uniform) {
+        so = ph * s_head;
+        dof = ph * d_head;
+    } else {
+        const int l = ph / n_heads, h = ph - l * n_heads;
+        so = l * s_layer + h * s_head;
+        dof = l * d_layer + h * d_head;
+    }
+    const gsrc_t sp = (gsrc_t)((tensor ? src1 : src0) + (uint64_t)(stream * s_stream + so));
+    const gdst_t dp = (gdst_t)((tensor ? dst1 : dst0) + (uint64_t)(stream * d_stream + dof));
+
+    const int r = lane >> 4, c = lane & 15;
+    const uint32_t i = (uint32_t)(r == 0 ? i0 : r == 1 ? i1 : r == 2 ? i2 : i3);
+    if (r0 + r >= n_rows) return;
+    const int j = row_begin + r0 + r;
+    VecT v = VecT{};
+    if (i < (uint32_t)n_src) {                                       // an index with no source slot leaves a zero row
+        const auto* p = (const __attribute__((address_space(1))) VecT*)(sp + ((off_t)i * (off_t)s_pos + (off_t)(c * 16)));
+        v = NT ? __builtin_nontemporal_load(p) : *p;
+    }
+    auto* q = (__attribute__((address_space(1))) VecT*)(dp + ((off_t)j * (off_t)d_pos + (off_t)(c * 16)));
+    if (NT) __builtin_nontemporal_store(v, q);
+    else *q = v;
 }
 
 // The cache is one buffer per tensor: plane -> base pointers by the layout's strides (uniform over the workgroup:
@@ -124,6 +203,7 @@ inline bool fill_launch(GatherLaunch& g, const GatherArgs& a, int row_begin, int
     g.stream0 = 0;
     g.lh = a.n_layers * a.n_heads;
     g.uniform = (a.s_layer == a.n_heads * a.s_head && a.d_layer == a.n_heads * a.d_head) ? 1 : 0;
+    g.rotate = 0;
     // 32-bit offsets inside a plane when both planes are below 4 GiB
     *off64 = (int64_t)a.n_src * a.s_pos + a.row_bytes > 0xffffffffLL ||
              (int64_t)a.n_keep * a.d_pos + a.row_bytes > 0xffffffffLL;

@@ -1,6 +1,6 @@
 // Plain streaming kernels that measure what this GPU's memory system gives a read-only scan, a write-only
 // fill and a copy, with the same access shape the library's kernels use (one 16-byte non-temporal vector per
-// lane per step), in workgroups of 128 or of 512 threads.  They are measurement references for bench.py, not part
+// lane per step), in workgroups of 64, 128 or 512 threads.  They are measurement references for bench.py, not part
 // of the retention path: the score scan is compared with the read stream, the K/V gather with the copy.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -39,14 +39,14 @@ __global__ __launch_bounds__(kBlock) void copy_kernel(u32x4* dst, const u32x4* s
     if (i < n_vec) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
-bool shape_ok(int threads) { return threads == 128 || threads == 512; }
+bool shape_ok(int threads) { return threads == 64 || threads == 128 || threads == 512; }
 bool aligned(const void* p, size_t bytes) { return ((uintptr_t)p & 15) == 0 && (bytes & 15) == 0 && bytes > 0 && bytes <= ((size_t)1 << 40); }
 
 }  // namespace
 
 extern "C" {
 
-// All three: device pointers, 16-byte aligned, `bytes` a multiple of 16, `threads` (per workgroup) 128 or 512; enqueue on
+// All three: device pointers, 16-byte aligned, `bytes` a multiple of 16, `threads` (per workgroup) 64, 128 or 512; enqueue on
 // `stream` and return at once.  Return 0, or -1 for bad arguments, -2 when the launch was refused.
 int membench_read(const void* src, size_t bytes, void* sink, int threads, void* stream)
 {
@@ -55,7 +55,10 @@ int membench_read(const void* src, size_t bytes, void* sink, int threads, void* 
     constexpr int UNROLL = 4;
     const uint64_t blocks = (n_vec + (uint64_t)threads * UNROLL - 1) / ((uint64_t)threads * UNROLL);
     if (blocks > 0x7fffffffull) return -1;
-    if (threads == 128)
+    if (threads == 64)
+        hipLaunchKernelGGL((read_kernel<64, UNROLL>), dim3((unsigned)blocks), dim3(64), 0, (hipStream_t)stream,
+                           (const u32x4*)src, n_vec, (uint32_t*)sink);
+    else if (threads == 128)
         hipLaunchKernelGGL((read_kernel<128, UNROLL>), dim3((unsigned)blocks), dim3(128), 0, (hipStream_t)stream,
                            (const u32x4*)src, n_vec, (uint32_t*)sink);
     else
@@ -70,7 +73,9 @@ int membench_write(void* dst, size_t bytes, int threads, void* stream)
     const uint64_t n_vec = bytes / 16;
     const uint64_t blocks = (n_vec + threads - 1) / threads;
     if (blocks > 0x7fffffffull) return -1;
-    if (threads == 128)
+    if (threads == 64)
+        hipLaunchKernelGGL(write_kernel<64>, dim3((unsigned)blocks), dim3(64), 0, (hipStream_t)stream, (u32x4*)dst, n_vec, 0x01020304u);
+    else if (threads == 128)
         hipLaunchKernelGGL(write_kernel<128>, dim3((unsigned)blocks), dim3(128), 0, (hipStream_t)stream, (u32x4*)dst, n_vec, 0x01020304u);
     else
         hipLaunchKernelGGL(write_kernel<512>, dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream, (u32x4*)dst, n_vec, 0x01020304u);
@@ -83,7 +88,9 @@ int membench_copy(void* dst, const void* src, size_t bytes, int threads, void* s
     const uint64_t n_vec = bytes / 16;
     const uint64_t blocks = (n_vec + threads - 1) / threads;
     if (blocks > 0x7fffffffull) return -1;
-    if (threads == 128)
+    if (threads == 64)
+        hipLaunchKernelGGL(copy_kernel<64>, dim3((unsigned)blocks), dim3(64), 0, (hipStream_t)stream, (u32x4*)dst, (const u32x4*)src, n_vec);
+    else if (threads == 128)
         hipLaunchKernelGGL(copy_kernel<128>, dim3((unsigned)blocks), dim3(128), 0, (hipStream_t)stream, (u32x4*)dst, (const u32x4*)src, n_vec);
     else
         hipLaunchKernelGGL(copy_kernel<512>, dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream, (u32x4*)dst, (const u32x4*)src, n_vec);

@@ -327,6 +327,28 @@ def test_compact_matches_oracle(b, ref, S, L, H, P, D, dtype):
     run_compact(b, ref, k, None, kept[:, : max(1, n_keep // 2)])
 
 
+@pytest.mark.parametrize("P", [512, 600, 4096], ids=["planes 128 KB apart", "planes 150 KB apart", "planes 1 MB apart"])
+@pytest.mark.parametrize("dtype,D", [(torch.bfloat16, 128), (torch.float32, 64)])
+def test_compact_rows_of_256_bytes(b, ref, P, dtype, D):
+    """Rows of 256 bytes take a kernel of their own: a wave copies four whole rows and fetches their four kept indices
+    by scalar loads (clamped at the end of the list); where the source planes lie a power of two apart (P = 512, 4096)
+    the tiles of every group of eight are exchanged by the plane index, the ragged last group excepted.  Kept counts
+    around the edges of a wave's four rows and of a group of eight tiles, twelve and twenty planes (every value of the
+    plane index modulo 8), lists with runs, with entries that have no source slot, K alone and K with V."""
+    rng = np.random.default_rng(P + D)
+    for S, L, H in ((1, 3, 4), (2, 5, 2)):
+        k = (synth.tagged_kv(S, L, H, P, D, 0) % 32749).to(dtype).to(DEV)
+        v = (synth.tagged_kv(S, L, H, P, D, 1) % 32719).to(dtype).to(DEV)
+        for n_keep in (1, 3, 4, 5, 31, 32, 33, 63, 100, P // 2 + 1, P - 1, P):
+            kept = np.stack([np.sort(rng.choice(P, n_keep, replace=False)) for _ in range(S)]).astype(np.int32)
+            if n_keep >= 33:
+                kept[0, n_keep // 2:] = np.arange(P - (n_keep - n_keep // 2), P)     # a run at the end, like a recent window
+                kept[0] = np.sort(kept[0])
+                kept[-1, 7] = P + 5                                                   # no such slot: a zero row
+            run_compact(b, ref, k, v, kept)
+        run_compact(b, ref, k, None, np.stack([np.arange(40, 40 + 77)] * S).astype(np.int32), n_src=100)   # slots >= 100: zero rows
+
+
 def test_compact_strided_views_and_bad_indices(b, ref):
     big = synth.tagged_kv(2, 2, 3, 40, 24, 0).to(torch.float32).to(DEV)
     k = big[:, :, :2, :30, :16]                       # padded heads, slots and channels

@@ -17,7 +17,7 @@ from paper_2405_12528_amd import binding as b, synth        # noqa: E402
 DEV = "cuda:0"
 KNOBS = ("SIRLLM_SCORE_BLOCK", "SIRLLM_SCORE_NT", "SIRLLM_GATHER_BLOCK", "SIRLLM_GATHER_UNROLL", "SIRLLM_GATHER_NT",
          "SIRLLM_FUSE_SELECT", "SIRLLM_INPLACE_BLOCK", "SIRLLM_INPLACE_UNROLL", "SIRLLM_INPLACE_PARTS",
-         "SIRLLM_INPLACE_NT", "SIRLLM_INPLACE_TICKET")
+         "SIRLLM_INPLACE_NT", "SIRLLM_INPLACE_TICKET", "SIRLLM_GATHER_SCALAR_IDX", "SIRLLM_GATHER_ROTATE")
 
 
 def set_knobs(**kw):
@@ -129,6 +129,12 @@ def main():
         for un in (1, 2):
             for nt in (0, 1):
                 label = set_knobs(GATHER_BLOCK=blk, GATHER_UNROLL=un, GATHER_NT=nt)
+                check_gather(label); n += 1
+                print("ok", label, flush=True)
+    for blk in (64, 128):                                      # rows of 256 bytes: scalar or per-lane indices, tiles exchanged or not
+        for scalar in (0, 1):
+            for rot in (0, 1):
+                label = set_knobs(GATHER_BLOCK=blk, GATHER_SCALAR_IDX=scalar, GATHER_ROTATE=rot)
                 check_gather(label); n += 1
                 print("ok", label, flush=True)
     for fuse in (0, 1):
