@@ -24,6 +24,12 @@ __global__ __launch_bounds__(BLOCK) void gather_rows16_kernel(GatherLaunch g)
     gather_dev::gather_tile_rows16<BLOCK, true, OFF64>(g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z);
 }
 
+template <bool OFF64>
+__global__ __launch_bounds__(64) void gather_rows16_layers_kernel(GatherLaunch g, LayerTable t)
+{
+    gather_dev::gather_tile_rows16<64, true, OFF64, true>(g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z, &t);
+}
+
 template <typename VecT, bool POW2, bool OFF64>
 __global__ __launch_bounds__(128) void gather_rows_layers_kernel(GatherLaunch g, LayerTable t)
 {
@@ -102,7 +108,7 @@ hipError_t launch_vec(const GatherArgs& a, int row_begin, int row_end, hipStream
     return hipSuccess;
 }
 
-// Per-layer buffers: the default launch shape only (128 threads, one vector per lane, non-temporal accesses).
+// Per-layer buffers: the default launch shapes only (one vector per lane, non-temporal accesses).
 template <typename VecT>
 hipError_t launch_vec_layers(const GatherArgs& a, const LayerTable& t, hipStream_t stream)
 {
@@ -110,16 +116,23 @@ hipError_t launch_vec_layers(const GatherArgs& a, const LayerTable& t, hipStream
     bool pow2, off64;
     if (!gather_dev::fill_launch<VecT>(g, a, 0, a.n_keep, &pow2, &off64)) return hipErrorInvalidValue;
     const int64_t n_items = (int64_t)a.n_keep * g.vpr;
-    const unsigned n_tiles = (unsigned)((n_items + 127) / 128);
+    // rows of 256 bytes: single-wave tiles with scalar index loads, as in launch_vec
+    const bool rows16 = sizeof(VecT) == 16 && g.vpr == 16;
+    const bool pow2_planes = a.s_head > 0 && (a.s_head & (a.s_head - 1)) == 0;
+    g.rotate = rows16 && pow2_planes ? 1 : 0;
+    const unsigned n_tiles = (unsigned)((n_items + (rows16 ? 63 : 127)) / (rows16 ? 64 : 128));
     const int planes = a.n_tensors * g.lh;            // at most 2 * 32 * n_heads
     constexpr int kMaxDim = 65535;
-    const dim3 block(128);
+    const dim3 block(rows16 ? 64 : 128);
     for (int s0 = 0; s0 < a.n_streams; s0 += kMaxDim) {
         for (int p0 = 0; p0 < planes; p0 += kMaxDim) {
             g.stream0 = s0;
             g.plane0 = p0;
             const dim3 grid(n_tiles, (unsigned)min(kMaxDim, planes - p0), (unsigned)min(kMaxDim, a.n_streams - s0));
-            if (pow2) {
+            if (rows16) {
+                if (off64) hipLaunchKernelGGL((gather_rows16_layers_kernel<true>), grid, block, 0, stream, g, t);
+                else       hipLaunchKernelGGL((gather_rows16_layers_kernel<false>), grid, block, 0, stream, g, t);
+            } else if (pow2) {
                 if (off64) hipLaunchKernelGGL((gather_rows_layers_kernel<VecT, true, true>), grid, block, 0, stream, g, t);
                 else       hipLaunchKernelGGL((gather_rows_layers_kernel<VecT, true, false>), grid, block, 0, stream, g, t);
             } else {

@@ -82,8 +82,10 @@ __device__ __forceinline__ void gather_tile_at(const GatherLaunch& g, int tile, 
 // scalar round trips, then the wave's first vector memory operation is the row load itself.  The kept list must not
 // be written while the launch runs (it is read through the constant address space), which every caller of the
 // compaction already guarantees: destination buffers and kept list may not overlap.
-template <int BLOCK, bool NT, bool OFF64>
-__device__ __forceinline__ void gather_tile_rows16(const GatherLaunch& g, int tile, int plane, int stream)
+// LAYERS: the cache is one buffer per layer and tensor, `table` holds their base pointers (else it is not read).
+template <int BLOCK, bool NT, bool OFF64, bool LAYERS = false>
+__device__ __forceinline__ void gather_tile_rows16(const GatherLaunch& g, int tile, int plane, int stream,
+                                                   const LayerTable* table = nullptr)
 {
     static_assert(BLOCK % 64 == 0, "four rows of sixteen 16-byte vectors per wave");
     using VecT = u32x4;
@@ -118,26 +120,37 @@ __device__ __forceinline__ void gather_tile_rows16(const GatherLaunch& g, int ti
     const int r0 = (tile * (BLOCK / 64) + wave) * 4;                 // first of the wave's four rows (relative to row_begin)
     if (r0 >= n_rows) return;                                        // wave-uniform
     const int last = n_rows - 1;
+    const int tensor = plane >= lh ? 1 : 0;
+    const int ph = plane - tensor * lh;
     const_idx_t idx = (const_idx_t)(idx_base + (uint64_t)((stream * idx_stride + row_begin) * 4));
     int32_t i0 = idx[r0];
     int32_t i1 = idx[min(r0 + 1, last)];
     int32_t i2 = idx[min(r0 + 2, last)];
     int32_t i3 = idx[min(r0 + 3, last)];
-    asm volatile("" : "+s"(i0), "+s"(i1), "+s"(i2), "+s"(i3));       // all four requested before any is looked at
-
-    const int tensor = plane >= lh ? 1 : 0;
-    const int ph = plane - tensor * lh;
+    uint64_t sbase, dbase;
     int64_t so, dof;
-    if (uniform) {
-        so = ph * s_head;
-        dof = ph * d_head;
-    } else {
+    if constexpr (LAYERS) {
         const int l = ph / n_heads, h = ph - l * n_heads;
-        so = l * s_layer + h * s_head;
-        dof = l * d_layer + h * d_head;
+        sbase = (uint64_t)(uintptr_t)table->src[tensor][l];          // second batch, together with the indices
+        dbase = (uint64_t)(uintptr_t)table->dst[tensor][l];
+        asm volatile("" : "+s"(sbase), "+s"(dbase));
+        so = h * s_head;
+        dof = h * d_head;
+    } else {
+        sbase = tensor ? src1 : src0;
+        dbase = tensor ? dst1 : dst0;
+        if (uniform) {
+            so = ph * s_head;
+            dof = ph * d_head;
+        } else {
+            const int l = ph / n_heads, h = ph - l * n_heads;
+            so = l * s_layer + h * s_head;
+            dof = l * d_layer + h * d_head;
+        }
     }
-    const gsrc_t sp = (gsrc_t)((tensor ? src1 : src0) + (uint64_t)(stream * s_stream + so));
-    const gdst_t dp = (gdst_t)((tensor ? dst1 : dst0) + (uint64_t)(stream * d_stream + dof));
+    asm volatile("" : "+s"(i0), "+s"(i1), "+s"(i2), "+s"(i3));       // all four requested before any is looked at
+    const gsrc_t sp = (gsrc_t)(sbase + (uint64_t)(stream * s_stream + so));
+    const gdst_t dp = (gdst_t)(dbase + (uint64_t)(stream * d_stream + dof));
 
     const int r = lane >> 4, c = lane & 15;
     const uint32_t i = (uint32_t)(r == 0 ? i0 : r == 1 ? i1 : r == 2 ? i2 : i3);

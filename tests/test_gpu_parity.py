@@ -264,6 +264,7 @@ def run_compact(b, ref, k_src, v_src, kept, n_src=None):
     (2, 2, 3, 41, 100, torch.bfloat16, True),       # 200-byte rows: 8-byte vectors
     (1, 2, 2, 33, 5, torch.int16, True),            # 10-byte rows: 2-byte vectors
     (1, 4, 8, 2000, 128, torch.bfloat16, True),     # several tiles per plane
+    (2, 3, 4, 1024, 128, torch.bfloat16, True),     # 256-byte rows, planes a power of two apart: tiles exchanged by plane
 ])
 def test_compact_per_layer_tensors_matches_oracle(b, ref, S, L, H, P, D, dtype, with_v):
     """sirllm_compact_kv_layers: the cache as one [streams, heads, slots, head_dim] tensor per layer, sources and
