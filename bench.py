@@ -267,7 +267,9 @@ def main():
     sb.gather()                                                                        # leave the step's own result behind
     log(f"[bench] the gather on the identity list (contiguous copy, same kernel): {ident_avg*1e3:.1f} us -> {ident_gbps:.0f} GB/s")
     if bytes_["compact"] >= bytes_["score"]:
-        dom, dom_bytes, dom_ms = "gather_rows_kernel", bytes_["compact"], gather_avg
+        # rows of 256 bytes are copied by a kernel of their own
+        gather_name = "gather_rows16_kernel" if w.head_dim * w.kv_elem_bytes == 256 else "gather_rows_kernel"
+        dom, dom_bytes, dom_ms = gather_name, bytes_["compact"], gather_avg
     else:
         dom, dom_bytes, dom_ms = "score_rows_kernel", bytes_["score"], score_avg
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
