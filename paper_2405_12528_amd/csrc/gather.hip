@@ -17,17 +17,24 @@ __global__ __launch_bounds__(BLOCK) void gather_rows_kernel(GatherLaunch g)
         g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z);
 }
 
-// Rows of sixteen 16-byte vectors, one vector per lane: the kept indices come through the scalar cache.
+// Rows of sixteen 16-byte vectors (256 bytes), one vector per lane: the kept indices come through the scalar cache.
 template <int BLOCK, bool OFF64>
 __global__ __launch_bounds__(BLOCK) void gather_rows16_kernel(GatherLaunch g)
 {
-    gather_dev::gather_tile_rows16<BLOCK, true, OFF64>(g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z);
+    gather_dev::gather_tile_wave_rows<BLOCK, true, OFF64, 4>(g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z);
+}
+
+// The same for rows of 32 vectors (LV = 5) and for rows of 64 vectors and more (LV = 6), single-wave tiles.
+template <int LV, bool OFF64>
+__global__ __launch_bounds__(64) void gather_wave_rows_kernel(GatherLaunch g)
+{
+    gather_dev::gather_tile_wave_rows<64, true, OFF64, LV>(g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z);
 }
 
 template <bool OFF64>
 __global__ __launch_bounds__(64) void gather_rows16_layers_kernel(GatherLaunch g, LayerTable t)
 {
-    gather_dev::gather_tile_rows16<64, true, OFF64, true>(g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z, &t);
+    gather_dev::gather_tile_wave_rows<64, true, OFF64, 4, true>(g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z, &t);
 }
 
 template <typename VecT, bool POW2, bool OFF64>
@@ -63,13 +70,17 @@ hipError_t launch_vec(const GatherArgs& a, int row_begin, int row_end, hipStream
     // less time, never more).  Rows of 256 bytes (sixteen vectors) have a kernel of their own that fetches the kept
     // indices by scalar loads; it runs best as single waves (64 threads: another 2 to 6 % on all but one workload).
     const bool rows16_shape = sizeof(VecT) == 16 && g.vpr == 16;
-    int block = tuning::get("SIRLLM_GATHER_BLOCK", rows16_shape ? 64 : 128);
+    // ... and so do longer rows that are a power of two of vectors (512 bytes: +2.5 %, 2 KB: +2 %; rows of 128 bytes, eight to
+    // a wave, measured 1.4 % slower than with per-lane index loads and stay with the general kernel)
+    const bool wave_rows_shape = sizeof(VecT) == 16 && pow2 && g.vpr >= 32;
+    int block = tuning::get("SIRLLM_GATHER_BLOCK", rows16_shape || wave_rows_shape ? 64 : 128);
     if (block != 64 && block != 256 && block != 512) block = 128;
     const int unroll = block == 64 ? 1 : (tuning::get("SIRLLM_GATHER_UNROLL", 1) == 2 ? 2 : 1);
     const bool nt = block == 64 || tuning::get("SIRLLM_GATHER_NT", 1) != 0;
-    const bool rows16 = rows16_shape && unroll == 1 && nt && (block == 64 || block == 128) &&
-                        tuning::get("SIRLLM_GATHER_SCALAR_IDX", 1) != 0;
-    // source planes a power of two apart: see gather_tile_rows16
+    const bool scalar_idx = tuning::get("SIRLLM_GATHER_SCALAR_IDX", 1) != 0;
+    const bool rows16 = rows16_shape && unroll == 1 && nt && (block == 64 || block == 128) && scalar_idx;
+    const bool wave_rows = wave_rows_shape && block == 64 && scalar_idx;
+    // source planes a power of two apart: see gather_tile_wave_rows
     const bool pow2_planes = a.s_head > 0 && (a.s_head & (a.s_head - 1)) == 0;
     g.rotate = tuning::get("SIRLLM_GATHER_ROTATE", pow2_planes ? 1 : 0) != 0 ? 1 : 0;
     const int per_block = block * unroll;
@@ -81,7 +92,15 @@ hipError_t launch_vec(const GatherArgs& a, int row_begin, int row_end, hipStream
             g.stream0 = s0;
             g.plane0 = p0;
             const dim3 grid(n_tiles, (unsigned)min(kMaxDim, planes - p0), (unsigned)min(kMaxDim, a.n_streams - s0));
-            if (rows16) {
+            if (wave_rows) {
+                if (g.vpr == 32) {
+                    if (off64) hipLaunchKernelGGL((gather_wave_rows_kernel<5, true>), grid, dim3(64), 0, stream, g);
+                    else       hipLaunchKernelGGL((gather_wave_rows_kernel<5, false>), grid, dim3(64), 0, stream, g);
+                } else {
+                    if (off64) hipLaunchKernelGGL((gather_wave_rows_kernel<6, true>), grid, dim3(64), 0, stream, g);
+                    else       hipLaunchKernelGGL((gather_wave_rows_kernel<6, false>), grid, dim3(64), 0, stream, g);
+                }
+            } else if (rows16) {
                 if (block == 64) {
                     if (off64) hipLaunchKernelGGL((gather_rows16_kernel<64, true>), grid, dim3(64), 0, stream, g);
                     else       hipLaunchKernelGGL((gather_rows16_kernel<64, false>), grid, dim3(64), 0, stream, g);

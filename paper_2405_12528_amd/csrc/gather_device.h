@@ -75,19 +75,22 @@ __device__ __forceinline__ void gather_tile_at(const GatherLaunch& g, int tile, 
         if (live[u]) st<VecT, NT>(dp + doff[u], v[u]);
 }
 
-// A tile for rows of exactly 16 vectors (256 bytes: 128 two-byte channels, the common head) and one vector per lane.
-// A wave covers four whole rows, so their four kept indices are wave-uniform and come through the scalar cache (four
-// scalar loads from clamped positions) instead of one vector load per lane; each lane then picks its row's index.
-// Every kernel argument the wave needs is requested in one batch at its start, the indices in a second one: two
-// scalar round trips, then the wave's first vector memory operation is the row load itself.  The kept list must not
-// be written while the launch runs (it is read through the constant address space), which every caller of the
-// compaction already guarantees: destination buffers and kept list may not overlap.
+// A tile for rows that are a power of two of 16-byte vectors, at least sixteen (256 bytes), one vector per lane.
+// LV = log2(vectors per row) for rows of 16 or 32 vectors: a wave covers 4 or 2 whole rows; LV = 6 stands for
+// every row of 64 vectors or more (the real shift is g.shift): a wave covers 64 consecutive vectors of ONE row.  Either
+// way the wave's kept indices are wave-uniform, so they come through the scalar cache (scalar loads from clamped
+// positions, the list read through the constant address space) instead of one vector load per lane; each lane then
+// picks its row's index.  Every kernel argument the wave needs is requested in one batch at its start, the indices in
+// a second one: two scalar round trips, then the wave's first vector memory operation is the row load itself.  The
+// kept list must not be written while the launch runs, which every caller of the compaction already guarantees:
+// destination buffers and kept list may not overlap.
 // LAYERS: the cache is one buffer per layer and tensor, `table` holds their base pointers (else it is not read).
-template <int BLOCK, bool NT, bool OFF64, bool LAYERS = false>
-__device__ __forceinline__ void gather_tile_rows16(const GatherLaunch& g, int tile, int plane, int stream,
-                                                   const LayerTable* table = nullptr)
+template <int BLOCK, bool NT, bool OFF64, int LV, bool LAYERS = false>
+__device__ __forceinline__ void gather_tile_wave_rows(const GatherLaunch& g, int tile, int plane, int stream,
+                                                      const LayerTable* table = nullptr)
 {
-    static_assert(BLOCK % 64 == 0, "four rows of sixteen 16-byte vectors per wave");
+    static_assert(BLOCK % 64 == 0 && LV >= 4 && LV <= 6, "whole waves; rows of 16, 32 or >= 64 vectors");
+    constexpr int R = 64 >> LV;                                       // whole rows per wave (1: one row, or a part of one)
     using VecT = u32x4;
     using off_t = typename std::conditional<OFF64, int64_t, uint32_t>::type;
     typedef const __attribute__((address_space(4))) int32_t* const_idx_t;     // read-only for the whole launch: scalar loads
@@ -98,12 +101,13 @@ __device__ __forceinline__ void gather_tile_rows16(const GatherLaunch& g, int ti
     uint64_t idx_base = (uint64_t)(uintptr_t)a.kept_idx;
     int64_t idx_stride = a.idx_stride;
     int row_begin = g.row_begin, row_end = g.row_end, lh = g.lh, uniform = g.uniform, n_heads = a.n_heads, n_src = a.n_src;
+    int shift = LV < 6 ? LV : g.shift;
     uint64_t src0 = (uint64_t)(uintptr_t)a.src[0], src1 = (uint64_t)(uintptr_t)a.src[1];
     uint64_t dst0 = (uint64_t)(uintptr_t)a.dst[0], dst1 = (uint64_t)(uintptr_t)a.dst[1];
     int64_t s_stream = a.s_stream, d_stream = a.d_stream, s_head = a.s_head, d_head = a.d_head, s_layer = a.s_layer,
             d_layer = a.d_layer, s_pos = a.s_pos, d_pos = a.d_pos;
     asm volatile("" : "+s"(idx_base), "+s"(idx_stride), "+s"(row_begin), "+s"(row_end), "+s"(lh), "+s"(uniform), "+s"(n_heads),
-                      "+s"(n_src));
+                      "+s"(n_src), "+s"(shift));
     asm volatile("" : "+s"(src0), "+s"(src1), "+s"(dst0), "+s"(dst1), "+s"(s_stream), "+s"(d_stream), "+s"(s_head), "+s"(d_head));
     asm volatile("" : "+s"(s_layer), "+s"(d_layer), "+s"(s_pos), "+s"(d_pos));
 
@@ -117,16 +121,16 @@ __device__ __forceinline__ void gather_tile_rows16(const GatherLaunch& g, int ti
     // XCD every residue in turn.  It costs 3-7 % where nothing needs curing (many planes, strides that are no power of
     // two), so the launcher asks for it only where it pays.
     if (g.rotate && tile < ((int)gridDim.x & ~7)) tile ^= plane & 7;
-    const int r0 = (tile * (BLOCK / 64) + wave) * 4;                 // first of the wave's four rows (relative to row_begin)
+    const int item0 = (tile * (BLOCK / 64) + wave) * 64;             // the wave's first vector, counted over the plane's rows
+    const int r0 = item0 >> shift;                                   // its first row (relative to row_begin)
     if (r0 >= n_rows) return;                                        // wave-uniform
     const int last = n_rows - 1;
     const int tensor = plane >= lh ? 1 : 0;
     const int ph = plane - tensor * lh;
     const_idx_t idx = (const_idx_t)(idx_base + (uint64_t)((stream * idx_stride + row_begin) * 4));
-    int32_t i0 = idx[r0];
-    int32_t i1 = idx[min(r0 + 1, last)];
-    int32_t i2 = idx[min(r0 + 2, last)];
-    int32_t i3 = idx[min(r0 + 3, last)];
+    int32_t iv[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) iv[q] = q < R ? idx[min(r0 + q, last)] : 0;
     uint64_t sbase, dbase;
     int64_t so, dof;
     if constexpr (LAYERS) {
@@ -148,12 +152,18 @@ __device__ __forceinline__ void gather_tile_rows16(const GatherLaunch& g, int ti
             dof = l * d_layer + h * d_head;
         }
     }
-    asm volatile("" : "+s"(i0), "+s"(i1), "+s"(i2), "+s"(i3));       // all four requested before any is looked at
+    // every index requested before any is looked at
+    if constexpr (R == 4) asm volatile("" : "+s"(iv[0]), "+s"(iv[1]), "+s"(iv[2]), "+s"(iv[3]));
+    else if constexpr (R == 2) asm volatile("" : "+s"(iv[0]), "+s"(iv[1]));
+    else asm volatile("" : "+s"(iv[0]));
     const gsrc_t sp = (gsrc_t)(sbase + (uint64_t)(stream * s_stream + so));
     const gdst_t dp = (gdst_t)(dbase + (uint64_t)(stream * d_stream + dof));
 
-    const int r = lane >> 4, c = lane & 15;
-    const uint32_t i = (uint32_t)(r == 0 ? i0 : r == 1 ? i1 : r == 2 ? i2 : i3);
+    const int r = R > 1 ? lane >> (LV < 6 ? LV : 0) : 0;             // which of the wave's rows
+    const int c = (item0 + lane) & ((1 << shift) - 1);               // which vector of the row
+    uint32_t i = (uint32_t)iv[0];
+#pragma unroll
+    for (int q = 1; q < R; ++q) i = r == q ? (uint32_t)iv[q] : i;
     if (r0 + r >= n_rows) return;
     const int j = row_begin + r0 + r;
     VecT v = VecT{};

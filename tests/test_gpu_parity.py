@@ -329,13 +329,15 @@ def test_compact_matches_oracle(b, ref, S, L, H, P, D, dtype):
 
 
 @pytest.mark.parametrize("P", [512, 600, 4096], ids=["planes 128 KB apart", "planes 150 KB apart", "planes 1 MB apart"])
-@pytest.mark.parametrize("dtype,D", [(torch.bfloat16, 128), (torch.float32, 64)])
-def test_compact_rows_of_256_bytes(b, ref, P, dtype, D):
-    """Rows of 256 bytes take a kernel of their own: a wave copies four whole rows and fetches their four kept indices
-    by scalar loads (clamped at the end of the list); where the source planes lie a power of two apart (P = 512, 4096)
-    the tiles of every group of eight are exchanged by the plane index, the ragged last group excepted.  Kept counts
-    around the edges of a wave's four rows and of a group of eight tiles, twelve and twenty planes (every value of the
-    plane index modulo 8), lists with runs, with entries that have no source slot, K alone and K with V."""
+@pytest.mark.parametrize("dtype,D", [(torch.bfloat16, 128), (torch.float32, 64), (torch.bfloat16, 256), (torch.float32, 512)],
+                         ids=["256-byte rows bf16", "256-byte rows f32", "512-byte rows", "2 KB rows"])
+def test_compact_power_of_two_rows(b, ref, P, dtype, D):
+    """Rows of 256 bytes, 512 bytes and of 1 KB and more (a power of two) take single-wave tiles: a wave copies four or
+    two whole rows, or 64 vectors of one, and fetches its kept indices by scalar loads (clamped at the end of the
+    list); where the source planes lie a power of two apart (P = 512, 4096) the tiles of every group of eight are
+    exchanged by the plane index, the ragged last group excepted.  Kept counts around the edges of a wave's rows and
+    of a group of eight tiles, twelve and twenty planes (every value of the plane index modulo 8), lists with runs,
+    with entries that have no source slot, K alone and K with V."""
     rng = np.random.default_rng(P + D)
     for S, L, H in ((1, 3, 4), (2, 5, 2)):
         k = (synth.tagged_kv(S, L, H, P, D, 0) % 32749).to(dtype).to(DEV)
