@@ -232,7 +232,8 @@ int sirllm_decay_select_static(const float* scores, int64_t scores_stride,
  *     dst(s, l, h, j, :) = src(s, l, h, kept_idx[s*idx_stride + j], :),   0 <= j < n_keep
  * for K (k_src -> k_dst) and V (v_src -> v_dst).  src and dst layouts must agree in
  * n_layers, n_kv_heads, head_dim and elem_bytes; strides may differ.  v_src/v_dst may both be
- * NULL to move one tensor only.  Source and destination must not overlap.
+ * NULL to move one tensor only.  Source and destination must not overlap, and kept_idx must lie outside every
+ * destination buffer (it is read while they are written; not checked).
  *   n_src   number of valid slots per (stream, layer, head) in the source; an index outside
  *           [0, n_src) cannot be reported without a device read-back, so the destination row
  *           is zero-filled instead of reading out of bounds.
