@@ -123,6 +123,10 @@ def measure_other_workload(torch, b, synth, name, dev, reps=5):
     spread between repetitions is part of the result."""
     w = synth.WORKLOADS[name]
     sb = StepBench(torch, b, synth, w, dev)
+    # gigabytes were handed back to the driver just before (the previous workload's buffers): one repetition in five
+    # came out 2-3 x slower right after that without a pause, always on the first workload measured here
+    torch.cuda.synchronize()
+    time.sleep(0.3)
     bytes_ = w.algorithmic_bytes()
     est_ms = max(bytes_["total"] / 6.0e12 * 1e3, 0.03)
     steps = int(max(4, min(60, 40.0 / est_ms)))                # about 40 ms of GPU time per repetition

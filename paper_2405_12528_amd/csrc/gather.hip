@@ -81,7 +81,9 @@ hipError_t launch_vec(const GatherArgs& a, int row_begin, int row_end, hipStream
     const bool rows16 = rows16_shape && unroll == 1 && nt && (block == 64 || block == 128) && scalar_idx;
     const bool wave_rows = wave_rows_shape && block == 64 && scalar_idx;
     // source planes a power of two apart: see gather_tile_wave_rows
-    const bool pow2_planes = a.s_head > 0 && (a.s_head & (a.s_head - 1)) == 0;
+    // (and compacted planes of 1 MiB and more: below that the dips only show on lists that are one run, and the
+    // exchange costs 3-6 % on scattered lists once there are thousands of planes)
+    const bool pow2_planes = a.s_head > 0 && (a.s_head & (a.s_head - 1)) == 0 && (int64_t)a.n_keep * a.d_pos >= (1 << 20);
     g.rotate = tuning::get("SIRLLM_GATHER_ROTATE", pow2_planes ? 1 : 0) != 0 ? 1 : 0;
     const int per_block = block * unroll;
     const unsigned n_tiles = (unsigned)((n_items + per_block - 1) / per_block);
@@ -137,7 +139,7 @@ hipError_t launch_vec_layers(const GatherArgs& a, const LayerTable& t, hipStream
     const int64_t n_items = (int64_t)a.n_keep * g.vpr;
     // rows of 256 bytes: single-wave tiles with scalar index loads, as in launch_vec
     const bool rows16 = sizeof(VecT) == 16 && g.vpr == 16;
-    const bool pow2_planes = a.s_head > 0 && (a.s_head & (a.s_head - 1)) == 0;
+    const bool pow2_planes = a.s_head > 0 && (a.s_head & (a.s_head - 1)) == 0 && (int64_t)a.n_keep * a.d_pos >= (1 << 20);
     g.rotate = rows16 && pow2_planes ? 1 : 0;
     const unsigned n_tiles = (unsigned)((n_items + (rows16 ? 63 : 127)) / (rows16 ? 64 : 128));
     const int planes = a.n_tensors * g.lh;            // at most 2 * 32 * n_heads

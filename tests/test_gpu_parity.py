@@ -264,7 +264,7 @@ def run_compact(b, ref, k_src, v_src, kept, n_src=None):
     (2, 2, 3, 41, 100, torch.bfloat16, True),       # 200-byte rows: 8-byte vectors
     (1, 2, 2, 33, 5, torch.int16, True),            # 10-byte rows: 2-byte vectors
     (1, 4, 8, 2000, 128, torch.bfloat16, True),     # several tiles per plane
-    (2, 3, 4, 1024, 128, torch.bfloat16, True),     # 256-byte rows, planes a power of two apart: tiles exchanged by plane
+    (2, 3, 4, 8192, 128, torch.bfloat16, True),     # 256-byte rows, planes 2 MiB apart, 1.2 MiB kept: tiles exchanged by plane
 ])
 def test_compact_per_layer_tensors_matches_oracle(b, ref, S, L, H, P, D, dtype, with_v):
     """sirllm_compact_kv_layers: the cache as one [streams, heads, slots, head_dim] tensor per layer, sources and
@@ -335,7 +335,8 @@ def test_compact_power_of_two_rows(b, ref, P, dtype, D):
     """Rows of 256 bytes, 512 bytes and of 1 KB and more (a power of two) take single-wave tiles: a wave copies four or
     two whole rows, or 64 vectors of one, and fetches its kept indices by scalar loads (clamped at the end of the
     list); where the source planes lie a power of two apart (P = 512, 4096) the tiles of every group of eight are
-    exchanged by the plane index, the ragged last group excepted.  Kept counts around the edges of a wave's rows and
+    exchanged by the plane index once a compacted plane holds 1 MiB, the ragged last group excepted (here: the largest
+    kept counts of P = 4096 and of the longer rows).  Kept counts around the edges of a wave's rows and
     of a group of eight tiles, twelve and twenty planes (every value of the plane index modulo 8), lists with runs,
     with entries that have no source slot, K alone and K with V."""
     rng = np.random.default_rng(P + D)
