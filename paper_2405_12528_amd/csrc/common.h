@@ -160,6 +160,11 @@ struct LayerTable {
     char* dst[2][kLayerTable];
 };
 hipError_t launch_gather_layers(const GatherArgs& a, const LayerTable& t, hipStream_t stream);
+// Ragged batches, out of place: stream s holds held_dev[s] + (cu_new_dev[s+1] - cu_new_dev[s]) slots; its n_keep_dev[s] kept
+// rows go to the destination (all of its rows while it is within its budget), nothing of a stream the selection flagged
+// (n_keep_dev[s] < 0); a.n_keep and a.n_src are upper bounds.
+hipError_t launch_gather_ragged(const GatherArgs& a, const int32_t* held_dev, const int32_t* cu_new_dev,
+                                const int32_t* n_keep_dev, int32_t budget, hipStream_t stream);
 
 // ---- gather_inplace.hip -----------------------------------------------------------------
 // src and dst of `a` are the same buffers and layouts; kept_idx must be strictly ascending.  `scratch` is optional:

@@ -18,23 +18,45 @@ __global__ __launch_bounds__(BLOCK) void gather_rows_kernel(GatherLaunch g)
 }
 
 // Rows of sixteen 16-byte vectors (256 bytes), one vector per lane: the kept indices come through the scalar cache.
+using gather_dev::WaveRowsArgs;
+
 template <int BLOCK, bool OFF64>
-__global__ __launch_bounds__(BLOCK) void gather_rows16_kernel(GatherLaunch g)
+__global__ __launch_bounds__(BLOCK) void gather_rows16_kernel(WaveRowsArgs w)
 {
-    gather_dev::gather_tile_wave_rows<BLOCK, true, OFF64, 4>(g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z);
+    gather_dev::gather_tile_wave_rows<BLOCK, true, OFF64, 4>(w, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z);
 }
 
 // The same for rows of 32 vectors (LV = 5) and for rows of 64 vectors and more (LV = 6), single-wave tiles.
 template <int LV, bool OFF64>
-__global__ __launch_bounds__(64) void gather_wave_rows_kernel(GatherLaunch g)
+__global__ __launch_bounds__(64) void gather_wave_rows_kernel(WaveRowsArgs w)
 {
-    gather_dev::gather_tile_wave_rows<64, true, OFF64, LV>(g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z);
+    gather_dev::gather_tile_wave_rows<64, true, OFF64, LV>(w, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z);
+}
+
+// Ragged batches (per-stream slot and row counts in device memory; streams flagged by the selection are left alone): the
+// single-wave tile for rows of 16, 32 or >= 64 vectors, the general tile for everything else.
+template <int LV, bool OFF64>
+__global__ __launch_bounds__(64) void gather_wave_rows_ragged_kernel(WaveRowsArgs w)
+{
+    gather_dev::gather_tile_wave_rows<64, true, OFF64, LV, false, true>(w, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z);
+}
+
+template <typename VecT, bool POW2, bool OFF64>
+__global__ __launch_bounds__(128) void gather_rows_ragged_kernel(GatherLaunch g, gather_dev::Ragged rg)
+{
+    const int stream = g.stream0 + (int)blockIdx.z;
+    int rows = 0;
+    const int n_src = gather_dev::ragged_rows(rg, stream, g.a.n_src, g.row_end - g.row_begin, rows);
+    if (n_src < 0) return;
+    g.a.n_src = n_src;
+    g.row_end = g.row_begin + rows;
+    gather_dev::gather_tile<VecT, 128, 1, true, POW2, OFF64>(g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, stream);
 }
 
 template <bool OFF64>
-__global__ __launch_bounds__(64) void gather_rows16_layers_kernel(GatherLaunch g, LayerTable t)
+__global__ __launch_bounds__(64) void gather_rows16_layers_kernel(WaveRowsArgs w, LayerTable t)
 {
-    gather_dev::gather_tile_wave_rows<64, true, OFF64, 4, true>(g, (int)blockIdx.x, g.plane0 + (int)blockIdx.y, g.stream0 + (int)blockIdx.z, &t);
+    gather_dev::gather_tile_wave_rows<64, true, OFF64, 4, true>(w, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, &t);
 }
 
 template <typename VecT, bool POW2, bool OFF64>
@@ -84,9 +106,10 @@ hipError_t launch_vec(const GatherArgs& a, int row_begin, int row_end, hipStream
     // (and compacted planes of 1 MiB and more: below that the dips only show on lists that are one run, and the
     // exchange costs 3-6 % on scattered lists once there are thousands of planes)
     const bool pow2_planes = a.s_head > 0 && (a.s_head & (a.s_head - 1)) == 0 && (int64_t)a.n_keep * a.d_pos >= (1 << 20);
-    g.rotate = tuning::get("SIRLLM_GATHER_ROTATE", pow2_planes ? 1 : 0) != 0 ? 1 : 0;
+    const bool rotate = tuning::get("SIRLLM_GATHER_ROTATE", pow2_planes ? 1 : 0) != 0;
     const int per_block = block * unroll;
     const unsigned n_tiles = (unsigned)((n_items + per_block - 1) / per_block);
+    g.rotate = rotate ? (int)(n_tiles & ~7u) : 0;
     const int planes = a.n_tensors * g.lh;
     constexpr int kMaxDim = 65535;
     for (int s0 = 0; s0 < a.n_streams; s0 += kMaxDim) {
@@ -94,21 +117,22 @@ hipError_t launch_vec(const GatherArgs& a, int row_begin, int row_end, hipStream
             g.stream0 = s0;
             g.plane0 = p0;
             const dim3 grid(n_tiles, (unsigned)min(kMaxDim, planes - p0), (unsigned)min(kMaxDim, a.n_streams - s0));
+            const WaveRowsArgs w = gather_dev::wave_rows_args(g, nullptr);
             if (wave_rows) {
                 if (g.vpr == 32) {
-                    if (off64) hipLaunchKernelGGL((gather_wave_rows_kernel<5, true>), grid, dim3(64), 0, stream, g);
-                    else       hipLaunchKernelGGL((gather_wave_rows_kernel<5, false>), grid, dim3(64), 0, stream, g);
+                    if (off64) hipLaunchKernelGGL((gather_wave_rows_kernel<5, true>), grid, dim3(64), 0, stream, w);
+                    else       hipLaunchKernelGGL((gather_wave_rows_kernel<5, false>), grid, dim3(64), 0, stream, w);
                 } else {
-                    if (off64) hipLaunchKernelGGL((gather_wave_rows_kernel<6, true>), grid, dim3(64), 0, stream, g);
-                    else       hipLaunchKernelGGL((gather_wave_rows_kernel<6, false>), grid, dim3(64), 0, stream, g);
+                    if (off64) hipLaunchKernelGGL((gather_wave_rows_kernel<6, true>), grid, dim3(64), 0, stream, w);
+                    else       hipLaunchKernelGGL((gather_wave_rows_kernel<6, false>), grid, dim3(64), 0, stream, w);
                 }
             } else if (rows16) {
                 if (block == 64) {
-                    if (off64) hipLaunchKernelGGL((gather_rows16_kernel<64, true>), grid, dim3(64), 0, stream, g);
-                    else       hipLaunchKernelGGL((gather_rows16_kernel<64, false>), grid, dim3(64), 0, stream, g);
+                    if (off64) hipLaunchKernelGGL((gather_rows16_kernel<64, true>), grid, dim3(64), 0, stream, w);
+                    else       hipLaunchKernelGGL((gather_rows16_kernel<64, false>), grid, dim3(64), 0, stream, w);
                 } else {
-                    if (off64) hipLaunchKernelGGL((gather_rows16_kernel<128, true>), grid, dim3(128), 0, stream, g);
-                    else       hipLaunchKernelGGL((gather_rows16_kernel<128, false>), grid, dim3(128), 0, stream, g);
+                    if (off64) hipLaunchKernelGGL((gather_rows16_kernel<128, true>), grid, dim3(128), 0, stream, w);
+                    else       hipLaunchKernelGGL((gather_rows16_kernel<128, false>), grid, dim3(128), 0, stream, w);
                 }
             } else if (block == 64) {
                 launch_shape<VecT, 64, 1, true>(g, grid, pow2, off64, stream);
@@ -140,8 +164,8 @@ hipError_t launch_vec_layers(const GatherArgs& a, const LayerTable& t, hipStream
     // rows of 256 bytes: single-wave tiles with scalar index loads, as in launch_vec
     const bool rows16 = sizeof(VecT) == 16 && g.vpr == 16;
     const bool pow2_planes = a.s_head > 0 && (a.s_head & (a.s_head - 1)) == 0 && (int64_t)a.n_keep * a.d_pos >= (1 << 20);
-    g.rotate = rows16 && pow2_planes ? 1 : 0;
     const unsigned n_tiles = (unsigned)((n_items + (rows16 ? 63 : 127)) / (rows16 ? 64 : 128));
+    g.rotate = rows16 && pow2_planes ? (int)(n_tiles & ~7u) : 0;
     const int planes = a.n_tensors * g.lh;            // at most 2 * 32 * n_heads
     constexpr int kMaxDim = 65535;
     const dim3 block(rows16 ? 64 : 128);
@@ -151,8 +175,9 @@ hipError_t launch_vec_layers(const GatherArgs& a, const LayerTable& t, hipStream
             g.plane0 = p0;
             const dim3 grid(n_tiles, (unsigned)min(kMaxDim, planes - p0), (unsigned)min(kMaxDim, a.n_streams - s0));
             if (rows16) {
-                if (off64) hipLaunchKernelGGL((gather_rows16_layers_kernel<true>), grid, block, 0, stream, g, t);
-                else       hipLaunchKernelGGL((gather_rows16_layers_kernel<false>), grid, block, 0, stream, g, t);
+                const WaveRowsArgs w = gather_dev::wave_rows_args(g, nullptr);
+                if (off64) hipLaunchKernelGGL((gather_rows16_layers_kernel<true>), grid, block, 0, stream, w, t);
+                else       hipLaunchKernelGGL((gather_rows16_layers_kernel<false>), grid, block, 0, stream, w, t);
             } else if (pow2) {
                 if (off64) hipLaunchKernelGGL((gather_rows_layers_kernel<VecT, true, true>), grid, block, 0, stream, g, t);
                 else       hipLaunchKernelGGL((gather_rows_layers_kernel<VecT, true, false>), grid, block, 0, stream, g, t);
@@ -167,7 +192,69 @@ hipError_t launch_vec_layers(const GatherArgs& a, const LayerTable& t, hipStream
     return hipSuccess;
 }
 
+// Ragged batches: default launch shapes only.
+template <typename VecT>
+hipError_t launch_vec_ragged(const GatherArgs& a, const gather_dev::Ragged& rg, hipStream_t stream)
+{
+    GatherLaunch g;
+    bool pow2, off64;
+    if (!gather_dev::fill_launch<VecT>(g, a, 0, a.n_keep, &pow2, &off64)) return hipErrorInvalidValue;
+    const int64_t n_items = (int64_t)a.n_keep * g.vpr;
+    const bool wave_rows = sizeof(VecT) == 16 && pow2 && g.vpr >= 16;
+    const bool pow2_planes = a.s_head > 0 && (a.s_head & (a.s_head - 1)) == 0 && (int64_t)a.n_keep * a.d_pos >= (1 << 20);
+    const int per_block = wave_rows ? 64 : 128;
+    const unsigned n_tiles = (unsigned)((n_items + per_block - 1) / per_block);
+    g.rotate = wave_rows && pow2_planes ? (int)(n_tiles & ~7u) : 0;
+    const int planes = a.n_tensors * g.lh;
+    constexpr int kMaxDim = 65535;
+    const dim3 block(per_block);
+    for (int s0 = 0; s0 < a.n_streams; s0 += kMaxDim) {
+        for (int p0 = 0; p0 < planes; p0 += kMaxDim) {
+            g.stream0 = s0;
+            g.plane0 = p0;
+            const dim3 grid(n_tiles, (unsigned)min(kMaxDim, planes - p0), (unsigned)min(kMaxDim, a.n_streams - s0));
+            if (wave_rows) {
+                const WaveRowsArgs w = gather_dev::wave_rows_args(g, &rg);
+                const int lv = g.vpr == 16 ? 4 : g.vpr == 32 ? 5 : 6;
+                if (lv == 4) {
+                    if (off64) hipLaunchKernelGGL((gather_wave_rows_ragged_kernel<4, true>), grid, block, 0, stream, w);
+                    else       hipLaunchKernelGGL((gather_wave_rows_ragged_kernel<4, false>), grid, block, 0, stream, w);
+                } else if (lv == 5) {
+                    if (off64) hipLaunchKernelGGL((gather_wave_rows_ragged_kernel<5, true>), grid, block, 0, stream, w);
+                    else       hipLaunchKernelGGL((gather_wave_rows_ragged_kernel<5, false>), grid, block, 0, stream, w);
+                } else {
+                    if (off64) hipLaunchKernelGGL((gather_wave_rows_ragged_kernel<6, true>), grid, block, 0, stream, w);
+                    else       hipLaunchKernelGGL((gather_wave_rows_ragged_kernel<6, false>), grid, block, 0, stream, w);
+                }
+            } else if (pow2) {
+                if (off64) hipLaunchKernelGGL((gather_rows_ragged_kernel<VecT, true, true>), grid, block, 0, stream, g, rg);
+                else       hipLaunchKernelGGL((gather_rows_ragged_kernel<VecT, true, false>), grid, block, 0, stream, g, rg);
+            } else {
+                if (off64) hipLaunchKernelGGL((gather_rows_ragged_kernel<VecT, false, true>), grid, block, 0, stream, g, rg);
+                else       hipLaunchKernelGGL((gather_rows_ragged_kernel<VecT, false, false>), grid, block, 0, stream, g, rg);
+            }
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+
 }  // namespace
+
+hipError_t launch_gather_ragged(const GatherArgs& a, const int32_t* held_dev, const int32_t* cu_new_dev,
+                                const int32_t* n_keep_dev, int32_t budget, hipStream_t stream)
+{
+    if (a.n_keep <= 0 || a.n_streams <= 0 || a.row_bytes <= 0 || a.n_layers <= 0 || a.n_heads <= 0) return hipSuccess;
+    const gather_dev::Ragged rg{held_dev, cu_new_dev, n_keep_dev, budget};
+    switch (gather_dev::vector_bytes(a)) {
+    case 16: return launch_vec_ragged<u32x4>(a, rg, stream);
+    case 8:  return launch_vec_ragged<u32x2>(a, rg, stream);
+    case 4:  return launch_vec_ragged<uint32_t>(a, rg, stream);
+    case 2:  return launch_vec_ragged<uint16_t>(a, rg, stream);
+    default: return launch_vec_ragged<uint8_t>(a, rg, stream);
+    }
+}
 
 hipError_t launch_gather_layers(const GatherArgs& a, const LayerTable& t, hipStream_t stream)
 {

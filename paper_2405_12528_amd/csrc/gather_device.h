@@ -36,8 +36,39 @@ struct GatherLaunch {
     int32_t stream0;      // first stream of this launch
     int32_t lh;           // n_layers * n_heads
     int32_t uniform;      // 1: s_layer == n_heads*s_head and d_layer == n_heads*d_head
-    int32_t rotate;       // rows-of-16-vectors kernel: exchange tiles inside groups of eight, differently from plane to plane
+    int32_t rotate;       // single-wave tiles: tiles below this index (a multiple of eight; 0: none) are exchanged inside their
+                          // group of eight, differently from plane to plane
 };
+
+// Ragged batches: per-stream slot counts in device memory.
+struct Ragged {
+    const int32_t* held_dev;    // null: uniform batch
+    const int32_t* cu_new_dev;
+    const int32_t* n_keep_dev;  // written by the selection launch that precedes this one on the stream
+    int32_t budget;
+};
+
+// Ragged batch: does stream s compact at all?  A stream the selection flagged (sizes negative or beyond the
+// caller's bounds: n_keep = -1) has no kept list of this call; its K/V stays as it is.  So does a stream that
+// is within its budget.  Returns the stream's slot count, or -1 when nothing moves.
+__device__ __forceinline__ int ragged_n_src(const Ragged& rg, int s, int n_src_bound)
+{
+    const int n_cand = rg.held_dev[s] + (rg.cu_new_dev[s + 1] - rg.cu_new_dev[s]);
+    if (rg.n_keep_dev[s] < 0 || n_cand <= rg.budget || n_cand > n_src_bound) return -1;
+    return n_cand;
+}
+
+// Ragged batch, out of place: every stream the selection accepted is moved, its n_keep_dev[s] kept rows (all of its
+// rows, in place order, while it is within its budget), so that afterwards the whole batch lives in the destination.
+// Returns the stream's slot count and its row count, or -1 for a flagged stream (nothing of it is touched).
+__device__ __forceinline__ int ragged_rows(const Ragged& rg, int s, int n_src_bound, int n_rows_bound, int& n_rows)
+{
+    const int n_cand = rg.held_dev[s] + (rg.cu_new_dev[s + 1] - rg.cu_new_dev[s]);
+    const int nk = rg.n_keep_dev[s];
+    if (nk < 0 || n_cand > n_src_bound) return -1;
+    n_rows = nk < n_rows_bound ? nk : n_rows_bound;
+    return n_cand;
+}
 
 // One tile of destination rows of the plane that starts at sp (source) / dp (destination) and belongs to `stream`.
 // POW2: vpr is a power of two.  OFF64: offsets inside a plane need more than 32 bits.
@@ -85,8 +116,40 @@ __device__ __forceinline__ void gather_tile_at(const GatherLaunch& g, int tile, 
 // kept list must not be written while the launch runs, which every caller of the compaction already guarantees:
 // destination buffers and kept list may not overlap.
 // LAYERS: the cache is one buffer per layer and tensor, `table` holds their base pointers (else it is not read).
-template <int BLOCK, bool NT, bool OFF64, int LV, bool LAYERS = false>
-__device__ __forceinline__ void gather_tile_wave_rows(const GatherLaunch& g, int tile, int plane, int stream,
+// RAGGED: every stream has its own slot and row counts in device memory, a flagged stream is left alone.
+//
+// The arguments of such a tile, packed so that every dword a wave fetches is one it needs (the compiler then has no
+// dead lane of a wide scalar load to reuse for a later load, which would force a wait in between).
+struct WaveRowsArgs {
+    uint64_t idx_base;                 // kept_idx
+    int64_t idx_stride;
+    uint64_t src0, src1, dst0, dst1;   // K | V bases (unused with LAYERS)
+    int64_t s_stream, d_stream, s_head, d_head, s_layer, d_layer, s_pos, d_pos;
+    int32_t row_begin, row_end, lh, uniform, n_heads, n_src, shift, rotate, plane0, stream0;
+    int32_t n_rows_pad[2];
+    uint64_t rg_held, rg_cu, rg_keep;  // RAGGED: n_held, cu_new, n_keep per stream
+};
+
+inline WaveRowsArgs wave_rows_args(const GatherLaunch& g, const Ragged* rg)
+{
+    WaveRowsArgs w;
+    const GatherArgs& a = g.a;
+    w.idx_base = (uint64_t)(uintptr_t)a.kept_idx; w.idx_stride = a.idx_stride;
+    w.src0 = (uint64_t)(uintptr_t)a.src[0]; w.src1 = (uint64_t)(uintptr_t)a.src[1];
+    w.dst0 = (uint64_t)(uintptr_t)a.dst[0]; w.dst1 = (uint64_t)(uintptr_t)a.dst[1];
+    w.s_stream = a.s_stream; w.d_stream = a.d_stream; w.s_head = a.s_head; w.d_head = a.d_head;
+    w.s_layer = a.s_layer; w.d_layer = a.d_layer; w.s_pos = a.s_pos; w.d_pos = a.d_pos;
+    w.row_begin = g.row_begin; w.row_end = g.row_end; w.lh = g.lh; w.uniform = g.uniform; w.n_heads = a.n_heads;
+    w.n_src = a.n_src; w.shift = g.shift; w.rotate = g.rotate; w.plane0 = g.plane0; w.stream0 = g.stream0;
+    w.n_rows_pad[0] = w.n_rows_pad[1] = 0;
+    w.rg_held = rg ? (uint64_t)(uintptr_t)rg->held_dev : 0;
+    w.rg_cu = rg ? (uint64_t)(uintptr_t)rg->cu_new_dev : 0;
+    w.rg_keep = rg ? (uint64_t)(uintptr_t)rg->n_keep_dev : 0;
+    return w;
+}
+
+template <int BLOCK, bool NT, bool OFF64, int LV, bool LAYERS = false, bool RAGGED = false>
+__device__ __forceinline__ void gather_tile_wave_rows(const WaveRowsArgs& w, int tile, int plane_in_launch, int stream_in_launch,
                                                       const LayerTable* table = nullptr)
 {
     static_assert(BLOCK % 64 == 0 && LV >= 4 && LV <= 6, "whole waves; rows of 16, 32 or >= 64 vectors");
@@ -96,22 +159,23 @@ __device__ __forceinline__ void gather_tile_wave_rows(const GatherLaunch& g, int
     typedef const __attribute__((address_space(4))) int32_t* const_idx_t;     // read-only for the whole launch: scalar loads
     typedef const __attribute__((address_space(1))) char* gsrc_t;
     typedef __attribute__((address_space(1))) char* gdst_t;
-    const GatherArgs& a = g.a;
-    // one batch of scalar loads from the argument block (addresses as integers, so that the batch can be pinned here)
-    uint64_t idx_base = (uint64_t)(uintptr_t)a.kept_idx;
-    int64_t idx_stride = a.idx_stride;
-    int row_begin = g.row_begin, row_end = g.row_end, lh = g.lh, uniform = g.uniform, n_heads = a.n_heads, n_src = a.n_src;
-    int shift = LV < 6 ? LV : g.shift;
-    uint64_t src0 = (uint64_t)(uintptr_t)a.src[0], src1 = (uint64_t)(uintptr_t)a.src[1];
-    uint64_t dst0 = (uint64_t)(uintptr_t)a.dst[0], dst1 = (uint64_t)(uintptr_t)a.dst[1];
-    int64_t s_stream = a.s_stream, d_stream = a.d_stream, s_head = a.s_head, d_head = a.d_head, s_layer = a.s_layer,
-            d_layer = a.d_layer, s_pos = a.s_pos, d_pos = a.d_pos;
-    asm volatile("" : "+s"(idx_base), "+s"(idx_stride), "+s"(row_begin), "+s"(row_end), "+s"(lh), "+s"(uniform), "+s"(n_heads),
-                      "+s"(n_src), "+s"(shift));
-    asm volatile("" : "+s"(src0), "+s"(src1), "+s"(dst0), "+s"(dst1), "+s"(s_stream), "+s"(d_stream), "+s"(s_head), "+s"(d_head));
-    asm volatile("" : "+s"(s_layer), "+s"(d_layer), "+s"(s_pos), "+s"(d_pos));
+    // one batch of scalar loads from the argument block
+    uint64_t idx_base = w.idx_base;
+    int64_t idx_stride = w.idx_stride;
+    int row_begin = w.row_begin, row_end = w.row_end, lh = w.lh, uniform = w.uniform, n_heads = w.n_heads, n_src = w.n_src;
+    int shift = LV < 6 ? LV : w.shift, rotate_below = w.rotate, plane = w.plane0 + plane_in_launch,
+        stream = w.stream0 + stream_in_launch;
+    uint64_t src0 = w.src0, src1 = w.src1, dst0 = w.dst0, dst1 = w.dst1;
+    int64_t s_stream = w.s_stream, d_stream = w.d_stream, s_head = w.s_head, d_head = w.d_head, s_layer = w.s_layer,
+            d_layer = w.d_layer, s_pos = w.s_pos, d_pos = w.d_pos;
+    uint64_t rg_held = RAGGED ? w.rg_held : 0, rg_cu = RAGGED ? w.rg_cu : 0, rg_keep = RAGGED ? w.rg_keep : 0;
+    asm volatile("" : "+s"(idx_base), "+s"(idx_stride), "+s"(src0), "+s"(src1), "+s"(dst0), "+s"(dst1));
+    asm volatile("" : "+s"(s_stream), "+s"(d_stream), "+s"(s_head), "+s"(d_head), "+s"(s_layer), "+s"(d_layer), "+s"(s_pos), "+s"(d_pos));
+    asm volatile("" : "+s"(row_begin), "+s"(row_end), "+s"(lh), "+s"(uniform), "+s"(n_heads), "+s"(n_src), "+s"(shift),
+                      "+s"(rotate_below), "+s"(plane), "+s"(stream));
+    if constexpr (RAGGED) asm volatile("" : "+s"(rg_held), "+s"(rg_cu), "+s"(rg_keep));
 
-    const int n_rows = row_end - row_begin;
+    int n_rows = row_end - row_begin;                                // ragged batch: an upper bound until the stream's own count is in
     const int lane = (int)threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
     // Workgroups are dealt to the eight XCDs round robin and a plane holds a multiple of eight tiles, so XCD x would
@@ -119,8 +183,8 @@ __device__ __forceinline__ void gather_tile_wave_rows(const GatherLaunch& g, int
     // a power of two apart, an XCD's traffic then keeps falling on the same few channels (measured: 5.2-5.9 instead of
     // 6.5 TB/s on long runs of kept slots).  Exchanging the tiles of each group of eight by the plane index gives every
     // XCD every residue in turn.  It costs 3-7 % where nothing needs curing (many planes, strides that are no power of
-    // two), so the launcher asks for it only where it pays.
-    if (g.rotate && tile < ((int)gridDim.x & ~7)) tile ^= plane & 7;
+    // two), so the launcher asks for it only where it pays (rotate_below: the end of the last whole group, or 0).
+    if (tile < rotate_below) tile ^= plane & 7;
     const int item0 = (tile * (BLOCK / 64) + wave) * 64;             // the wave's first vector, counted over the plane's rows
     const int r0 = item0 >> shift;                                   // its first row (relative to row_begin)
     if (r0 >= n_rows) return;                                        // wave-uniform
@@ -131,6 +195,20 @@ __device__ __forceinline__ void gather_tile_wave_rows(const GatherLaunch& g, int
     int32_t iv[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) iv[q] = q < R ? idx[min(r0 + q, last)] : 0;
+    if constexpr (RAGGED) {
+        // The stream's own sizes, in the same batch of scalar loads as the indices (which were clamped by the bound:
+        // the kept list has that many entries for every stream).  Inputs of the launch, or written by the selection
+        // launch before it: read-only here.
+        int32_t held = ((const_idx_t)rg_held)[stream];
+        int32_t cu0 = ((const_idx_t)rg_cu)[stream], cu1 = ((const_idx_t)rg_cu)[stream + 1];
+        int32_t nk = ((const_idx_t)rg_keep)[stream];
+        asm volatile("" : "+s"(held), "+s"(cu0), "+s"(cu1), "+s"(nk), "+s"(iv[0]), "+s"(iv[1]), "+s"(iv[2]), "+s"(iv[3]));
+        const int n_cand = held + (cu1 - cu0);
+        if (nk < 0 || n_cand > n_src) return;                        // a stream the selection flagged: nothing of it is touched
+        n_src = n_cand;
+        n_rows = nk < n_rows ? nk : n_rows;
+        if (r0 >= n_rows) return;
+    }
     uint64_t sbase, dbase;
     int64_t so, dof;
     if constexpr (LAYERS) {

@@ -25,22 +25,8 @@ namespace {
 
 using gather_dev::GatherLaunch;
 
-struct Ragged {
-    const int32_t* held_dev;    // null: uniform batch
-    const int32_t* cu_new_dev;
-    const int32_t* n_keep_dev;  // written by the selection launch that precedes this one on the stream
-    int32_t budget;
-};
-
-// Ragged batch: does stream s compact at all?  A stream the selection flagged (sizes negative or beyond the
-// caller's bounds: n_keep = -1) has no kept list of this call; its K/V stays as it is.  So does a stream that
-// is within its budget.  Returns the stream's slot count, or -1 when nothing moves.
-__device__ __forceinline__ int ragged_n_src(const Ragged& rg, int s, int n_src_bound)
-{
-    const int n_cand = rg.held_dev[s] + (rg.cu_new_dev[s + 1] - rg.cu_new_dev[s]);
-    if (rg.n_keep_dev[s] < 0 || n_cand <= rg.budget || n_cand > n_src_bound) return -1;
-    return n_cand;
-}
+using gather_dev::Ragged;
+using gather_dev::ragged_n_src;
 
 // Base address of plane `plane` of stream `stream` (uniform over the workgroup: scalar arithmetic).
 __device__ __forceinline__ char* plane_base(const GatherLaunch& g, int plane, int stream)

@@ -308,6 +308,30 @@ def test_inplace_and_ragged_argument_errors(b):
     assert ragged(l=None) == b.SIRLLM_ERR_INVALID_ARG
     assert ragged(n_streams=0) == b.SIRLLM_OK
 
+    lay_dst = b.sirllm_kv_layout(2, 2, 16, 4, 2 * 2 * 32 * 16, 2 * 32 * 16, 32 * 16, 16)
+    def ragged_oop(logits=0x1000, dt=0, vocab=1000, ld=1000, tok=0x2000000, scores=0x3000000, sstr=128, n_streams=2,
+                   held=0x7000000, cu=0x7100000, total=64, max_cand=100, max_new=64, pol=p, k=0x10000000, v=0x20000000,
+                   l=lay, kd=0x40000000, vd=0x48000000, ld_=lay_dst, idx=0x5000000, istr=32, out=0x6000000, ostr=32,
+                   keep=0x7200000, ws=None, ws_bytes=0):
+        return L.sirllm_step_ragged_out_of_place(logits, dt, vocab, ld, tok, scores, sstr, n_streams, held, cu, total,
+                                                 max_cand, max_new, C.byref(pol) if pol else None, k, v,
+                                                 C.byref(l) if l else None, kd, vd, C.byref(ld_) if ld_ else None, idx, istr,
+                                                 out, ostr, keep, ws, ws_bytes, None)
+    assert ragged_oop(kd=None) == b.SIRLLM_ERR_INVALID_ARG              # max_cand > budget: somewhere to compact to is needed
+    assert ragged_oop(ld_=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged_oop(vd=None) == b.SIRLLM_ERR_INVALID_ARG              # V on one side only
+    assert ragged_oop(kd=0x10000000 + 4096) == b.SIRLLM_ERR_INVALID_ARG  # destination inside the source
+    assert ragged_oop(vd=0x40000000 + 64) == b.SIRLLM_ERR_INVALID_ARG   # the two destinations overlap
+    other = b.sirllm_kv_layout(2, 2, 32, 4, 2 * 2 * 32 * 32, 2 * 32 * 32, 32 * 32, 32)
+    assert ragged_oop(ld_=other) == b.SIRLLM_ERR_INVALID_ARG            # head_dim differs between the two sides
+    assert ragged_oop(k=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged_oop(pol=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged_oop(dt=9) == b.SIRLLM_ERR_UNSUPPORTED
+    assert ragged_oop(max_new=101) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged_oop(istr=31) == b.SIRLLM_ERR_INVALID_ARG
+    assert ragged_oop(max_cand=40000, sstr=40000) in (b.SIRLLM_ERR_WORKSPACE, b.SIRLLM_ERR_INVALID_ARG)
+    assert ragged_oop(n_streams=0) == b.SIRLLM_OK
+
     def lm_ragged(hidden=0x1000, ld_h=64, weight=0x8000000, ld_w=64, dt=1, d_model=64, vocab=1000, tok=0x2000000,
                   scores=0x3000000, sstr=128, n_streams=2, held=0x7000000, cu=0x7100000, total=64, max_cand=100,
                   max_new=64, pol=p, k=0x10000000, v=0x20000000, l=lay, idx=0x5000000, istr=32, out=0x6000000, ostr=32,

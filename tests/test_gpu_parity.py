@@ -775,12 +775,14 @@ def test_compact_inplace_strided_view_and_bad_indices(b, ref):
 
 # ------------------------------------------------------------------------------ ragged batches
 def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=torch.float32, cap=None,
-               tight_new=True, new_cap=None, lmhead_d=None):
+               tight_new=True, new_cap=None, lmhead_d=None, out_of_place=False):
     """One ragged step on the GPU and in the oracle; compares everything the step writes.  cap / new_cap: the
     bounds on n_cand[s] / n_new[s] promised to the library when they are lower than what the streams hold; a
     stream beyond either, or with a negative n_held, must come back flagged with nothing of its kept list or
     K/V touched.  lmhead_d: the scores come from hidden states of that width and an output embedding matrix
-    (sirllm_step_lmhead_ragged) instead of stored logits."""
+    (sirllm_step_lmhead_ragged) instead of stored logits.  out_of_place: sirllm_step_ragged_out_of_place -- every accepted
+    stream's kept slots land in a second pair of buffers (compacted when over budget, as they are otherwise), which must
+    keep their sentinel past n_keep and for flagged streams; no source byte may change."""
     n_held, n_new = np.asarray(n_held), np.asarray(n_new)
     n_cand = n_held + n_new
     max_cand = int(n_cand.max()) if cap is None else cap
@@ -816,7 +818,12 @@ def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=
         max_new = new_cap
     bound_new = max_new if max_new is not None else min(total, max_cand)
     fits_all = (n_held >= 0) & (n_new <= bound_new) & (n_cand <= max_cand)
-    if lmhead_d is None:
+    if out_of_place:
+        kd = torch.full((S, L, H, keep_cap + 1, D), 77, dtype=kv_dt, device=DEV)
+        vd = torch.full((S, L, H, keep_cap + 1, D), 77, dtype=kv_dt, device=DEV)
+        b.sirllm_step_ragged_out_of_place(z, tok, V, scores, held_dev, cu, total, max_cand, pol, k, v, kd, vd, kept, out,
+                                          n_keep_dev, max_new=max_new, workspace=ws)
+    elif lmhead_d is None:
         b.sirllm_step_ragged(z, tok, V, scores, held_dev, cu, total, max_cand, pol, k, v, kept, out, n_keep_dev,
                              max_new=max_new, workspace=ws)
     else:
@@ -851,6 +858,8 @@ def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=
         np.testing.assert_array_equal(gs[s, n_cand[s]:], hs[s, n_cand[s]:])
     ok = [s for s in range(S) if fits_all[s]]
     forced = gs.copy()
+    if out_of_place:
+        want_kd, want_vd = to_np(torch.full_like(kd, 77)), to_np(torch.full_like(vd, 77))
     # the oracle recomputes the new scores itself; overwrite them with the GPU's afterwards by calling the pieces
     for s in ok:
         h, n = int(n_held[s]), int(n_new[s])
@@ -862,10 +871,16 @@ def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=
         np.testing.assert_array_equal(to_np(kept)[s, :ki.shape[1]], ki[0])
         np.testing.assert_array_equal(to_np(out)[s, :ki.shape[1]].view(np.uint32), so[0].view(np.uint32))
         assert (to_np(kept)[s, ki.shape[1]:] == -7).all()
-        if h + n > budget:
+        if out_of_place:                                  # every accepted stream moves: compacted, or as it is
+            rk, rv = ref.compact_kv(hk[s:s + 1], hv[s:s + 1], ki, n_src=h + n)
+            want_kd[s, :, :, :ki.shape[1]], want_vd[s, :, :, :ki.shape[1]] = rk[0], rv[0]
+        elif h + n > budget:
             ref.compact_kv_inplace(hk[s:s + 1], hv[s:s + 1], ki, n_src=h + n)
     assert np.array_equal(to_np(k), hk), "K differs (compacted streams, untouched streams or tails)"
     assert np.array_equal(to_np(v), hv), "V differs"
+    if out_of_place:
+        assert np.array_equal(to_np(kd), want_kd), "destination K differs (compacted streams, or written where nothing may be)"
+        assert np.array_equal(to_np(vd), want_vd), "destination V differs"
 
 
 def test_step_ragged_matches_oracle(b, ref):
@@ -902,6 +917,36 @@ def test_step_ragged_matches_oracle(b, ref):
         run_ragged(b, ref, rng, S, b.Policy(int(rng.integers(0, 5)), int(rng.integers(0, 60)), int(rng.integers(0, 20)), 0.7),
                    int(rng.integers(2, 900)), torch.float32 if rng.integers(2) else torch.bfloat16,
                    rng.integers(0, 150, S), rng.integers(0, 40, S))
+
+
+def test_step_ragged_out_of_place_matches_oracle(b, ref):
+    """sirllm_step_ragged_out_of_place against the oracle stream by stream: every accepted stream's kept slots arrive
+    in the second pair of buffers, compacted when over budget and as they are otherwise (rows of 64 and 10 bytes: the
+    general kernel; of 256 bytes, 512 bytes and 2 KB: the single-wave tiles), flagged streams and everything past a
+    stream's n_keep keep the sentinel, no source byte changes; streams under budget, empty streams, fused and
+    three-launch selection, a selection over several workgroups."""
+    rng = np.random.default_rng(78)
+    pol = b.Policy(4, 20, 8, 0.9)                       # budget 32
+    run_ragged(b, ref, rng, 6, pol, 500, torch.float32, [0, 10, 24, 40, 90, 0], [5, 22, 8, 0, 17, 0], out_of_place=True)
+    run_ragged(b, ref, rng, 3, pol, 777, torch.bfloat16, [100, 31, 0], [1, 1, 64], kv_dt=torch.bfloat16, D=128, out_of_place=True)
+    run_ragged(b, ref, rng, 3, pol, 300, torch.bfloat16, [100, 31, 60], [1, 1, 7], kv_dt=torch.bfloat16, D=256, out_of_place=True)
+    run_ragged(b, ref, rng, 3, pol, 300, torch.float32, [100, 31, 60], [1, 1, 7], kv_dt=torch.float32, D=512, out_of_place=True)
+    run_ragged(b, ref, rng, 2, pol, 300, torch.float32, [100, 31], [1, 1], kv_dt=torch.int16, D=5, out_of_place=True)
+    run_ragged(b, ref, rng, 1, pol, 64, torch.float32, [200], [0], out_of_place=True)
+    run_ragged(b, ref, rng, 4, b.Policy(4, 1020, 0, 0.8), 300, torch.bfloat16, [1024, 1000, 500, 1024], [54, 54, 54, 1],
+               L=1, H=2, D=64, kv_dt=torch.bfloat16, out_of_place=True)
+    run_ragged(b, ref, rng, 3, pol, 100, torch.float32, [10, 60, 20], [5, 30, 5], cap=40, tight_new=False, out_of_place=True)
+    run_ragged(b, ref, rng, 4, pol, 100, torch.float32, [40, 30, 50, 45], [5, 20, 8, 3], new_cap=8, out_of_place=True)
+    run_ragged(b, ref, rng, 4, pol, 100, torch.bfloat16, [40, -3, 50, -40], [5, 60, 8, 90], cap=100, new_cap=90, out_of_place=True)
+    run_ragged(b, ref, rng, 3, b.Policy(4, 3068, 1024, 0.85), 2000, torch.bfloat16, [7168, 100, 4000], [1024, 1000, 96],
+               L=2, H=4, D=128, kv_dt=torch.bfloat16, out_of_place=True)
+    run_ragged(b, ref, rng, 2, b.Policy(4, 30000, 2000, 0.9), 50, torch.float32, [39000, 500], [1000, 20], L=1, H=1, D=8,
+               out_of_place=True)
+    for _ in range(10):
+        S = int(rng.integers(1, 9))
+        run_ragged(b, ref, rng, S, b.Policy(int(rng.integers(0, 5)), int(rng.integers(0, 60)), int(rng.integers(0, 20)), 0.7),
+                   int(rng.integers(2, 900)), torch.float32 if rng.integers(2) else torch.bfloat16,
+                   rng.integers(0, 150, S), rng.integers(0, 40, S), D=int(rng.choice([16, 64, 128])), out_of_place=True)
 
 
 @pytest.mark.parametrize("tight_new", [True, False])
