@@ -439,6 +439,24 @@ size_t sirllm_step_lmhead_ragged_workspace_bytes(int32_t n_streams, int32_t max_
                                                  int32_t vocab);
 
 /*
+ * The ragged step from hidden states with a second buffer pair: sirllm_step_lmhead_ragged's scoring operands,
+ * workspace and rules, sirllm_step_ragged_out_of_place's K/V arguments and its copy-all rule (every accepted stream's
+ * kept slots land in k_dst / v_dst, a flagged stream's destination is left as it was, nothing of k_src / v_src is
+ * written).  Paper Algorithm 1 per stream; Sec. 3.2 for where the score comes from.
+ */
+int sirllm_step_lmhead_ragged_out_of_place(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w,
+                                           sirllm_dtype dt, int32_t d_model, int32_t vocab, const int32_t* token_ids,
+                                           float* scores, int64_t scores_stride,
+                                           int32_t n_streams, const int32_t* n_held, const int32_t* cu_new,
+                                           int64_t total_new, int32_t max_cand, int32_t max_new,
+                                           const sirllm_policy* policy,
+                                           const void* k_src, const void* v_src, const sirllm_kv_layout* src,
+                                           void* k_dst, void* v_dst, const sirllm_kv_layout* dst,
+                                           int32_t* kept_idx, int64_t idx_stride,
+                                           float* scores_out, int64_t out_stride, int32_t* n_keep_out,
+                                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Baseline retention policies on the same compaction path (Sec. 4.1 "Baselines"): they pick the
  * n_topk slots of the middle region [n_sink, n_cand - n_recent) without looking at any score;
  * sinks and the recent window are kept as in sirllm_decay_select, and kept_idx comes out in the

@@ -51,7 +51,7 @@ EXPORTS = ("sirllm_score", "sirllm_decay_select", "sirllm_decay_select_static", 
            "sirllm_compact_kv_inplace", "sirllm_step_ragged", "sirllm_step_ragged_out_of_place", "sirllm_score_partial",
            "sirllm_score_merge", "sirllm_lmhead_score", "sirllm_lmhead_workspace_bytes",
            "sirllm_step_lmhead", "sirllm_step_lmhead_workspace_bytes", "sirllm_step_lmhead_ragged",
-           "sirllm_step_lmhead_ragged_workspace_bytes", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
+           "sirllm_step_lmhead_ragged_out_of_place", "sirllm_step_lmhead_ragged_workspace_bytes", "sirllm_workspace_bytes", "sirllm_status_string", "sirllm_version")
 
 _vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
 _PP, _LP = C.POINTER(sirllm_policy), C.POINTER(sirllm_kv_layout)
@@ -96,6 +96,10 @@ _lib.sirllm_step_lmhead_workspace_bytes.restype = _sz
 _lib.sirllm_step_lmhead_ragged.argtypes = [_vp, _i64, _vp, _i64, C.c_int, _i32, _i32, _vp, _vp, _i64, _i32, _vp, _vp, _i64,
                                            _i32, _i32, _PP, _vp, _vp, _LP, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _vp]
 _lib.sirllm_step_lmhead_ragged.restype = C.c_int
+_lib.sirllm_step_lmhead_ragged_out_of_place.argtypes = [_vp, _i64, _vp, _i64, C.c_int, _i32, _i32, _vp, _vp, _i64, _i32, _vp, _vp,
+                                                        _i64, _i32, _i32, _PP, _vp, _vp, _LP, _vp, _vp, _LP, _vp, _i64, _vp,
+                                                        _i64, _vp, _vp, _sz, _vp]
+_lib.sirllm_step_lmhead_ragged_out_of_place.restype = C.c_int
 _lib.sirllm_step_lmhead_ragged_workspace_bytes.argtypes = [_i32, _i32, _i64, _i32]
 _lib.sirllm_step_lmhead_ragged_workspace_bytes.restype = _sz
 for _n in ("sirllm_score", "sirllm_decay_select", "sirllm_compact_kv", "sirllm_step"):
@@ -576,8 +580,9 @@ def sirllm_step_ragged_out_of_place(logits: torch.Tensor, token_ids: torch.Tenso
                                     k_src: torch.Tensor, v_src, k_dst: torch.Tensor, v_dst, kept_idx: torch.Tensor,
                                     scores_out: torch.Tensor, n_keep_out: torch.Tensor, max_new: int | None = None,
                                     workspace: torch.Tensor | None = None, stream=None) -> None:
-    """Ragged step that compacts the streams over their budget from (k_src, v_src) into (k_dst, v_dst) and leaves the
-    destination of every other stream untouched; arguments otherwise as for sirllm_step_ragged."""
+    """Ragged step that writes every accepted stream's kept slots from (k_src, v_src) into (k_dst, v_dst) -- compacted when
+    the stream is over its budget, all of them otherwise -- and leaves a flagged stream's destination untouched; arguments
+    otherwise as for sirllm_step_ragged."""
     _on_device(logits, token_ids, scores, n_held, cu_new, k_src, v_src, k_dst, v_dst, kept_idx, scores_out, n_keep_out, workspace)
     n_streams = scores.shape[0]
     for t, n in ((n_held, n_streams), (cu_new, n_streams + 1), (n_keep_out, n_streams)):
@@ -658,6 +663,57 @@ def sirllm_step_lmhead_ragged(hidden: torch.Tensor, weight: torch.Tensor, token_
                                           _ptr(k), _ptr(v), C.byref(lay), _ptr(kept_idx), _row_stride(kept_idx),
                                           _ptr(scores_out), _row_stride(scores_out), _ptr(n_keep_out), wp, wb,
                                           _stream(stream)), "sirllm_step_lmhead_ragged")
+
+
+def sirllm_step_lmhead_ragged_out_of_place(hidden: torch.Tensor, weight: torch.Tensor, token_ids: torch.Tensor,
+                                           scores: torch.Tensor, n_held: torch.Tensor, cu_new: torch.Tensor, total_new: int,
+                                           max_cand: int, policy, k_src: torch.Tensor, v_src, k_dst: torch.Tensor, v_dst,
+                                           kept_idx: torch.Tensor, scores_out: torch.Tensor, n_keep_out: torch.Tensor,
+                                           workspace: torch.Tensor, max_new: int | None = None, d_model: int | None = None,
+                                           vocab: int | None = None, stream=None) -> None:
+    """sirllm_step_lmhead_ragged with every accepted stream's kept slots written from (k_src, v_src) into (k_dst, v_dst), as
+    sirllm_step_ragged_out_of_place does."""
+    _on_device(hidden, weight, token_ids, scores, n_held, cu_new, k_src, v_src, k_dst, v_dst, kept_idx, scores_out, n_keep_out,
+               workspace)
+    n_streams = scores.shape[0]
+    for t, n in ((n_held, n_streams), (cu_new, n_streams + 1), (n_keep_out, n_streams)):
+        if t.dtype != torch.int32 or t.dim() != 1 or t.numel() != n or not t.is_contiguous():
+            raise ValueError("n_held [S], cu_new [S+1], n_keep_out [S] must be contiguous int32 device vectors")
+    for t in (hidden, weight):
+        if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise ValueError("hidden / weight must be 2-D with contiguous rows")
+    if hidden.dtype != weight.dtype:
+        raise TypeError("hidden and weight must have the same element type")
+    if hidden.shape[0] != total_new or token_ids.numel() != total_new:
+        raise ValueError("one hidden-state row and one token id per new token")
+    if token_ids.dtype != torch.int32 or not token_ids.is_contiguous():
+        raise TypeError("token_ids must be contiguous int32")
+    for t, dt in ((scores, torch.float32), (kept_idx, torch.int32), (scores_out, torch.float32)):
+        if t.dim() != 2 or t.dtype != dt or (t.shape[1] > 1 and t.stride(1) != 1) or t.shape[0] != n_streams:
+            raise ValueError("scores / kept_idx / scores_out must be [n_streams, n] with contiguous rows")
+    d_model = min(hidden.shape[1], weight.shape[1]) if d_model is None else int(d_model)
+    vocab = weight.shape[0] if vocab is None else int(vocab)
+    if vocab > weight.shape[0] or d_model > hidden.shape[1] or d_model > weight.shape[1]:
+        raise ValueError("vocab / d_model exceed the arrays")
+    if (v_src is None) != (v_dst is None):
+        raise ValueError("V on both sides or on neither")
+    if v_src is not None and (kv_layout_tuple(v_src) != kv_layout_tuple(k_src) or kv_layout_tuple(v_dst) != kv_layout_tuple(k_dst)):
+        raise ValueError("K and V must share one layout on each side")
+    if k_src.shape[0] != n_streams or k_src.shape[3] < max_cand or k_dst.shape[0] != n_streams:
+        raise ValueError("the source cache must hold max_cand slots for every stream")
+    p = _policy(policy)
+    if k_dst.shape[3] < min(max_cand, p.n_sink + p.n_topk + p.n_recent):
+        raise ValueError("the destination cache must hold the budget for every stream")
+    ls, ld_ = kv_layout(k_src), kv_layout(k_dst)
+    wp, wb = _ws(workspace)
+    _check(_lib.sirllm_step_lmhead_ragged_out_of_place(
+        _ptr(hidden) if total_new else None, _row_stride(hidden), _ptr(weight), _row_stride(weight), _dtype_code(hidden),
+        d_model, vocab, _ptr(token_ids) if total_new else None, _ptr(scores), _row_stride(scores), n_streams, _ptr(n_held),
+        _ptr(cu_new), int(total_new), int(max_cand), int(min(total_new, max_cand) if max_new is None else max_new),
+        C.byref(p), _ptr(k_src), _ptr(v_src), C.byref(ls), _ptr(k_dst), _ptr(v_dst), C.byref(ld_), _ptr(kept_idx),
+        _row_stride(kept_idx), _ptr(scores_out), _row_stride(scores_out), _ptr(n_keep_out), wp, wb, _stream(stream)),
+        "sirllm_step_lmhead_ragged_out_of_place")
+
 
 
 def sirllm_score_partial(logits_chunk: torch.Tensor, v_begin: int, token_ids: torch.Tensor, partial: torch.Tensor,

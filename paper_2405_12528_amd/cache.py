@@ -269,6 +269,7 @@ class RaggedTwoBufferCache:
         self.n_held = [0] * n_streams                  # host mirror
         nbytes = b.sirllm_workspace_bytes(n_streams, self.capacity, n_streams * max_new, 1 << 20)
         self._ws = torch.zeros(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+        self._lm_ws = None
 
     @property
     def k(self) -> torch.Tensor:
@@ -305,6 +306,29 @@ class RaggedTwoBufferCache:
                                           max_cand, self.policy, self._k[cur], self._v[cur], self._k[oth], self._v[oth],
                                           self.kept_idx, self._scores[oth], self._held_dev[oth],
                                           max_new=max(int(n) for n in n_new), workspace=self._ws, stream=stream)
+        self._cur = oth
+        evicted = [h + int(n) > self.budget for h, n in zip(self.n_held, n_new)]
+        self.n_held = [min(h + int(n), self.budget) for h, n in zip(self.n_held, n_new)]
+        return evicted
+
+    def step_from_hidden(self, hidden: torch.Tensor, weight: torch.Tensor, token_ids: torch.Tensor, n_new, stream=None):
+        """step() with the scores taken straight from the final hidden states [sum(n_new), d_model] (rows concatenated
+        stream by stream) and the output embedding matrix [vocab, d_model] (bf16 or f16): no logits are stored."""
+        if len(n_new) != self.n_streams or max(n_new) > self.max_new or min(n_new) < 0:
+            raise ValueError("n_new must give 0..max_new tokens for every stream")
+        cu = [0]
+        for n in n_new:
+            cu.append(cu[-1] + int(n))
+        cu_dev = torch.tensor(cu, dtype=torch.int32, device=self.device)
+        max_cand = max(h + int(n) for h, n in zip(self.n_held, n_new))
+        need = b.sirllm_step_lmhead_ragged_workspace_bytes(self.n_streams, max_cand, cu[-1], weight.shape[0])
+        if self._lm_ws is None or self._lm_ws.numel() < need:
+            self._lm_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        cur, oth = self._cur, 1 - self._cur
+        b.sirllm_step_lmhead_ragged_out_of_place(hidden, weight, token_ids, self._scores[cur], self._held_dev[cur], cu_dev,
+                                                 cu[-1], max_cand, self.policy, self._k[cur], self._v[cur], self._k[oth],
+                                                 self._v[oth], self.kept_idx, self._scores[oth], self._held_dev[oth],
+                                                 self._lm_ws, max_new=max(int(n) for n in n_new), stream=stream)
         self._cur = oth
         evicted = [h + int(n) > self.budget for h, n in zip(self.n_held, n_new)]
         self.n_held = [min(h + int(n), self.budget) for h, n in zip(self.n_held, n_new)]

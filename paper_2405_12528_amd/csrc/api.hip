@@ -822,6 +822,63 @@ int step_ragged_common(const void* logits, sirllm_dtype dt, int32_t vocab, int64
     return ragged_select_compact(s, max_cand, policy, k, v, layout, dst, workspace, workspace_bytes, stream);
 }
 
+// The destination side of a ragged step with two buffer pairs, and source against destination (the source side is
+// checked with the rest of the step).
+int validate_ragged_dst(int32_t max_cand, int32_t n_streams, const sirllm_policy* policy, const void* k_src, const void* v_src,
+                        const sirllm_kv_layout* src, void* k_dst, void* v_dst, const sirllm_kv_layout* dst,
+                        const int32_t* kept_idx, int64_t idx_stride)
+{
+    if (max_cand < 0 || n_streams < 0 || !policy_ok(policy)) return SIRLLM_ERR_INVALID_ARG;
+    const int64_t budget = budget_of(policy);
+    if (n_streams > 0 && max_cand > 0) {
+        const int rc = validate_compact(k_src, v_src, src, max_cand, k_dst, v_dst, dst, kept_idx, idx_stride, n_streams,
+                                        (int32_t)(max_cand < budget ? max_cand : budget));
+        if (rc) return rc;
+        if (budget > 0 && !k_dst) return SIRLLM_ERR_INVALID_ARG;
+    }
+    return SIRLLM_OK;
+}
+
+size_t lmhead_ragged_workspace_bytes(int32_t n_streams, int32_t max_cand, int64_t total_new, int32_t vocab)
+{
+    const size_t sel = sirllm_workspace_bytes(n_streams, max_cand, 0, 0);
+    return sirllm_lmhead_workspace_bytes(total_new, vocab) +
+           (sel > (size_t)SIRLLM_INPLACE_WORKSPACE_BYTES ? sel : (size_t)SIRLLM_INPLACE_WORKSPACE_BYTES);
+}
+
+int step_lmhead_ragged_common(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, sirllm_dtype dt,
+                              int32_t d_model, int32_t vocab, const int32_t* token_ids,
+                              float* scores, int64_t scores_stride, int32_t n_streams, const int32_t* n_held,
+                              const int32_t* cu_new, int64_t total_new, int32_t max_cand, int32_t max_new,
+                              const sirllm_policy* policy, void* k, void* v, const sirllm_kv_layout* layout,
+                              const RaggedDst& dst, int32_t* kept_idx, int64_t idx_stride, float* scores_out, int64_t out_stride,
+                              int32_t* n_keep_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (total_new < 0) return SIRLLM_ERR_INVALID_ARG;
+    int rc = validate_lmhead(hidden, ld_h, weight, ld_w, dt, d_model, total_new, vocab, token_ids);
+    if (rc) return rc;
+    rc = validate_ragged(scores, scores_stride, n_streams, n_held, cu_new, total_new, max_cand, max_new, policy, k, v,
+                         layout, kept_idx, idx_stride, scores_out, out_stride, n_keep_out);
+    if (rc || n_streams == 0) return rc;
+    rc = workspace_check(workspace, workspace_bytes,
+                         lmhead_ragged_workspace_bytes(n_streams, max_cand, total_new, vocab));
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const size_t lm_bytes = sirllm_lmhead_workspace_bytes(total_new, vocab);
+
+    // E_t = Entropy(new tokens) from z = h W^T; token t of stream s lands behind that stream's held scores
+    if (total_new > 0) {
+        const LmHeadArgs a = make_lmhead_args(hidden, ld_h, weight, ld_w, d_model, total_new, vocab, token_ids, workspace);
+        const LmHeadRagged rg = {cu_new, n_held, n_streams};
+        rc = hip_status(launch_lmhead_score(a, dt, scores, 1, scores_stride, stream, &rg));
+        if (rc) return rc;
+    }
+    const SelectArgs s = make_ragged_select_args(scores, scores_stride, n_streams, n_held, cu_new, max_cand, max_new,
+                                                 policy, kept_idx, idx_stride, scores_out, out_stride, n_keep_out);
+    return ragged_select_compact(s, max_cand, policy, k, v, layout, dst,
+                                 (char*)workspace + lm_bytes, workspace_bytes - lm_bytes, stream);
+}
+
 }  // namespace
 
 int sirllm_step_ragged(const void* logits, sirllm_dtype dt, int32_t vocab, int64_t ld, const int32_t* token_ids,
@@ -847,16 +904,8 @@ int sirllm_step_ragged_out_of_place(const void* logits, sirllm_dtype dt, int32_t
                                     float* scores_out, int64_t out_stride, int32_t* n_keep_out, void* workspace,
                                     size_t workspace_bytes, void* hip_stream)
 {
-    using namespace sirllm;
-    if (max_cand < 0 || n_streams < 0 || !policy_ok(policy)) return SIRLLM_ERR_INVALID_ARG;
-    const int64_t budget = budget_of(policy);
-    if (n_streams > 0 && max_cand > 0) {
-        // the destination side, and source against destination (the source side is checked with the rest of the step)
-        const int rc = validate_compact(k_src, v_src, src, max_cand, k_dst, v_dst, dst, kept_idx, idx_stride, n_streams,
-                                        (int32_t)(max_cand < budget ? max_cand : budget));
-        if (rc) return rc;
-        if (budget > 0 && !k_dst) return SIRLLM_ERR_INVALID_ARG;
-    }
+    const int rc = validate_ragged_dst(max_cand, n_streams, policy, k_src, v_src, src, k_dst, v_dst, dst, kept_idx, idx_stride);
+    if (rc) return rc;
     return step_ragged_common(logits, dt, vocab, ld, token_ids, scores, scores_stride, n_streams, n_held, cu_new, total_new,
                               max_cand, max_new, policy, const_cast<void*>(k_src), const_cast<void*>(v_src), src,
                               RaggedDst{k_dst, v_dst, dst}, kept_idx, idx_stride, scores_out, out_stride, n_keep_out, workspace,
@@ -865,9 +914,7 @@ int sirllm_step_ragged_out_of_place(const void* logits, sirllm_dtype dt, int32_t
 
 size_t sirllm_step_lmhead_ragged_workspace_bytes(int32_t n_streams, int32_t max_cand, int64_t total_new, int32_t vocab)
 {
-    const size_t sel = sirllm_workspace_bytes(n_streams, max_cand, 0, 0);
-    return sirllm_lmhead_workspace_bytes(total_new, vocab) +
-           (sel > (size_t)SIRLLM_INPLACE_WORKSPACE_BYTES ? sel : (size_t)SIRLLM_INPLACE_WORKSPACE_BYTES);
+    return lmhead_ragged_workspace_bytes(n_streams, max_cand, total_new, vocab);
 }
 
 int sirllm_step_lmhead_ragged(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, sirllm_dtype dt,
@@ -878,29 +925,28 @@ int sirllm_step_lmhead_ragged(const void* hidden, int64_t ld_h, const void* weig
                               int32_t* kept_idx, int64_t idx_stride, float* scores_out, int64_t out_stride,
                               int32_t* n_keep_out, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    if (total_new < 0) return SIRLLM_ERR_INVALID_ARG;
-    int rc = validate_lmhead(hidden, ld_h, weight, ld_w, dt, d_model, total_new, vocab, token_ids);
-    if (rc) return rc;
-    rc = validate_ragged(scores, scores_stride, n_streams, n_held, cu_new, total_new, max_cand, max_new, policy, k, v,
-                         layout, kept_idx, idx_stride, scores_out, out_stride, n_keep_out);
-    if (rc || n_streams == 0) return rc;
-    rc = workspace_check(workspace, workspace_bytes,
-                         sirllm_step_lmhead_ragged_workspace_bytes(n_streams, max_cand, total_new, vocab));
-    if (rc) return rc;
-    hipStream_t stream = (hipStream_t)hip_stream;
-    const size_t lm_bytes = sirllm_lmhead_workspace_bytes(total_new, vocab);
+    return step_lmhead_ragged_common(hidden, ld_h, weight, ld_w, dt, d_model, vocab, token_ids, scores, scores_stride, n_streams,
+                                     n_held, cu_new, total_new, max_cand, max_new, policy, k, v, layout,
+                                     RaggedDst{nullptr, nullptr, nullptr}, kept_idx, idx_stride, scores_out, out_stride,
+                                     n_keep_out, workspace, workspace_bytes, hip_stream);
+}
 
-    // E_t = Entropy(new tokens) from z = h W^T; token t of stream s lands behind that stream's held scores
-    if (total_new > 0) {
-        const LmHeadArgs a = make_lmhead_args(hidden, ld_h, weight, ld_w, d_model, total_new, vocab, token_ids, workspace);
-        const LmHeadRagged rg = {cu_new, n_held, n_streams};
-        rc = hip_status(launch_lmhead_score(a, dt, scores, 1, scores_stride, stream, &rg));
-        if (rc) return rc;
-    }
-    const SelectArgs s = make_ragged_select_args(scores, scores_stride, n_streams, n_held, cu_new, max_cand, max_new,
-                                                 policy, kept_idx, idx_stride, scores_out, out_stride, n_keep_out);
-    return ragged_select_compact(s, max_cand, policy, k, v, layout, RaggedDst{nullptr, nullptr, nullptr},
-                                 (char*)workspace + lm_bytes, workspace_bytes - lm_bytes, stream);
+int sirllm_step_lmhead_ragged_out_of_place(const void* hidden, int64_t ld_h, const void* weight, int64_t ld_w, sirllm_dtype dt,
+                                           int32_t d_model, int32_t vocab, const int32_t* token_ids,
+                                           float* scores, int64_t scores_stride, int32_t n_streams, const int32_t* n_held,
+                                           const int32_t* cu_new, int64_t total_new, int32_t max_cand, int32_t max_new,
+                                           const sirllm_policy* policy,
+                                           const void* k_src, const void* v_src, const sirllm_kv_layout* src,
+                                           void* k_dst, void* v_dst, const sirllm_kv_layout* dst,
+                                           int32_t* kept_idx, int64_t idx_stride, float* scores_out, int64_t out_stride,
+                                           int32_t* n_keep_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    const int rc = validate_ragged_dst(max_cand, n_streams, policy, k_src, v_src, src, k_dst, v_dst, dst, kept_idx, idx_stride);
+    if (rc) return rc;
+    return step_lmhead_ragged_common(hidden, ld_h, weight, ld_w, dt, d_model, vocab, token_ids, scores, scores_stride, n_streams,
+                                     n_held, cu_new, total_new, max_cand, max_new, policy, const_cast<void*>(k_src),
+                                     const_cast<void*>(v_src), src, RaggedDst{k_dst, v_dst, dst}, kept_idx, idx_stride,
+                                     scores_out, out_stride, n_keep_out, workspace, workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

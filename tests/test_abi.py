@@ -358,6 +358,28 @@ def test_inplace_and_ragged_argument_errors(b):
     assert lm_ragged(ws=0x30000010) == b.SIRLLM_ERR_WORKSPACE
     assert lm_ragged(n_streams=0) == b.SIRLLM_OK
 
+    def lm_ragged_oop(hidden=0x1000, ld_h=64, weight=0x8000000, ld_w=64, dt=1, d_model=64, vocab=1000, tok=0x2000000,
+                      scores=0x3000000, sstr=128, n_streams=2, held=0x7000000, cu=0x7100000, total=64, max_cand=100,
+                      max_new=64, pol=p, k=0x10000000, v=0x20000000, l=lay, kd=0x40000000, vd=0x48000000, ld_=lay_dst,
+                      idx=0x5000000, istr=32, out=0x6000000, ostr=32, keep=0x7200000, ws=0x30000000, ws_bytes=1 << 30):
+        return L.sirllm_step_lmhead_ragged_out_of_place(hidden, ld_h, weight, ld_w, dt, d_model, vocab, tok, scores, sstr,
+                                                        n_streams, held, cu, total, max_cand, max_new,
+                                                        C.byref(pol) if pol else None, k, v, C.byref(l) if l else None, kd, vd,
+                                                        C.byref(ld_) if ld_ else None, idx, istr, out, ostr, keep, ws,
+                                                        ws_bytes, None)
+    assert lm_ragged_oop(kd=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged_oop(ld_=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged_oop(vd=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged_oop(kd=0x10000000 + 4096) == b.SIRLLM_ERR_INVALID_ARG   # destination inside the source
+    assert lm_ragged_oop(ld_=other) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged_oop(dt=0) == b.SIRLLM_ERR_UNSUPPORTED
+    assert lm_ragged_oop(hidden=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged_oop(pol=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged_oop(k=None) == b.SIRLLM_ERR_INVALID_ARG
+    assert lm_ragged_oop(ws=None) == b.SIRLLM_ERR_WORKSPACE
+    assert lm_ragged_oop(ws_bytes=need - 1) == b.SIRLLM_ERR_WORKSPACE
+    assert lm_ragged_oop(n_streams=0) == b.SIRLLM_OK
+
 
 def test_score_chunk_argument_errors(b):
     L = b.raw()

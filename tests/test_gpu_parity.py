@@ -821,6 +821,12 @@ def run_ragged(b, ref, rng, S, pol, V, dt, n_held, n_new, L=2, H=2, D=16, kv_dt=
     if out_of_place:
         kd = torch.full((S, L, H, keep_cap + 1, D), 77, dtype=kv_dt, device=DEV)
         vd = torch.full((S, L, H, keep_cap + 1, D), 77, dtype=kv_dt, device=DEV)
+    if out_of_place and lmhead_d is not None:
+        ws = torch.full((b.sirllm_step_lmhead_ragged_workspace_bytes(S, max_cand, total, V),), 0x5a, dtype=torch.uint8,
+                        device=DEV)
+        b.sirllm_step_lmhead_ragged_out_of_place(hid, emb, tok, scores, held_dev, cu, total, max_cand, pol, k, v, kd, vd,
+                                                 kept, out, n_keep_dev, ws, max_new=max_new, vocab=V)
+    elif out_of_place:
         b.sirllm_step_ragged_out_of_place(z, tok, V, scores, held_dev, cu, total, max_cand, pol, k, v, kd, vd, kept, out,
                                           n_keep_dev, max_new=max_new, workspace=ws)
     elif lmhead_d is None:
@@ -947,6 +953,22 @@ def test_step_ragged_out_of_place_matches_oracle(b, ref):
         run_ragged(b, ref, rng, S, b.Policy(int(rng.integers(0, 5)), int(rng.integers(0, 60)), int(rng.integers(0, 20)), 0.7),
                    int(rng.integers(2, 900)), torch.float32 if rng.integers(2) else torch.bfloat16,
                    rng.integers(0, 150, S), rng.integers(0, 40, S), D=int(rng.choice([16, 64, 128])), out_of_place=True)
+
+
+def test_step_lmhead_ragged_out_of_place_matches_oracle(b, ref):
+    """sirllm_step_lmhead_ragged_out_of_place: the scores from hidden states and the output embedding matrix, the kept slots of
+    every accepted stream in the second buffer pair; idle, empty and flagged streams, rows of 256 bytes and of other lengths."""
+    rng = np.random.default_rng(78)
+    pol = b.Policy(4, 20, 8, 0.9)
+    run_ragged(b, ref, rng, 6, pol, 500, torch.bfloat16, [0, 10, 24, 40, 90, 0], [5, 22, 8, 0, 17, 0], lmhead_d=64, out_of_place=True)
+    run_ragged(b, ref, rng, 3, pol, 777, torch.bfloat16, [100, 31, 0], [1, 1, 64], kv_dt=torch.bfloat16, D=128, lmhead_d=96,
+               out_of_place=True)
+    run_ragged(b, ref, rng, 2, pol, 300, torch.float16, [100, 31], [1, 1], kv_dt=torch.int16, D=5, lmhead_d=32, out_of_place=True)
+    run_ragged(b, ref, rng, 4, pol, 100, torch.bfloat16, [40, -3, 50, -40], [5, 60, 8, 90], cap=100, new_cap=90, lmhead_d=64,
+               out_of_place=True)
+    run_ragged(b, ref, rng, 1, pol, 64, torch.bfloat16, [200], [0], lmhead_d=32, out_of_place=True)
+    run_ragged(b, ref, rng, 3, b.Policy(4, 3068, 1024, 0.85), 2000, torch.bfloat16, [7168, 100, 4000], [1024, 1000, 96],
+               L=2, H=4, D=128, kv_dt=torch.bfloat16, lmhead_d=128, out_of_place=True)
 
 
 @pytest.mark.parametrize("tight_new", [True, False])

@@ -408,19 +408,19 @@ def test_per_layer_step_replays_from_a_captured_graph(b):
     assert eager["k0"].abs().sum() > 0
 
 
-@pytest.mark.parametrize("kind", ["logits", "hidden states", "two buffers"])
+@pytest.mark.parametrize("kind", ["logits", "hidden states", "two buffers", "two buffers, hidden states"])
 def test_ragged_dialogues_of_unequal_length(b, ref, kind):
     """Six dialogues in one serving batch, each with its own arrival turn and its own number of tokens per
     turn (some turns idle), stepped together by sirllm_step_ragged (or, fed with hidden states and the output
-    embedding matrix, by sirllm_step_lmhead_ragged) with in-place compaction, or by sirllm_step_ragged_out_of_place
-    between two buffer pairs that swap every step; the oracle replays every stream on its own and every turn is
+    embedding matrix, by sirllm_step_lmhead_ragged) with in-place compaction, or by sirllm_step_ragged_out_of_place (fed with
+    hidden states: sirllm_step_lmhead_ragged_out_of_place) between two buffer pairs that swap every step; the oracle replays every stream on its own and every turn is
     compared in full."""
     from paper_2405_12528_amd.cache import RaggedRetentiveCache, RaggedTwoBufferCache
-    from_hidden = kind == "hidden states"
+    from_hidden = kind.endswith("hidden states")
     S, L, H, D, V = 6, 2, 2, 16, 400
     pol = (4, 20, 8, 0.9)
     rng = np.random.default_rng(11)
-    make = RaggedTwoBufferCache if kind == "two buffers" else RaggedRetentiveCache
+    make = RaggedTwoBufferCache if kind.startswith("two buffers") else RaggedRetentiveCache
     cache = make(S, L, H, D, pol, max_new=40, kv_dtype=torch.float32, device=DEV)
     g0 = torch.Generator(device=DEV).manual_seed(3)
     d_model = 64
