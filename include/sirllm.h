@@ -28,7 +28,7 @@
  *     variables (integers; unset = the default in brackets) -- otherwise none of them is ever read:
  *       SIRLLM_SCORE_BLOCK [by row length: 1024, 512 or 256]  threads per scored row
  *       SIRLLM_SCORE_NT [1], SIRLLM_GATHER_NT [1], SIRLLM_INPLACE_NT [1]   non-temporal (1) or cached (0) accesses
- *       SIRLLM_GATHER_BLOCK [64 for rows of 256 bytes, else 128] (or 64, 128, 256, 512), SIRLLM_GATHER_UNROLL [1] (or 2; 64 threads:
+ *       SIRLLM_GATHER_BLOCK [64 for rows of 256 or 512 bytes or a power of two from 1 KB on, else 128] (or 64, 128, 256, 512), SIRLLM_GATHER_UNROLL [1] (or 2; 64 threads:
  *                                1, non-temporal only)   threads and 16-byte vectors per lane of a gather tile
  *       SIRLLM_GATHER_SCALAR_IDX [1], SIRLLM_GATHER_ROTATE [1 when the source planes lie a power of two apart and a compacted plane has 1 MiB or more, else 0]
  *                                rows of 256 bytes in tiles of 64 or 128 threads: kept indices by scalar loads (1) or per lane (0);
