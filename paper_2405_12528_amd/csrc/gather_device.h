@@ -126,7 +126,6 @@ struct WaveRowsArgs {
     uint64_t src0, src1, dst0, dst1;   // K | V bases (unused with LAYERS)
     int64_t s_stream, d_stream, s_head, d_head, s_layer, d_layer, s_pos, d_pos;
     int32_t row_begin, row_end, lh, uniform, n_heads, n_src, shift, rotate, plane0, stream0;
-    int32_t n_rows_pad[2];
     uint64_t rg_held, rg_cu, rg_keep;  // RAGGED: n_held, cu_new, n_keep per stream
 };
 
@@ -141,7 +140,6 @@ inline WaveRowsArgs wave_rows_args(const GatherLaunch& g, const Ragged* rg)
     w.s_layer = a.s_layer; w.d_layer = a.d_layer; w.s_pos = a.s_pos; w.d_pos = a.d_pos;
     w.row_begin = g.row_begin; w.row_end = g.row_end; w.lh = g.lh; w.uniform = g.uniform; w.n_heads = a.n_heads;
     w.n_src = a.n_src; w.shift = g.shift; w.rotate = g.rotate; w.plane0 = g.plane0; w.stream0 = g.stream0;
-    w.n_rows_pad[0] = w.n_rows_pad[1] = 0;
     w.rg_held = rg ? (uint64_t)(uintptr_t)rg->held_dev : 0;
     w.rg_cu = rg ? (uint64_t)(uintptr_t)rg->cu_new_dev : 0;
     w.rg_keep = rg ? (uint64_t)(uintptr_t)rg->n_keep_dev : 0;
