@@ -64,6 +64,68 @@ def test_full_size_step(b, ref, name):
     assert np.array_equal(to_np(v_dst), rv), "compacted V differs from the oracle"
 
 
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("name,held_new", [
+    ("llama3_8b", None),                                                         # the shape bench.py times, through the ragged calls
+    ("mistral_7b", None),
+    ("batched_dialogue", [(2048, 256), (1500, 256), (2048, 100), (300, 256)]),   # unequal streams of the dialogue shape
+])
+def test_full_size_ragged_two_buffer_step(b, ref, name, held_new):
+    """sirllm_step_ragged_out_of_place at the benchmark shapes (the launch bench.py times as the ragged out-of-place step): scores,
+    kept lists, compacted scores and the whole destination K/V of every stream against the oracle; the source is not written."""
+    w = synth.WORKLOADS[name]
+    ref.set_threads(16)
+    pol = b.Policy(w.n_sink, w.n_topk, w.n_recent, w.decay)
+    if held_new is None:
+        held_new = [(w.n_held, w.n_new)] * w.n_streams
+    S = len(held_new)
+    n_held = np.array([h for h, _ in held_new]); n_new = np.array([n for _, n in held_new])
+    n_cand = n_held + n_new
+    max_cand, total, budget = int(n_cand.max()), int(n_new.sum()), w.budget
+    g0 = torch.Generator(device=DEV).manual_seed(5)
+    dt = torch.float32 if w.logits_dtype == "f32" else torch.bfloat16
+    z = (torch.randn((total, w.vocab), generator=g0, device=DEV) * w.sigma).to(dt)
+    tok = torch.randint(0, w.vocab, (total,), generator=g0, device=DEV, dtype=torch.int32)
+    scores = torch.full((S, max_cand), -3.0, device=DEV)
+    for s in range(S):
+        scores[s, :n_held[s]] = torch.rand((int(n_held[s]),), generator=g0, device=DEV) * 9.0
+    shape = (S, w.n_layers, w.n_kv_heads, max_cand, w.head_dim)
+    k = torch.randint(-30000, 30000, shape, generator=g0, device=DEV, dtype=torch.int16).view(torch.bfloat16)
+    v = torch.randint(-30000, 30000, shape, generator=g0, device=DEV, dtype=torch.int16).view(torch.bfloat16)
+    keep_cap = min(max_cand, budget)
+    kd = torch.full((S, w.n_layers, w.n_kv_heads, keep_cap, w.head_dim), 77, dtype=torch.bfloat16, device=DEV)
+    vd = torch.full_like(kd, 77)
+    kept = torch.full((S, keep_cap), -7, dtype=torch.int32, device=DEV)
+    out = torch.full((S, keep_cap), -7.0, device=DEV)
+    n_keep_dev = torch.full((S,), -9, dtype=torch.int32, device=DEV)
+    held_dev = torch.from_numpy(n_held.astype(np.int32)).to(DEV)
+    cu = torch.from_numpy(np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)).to(DEV)
+    hs = to_np(scores).copy()
+    k_sum, v_sum = k.view(torch.int16).sum(dtype=torch.int64).item(), v.view(torch.int16).sum(dtype=torch.int64).item()
+    b.sirllm_step_ragged_out_of_place(z, tok, w.vocab, scores, held_dev, cu, total, max_cand, pol, k, v, kd, vd, kept, out,
+                                      n_keep_dev, max_new=int(n_new.max()))
+    torch.cuda.synchronize()
+    gs, gkeep = to_np(scores), to_np(n_keep_dev)
+    e = ref.score(to_np(z), to_np(tok), vocab=w.vocab)
+    assert k.view(torch.int16).sum(dtype=torch.int64).item() == k_sum and v.view(torch.int16).sum(dtype=torch.int64).item() == v_sum
+    r0 = 0
+    for s in range(S):
+        h, n = int(n_held[s]), int(n_new[s])
+        assert_scores_close(gs[s, h:h + n], e[r0:r0 + n])
+        np.testing.assert_array_equal(gs[s, :h], hs[s, :h])
+        r0 += n
+        ki, so = ref.decay_select(gs[s:s + 1, :h + n], h, n, ref.Policy(*pol))
+        nk = ki.shape[1]
+        assert gkeep[s] == nk == min(h + n, budget)
+        np.testing.assert_array_equal(to_np(kept)[s, :nk], ki[0])
+        np.testing.assert_array_equal(to_np(out)[s, :nk].view(np.uint32), so[0].view(np.uint32))
+        rk, rv = ref.compact_kv(to_np(k[s:s + 1].view(torch.int16)), to_np(v[s:s + 1].view(torch.int16)), ki, n_src=h + n)
+        gk, gv = to_np(kd[s:s + 1].view(torch.int16)), to_np(vd[s:s + 1].view(torch.int16))
+        assert np.array_equal(gk[:, :, :, :nk], rk) and np.array_equal(gv[:, :, :, :nk], rv), f"stream {s}: K/V differ from the oracle"
+        pad = torch.tensor(77, dtype=torch.bfloat16).view(torch.int16).item()
+        assert (gk[:, :, :, nk:] == pad).all() and (gv[:, :, :, nk:] == pad).all(), f"stream {s}: written past its kept slots"
+
+
 @pytest.mark.timeout(600)
 def test_long_context_step(b, ref):
     """A 128K-slot budget at the Llama-3-8B shape: 133120 candidates (selection by the multi-workgroup path),
