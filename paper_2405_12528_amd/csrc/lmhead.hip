@@ -14,6 +14,7 @@
 
 #include "common.h"
 #include "score_device.h"
+#include "tuning.h"
 
 namespace sirllm {
 namespace {
@@ -246,10 +247,12 @@ __global__ __launch_bounds__(256) void lmhead_score_general_kernel(LmHeadArgs a)
 
 // 16 bytes per lane straight from global memory into LDS (global_load_lds_dwordx4): lane l's chunk lands at
 // lds_block + 16 l, so one wave instruction fills 1 KB = 8 tile rows.  lds_block must be wave uniform.
+// NT: with the non-temporal hint (bytes that are read exactly once).
+template <bool NT = false>
 __device__ __forceinline__ void load_to_lds(const char* g, char* lds_block)
 {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                     (__attribute__((address_space(3))) void*)lds_block, 16, 0, 0);
+                                     (__attribute__((address_space(3))) void*)lds_block, 16, 0, NT ? 2 : 0);
 }
 
 // Fast kernel (d_model a multiple of 32).  The workgroup is 2 x 2 waves; a wave owns NVB x NTB result blocks of
@@ -263,8 +266,9 @@ __device__ __forceinline__ void load_to_lds(const char* g, char* lds_block)
 //   wait until this wave's loads of stage ks + 1 have landed (the younger ones stay in flight), barrier: every
 //   wave has finished reading stage ks, so its buffer is free for stage ks + RING
 //   slice 1: MFMAs under the LDS reads of slice 0 of stage ks + 1 and under this wave's loads of stage ks + RING.
+// The tiles for up to 128 rows take stages of 64 K elements instead when d_model allows (FKE = 64: tile rows of 128
+// bytes, four slices, three of them in front of the barrier): a wave load then fetches whole 128-byte lines.
 constexpr int FK = 32;
-constexpr int kFastRow = FK * 2;                       // 64 bytes per tile row
 
 // Wait until at most N vector-memory operations of this wave are outstanding and every LDS operation is done, then
 // barrier.  What the callers rely on, and what an edit must keep:
@@ -284,22 +288,30 @@ __device__ __forceinline__ void wait_barrier()
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <int NVB, int NTB, int RING>
+// FKE: K elements per stage, 32 or 64 (tile rows of 64 or 128 bytes).
+template <int NVB, int NTB, int RING, int FKE = FK>
 struct FastCfg {
+    static_assert(FKE == 32 || FKE == 64, "tile rows of 64 or 128 bytes");
     static constexpr int kBV = 64 * NVB, kBT = 64 * NTB;
-    static constexpr int kTileW = kBV * kFastRow;                  // bytes of the W tile of one stage
-    static constexpr int kStage = (kBV + kBT) * kFastRow;
-    static constexpr int kLpw = NVB + NTB;                         // 1 KB loads per wave and stage
+    static constexpr int kRow = FKE * 2;                           // bytes of a tile row
+    static constexpr int kChunks = kRow / 16;                      // 16-byte chunks per row
+    static constexpr int kRowsPerLine = 256 / kRow;                // rows per 256-byte bank line
+    static constexpr int kRowsPerBlock = 1024 / kRow;              // rows one wave load fills
+    static constexpr int kSlices = FKE / 16;                       // 16-wide MFMA slices per stage
+    static constexpr int kTileW = kBV * kRow;                      // bytes of the W tile of one stage
+    static constexpr int kStage = (kBV + kBT) * kRow;
+    static constexpr int kLpw = (NVB + NTB) * kRow / 64;           // 1 KB loads per wave and stage
     static constexpr int kDump = 256;                              // where the L2 warm-up loads drop their bytes
     static constexpr int kLds = RING * kStage + kDump;             // the epilogue's scratch reuses the ring
     static_assert((RING - 1) * kLpw <= 63, "vmcnt is a 6-bit counter");
     static_assert(RING * kStage >= 2 * kBT * 3 * 4 && kLds <= 160 * 1024, "LDS budget");
 };
 
-template <int DT, int NVB, int NTB, int RING, bool PIN, bool WARM>
+template <int DT, int NVB, int NTB, int RING, bool PIN, bool WARM, int FKE = FK, bool WNT = false>
 __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
 {
-    using Cfg = FastCfg<NVB, NTB, RING>;
+    using Cfg = FastCfg<NVB, NTB, RING, FKE>;
+    static_assert(FKE == FK || (!PIN && !WARM), "the pinned schedule and the L2 touches are written for 64-byte tile rows");
     extern __shared__ __align__(16) char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wv = wave & 1, wt = wave >> 1;
@@ -308,30 +320,33 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
     const int v0 = vt * Cfg::kBV;
     const int64_t t0 = (int64_t)tt * Cfg::kBT;
 
-    // ---- loads: a stage is 4 (NVB + NTB) blocks of 1 KB (16 rows x 64 B): first the W tile, then the h tile.
-    // Wave w issues blocks kLpw w + j.  Within a block lane l fills row l / 4, chunk position l % 4, which holds
-    // chunk (l % 4) ^ ((row / 4) % 4) of that row: rows are 64 bytes, four to a 256-byte bank line, and the 16
+    // ---- loads: a stage is 4 kLpw blocks of 1 KB (16 rows x 64 B, or 8 rows x 128 B): first the W tile, then the h
+    // tile.  Wave w issues blocks kLpw w + j.  With 64-byte rows lane l of a block fills row l / 4, chunk position
+    // l % 4, which holds chunk (l % 4) ^ ((row / 4) % 4) of that row: four rows share a 256-byte bank line, and the 16
     // rows a quarter wave reads from one chunk column land in 16 different 16-byte slots (the LDS has 64 banks
-    // and serves a 16-byte-per-lane read 16 lanes at a time).
+    // and serves a 16-byte-per-lane read 16 lanes at a time).  With 128-byte rows (two to a bank line) it is row l / 8,
+    // position l % 8, chunk (l % 8) ^ ((row / 2) % 8): again 16 different slots.  Then one wave load takes whole
+    // 128-byte lines of W, which streams from HBM 20 % faster than half lines in two loads.
     const int rows_w = a.vocab - v0;
     const int rows_h = (int)((a.n_rows - t0 < Cfg::kBT) ? a.n_rows - t0 : Cfg::kBT);
     // A load address is a wave-uniform base (tile origin + stage offset, scalar registers) plus a 32-bit per-lane
     // offset (row * pitch + chunk): no vector arithmetic per load.
-    const uint32_t lane_chunk = (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+    constexpr int kWBlocks = Cfg::kBV / Cfg::kRowsPerBlock;               // blocks of the W tile
     const char* ubase[Cfg::kLpw];
     uint32_t goff[Cfg::kLpw];
 #pragma unroll
     for (int j = 0; j < Cfg::kLpw; ++j) {
         const int blk = __builtin_amdgcn_readfirstlane(wave) * Cfg::kLpw + j;
-        const bool is_w = blk < 4 * NVB;
-        int r = (is_w ? blk : blk - 4 * NVB) * 16 + (lane >> 2);
+        const bool is_w = blk < kWBlocks;
+        const int tr = (is_w ? blk : blk - kWBlocks) * Cfg::kRowsPerBlock + lane / Cfg::kChunks;   // row of its tile
+        const uint32_t lane_chunk = (uint32_t)(((lane % Cfg::kChunks) ^ ((tr / Cfg::kRowsPerLine) % Cfg::kChunks)) << 4);
         const int rows_left = is_w ? rows_w : rows_h;
-        if (r >= rows_left) r = rows_left - 1;                            // rows past the end re-read the last row
+        const int r = tr < rows_left ? tr : rows_left - 1;                // rows past the end re-read the last row
         ubase[j] = is_w ? (const char*)a.weight + (int64_t)v0 * a.ld_w * 2 : (const char*)a.hidden + t0 * a.ld_h * 2;
         goff[j] = (uint32_t)r * (uint32_t)((is_w ? a.ld_w : a.ld_h) * 2) + lane_chunk;
     }
     char* const my_blocks = lds + __builtin_amdgcn_readfirstlane(wave) * Cfg::kLpw * 1024;
-    const int nk = a.d_model / FK;             // >= 1
+    const int nk = a.d_model / FKE;            // >= 1
     // Workgroups start their walk over K at different stages (and wrap around): at any moment the chip then
     // reads many different column stripes of W instead of one 64-byte-wide stripe with a row pitch of d_model
     // elements, which would land on few memory channels.  A dot product does not care where its sum starts.
@@ -343,16 +358,21 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
     auto issue_load = [&](int ks, int buf, int j) {
         int st = (ks < nk ? ks : nk - 1) + kstart;
         if (st >= nk) st -= nk;
-        load_to_lds(ubase[j] + (int64_t)st * (FK * 2) + goff[j], my_blocks + buf * Cfg::kStage + j * 1024);
+        const char* g = ubase[j] + (int64_t)st * Cfg::kRow + goff[j];
+        char* l = my_blocks + buf * Cfg::kStage + j * 1024;
+        // blocks below kWBlocks belong to W: read exactly once when there is a single token tile
+        if (WNT && __builtin_amdgcn_readfirstlane(wave) * Cfg::kLpw + j < kWBlocks) load_to_lds<true>(g, l);
+        else load_to_lds<false>(g, l);
     };
 
     // ---- fragments: row = 32 NVB (or NTB) * (wave half) + 32 * block + lane % 32, chunk = 2 kk + lane / 32
     const int frag_row = lane & 31, khalf = lane >> 5;
-    const int a_base = (wv * (32 * NVB) + frag_row) * kFastRow;
-    const int b_base = Cfg::kTileW + (wt * (32 * NTB) + frag_row) * kFastRow;
-    int cpos[2];
+    const int a_base = (wv * (32 * NVB) + frag_row) * Cfg::kRow;
+    const int b_base = Cfg::kTileW + (wt * (32 * NTB) + frag_row) * Cfg::kRow;
+    int cpos[Cfg::kSlices];
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) cpos[kk] = ((2 * kk + khalf) ^ ((frag_row >> 2) & 3)) << 4;
+    for (int kk = 0; kk < Cfg::kSlices; ++kk)
+        cpos[kk] = ((2 * kk + khalf) ^ ((frag_row / Cfg::kRowsPerLine) % Cfg::kChunks)) << 4;
 
     f32x16 acc[NVB][NTB];
 #pragma unroll
@@ -365,8 +385,8 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
     u32x4 af[2][NVB], bf[2][NTB];
     // fragment i of slice kk: i < NVB the W blocks, then the h blocks
     auto read_frag = [&](const char* s, int kk, int set, int i) {
-        if (i < NVB) af[set][i] = *(const u32x4*)(s + a_base + i * 32 * kFastRow + cpos[kk]);
-        else bf[set][i - NVB] = *(const u32x4*)(s + b_base + (i - NVB) * 32 * kFastRow + cpos[kk]);
+        if (i < NVB) af[set][i] = *(const u32x4*)(s + a_base + i * 32 * Cfg::kRow + cpos[kk]);
+        else bf[set][i - NVB] = *(const u32x4*)(s + b_base + (i - NVB) * 32 * Cfg::kRow + cpos[kk]);
     };
     // One slice: NVB x NTB MFMAs on fragment set `use`, and in their shadow the LDS reads of the next slice
     // (into the other set) and, in slice 1, the loads of a later stage.  With PIN the order is fixed: behind each
@@ -462,7 +482,13 @@ __global__ __launch_bounds__(256) void lmhead_score_kernel(LmHeadArgs a)
         const int blast = bcur == 0 ? RING - 1 : bcur - 1;             // (ks + RING - 1) % RING
         const char* cur = lds + bcur * Cfg::kStage;
         const char* nxt = lds + bnext * Cfg::kStage;
-        slice(0, cur, 1, ks + RING - 1, blast, Cfg::kLpw - kHalf, kHalf);
+        if constexpr (Cfg::kSlices == 2) {
+            slice(0, cur, 1, ks + RING - 1, blast, Cfg::kLpw - kHalf, kHalf);
+        } else {                                           // four slices: three of them in front of the barrier
+            slice(0, cur, 1, 0, 0, 0, 0);
+            slice(1, cur, 2, 0, 0, 0, 0);
+            slice(0, cur, 3, 0, 0, 0, 0);
+        }
         // issued after stage ks + 1: stages ks + 2 .. ks + RING - 1 whole = (RING - 2) * kLpw loads (plus, for one
         // wave in four iterations, the touch below: a stricter wait, see wait_barrier)
         wait_barrier<(RING - 2) * Cfg::kLpw>();            // stage ks + 1 landed; all reads of stage ks done
@@ -571,13 +597,13 @@ inline hipError_t allow_dynamic_lds(const void* fn, int bytes, std::atomic<uint6
     return e;
 }
 
-template <int DT, int NVB, int NTB, int RING, bool PIN, bool WARM>
+template <int DT, int NVB, int NTB, int RING, bool PIN, bool WARM, int FKE = FK, bool WNT = false>
 hipError_t launch_fast(const LmHeadArgs& a, hipStream_t stream)
 {
-    using Cfg = FastCfg<NVB, NTB, RING>;
+    using Cfg = FastCfg<NVB, NTB, RING, FKE>;
     const int64_t groups = lmhead_grid(a);
     if (groups > 0x7fffffff) return hipErrorInvalidValue;
-    auto fn = lmhead_score_kernel<DT, NVB, NTB, RING, PIN, WARM>;
+    auto fn = lmhead_score_kernel<DT, NVB, NTB, RING, PIN, WARM, FKE, WNT>;
     static std::atomic<uint64_t> lds_allowed{0};
     const hipError_t e = allow_dynamic_lds((const void*)fn, Cfg::kLds, lds_allowed);
     if (e != hipSuccess) return e;
@@ -610,8 +636,15 @@ hipError_t launch_dtype(LmHeadArgs& a, hipStream_t stream)
     tile_shape(a.n_rows, a.vocab, bv, bt);
     a.n_vtiles = (a.vocab + bv - 1) / bv;
     a.n_ttiles = (int)((a.n_rows + bt - 1) / bt);
-    if (bt == 64 && bv == 256) return launch_fast<DT, 4, 1, 4, false, false>(a, stream);
-    if (bt == 64) return launch_fast<DT, 2, 1, 6, false, false>(a, stream);
+    // Up to 128 rows the kernel is bound by streaming W, and whole 128-byte lines per load stream faster than halves
+    // (tile rows of 64 K elements; d_model must be a multiple of 64).  With at most 64 rows there is one token tile, so
+    // every byte of W is read exactly once and carries the non-temporal hint.
+    const bool wide = a.d_model % 64 == 0 && tuning::get("SIRLLM_LMHEAD_WIDE", 1) != 0;
+    if (bt == 64 && bv == 256)
+        return wide ? launch_fast<DT, 4, 1, 3, false, false, 64, true>(a, stream) : launch_fast<DT, 4, 1, 4, false, false>(a, stream);
+    if (bt == 64)
+        return wide ? launch_fast<DT, 2, 1, 3, false, false, 64, true>(a, stream) : launch_fast<DT, 2, 1, 6, false, false>(a, stream);
+    if (bt == 128 && wide) return launch_fast<DT, 2, 2, 3, false, false, 64, false>(a, stream);
     if (bt == 128) return launch_fast<DT, 2, 2, 5, false, false>(a, stream);
     return launch_fast<DT, 4, 4, 4, true, true>(a, stream);
 }

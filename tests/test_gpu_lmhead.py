@@ -79,6 +79,8 @@ def test_lmhead_score_matches_oracle(b, ref, dtype, n_rows, d, V):
     (100, 1024, 5000),       # 65..128 rows: 128 x 128 tiles
     (128, 512, 1000), (65, 64, 129), (64, 32, 128),
     (33, 64, 70001),         # few rows, large vocabulary: 256 x 64 tiles, ragged last tile
+    (20, 96, 66000),         # the same tiles with d_model a multiple of 32 only: stages of 32 K elements
+    (128, 4096, 3000),       # 128 x 128 tiles over the full inner dimension, stages of 64 K elements
 ])
 def test_lmhead_few_rows_every_row_against_the_oracle(b, ref, n_rows, d, V):
     w_ = synth.WORKLOADS["rps_dialogue"]

@@ -1,4 +1,4 @@
-"""The launch-shape overrides (SIRLLM_TUNE=1 plus SIRLLM_SCORE_*, SIRLLM_GATHER_*, SIRLLM_INPLACE_*, SIRLLM_FUSE_SELECT)
+"""The launch-shape overrides (SIRLLM_TUNE=1 plus SIRLLM_SCORE_*, SIRLLM_GATHER_*, SIRLLM_INPLACE_*, SIRLLM_FUSE_SELECT, SIRLLM_LMHEAD_WIDE)
 are part of the library: a sweep must be able to trust every setting.  The switch is read at the library's first
 launch in a process, so the matrix runs in a child process (tests/tuning_child.py), which checks each setting
 against the oracle."""

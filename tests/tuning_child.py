@@ -17,7 +17,7 @@ from paper_2405_12528_amd import binding as b, synth        # noqa: E402
 DEV = "cuda:0"
 KNOBS = ("SIRLLM_SCORE_BLOCK", "SIRLLM_SCORE_NT", "SIRLLM_GATHER_BLOCK", "SIRLLM_GATHER_UNROLL", "SIRLLM_GATHER_NT",
          "SIRLLM_FUSE_SELECT", "SIRLLM_INPLACE_BLOCK", "SIRLLM_INPLACE_UNROLL", "SIRLLM_INPLACE_PARTS",
-         "SIRLLM_INPLACE_NT", "SIRLLM_INPLACE_TICKET", "SIRLLM_GATHER_SCALAR_IDX", "SIRLLM_GATHER_ROTATE")
+         "SIRLLM_INPLACE_NT", "SIRLLM_INPLACE_TICKET", "SIRLLM_GATHER_SCALAR_IDX", "SIRLLM_GATHER_ROTATE", "SIRLLM_LMHEAD_WIDE")
 
 
 def set_knobs(**kw):
@@ -116,6 +116,21 @@ def check_step(label):
         assert np.array_equal(to_np(kd), rk) and np.array_equal(to_np(vd), rv), f"step K/V under {label}"
 
 
+def check_lmhead(label):
+    for n, d, V in ((54, 256, 3000), (7, 128, 66000), (100, 192, 700), (64, 96, 500)):      # every tile shape for up to 128 rows
+        g = torch.Generator(device=DEV).manual_seed(n + V)
+        h = (torch.randn((n, d), generator=g, device=DEV) + 0.5).to(torch.bfloat16)
+        w = (torch.randn((V, d), generator=g, device=DEV) * (3.0 / d ** 0.5)).to(torch.bfloat16)
+        tok = torch.randint(0, V, (n,), generator=g, device=DEV, dtype=torch.int32)
+        out = torch.zeros(n, device=DEV)
+        ws = torch.empty(b.sirllm_lmhead_workspace_bytes(n, V), dtype=torch.uint8, device=DEV)
+        b.sirllm_lmhead_score(h, w, tok, out, ws)
+        torch.cuda.synchronize()
+        want = ref.lmhead_score(to_np(h), to_np(w), to_np(tok))
+        err = np.abs(to_np(out).astype(np.float64) - want)
+        assert bool((err <= 2e-5 + 1e-5 * np.abs(want)).all()), f"lmhead {n}x{d}x{V} under {label}"
+
+
 def main():
     assert os.environ.get("SIRLLM_TUNE"), "run with SIRLLM_TUNE=1"
     assert torch.cuda.is_available()
@@ -137,6 +152,10 @@ def main():
                 label = set_knobs(GATHER_BLOCK=blk, GATHER_SCALAR_IDX=scalar, GATHER_ROTATE=rot)
                 check_gather(label); n += 1
                 print("ok", label, flush=True)
+    for wide in (0, 1):                                        # LM-head tiles for up to 128 rows: stages of 32 or of 64 K elements
+        label = set_knobs(LMHEAD_WIDE=wide)
+        check_lmhead(label); n += 1
+        print("ok", label, flush=True)
     for fuse in (0, 1):
         label = set_knobs(FUSE_SELECT=fuse)
         check_step(label); n += 1
