@@ -34,7 +34,7 @@
  *                                rows of 256 bytes in tiles of 64 or 128 threads: kept indices by scalar loads (1) or per lane (0);
  *                                tiles of each group of eight exchanged by the plane index (1) or not (0)
  *       SIRLLM_FUSE_SELECT [1]   0: score and select in separate launches even when they are independent
- *       SIRLLM_LMHEAD_WIDE [1]   LM-head score of up to 128 rows with d_model a multiple of 64: pipeline stages of 64 (1) or 32 (0)
+ *       SIRLLM_LMHEAD_WIDE [1]   LM-head score of up to 128 rows (256 against a vocabulary below 65536 rows) with d_model a multiple of 64: pipeline stages of 64 (1) or 32 (0)
  *                                K elements, i.e. whole or half 128-byte lines of the embedding matrix per load
  *       SIRLLM_INPLACE_BLOCK [1024] (512, 256), SIRLLM_INPLACE_UNROLL [4] (2, 8), SIRLLM_INPLACE_PARTS [by plane count]
  *                                threads, vectors per lane and column parts of the in-place walk

@@ -117,7 +117,7 @@ def check_step(label):
 
 
 def check_lmhead(label):
-    for n, d, V in ((54, 256, 3000), (7, 128, 66000), (100, 192, 700), (64, 96, 500), (90, 64, 66000)):      # every tile shape for up to 128 rows
+    for n, d, V in ((54, 256, 3000), (7, 128, 66000), (100, 192, 700), (64, 96, 500), (90, 64, 66000), (200, 128, 900)):      # every tile shape that has two stage widths
         g = torch.Generator(device=DEV).manual_seed(n + V)
         h = (torch.randn((n, d), generator=g, device=DEV) + 0.5).to(torch.bfloat16)
         w = (torch.randn((V, d), generator=g, device=DEV) * (3.0 / d ** 0.5)).to(torch.bfloat16)
