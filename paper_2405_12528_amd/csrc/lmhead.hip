@@ -259,7 +259,8 @@ __device__ __forceinline__ void load_to_lds(const char* g, char* lds_block)
 // 32 x 32, so the tile is (64 NVB) vocabulary rows x (64 NTB) tokens:
 //   NVB = NTB = 4   256 x 256, 256 accumulator registers per lane, one workgroup per CU: MFMA bound
 //   NVB = 2, NTB = 4   128 x 256 for 129 to 256 rows against a vocabulary below 65536 rows
-//   NVB = NTB = 2   128 x 128 for 65 to 128 rows (NVB = 4: 256 x 128 against a vocabulary of 65536 rows or more)
+//   NVB = NTB = 2   128 x 128 for 65 to 128 rows (NVB = 4: 256 x 128 against a vocabulary of 65536 rows or more, there
+//                   also for 257 to 384 rows)
 //   NVB = 2, NTB = 1   128 x 64 for up to 64 rows (a turn of a dialogue): bound by streaming W from HBM
 // Tiles go from global memory straight into LDS, no staging registers, through a ring of RING buffers (stage =
 // 32 K elements of both tiles; buffer = stage % RING).  One stage is two 16-wide slices:
@@ -584,6 +585,9 @@ void tile_shape(int64_t n_rows, int32_t vocab, int& bv, int& bt)
     else if (n_rows <= 128) { bv = vocab >= 65536 ? 256 : 128; bt = 128; }
     // 129 to 256 rows: one token tile; a vocabulary below 65536 rows has too few 256-row tiles to fill the chip
     else if (n_rows <= 256 && vocab < 65536) { bv = 128; bt = 256; }
+    // 257 to 384 rows against a large vocabulary: three token tiles of 128 rows waste fewer MFMAs than two of 256
+    // (300 x 4096 x 128256: 541 -> 460 us); from 385 rows on the 256 x 256 tile's pinned schedule wins again
+    else if (n_rows > 256 && n_rows <= 384 && vocab >= 65536) { bv = 256; bt = 128; }
     else { bv = 256; bt = 256; }
 }
 

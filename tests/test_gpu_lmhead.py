@@ -83,6 +83,7 @@ def test_lmhead_score_matches_oracle(b, ref, dtype, n_rows, d, V):
     (128, 4096, 3000),       # 128 x 128 tiles over the full inner dimension, stages of 64 K elements
     (100, 128, 66000), (70, 96, 66000),   # 65..128 rows against a large vocabulary: 256 x 128 tiles, stages of 64 and of 32
     (200, 4096, 1500), (150, 96, 2000),   # 129..256 rows against a small vocabulary: 128 x 256 tiles, stages of 64 and of 32
+    (300, 128, 66000), (384, 96, 66000),  # 257..384 rows against a large vocabulary: three token tiles of 256 x 128
 ])
 def test_lmhead_few_rows_every_row_against_the_oracle(b, ref, n_rows, d, V):
     w_ = synth.WORKLOADS["rps_dialogue"]
