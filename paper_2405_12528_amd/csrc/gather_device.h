@@ -26,6 +26,23 @@ __device__ __forceinline__ void st(char* p, VecT v)
     else *(VecT*)p = v;
 }
 
+// A streaming store of bytes that this launch never touches again: base (wave uniform) + off.  16-byte vectors go
+// out at agent scope with the non-temporal hint (`sc1 nt`): written through instead of left dirty in the L2, which
+// measured 6.7 against 6.3 TB/s for a plain 1 GiB fill and 1 % on the gather; the other widths take the compiler's
+// non-temporal store.
+template <typename VecT, typename OffT>
+__device__ __forceinline__ void st_stream(char* base, OffT off, VecT v)
+{
+    if constexpr (sizeof(VecT) == 16 && sizeof(OffT) == 4) {
+        asm volatile("global_store_dwordx4 %0, %1, %2 sc1 nt" ::"v"(off), "v"(v), "s"(base) : "memory");
+    } else if constexpr (sizeof(VecT) == 16) {
+        char* p = base + off;
+        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" ::"v"(p), "v"(v) : "memory");
+    } else {
+        __builtin_nontemporal_store(v, (VecT*)(base + off));
+    }
+}
+
 struct GatherLaunch {
     GatherArgs a;
     int32_t vpr;          // vectors per row
@@ -103,7 +120,10 @@ __device__ __forceinline__ void gather_tile_at(const GatherLaunch& g, int tile, 
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
-        if (live[u]) st<VecT, NT>(dp + doff[u], v[u]);
+        if (live[u]) {
+            if constexpr (NT) st_stream<VecT, off_t>(dp, doff[u], v[u]);
+            else st<VecT, false>(dp + doff[u], v[u]);
+        }
 }
 
 // A tile for rows that are a power of two of 16-byte vectors, at least sixteen (256 bytes), one vector per lane.
@@ -247,9 +267,9 @@ __device__ __forceinline__ void gather_tile_wave_rows(const WaveRowsArgs& w, int
         const auto* p = (const __attribute__((address_space(1))) VecT*)(sp + ((off_t)i * (off_t)s_pos + (off_t)(c * 16)));
         v = NT ? __builtin_nontemporal_load(p) : *p;
     }
-    auto* q = (__attribute__((address_space(1))) VecT*)(dp + ((off_t)j * (off_t)d_pos + (off_t)(c * 16)));
-    if (NT) __builtin_nontemporal_store(v, q);
-    else *q = v;
+    const off_t qoff = (off_t)j * (off_t)d_pos + (off_t)(c * 16);
+    if constexpr (NT) st_stream<VecT, off_t>((char*)(uintptr_t)(uint64_t)dp, qoff, v);
+    else *(__attribute__((address_space(1))) VecT*)(dp + qoff) = v;
 }
 
 // The cache is one buffer per tensor: plane -> base pointers by the layout's strides (uniform over the workgroup:
