@@ -30,14 +30,16 @@ __device__ __forceinline__ void st(char* p, VecT v)
 // out at agent scope with the non-temporal hint (`sc1 nt`): written through instead of left dirty in the L2, which
 // measured 6.7 against 6.3 TB/s for a plain 1 GiB fill and 1 % on the gather; the other widths take the compiler's
 // non-temporal store.
-// The instruction is written out, so the compiler does not see a store there: what it would otherwise look after --
-// the wait states a store of more than 8 bytes needs before its data registers may be overwritten -- is the two
-// `s_nop` behind it (a kernel that ends right after the store does not need them, one that loops does).
+// The instruction is written out, so the compiler does not see a store there.  What it would otherwise look after is
+// spelled out around it: five wait states in front (a scalar base that a vector instruction has just written, e.g. a
+// v_readfirstlane, must not be read sooner) and two behind (a store of more than 8 bytes must have read its data
+// registers before they are overwritten; a kernel that ends right after the store does not need them, one that loops
+// does).  A few cycles in a wave that lives for microseconds: no difference in time (159.0 us either way).
 template <typename VecT, typename OffT>
 __device__ __forceinline__ void st_stream(char* base, OffT off, VecT v)
 {
     if constexpr (sizeof(VecT) == 16 && sizeof(OffT) == 4) {
-        asm volatile("global_store_dwordx4 %0, %1, %2 sc1 nt\n\ts_nop 1" ::"v"(off), "v"(v), "s"(base) : "memory");
+        asm volatile("s_nop 4\n\tglobal_store_dwordx4 %0, %1, %2 sc1 nt\n\ts_nop 1" ::"v"(off), "v"(v), "s"(base) : "memory");
     } else if constexpr (sizeof(VecT) == 16) {
         char* p = base + off;
         asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
